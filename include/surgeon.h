@@ -1,0 +1,149 @@
+/*
+ * surgeon.h -- C ABI of the MI355X (gfx950) hot path of SURGEON's adaptation step
+ * (layer-wise dynamic activation pruning, Section 4 of the paper).
+ *
+ * The four operations follow Algorithm 1 and Eq. 2, 4-7:
+ *   - surgeon_grad_importance : Eq. 4       (RMS of one layer's weight gradient)
+ *   - surgeon_layer_ratios    : Eq. 5, 6, 7 (Layer Activation Memory, combined indicator, pruning ratio)
+ *   - surgeon_prune_pack      : Alg. 1 lines 6-7 (prune A_i at ratio p_i, cache as non-zero values + 1 bit/element)
+ *   - surgeon_dw_from_packed  : Alg. 1 lines 11-12 with Eq. 2 (rebuild the pruned activation, weight gradient)
+ *
+ * Conventions shared by every entry point
+ *   - "device" pointers are HIP device memory the CALLER owns; the library never allocates, frees or
+ *     retains device memory and keeps no state between calls.  "host" pointers are ordinary memory.
+ *   - All device work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream)
+ *     and the call returns without synchronising.
+ *   - The return value is a surgeon_status.  Argument errors are found on the host before any launch and
+ *     leave every output untouched.  surgeon_last_error() returns a thread-local description.
+ *   - Inputs are read-only; outputs are fully overwritten (never accumulated into).
+ *   - Workspaces (`ws`) are scratch device memory whose size comes from the matching *_ws_bytes query;
+ *     contents on entry are irrelevant and contents on exit are unspecified.  Pointers must be 16-byte
+ *     aligned (any torch / hipMalloc allocation is).
+ */
+#ifndef SURGEON_H_
+#define SURGEON_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SURGEON_F32 = 0,  /* IEEE binary32                                   */
+  SURGEON_BF16 = 1  /* bfloat16 storage; every accumulation is in fp32 */
+} surgeon_dtype;
+
+typedef enum {
+  SURGEON_OK = 0,
+  SURGEON_EINVAL = 1,       /* null pointer, negative size, r outside [0,1] or NaN, group_len < 1, bad dtype */
+  SURGEON_ESIZE = 2,        /* a caller buffer or workspace is too small                                    */
+  SURGEON_EUNSUPPORTED = 3, /* shape / layout outside the implemented set                                   */
+  SURGEON_EHIP = 4          /* a HIP runtime call failed; see surgeon_last_error()                          */
+} surgeon_status;
+
+typedef enum { SURGEON_LINEAR = 0, SURGEON_CONV2D = 1 } surgeon_layer_kind;
+
+/*
+ * Shape of one adapted layer for surgeon_dw_from_packed (Eq. 2, second line).
+ *   LINEAR : cached activation A is [M tokens x K in-features] row-major, dY is [M x N out-features]
+ *            row-major, dW is [N x K] row-major (the layout of a framework's `weight`; it is the
+ *            transpose of Eq. 2's A^T dY).
+ *   CONV2D : A is [Nb, Ci, H, W], dY is [Nb, Co, OH, OW], dW is [Co, Ci, kh, kw], all contiguous NCHW,
+ *            OH = (H + 2*pad - kh)/stride + 1 (same for OW); cross-correlation, zero padding,
+ *            no dilation, groups = 1, no bias.
+ * dtype is the element type of vals and dY; dW is always fp32.
+ * k_total is the number of values in the packed stream (as returned by surgeon_packed_sizes);
+ * it bounds every read of `vals`.
+ */
+typedef struct {
+  int32_t kind;  /* surgeon_layer_kind */
+  int32_t dtype; /* surgeon_dtype      */
+  int64_t M, K, N;                                   /* LINEAR */
+  int64_t Nb, Ci, H, W, Co, kh, kw, stride, pad;     /* CONV2D */
+  int64_t k_total;
+} surgeon_layer_desc;
+
+/*
+ * Number of elements kept out of `len` at prune ratio r (Alg. 1 line 6 leaves the rounding open; this
+ * is the single formula both the library and its callers use):
+ *     clamp( (int64) ceil( (1.0 - (double)r) * (double)len ), 0, len )
+ * evaluated in IEEE double from the float32 r, no FMA contraction.  Host only.  Returns -1 if r is NaN
+ * or outside [0,1] or len < 0.
+ */
+int64_t surgeon_keep_count(int64_t len, float r);
+
+/*
+ * Sizes of the packed form of an n-element activation pruned in groups of group_len consecutive
+ * elements (the last group may be shorter).  Host only.  Any output pointer may be NULL.
+ *   k_total    : sum over groups of surgeon_keep_count(len_g, r)
+ *   vals_bytes : k_total * sizeof(element)
+ *   mask_bytes : 8 * ceil(n / 64)
+ *   ws_bytes   : workspace surgeon_prune_pack needs for this call
+ */
+int surgeon_packed_sizes(int64_t n, int64_t group_len, float r, int dt,
+                         int64_t* k_total, size_t* vals_bytes, size_t* mask_bytes, size_t* ws_bytes);
+
+/*
+ * Eq. 5-7.  Host only; G, m, r_out are host arrays of length l.
+ *   M_i = -log(m_i / sum_j m_j)                              (Eq. 5; m_i = size of A_i, caller's unit)
+ *   I_i = (M_i / max_j M_j) * (G_i / max_j G_j)              (Eq. 6, max normalisation; 0/0 := 1)
+ *   p_i = 1 - I_i / max_j I_j                                (Eq. 7; max I = 0 gives p = 0)
+ *   r_out[i] = r_lo + (r_hi - r_lo) * p_i                    ((r_lo, r_hi) = (0, 1) is Eq. 7 itself)
+ * computed in double, rounded once to float.  Errors: l < 1, null pointers, any m_i == 0, G_i negative
+ * or non-finite, r_lo/r_hi outside [0,1] or r_lo > r_hi  ->  SURGEON_EINVAL.
+ */
+int surgeon_layer_ratios(const float* G, const uint64_t* m, int l, float r_lo, float r_hi, float* r_out);
+
+/*
+ * Alg. 1 lines 6-7: prune and pack.  A, vals, mask, idx, ws are device pointers.
+ * Within every group the k_g = surgeon_keep_count(len_g, r) elements of largest magnitude are kept,
+ * under the total order (key descending, index ascending) with key = the element's bit pattern with the
+ * sign bit cleared, read as an unsigned integer (so +0 and -0 tie, Inf is above every finite value and
+ * NaNs above Inf).  Outputs:
+ *   vals : k_total elements of dtype dt, bit-exact copies of the kept elements in ascending flat index
+ *          (group j's values start at element sum_{j'<j} k_j').
+ *   mask : ceil(n/64) uint64 words; element e <-> bit (e % 64) of word e / 64; padding bits are 0.
+ *   idx  : NULL, or k_total uint32 = offset of each kept element inside its group, same order as vals.
+ * n == 0 or k_total == 0 is legal.  ws/ws_bytes as reported by surgeon_packed_sizes (ws may be NULL when
+ * that size is 0).  Requires n < 2^31 * 64 and group_len <= n rounded up (group_len > n is treated as n).
+ */
+int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, float r, int dt,
+                       void* vals, uint64_t* mask, uint32_t* idx,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* Workspace surgeon_dw_from_packed needs for `desc`.  Host only. */
+int surgeon_dw_ws_bytes(const surgeon_layer_desc* desc, size_t* ws_bytes);
+
+/*
+ * Alg. 1 lines 11-12 / Eq. 2 (weight gradient): dW = dY^T . A_pruned, where A_pruned is rebuilt from
+ * (vals, mask) inside the kernels (dropped positions are +0) and never written to memory.
+ * vals, mask, dY, dW, ws are device pointers; desc is a host pointer.  dW (fp32) is overwritten.
+ * The result does not depend on the group_len / r the packing used.  Deterministic: the same inputs give
+ * the same bits on every call.
+ */
+int surgeon_dw_from_packed(const surgeon_layer_desc* desc, const void* vals, const uint64_t* mask,
+                           const void* dY, float* dW, void* ws, size_t ws_bytes, void* stream);
+
+/* Workspace surgeon_grad_importance needs for n_w elements.  Host only. */
+size_t surgeon_grad_importance_ws_bytes(int64_t n_w);
+
+/*
+ * Eq. 4: G = sqrt( sum_j dW_j^2 / n_w ) with N_i read as the number of weight elements of the layer.
+ * dW: n_w fp32 on the device; G_out: one fp32 on the device (the caller copies all layers' scalars back
+ * in one transfer).  Accumulation is in fp64 in a fixed order (deterministic).  n_w == 0 writes 0.
+ */
+int surgeon_grad_importance(const float* dW, int64_t n_w, float* G_out,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* Description of the last error on the calling thread (static storage, never NULL). */
+const char* surgeon_last_error(void);
+
+/* Library version string, e.g. "surgeon-gfx950 0.1". */
+const char* surgeon_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SURGEON_H_ */
