@@ -1,0 +1,47 @@
+// Internal helpers shared by the translation units of libsurgeon (gfx950 only; not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "surgeon.h"
+
+namespace surgeon {
+
+// thread-local error text behind surgeon_last_error()
+void set_error(const char* fmt, ...);
+int fail(int status, const char* fmt, ...);
+
+#define SURGEON_HIP_CHECK(expr)                                                                   \
+  do {                                                                                            \
+    hipError_t e_ = (expr);                                                                       \
+    if (e_ != hipSuccess)                                                                         \
+      return ::surgeon::fail(SURGEON_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), \
+                             __FILE__, __LINE__);                                                 \
+  } while (0)
+
+// launch check: catches bad launch configurations without synchronising
+#define SURGEON_LAUNCH_CHECK() SURGEON_HIP_CHECK(hipGetLastError())
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- layout of the packed-sizes arithmetic, shared by host entry points ----
+struct GroupPlan {
+  int64_t n, g, n_groups, len_last, k_full, k_last, k_total;
+};
+// returns false when (n, group_len, r) is invalid
+bool make_group_plan(int64_t n, int64_t group_len, float r, GroupPlan* p);
+
+// workspace of the large-group (multi-kernel radix select) path of prune_pack; 0 for the in-register path
+size_t prune_pack_ws_bytes(const GroupPlan& p);
+
+// selection paths of prune_pack
+enum PrunePath { PATH_WAVE_REG = 0, PATH_WAVE_MEM = 1, PATH_GLOBAL = 2 };
+PrunePath choose_prune_path(const GroupPlan& p);
+
+constexpr int kWaveRegMaxGroup = 4096;  // largest group one wavefront keeps in registers (64 lanes x 64)
+constexpr int kGlobalHistChunk = 4096;  // elements per block in the histogram passes of the global path
+constexpr int kGlobalWaveChunk = 1024;  // elements per wavefront in the count / pack passes of the global path
+
+}  // namespace surgeon

@@ -1,0 +1,653 @@
+// Weight gradient from the packed activation (Alg. 1 lines 11-12, Eq. 2): dW = dY^T . A_pruned.
+//
+// The dense pruned activation is never written to memory: every workgroup rebuilds the tile it needs from
+// (vals, mask) straight into LDS -- element e is vals[rank(e)] if bit e of the mask is set, else 0, where
+// rank(e) = (set bits before e) comes from a per-64-element prefix table built by a small pre-pass over the
+// mask -- and feeds MFMA from there.  This is the only dense contraction of the path, hence the only MFMA user.
+//
+//   conv2d : implicit GEMM with the output positions (b, oh, ow) as the contraction dimension.  A workgroup
+//            owns a [co x ci] tile for ALL taps (u, v) of the filter (or one filter row for large filters): a
+//            K-tile is R output rows of one image; its dY rows and the matching input patch (with halo) sit in
+//            LDS, and the taps are just shifted LDS reads of the same patch, so every un-packed activation
+//            element is reused kh*kw*tile_co times.
+//   linear : dW[o][i] = sum_m dY[m][o] * A[m][i]; K-tiles of TM tokens.
+// Long contractions are split over workgroups; each split writes its partial tile to the workspace and a last
+// kernel adds the splits in index order (no floating-point atomics: results are reproducible bit for bit).
+// Inputs in bf16 are widened to fp32 while staging (exact), so all products and sums are fp32 MFMA.
+#include <algorithm>
+
+#include "common.hpp"
+
+namespace surgeon {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+template <typename InT>
+__device__ __forceinline__ float widen(InT v);
+template <>
+__device__ __forceinline__ float widen<float>(float v) {
+  return v;
+}
+template <>
+__device__ __forceinline__ float widen<uint16_t>(uint16_t v) {
+  return __uint_as_float((uint32_t)v << 16);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// rank table: word_rank[w] = number of set mask bits before word w
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kRankBlock = 256;
+constexpr int kRankWordsPerBlock = 1024;  // 4 words per thread
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t t = (uint32_t)__shfl_up((int)v, off, 64);
+    if (lane >= off) v += t;
+  }
+  return v;
+}
+
+// exclusive prefix of `v` over the 256 threads of the block (and the block total in *total)
+__device__ __forceinline__ uint32_t block_excl_scan_u32(uint32_t v, uint32_t* lds4, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t incl = wave_incl_scan_u32(v, lane);
+  if (lane == 63) lds4[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kRankBlock / 64; ++w) {
+    const uint32_t s = lds4[w];
+    if (w < wave) base += s;
+    tot += s;
+  }
+  *total = tot;
+  return base + incl - v;
+}
+
+__global__ __launch_bounds__(kRankBlock) void rank_block_sum_kernel(const uint64_t* __restrict__ mask, int64_t n_words,
+                                                                    uint32_t* __restrict__ block_sum) {
+  __shared__ uint32_t lds4[kRankBlock / 64];
+  const int64_t w0 = (int64_t)blockIdx.x * kRankWordsPerBlock + threadIdx.x * 4;
+  uint32_t s = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if (w0 + q < n_words) s += (uint32_t)__popcll(mask[w0 + q]);
+  uint32_t total;
+  block_excl_scan_u32(s, lds4, &total);
+  if (threadIdx.x == 0) block_sum[blockIdx.x] = total;
+}
+
+// single block: in-place exclusive scan of the block sums
+__global__ __launch_bounds__(1024) void rank_scan_kernel(uint32_t* __restrict__ block_sum, int n_blocks) {
+  __shared__ uint32_t part[1024];
+  const int tid = threadIdx.x;
+  const int per = (n_blocks + 1023) / 1024;
+  const int begin = min(tid * per, n_blocks), end = min(begin + per, n_blocks);
+  uint32_t s = 0;
+  for (int i = begin; i < end; ++i) s += block_sum[i];
+  part[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t acc = 0;
+    for (int t = 0; t < 1024; ++t) {
+      const uint32_t v = part[t];
+      part[t] = acc;
+      acc += v;
+    }
+  }
+  __syncthreads();
+  uint32_t acc = part[tid];
+  for (int i = begin; i < end; ++i) {
+    const uint32_t v = block_sum[i];
+    block_sum[i] = acc;
+    acc += v;
+  }
+}
+
+__global__ __launch_bounds__(kRankBlock) void rank_write_kernel(const uint64_t* __restrict__ mask, int64_t n_words,
+                                                                const uint32_t* __restrict__ block_base,
+                                                                uint32_t* __restrict__ word_rank) {
+  __shared__ uint32_t lds4[kRankBlock / 64];
+  const int64_t w0 = (int64_t)blockIdx.x * kRankWordsPerBlock + threadIdx.x * 4;
+  uint32_t c[4];
+  uint32_t s = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    c[q] = (w0 + q < n_words) ? (uint32_t)__popcll(mask[w0 + q]) : 0u;
+    s += c[q];
+  }
+  uint32_t total;
+  uint32_t base = block_base[blockIdx.x] + block_excl_scan_u32(s, lds4, &total);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if (w0 + q < n_words) word_rank[w0 + q] = base;
+    base += c[q];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// un-pack of one element (Alg. 1 line 11)
+// ---------------------------------------------------------------------------------------------------------
+template <typename InT>
+struct Packed {
+  const InT* __restrict__ vals;
+  const uint64_t* __restrict__ mask;
+  const uint32_t* __restrict__ word_rank;
+  int64_t k_last;  // k_total - 1: every read of vals is clamped to it
+};
+
+template <typename InT>
+__device__ __forceinline__ float unpack_at(const Packed<InT>& p, int64_t e) {
+  const int64_t w = e >> 6;
+  const int bit = (int)(e & 63);
+  const uint64_t word = p.mask[w];
+  if (!((word >> bit) & 1ull)) return 0.0f;
+  int64_t r = (int64_t)p.word_rank[w] + __popcll(word & ((1ull << bit) - 1ull));
+  r = r > p.k_last ? p.k_last : r;
+  return widen<InT>(p.vals[r]);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// conv2d
+// ---------------------------------------------------------------------------------------------------------
+struct ConvGeom {
+  int Nb, Ci, H, W, Co, OH, OW, KH, KW, stride, pad;
+  int R;                // output rows per K-tile (divides OH)
+  int tiles_per_img;    // OH / R
+  int n_ktiles;         // Nb * tiles_per_img
+  int tiles_per_split;  // K-tiles per workgroup along the contraction
+  int PR, PW, PS;       // patch rows / cols kept in LDS per input channel, and the per-channel stride (floats)
+  int lds_step;         // LDS distance between horizontally adjacent output positions (1 for 1x1 filters: only
+                        // the pixels a strided 1x1 filter touches are staged), fill_step = stride / lds_step
+  int fill_step;
+  int ci_tiles;         // output tiles along ci (blockIdx.x = co_tile * ci_tiles + ci_tile)
+  int64_t n_w;          // Co*Ci*KH*KW
+};
+
+// Workgroup = 4 wavefronts as 2 (co) x 2 (ci); wavefront tile = MT x NT MFMA 16x16 tiles for KHC*KW taps.
+// blockIdx.y = split along the contraction, blockIdx.z = first filter row handled (u0 = z * KHC).
+template <typename InT, int KHC, int KW, int MT, int NT, int P>
+__global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) void dw_conv_kernel(ConvGeom gm, Packed<InT> pk,
+                                                                                      const InT* __restrict__ dY,
+                                                                                      float* __restrict__ out) {
+  constexpr int TCO = 2 * MT * 16, TCI = 2 * NT * 16, SY = P + 4, TAPS = KHC * KW, STEPS = P / 4;
+  extern __shared__ float smem[];
+  float* __restrict__ dYs = smem;            // [TCO][SY]
+  float* __restrict__ As = smem + TCO * SY;  // [TCI][PS]: PR patch rows followed by KHC rows of zeros
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int i16 = lane & 15, kk = lane >> 4;
+  const int co_tile = blockIdx.x / gm.ci_tiles, ci_tile = blockIdx.x % gm.ci_tiles;
+  const int co0 = co_tile * TCO, ci0 = ci_tile * TCI;
+  const int u0 = blockIdx.z * KHC;
+  const int PW = gm.PW, PS = gm.PS;
+
+  // LDS offset of the input pixel under tap (0,0) for each contraction position this lane feeds;
+  // positions past R*OW point at the zero rows (their dY is zero as well)
+  int aoff[STEPS];
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+    const int k = 4 * s + kk;
+    const int r = k / gm.OW, ow = k - r * gm.OW;
+    aoff[s] = (r < gm.R) ? (r * gm.lds_step) * PW + ow * gm.lds_step : gm.PR * PW;
+  }
+  // zero rows at the end of every channel's patch (written once)
+  for (int c = 0; c < TCI; ++c)
+    for (int t = tid; t < KHC * PW; t += 256) As[c * PS + gm.PR * PW + t] = 0.0f;
+
+  floatx4 acc[MT][NT][TAPS];
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int b = 0; b < NT; ++b)
+#pragma unroll
+      for (int t = 0; t < TAPS; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int t_begin = blockIdx.y * gm.tiles_per_split;
+  const int t_end = min(t_begin + gm.tiles_per_split, gm.n_ktiles);
+  const int valid_pos = gm.R * gm.OW;
+
+  for (int tile = t_begin; tile < t_end; ++tile) {
+    const int b = tile / gm.tiles_per_img;
+    const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
+    __syncthreads();  // the previous tile's MFMA reads are done
+    // ---- stage dY[b, co0.., oh0..oh0+R, :] : R*OW contiguous elements per output channel
+    for (int idx = tid; idx < TCO * P; idx += 256) {
+      const int c = idx / P, k = idx - c * P;
+      float v = 0.0f;
+      if (co0 + c < gm.Co && k < valid_pos)
+        v = widen<InT>(dY[(((int64_t)b * gm.Co + co0 + c) * gm.OH + oh0) * gm.OW + k]);
+      dYs[c * SY + k] = v;
+    }
+    // ---- stage the un-packed input patch: PR rows from ih0 and PW columns from -pad, every fill_step-th pixel
+    const int ih0 = oh0 * gm.stride + u0 - gm.pad;
+    for (int c = wave * (TCI / 4); c < (wave + 1) * (TCI / 4); ++c) {
+      const int ci = ci0 + c;
+      for (int pr = 0; pr < gm.PR; ++pr) {
+        const int ih = ih0 + pr * gm.fill_step;
+        const bool row_ok = ci < gm.Ci && ih >= 0 && ih < gm.H;
+        const int64_t e_row = (((int64_t)b * gm.Ci + ci) * gm.H + ih) * gm.W;
+        for (int col = lane; col < PW; col += 64) {
+          const int iw = col * gm.fill_step - gm.pad;
+          float v = 0.0f;
+          if (row_ok && iw >= 0 && iw < gm.W) v = unpack_at<InT>(pk, e_row + iw);
+          As[c * PS + pr * PW + col] = v;
+        }
+      }
+    }
+    __syncthreads();
+    // ---- MFMA over the positions of this tile; taps are shifted reads of the same patch
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      float av[MT];
+#pragma unroll
+      for (int a = 0; a < MT; ++a) av[a] = dYs[(wm * MT * 16 + a * 16 + i16) * SY + 4 * s + kk];
+#pragma unroll
+      for (int du = 0; du < KHC; ++du) {
+#pragma unroll
+        for (int v = 0; v < KW; ++v) {
+#pragma unroll
+          for (int bn = 0; bn < NT; ++bn) {
+            const float bv = As[(wn * NT * 16 + bn * 16 + i16) * PS + aoff[s] + du * PW + v];
+#pragma unroll
+            for (int a = 0; a < MT; ++a)
+              acc[a][bn][du * KW + v] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv, acc[a][bn][du * KW + v], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+
+  // ---- write this split's partial tile: lane holds rows 4*kk..4*kk+3 (co), column i16 (ci) of each 16x16 tile
+  float* __restrict__ dst = out + (int64_t)blockIdx.y * gm.n_w;
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+#pragma unroll
+    for (int bn = 0; bn < NT; ++bn) {
+      const int ci = ci0 + wn * NT * 16 + bn * 16 + i16;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int co = co0 + wm * MT * 16 + a * 16 + 4 * kk + r;
+        if (co < gm.Co && ci < gm.Ci) {
+          const int64_t base = (((int64_t)co * gm.Ci + ci) * gm.KH + u0) * gm.KW;
+#pragma unroll
+          for (int du = 0; du < KHC; ++du)
+#pragma unroll
+            for (int v = 0; v < KW; ++v) dst[base + du * gm.KW + v] = acc[a][bn][du * KW + v][r];
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// linear
+// ---------------------------------------------------------------------------------------------------------
+struct LinGeom {
+  int64_t M, K, N;
+  int i_tiles;            // tiles along in-features (blockIdx.x = o_tile * i_tiles + i_tile)
+  int64_t rows_per_split; // tokens per workgroup along the contraction (multiple of TM)
+  int64_t n_w;
+};
+
+template <typename InT, int MT, int NT, int TM>
+__global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) void dw_linear_kernel(LinGeom gm, Packed<InT> pk,
+                                                                                        const InT* __restrict__ dY,
+                                                                                        float* __restrict__ out) {
+  constexpr int TO = 2 * MT * 16, TI = 2 * NT * 16, SO = TO + 16, SI = TI + 16, STEPS = TM / 4;
+  __shared__ float dYs[TM * SO];
+  __shared__ float As[TM * SI];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int i16 = lane & 15, kk = lane >> 4;
+  const int o_tile = blockIdx.x / gm.i_tiles, i_tile = blockIdx.x % gm.i_tiles;
+  const int64_t o0 = (int64_t)o_tile * TO, i0 = (int64_t)i_tile * TI;
+
+  floatx4 acc[MT][NT];
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int b = 0; b < NT; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int64_t m_begin = (int64_t)blockIdx.y * gm.rows_per_split;
+  const int64_t m_end = min(m_begin + gm.rows_per_split, gm.M);
+  for (int64_t m0 = m_begin; m0 < m_end; m0 += TM) {
+    __syncthreads();
+    for (int idx = tid; idx < TM * TO; idx += 256) {
+      const int r = idx / TO, c = idx - r * TO;
+      const int64_t m = m0 + r, o = o0 + c;
+      dYs[r * SO + c] = (m < m_end && o < gm.N) ? widen<InT>(dY[m * gm.N + o]) : 0.0f;
+    }
+    for (int idx = tid; idx < TM * TI; idx += 256) {
+      const int r = idx / TI, c = idx - r * TI;
+      const int64_t m = m0 + r, i = i0 + c;
+      As[r * SI + c] = (m < m_end && i < gm.K) ? unpack_at<InT>(pk, m * gm.K + i) : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      float av[MT], bv[NT];
+#pragma unroll
+      for (int a = 0; a < MT; ++a) av[a] = dYs[(4 * s + kk) * SO + wm * MT * 16 + a * 16 + i16];
+#pragma unroll
+      for (int b = 0; b < NT; ++b) bv[b] = As[(4 * s + kk) * SI + wn * NT * 16 + b * 16 + i16];
+#pragma unroll
+      for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int b = 0; b < NT; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+    }
+  }
+  float* __restrict__ dst = out + (int64_t)blockIdx.y * gm.n_w;
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int b = 0; b < NT; ++b) {
+      const int64_t i = i0 + wn * NT * 16 + b * 16 + i16;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int64_t o = o0 + wm * MT * 16 + a * 16 + 4 * kk + r;
+        if (o < gm.N && i < gm.K) dst[o * gm.K + i] = acc[a][b][r];
+      }
+    }
+}
+
+// adds the split partials in index order
+__global__ __launch_bounds__(256) void dw_reduce_splits_kernel(const float* __restrict__ part, int n_splits, int64_t n_w,
+                                                               float* __restrict__ dW) {
+  for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n_w; x += (int64_t)gridDim.x * 256) {
+    float s = part[x];
+    for (int k = 1; k < n_splits; ++k) s += part[(int64_t)k * n_w + x];
+    dW[x] = s;
+  }
+}
+
+__global__ void fill_zero_f32_kernel(float* __restrict__ p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// host planning
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kSplitSlots = 512;   // two workgroups on each of the 256 compute units
+constexpr int kMaxSplits = 256;
+constexpr size_t kMaxLds = 160 * 1024;
+
+struct ConvPlan {
+  ConvGeom g;
+  int khc, kw_t, mt, nt, p;  // kernel variant
+  int co_tiles, z, splits;
+  size_t lds_bytes;
+};
+
+struct LinPlan {
+  LinGeom g;
+  int mt, nt, tm;
+  int o_tiles, splits;
+};
+
+struct DwPlan {
+  bool conv;
+  ConvPlan c;
+  LinPlan l;
+  int64_t n, n_words, n_rank_blocks, n_w;
+  int splits;
+  size_t off_rank, off_blocks, off_part, ws_bytes;
+};
+
+static int choose_splits(int64_t k_tiles, int64_t out_tiles, int64_t* tiles_per_split) {
+  int64_t s = std::max<int64_t>(1, std::min<int64_t>(k_tiles, kSplitSlots / std::max<int64_t>(1, out_tiles)));
+  s = std::min<int64_t>(s, kMaxSplits);
+  const int64_t per = ceil_div(k_tiles, s);
+  *tiles_per_split = per;
+  return (int)ceil_div(k_tiles, per);
+}
+
+static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
+  if (d->Nb < 1 || d->Ci < 1 || d->H < 1 || d->W < 1 || d->Co < 1 || d->kh < 1 || d->kw < 1 || d->stride < 1 ||
+      d->pad < 0)
+    return fail(SURGEON_EINVAL, "dw_from_packed: bad conv shape");
+  if (d->H + 2 * d->pad < d->kh || d->W + 2 * d->pad < d->kw)
+    return fail(SURGEON_EINVAL, "dw_from_packed: filter larger than the padded input");
+  const int64_t big = (int64_t)1 << 31;
+  if (d->Nb * d->Ci * d->H * d->W > big || d->Nb >= (1 << 24) || d->Co * d->Ci * d->kh * d->kw > big)
+    return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv tensor too large");
+  ConvGeom& g = cp->g;
+  g.Nb = (int)d->Nb; g.Ci = (int)d->Ci; g.H = (int)d->H; g.W = (int)d->W; g.Co = (int)d->Co;
+  g.KH = (int)d->kh; g.KW = (int)d->kw; g.stride = (int)d->stride; g.pad = (int)d->pad;
+  g.OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1;
+  g.OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
+  g.n_w = (int64_t)g.Co * g.Ci * g.KH * g.KW;
+  if (g.KH == 3 && g.KW == 3) {
+    cp->khc = 3; cp->kw_t = 3;
+  } else if (g.KW == 1 || g.KW == 3 || g.KW == 5 || g.KW == 7) {
+    cp->khc = 1; cp->kw_t = g.KW;
+  } else {
+    return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: filter width %d not implemented (1, 3, 5, 7)", g.KW);
+  }
+  cp->z = g.KH / cp->khc;
+  if (g.OW > 128) return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: output width %d > 128 not implemented", g.OW);
+  cp->p = g.OW <= 64 ? 64 : 128;
+  g.lds_step = (g.KH == 1 && g.KW == 1) ? 1 : g.stride;
+  g.fill_step = g.stride / g.lds_step;
+  // tile shape
+  if (cp->kw_t == 1 && cp->khc == 1) {
+    cp->mt = (g.Co > 64 || g.Ci > 64) ? 4 : 2;  // implemented pairs: (4,4) and (2,2)
+    cp->nt = cp->mt;
+  } else if (cp->khc == 3) {
+    cp->nt = 1;
+    cp->mt = (g.Co % 160 == 0) ? 5 : (g.Co > 64 ? 4 : 2);
+  } else {
+    cp->nt = 1;
+    cp->mt = g.Co > 64 ? 4 : 2;
+  }
+  const int tco = 2 * cp->mt * 16, tci = 2 * cp->nt * 16;
+  cp->co_tiles = (int)ceil_div(g.Co, tco);
+  g.ci_tiles = (int)ceil_div(g.Ci, tci);
+  // R: the largest divisor of OH whose rows fit one K-tile and whose patch fits LDS
+  bool fits = false;
+  for (int r = g.OH; r >= 1 && !fits; --r) {
+    if (g.OH % r != 0 || r * g.OW > cp->p) continue;
+    g.R = r;
+    g.PR = (r - 1) * g.lds_step + cp->khc;
+    g.PW = (g.OW - 1) * g.lds_step + g.KW;
+    g.PS = (g.PR + cp->khc) * g.PW;
+    g.PS += (4 - g.PS % 32 + 32) % 32;  // per-channel stride = 4 (mod 32) floats: spreads channels over LDS banks
+    cp->lds_bytes = ((size_t)tco * (cp->p + 4) + (size_t)tci * g.PS) * sizeof(float);
+    fits = cp->lds_bytes <= kMaxLds;
+  }
+  if (!fits) return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv tile needs %zu bytes of LDS", cp->lds_bytes);
+  g.tiles_per_img = g.OH / g.R;
+  g.n_ktiles = g.Nb * g.tiles_per_img;
+  int64_t per;
+  cp->splits = choose_splits(g.n_ktiles, (int64_t)cp->co_tiles * g.ci_tiles * cp->z, &per);
+  g.tiles_per_split = (int)per;
+  return SURGEON_OK;
+}
+
+static int plan_linear(const surgeon_layer_desc* d, LinPlan* lp) {
+  if (d->M < 0 || d->K < 1 || d->N < 1) return fail(SURGEON_EINVAL, "dw_from_packed: bad linear shape");
+  const int64_t big = (int64_t)1 << 31;
+  if (d->M * d->K > big || d->N * d->K > big || d->M * d->N > ((int64_t)1 << 40))
+    return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: linear tensor too large");
+  LinGeom& g = lp->g;
+  g.M = d->M; g.K = d->K; g.N = d->N;
+  g.n_w = d->N * d->K;
+  const bool small = d->N <= 64 && d->K <= 64;
+  lp->mt = small ? 2 : 4;
+  lp->nt = small ? 2 : 4;
+  lp->tm = 32;
+  const int to = 2 * lp->mt * 16, ti = 2 * lp->nt * 16;
+  lp->o_tiles = (int)ceil_div(d->N, to);
+  g.i_tiles = (int)ceil_div(d->K, ti);
+  int64_t per;
+  const int64_t k_tiles = std::max<int64_t>(1, ceil_div(d->M, lp->tm));
+  lp->splits = choose_splits(k_tiles, (int64_t)lp->o_tiles * g.i_tiles, &per);
+  g.rows_per_split = per * lp->tm;
+  return SURGEON_OK;
+}
+
+static int plan_dw(const surgeon_layer_desc* d, DwPlan* p) {
+  if (!d) return fail(SURGEON_EINVAL, "dw_from_packed: null descriptor");
+  if (d->dtype != SURGEON_F32 && d->dtype != SURGEON_BF16) return fail(SURGEON_EINVAL, "dw_from_packed: bad dtype");
+  if (d->k_total < 0) return fail(SURGEON_EINVAL, "dw_from_packed: k_total < 0");
+  int rc;
+  if (d->kind == SURGEON_CONV2D) {
+    p->conv = true;
+    if ((rc = plan_conv(d, &p->c)) != SURGEON_OK) return rc;
+    p->n = d->Nb * d->Ci * d->H * d->W;
+    p->n_w = p->c.g.n_w;
+    p->splits = p->c.splits;
+  } else if (d->kind == SURGEON_LINEAR) {
+    p->conv = false;
+    if ((rc = plan_linear(d, &p->l)) != SURGEON_OK) return rc;
+    p->n = d->M * d->K;
+    p->n_w = p->l.g.n_w;
+    p->splits = p->l.splits;
+  } else {
+    return fail(SURGEON_EINVAL, "dw_from_packed: bad layer kind %d", d->kind);
+  }
+  if (d->k_total > p->n) return fail(SURGEON_EINVAL, "dw_from_packed: k_total exceeds the activation size");
+  p->n_words = ceil_div(p->n, 64);
+  p->n_rank_blocks = ceil_div(p->n_words, kRankWordsPerBlock);
+  size_t off = 0;
+  p->off_rank = off;
+  off += align_up((size_t)p->n_words * 4, 256);
+  p->off_blocks = off;
+  off += align_up((size_t)p->n_rank_blocks * 4, 256);
+  p->off_part = off;
+  if (p->splits > 1) off += align_up((size_t)p->splits * (size_t)p->n_w * 4, 256);
+  p->ws_bytes = off;
+  return SURGEON_OK;
+}
+
+template <typename K>
+static int allow_lds(K kernel, size_t bytes) {
+  if (bytes > 48 * 1024)
+    SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  return SURGEON_OK;
+}
+
+template <typename InT, int KHC, int KW, int MT, int NT, int P>
+static int launch_conv_variant(const ConvPlan& cp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
+  auto kernel = dw_conv_kernel<InT, KHC, KW, MT, NT, P>;
+  const int rc = allow_lds(kernel, cp.lds_bytes);
+  if (rc != SURGEON_OK) return rc;
+  const dim3 grid((unsigned)(cp.co_tiles * cp.g.ci_tiles), (unsigned)cp.splits, (unsigned)cp.z);
+  hipLaunchKernelGGL(kernel, grid, dim3(256), cp.lds_bytes, st, cp.g, pk, (const InT*)dY, out);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+template <typename InT, int KHC, int KW, int MT, int NT>
+static int launch_conv_p(const ConvPlan& cp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
+  if (cp.p == 64) return launch_conv_variant<InT, KHC, KW, MT, NT, 64>(cp, pk, dY, out, st);
+  return launch_conv_variant<InT, KHC, KW, MT, NT, 128>(cp, pk, dY, out, st);
+}
+
+template <typename InT>
+static int launch_conv(const ConvPlan& cp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
+  if (cp.khc == 3) {
+    if (cp.mt == 5) return launch_conv_p<InT, 3, 3, 5, 1>(cp, pk, dY, out, st);
+    if (cp.mt == 4) return launch_conv_p<InT, 3, 3, 4, 1>(cp, pk, dY, out, st);
+    return launch_conv_p<InT, 3, 3, 2, 1>(cp, pk, dY, out, st);
+  }
+  if (cp.kw_t == 1) {
+    if (cp.mt == 4) return launch_conv_p<InT, 1, 1, 4, 4>(cp, pk, dY, out, st);
+    return launch_conv_p<InT, 1, 1, 2, 2>(cp, pk, dY, out, st);
+  }
+  if (cp.kw_t == 3) {
+    if (cp.mt == 4) return launch_conv_p<InT, 1, 3, 4, 1>(cp, pk, dY, out, st);
+    return launch_conv_p<InT, 1, 3, 2, 1>(cp, pk, dY, out, st);
+  }
+  if (cp.kw_t == 5) {
+    if (cp.mt == 4) return launch_conv_p<InT, 1, 5, 4, 1>(cp, pk, dY, out, st);
+    return launch_conv_p<InT, 1, 5, 2, 1>(cp, pk, dY, out, st);
+  }
+  if (cp.mt == 4) return launch_conv_p<InT, 1, 7, 4, 1>(cp, pk, dY, out, st);
+  return launch_conv_p<InT, 1, 7, 2, 1>(cp, pk, dY, out, st);
+}
+
+template <typename InT>
+static int launch_linear(const LinPlan& lp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
+  const dim3 grid((unsigned)(lp.o_tiles * lp.g.i_tiles), (unsigned)lp.splits);
+  if (lp.mt == 4)
+    hipLaunchKernelGGL((dw_linear_kernel<InT, 4, 4, 32>), grid, dim3(256), 0, st, lp.g, pk, (const InT*)dY, out);
+  else
+    hipLaunchKernelGGL((dw_linear_kernel<InT, 2, 2, 32>), grid, dim3(256), 0, st, lp.g, pk, (const InT*)dY, out);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+template <typename InT>
+static int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const uint64_t* mask, const void* dY,
+                  float* dW, void* ws, hipStream_t st) {
+  char* w = (char*)ws;
+  uint32_t* word_rank = (uint32_t*)(w + p.off_rank);
+  uint32_t* block_sum = (uint32_t*)(w + p.off_blocks);
+  float* part = (float*)(w + p.off_part);
+
+  // nothing kept (or no tokens): the gradient is exactly zero
+  if (d->k_total == 0 || p.n == 0) {
+    const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 4096);
+    hipLaunchKernelGGL(fill_zero_f32_kernel, dim3(blocks), dim3(256), 0, st, dW, p.n_w);
+    SURGEON_LAUNCH_CHECK();
+    return SURGEON_OK;
+  }
+  // rank table
+  hipLaunchKernelGGL(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
+                     block_sum);
+  SURGEON_LAUNCH_CHECK();
+  hipLaunchKernelGGL(rank_scan_kernel, dim3(1), dim3(1024), 0, st, block_sum, (int)p.n_rank_blocks);
+  SURGEON_LAUNCH_CHECK();
+  hipLaunchKernelGGL(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
+                     (const uint32_t*)block_sum, word_rank);
+  SURGEON_LAUNCH_CHECK();
+
+  Packed<InT> pk;
+  pk.vals = (const InT*)vals;
+  pk.mask = mask;
+  pk.word_rank = word_rank;
+  pk.k_last = d->k_total - 1;
+  float* out = p.splits > 1 ? part : dW;
+  int rc = p.conv ? launch_conv<InT>(p.c, pk, dY, out, st) : launch_linear<InT>(p.l, pk, dY, out, st);
+  if (rc != SURGEON_OK) return rc;
+  if (p.splits > 1) {
+    const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 8192);
+    hipLaunchKernelGGL(dw_reduce_splits_kernel, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w, dW);
+    SURGEON_LAUNCH_CHECK();
+  }
+  return SURGEON_OK;
+}
+
+}  // namespace surgeon
+
+using namespace surgeon;
+
+extern "C" int surgeon_dw_ws_bytes(const surgeon_layer_desc* desc, size_t* ws_bytes) {
+  if (!ws_bytes) return fail(SURGEON_EINVAL, "dw_ws_bytes: null pointer");
+  DwPlan p;
+  const int rc = plan_dw(desc, &p);
+  if (rc != SURGEON_OK) return rc;
+  *ws_bytes = p.ws_bytes;
+  return SURGEON_OK;
+}
+
+extern "C" int surgeon_dw_from_packed(const surgeon_layer_desc* desc, const void* vals, const uint64_t* mask,
+                                      const void* dY, float* dW, void* ws, size_t ws_bytes, void* stream) {
+  DwPlan p;
+  const int rc = plan_dw(desc, &p);
+  if (rc != SURGEON_OK) return rc;
+  if (!dW) return fail(SURGEON_EINVAL, "dw_from_packed: null dW");
+  if (p.n > 0 && desc->k_total > 0 && (!vals || !mask || !dY)) return fail(SURGEON_EINVAL, "dw_from_packed: null pointer");
+  if (p.ws_bytes > 0 && (!ws || ws_bytes < p.ws_bytes))
+    return fail(SURGEON_ESIZE, "dw_from_packed: workspace of %zu bytes needed, %zu given", p.ws_bytes, ws_bytes);
+  if (((uintptr_t)ws % 16) || ((uintptr_t)mask % 8) || ((uintptr_t)dW % 4))
+    return fail(SURGEON_EINVAL, "dw_from_packed: misaligned pointer");
+  hipStream_t st = (hipStream_t)stream;
+  if (desc->dtype == SURGEON_F32) return run_dw<float>(p, desc, vals, mask, dY, dW, ws, st);
+  return run_dw<uint16_t>(p, desc, vals, mask, dY, dW, ws, st);
+}

@@ -1,0 +1,137 @@
+// Gradient Importance (Eq. 4): G = sqrt( sum_j dW_j^2 / n_w ), an HBM-bound reduction.
+//
+// One pass over dW with 16-byte loads; squares are accumulated in fp64 (full-rate on CDNA) so the result
+// does not depend on n_w's size; partial sums are combined in a fixed order, so the result is reproducible.
+#include "common.hpp"
+
+namespace surgeon {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kImpBlock = 256;
+constexpr int kImpMaxBlocks = 2048;
+constexpr int kImpPerThread = 16;  // floats per thread per grid-stride step (4 x float4)
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;
+}
+
+// block-wide sum in a fixed order; valid in thread 0
+__device__ __forceinline__ double block_sum(double v, double* lds) {
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) lds[wave] = v;
+  __syncthreads();
+  double total = 0.0;
+  if (threadIdx.x == 0) {
+    for (int w = 0; w < kImpBlock / 64; ++w) total += lds[w];
+  }
+  return total;
+}
+
+template <bool VEC4>
+__device__ __forceinline__ double thread_sumsq(const float* __restrict__ x, int64_t n) {
+  double acc0 = 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+  const int64_t tid = (int64_t)blockIdx.x * kImpBlock + threadIdx.x;
+  const int64_t nthreads = (int64_t)gridDim.x * kImpBlock;
+  if (VEC4) {
+    const f32x4* x4 = reinterpret_cast<const f32x4*>(x);
+    const int64_t n4 = n >> 2;
+    int64_t i = tid;
+    // four independent 16-byte loads in flight per thread
+    for (; i + 3 * nthreads < n4; i += 4 * nthreads) {
+      const f32x4 a = __builtin_nontemporal_load(&x4[i]);
+      const f32x4 b = __builtin_nontemporal_load(&x4[i + nthreads]);
+      const f32x4 c = __builtin_nontemporal_load(&x4[i + 2 * nthreads]);
+      const f32x4 d = __builtin_nontemporal_load(&x4[i + 3 * nthreads]);
+      acc0 += (double)a.x * a.x + (double)a.y * a.y + (double)a.z * a.z + (double)a.w * a.w;
+      acc1 += (double)b.x * b.x + (double)b.y * b.y + (double)b.z * b.z + (double)b.w * b.w;
+      acc2 += (double)c.x * c.x + (double)c.y * c.y + (double)c.z * c.z + (double)c.w * c.w;
+      acc3 += (double)d.x * d.x + (double)d.y * d.y + (double)d.z * d.z + (double)d.w * d.w;
+    }
+    for (; i < n4; i += nthreads) {
+      const f32x4 a = x4[i];
+      acc0 += (double)a.x * a.x + (double)a.y * a.y + (double)a.z * a.z + (double)a.w * a.w;
+    }
+    for (int64_t j = (n4 << 2) + tid; j < n; j += nthreads) acc1 += (double)x[j] * x[j];
+  } else {
+    for (int64_t j = tid; j < n; j += nthreads) acc0 += (double)x[j] * x[j];
+  }
+  return (acc0 + acc1) + (acc2 + acc3);
+}
+
+template <bool VEC4>
+__global__ __launch_bounds__(kImpBlock) void sumsq_partial_kernel(const float* __restrict__ x, int64_t n,
+                                                                  double* __restrict__ partial) {
+  __shared__ double lds[kImpBlock / 64];
+  const double total = block_sum(thread_sumsq<VEC4>(x, n), lds);
+  if (threadIdx.x == 0) partial[blockIdx.x] = total;
+}
+
+// one block: adds the per-block partials in index order and finishes Eq. 4
+__global__ __launch_bounds__(kImpBlock) void sumsq_final_kernel(const double* __restrict__ partial, int n_partial,
+                                                                int64_t n, float* __restrict__ out) {
+  __shared__ double lds[kImpBlock / 64];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < n_partial; i += kImpBlock) acc += partial[i];
+  const double total = block_sum(acc, lds);
+  if (threadIdx.x == 0) out[0] = (float)sqrt(total / (double)n);
+}
+
+// small layers: a single block does both steps
+template <bool VEC4>
+__global__ __launch_bounds__(kImpBlock) void sumsq_single_kernel(const float* __restrict__ x, int64_t n,
+                                                                 float* __restrict__ out) {
+  __shared__ double lds[kImpBlock / 64];
+  const double total = block_sum(thread_sumsq<VEC4>(x, n), lds);
+  if (threadIdx.x == 0) out[0] = n > 0 ? (float)sqrt(total / (double)n) : 0.0f;
+}
+
+static int importance_blocks(int64_t n_w) {
+  int64_t b = ceil_div(n_w, (int64_t)kImpBlock * kImpPerThread);
+  if (b < 1) b = 1;
+  if (b > kImpMaxBlocks) b = kImpMaxBlocks;
+  return (int)b;
+}
+
+}  // namespace surgeon
+
+using namespace surgeon;
+
+extern "C" size_t surgeon_grad_importance_ws_bytes(int64_t n_w) {
+  if (n_w < 0) return 0;
+  const int nb = importance_blocks(n_w);
+  return nb > 1 ? align_up((size_t)nb * sizeof(double), 256) : 0;
+}
+
+extern "C" int surgeon_grad_importance(const float* dW, int64_t n_w, float* G_out, void* ws, size_t ws_bytes,
+                                       void* stream) {
+  if (n_w < 0) return fail(SURGEON_EINVAL, "grad_importance: n_w = %lld", (long long)n_w);
+  if (!G_out || (n_w > 0 && !dW)) return fail(SURGEON_EINVAL, "grad_importance: null pointer");
+  if (((uintptr_t)dW & 3) != 0) return fail(SURGEON_EINVAL, "grad_importance: dW is not 4-byte aligned");
+  const size_t need = surgeon_grad_importance_ws_bytes(n_w);
+  if (need > 0 && (!ws || ws_bytes < need))
+    return fail(SURGEON_ESIZE, "grad_importance: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  const bool vec4 = ((uintptr_t)dW & 15) == 0;
+  const int nb = importance_blocks(n_w);
+  if (nb == 1) {
+    if (vec4)
+      hipLaunchKernelGGL(sumsq_single_kernel<true>, dim3(1), dim3(kImpBlock), 0, st, dW, n_w, G_out);
+    else
+      hipLaunchKernelGGL(sumsq_single_kernel<false>, dim3(1), dim3(kImpBlock), 0, st, dW, n_w, G_out);
+    SURGEON_LAUNCH_CHECK();
+    return SURGEON_OK;
+  }
+  double* partial = (double*)ws;
+  if (vec4)
+    hipLaunchKernelGGL(sumsq_partial_kernel<true>, dim3(nb), dim3(kImpBlock), 0, st, dW, n_w, partial);
+  else
+    hipLaunchKernelGGL(sumsq_partial_kernel<false>, dim3(nb), dim3(kImpBlock), 0, st, dW, n_w, partial);
+  SURGEON_LAUNCH_CHECK();
+  hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(kImpBlock), 0, st, (const double*)partial, nb, n_w, G_out);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}

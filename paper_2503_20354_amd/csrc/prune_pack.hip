@@ -1,0 +1,626 @@
+// Prune + pack (Alg. 1 lines 6-7): per group keep the k elements of largest magnitude (ties: lowest index),
+// store the kept values in ascending index order plus one bit per element.
+//
+// Three selection paths, chosen on the host from group_len:
+//   1. wave-in-registers (group_len % 64 == 0, group_len <= 4096): one wavefront owns one group, holds it in
+//      registers (lane l, slot j <-> element 64*j + l, so one wave ballot IS one 64-bit mask word), finds the
+//      threshold by counting with ballots, then compacts with mbcnt prefix ranks.  The activation is read from
+//      HBM exactly once and nothing but the packed result is written: select and pack are fused.
+//   2. wave-from-memory (other group_len <= 4096): same ownership, elements re-read from cache, bitwise search.
+//   3. global (group_len > 4096, including the whole-tensor scope): MSB-first radix select with per-group digit
+//      histograms in the workspace, then count / scan / pack kernels over 1024-element wave chunks.
+// Paths 2 and 3 set mask bits with atomicOr on a zeroed mask because groups need not start on a word boundary.
+// No floating-point arithmetic decides anything: keys are integer bit patterns, so results are bit-exact.
+#include "common.hpp"
+
+namespace surgeon {
+
+// ---------------------------------------------------------------------------------------------------------
+// key handling.  "rot" form = magnitude bits shifted left by one with the sign bit moved to bit 0, so that
+//   (rot >= 2*t)  <=>  (magnitude key >= t)   and the original bits are recoverable for the value store.
+// ---------------------------------------------------------------------------------------------------------
+template <typename BitsT>
+struct Key;
+template <>
+struct Key<uint32_t> {
+  static constexpr int kBits = 31;
+  static constexpr uint32_t kMask = 0x7fffffffu;
+  __device__ static __forceinline__ uint32_t rot(uint32_t b) { return (b << 1) | (b >> 31); }
+  __device__ static __forceinline__ uint32_t unrot(uint32_t k) { return (k >> 1) | (k << 31); }
+};
+template <>
+struct Key<uint16_t> {
+  static constexpr int kBits = 15;
+  static constexpr uint32_t kMask = 0x7fffu;
+  __device__ static __forceinline__ uint32_t rot(uint16_t b) { return (((uint32_t)b & 0x7fffu) << 1) | ((uint32_t)b >> 15); }
+  __device__ static __forceinline__ uint16_t unrot(uint32_t k) { return (uint16_t)((k >> 1) | ((k & 1u) << 15)); }
+};
+
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+// number of set bits of b below the calling lane, plus base
+__device__ __forceinline__ uint32_t lane_rank(uint64_t b, uint32_t base) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, base));
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, off, 64));
+  return v;
+}
+
+template <int E>
+__device__ __forceinline__ int count_ge(const uint32_t (&kr)[E], uint32_t thr2) {
+  int c = 0;
+#pragma unroll
+  for (int j = 0; j < E; ++j) c += __popcll(ballot64(kr[j] >= thr2));
+  return c;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// path 1: one wavefront per group, group in registers
+// ---------------------------------------------------------------------------------------------------------
+template <int E, typename BitsT, bool WITH_IDX>
+__global__ __launch_bounds__(256) void select_pack_wave_reg_kernel(const BitsT* __restrict__ A,
+                                                                   BitsT* __restrict__ vals,
+                                                                   uint64_t* __restrict__ mask,
+                                                                   uint32_t* __restrict__ idx, int64_t n_groups,
+                                                                   int g, int len_last, int k_full, int k_last) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t grp = (int64_t)blockIdx.x * 4 + wave;
+  if (grp >= n_groups) return;
+  const bool is_last = grp == n_groups - 1;
+  const int len = is_last ? len_last : g;
+  const int k = is_last ? k_last : k_full;
+  const int64_t gstart = grp * (int64_t)g;
+  const BitsT* __restrict__ src = A + gstart;
+
+  uint32_t kr[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const int pos = j * 64 + lane;
+    kr[j] = pos < len ? Key<BitsT>::rot(src[pos]) : 0u;  // padding: magnitude 0 at the highest indices
+  }
+
+  BitsT* __restrict__ out_vals = vals + grp * (int64_t)k_full;
+  uint32_t* __restrict__ out_idx = WITH_IDX ? idx + grp * (int64_t)k_full : nullptr;
+  uint64_t* __restrict__ out_mask = mask + (gstart >> 6);
+  const int n_words = (len + 63) >> 6;
+  uint64_t my_word = 0;  // lane j ends up holding mask word j of this group
+
+  enum { MODE_ALL, MODE_THRESHOLD, MODE_TIE };
+  int mode;
+  uint32_t thr2 = 0;          // MODE_THRESHOLD: keep rot >= thr2
+  uint32_t t_key = 0;         // MODE_TIE: threshold magnitude key
+  uint32_t need = 0;          // MODE_TIE: how many elements equal to t_key are kept (lowest index first)
+
+  if (k >= len) {
+    mode = MODE_ALL;
+  } else {
+    // invariant: count(key >= lo) >= k (c_lo) and count(key >= hi) < k (c_hi); the k-th largest key is in [lo, hi)
+    uint32_t m = 0;
+#pragma unroll
+    for (int j = 0; j < E; ++j) m = max(m, kr[j]);
+    m = wave_max_u32(m);
+    uint32_t lo = 0, hi = (m >> 1) + 1;
+    int c_lo = E * 64, c_hi = 0;
+    bool found = false;
+    // first probe: the non-zero count settles post-ReLU groups whose threshold is the tie at zero
+    if (hi > 1) {
+      const int c = count_ge<E>(kr, 2u);
+      if (c == k) {
+        found = true;
+        thr2 = 2u;
+      } else if (c > k) {
+        lo = 1;
+        c_lo = c;
+      } else {
+        hi = 1;
+        c_hi = c;
+      }
+    }
+    int streak = 0;  // >0: lo moved that many times in a row, <0: hi did
+    while (!found && hi - lo > 1) {
+      const uint32_t span = hi - lo;
+      uint32_t d;
+      if (streak >= 2 || streak <= -2) {
+        d = span >> 1;  // the other end is stuck: halve instead of interpolating
+        streak = 0;
+      } else {
+        const float f = (float)(c_lo - k) / (float)(c_lo - c_hi);
+        d = (uint32_t)(f * (float)span);
+      }
+      d = min(max(d, 1u), span - 1u);
+      const uint32_t mid = lo + d;
+      const int c = count_ge<E>(kr, mid << 1);
+      if (c == k) {
+        found = true;
+        thr2 = mid << 1;
+      } else if (c > k) {
+        lo = mid;
+        c_lo = c;
+        streak = streak > 0 ? streak + 1 : 1;
+      } else {
+        hi = mid;
+        c_hi = c;
+        streak = streak < 0 ? streak - 1 : -1;
+      }
+    }
+    if (found) {
+      mode = MODE_THRESHOLD;
+    } else {
+      mode = MODE_TIE;  // hi == lo + 1: more than k keys are >= lo, fewer than k are > lo
+      t_key = lo;
+      need = (uint32_t)(k - c_hi);
+    }
+  }
+
+  uint32_t run = 0;  // kept elements in slots before j
+  if (mode == MODE_TIE) {
+    const uint32_t eq_lo = t_key << 1, gt_lo = (t_key << 1) | 1u;
+    uint32_t eq_run = 0;
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const bool gt = kr[j] > gt_lo;
+      const bool eq = !gt && kr[j] >= eq_lo;
+      const uint64_t beq = ballot64(eq);
+      const bool keep = gt || (eq && lane_rank(beq, eq_run) < need);
+      const uint64_t b = ballot64(keep);
+      if (lane == j) my_word = b;
+      if (keep) {
+        const uint32_t pos = lane_rank(b, run);
+        out_vals[pos] = Key<BitsT>::unrot(kr[j]);
+        if (WITH_IDX) out_idx[pos] = (uint32_t)(j * 64 + lane);
+      }
+      run += (uint32_t)__popcll(b);
+      eq_run += (uint32_t)__popcll(beq);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const bool keep = mode == MODE_ALL ? (j * 64 + lane < len) : (kr[j] >= thr2);
+      const uint64_t b = ballot64(keep);
+      if (lane == j) my_word = b;
+      if (keep) {
+        const uint32_t pos = lane_rank(b, run);
+        out_vals[pos] = Key<BitsT>::unrot(kr[j]);
+        if (WITH_IDX) out_idx[pos] = (uint32_t)(j * 64 + lane);
+      }
+      run += (uint32_t)__popcll(b);
+    }
+  }
+  if (lane < n_words) out_mask[lane] = my_word;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// shared by paths 2 and 3
+// ---------------------------------------------------------------------------------------------------------
+__global__ void fill_zero_u64_kernel(uint64_t* __restrict__ p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+// OR the ballot of 64 consecutive elements starting at flat index e_first into the (zeroed) mask
+__device__ __forceinline__ void or_into_mask(uint64_t* __restrict__ mask, int64_t e_first, uint64_t b, int lane) {
+  if (lane == 0 && b) {
+    const int64_t w = e_first >> 6;
+    const int sh = (int)(e_first & 63);
+    atomicOr((unsigned long long*)&mask[w], (unsigned long long)(b << sh));
+    if (sh) {
+      const uint64_t hi_part = b >> (64 - sh);
+      if (hi_part) atomicOr((unsigned long long*)&mask[w + 1], (unsigned long long)hi_part);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// path 2: one wavefront per group, elements re-read from memory (any group_len; used for group_len <= 4096)
+// ---------------------------------------------------------------------------------------------------------
+template <typename BitsT, bool WITH_IDX>
+__global__ __launch_bounds__(256) void select_pack_wave_mem_kernel(const BitsT* __restrict__ A,
+                                                                   BitsT* __restrict__ vals,
+                                                                   uint64_t* __restrict__ mask,
+                                                                   uint32_t* __restrict__ idx, int64_t n_groups,
+                                                                   int g, int len_last, int k_full, int k_last) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t grp = (int64_t)blockIdx.x * 4 + wave;
+  if (grp >= n_groups) return;
+  const bool is_last = grp == n_groups - 1;
+  const int len = is_last ? len_last : g;
+  const int k = is_last ? k_last : k_full;
+  const int64_t gstart = grp * (int64_t)g;
+  const BitsT* __restrict__ src = A + gstart;
+
+  // largest t with count(key >= t) >= k, one bit at a time from the top: the k-th largest key
+  uint32_t t_key = 0;
+  for (int bit = Key<BitsT>::kBits - 1; bit >= 0; --bit) {
+    const uint32_t cand = t_key | (1u << bit);
+    int c = 0;
+    for (int base = 0; base < len; base += 64) {
+      const int pos = base + lane;
+      const bool p = pos < len && ((uint32_t)src[pos] & Key<BitsT>::kMask) >= cand;
+      c += __popcll(ballot64(p));
+    }
+    if (c >= k) t_key = cand;
+  }
+  int c_gt = 0;
+  for (int base = 0; base < len; base += 64) {
+    const int pos = base + lane;
+    c_gt += __popcll(ballot64(pos < len && ((uint32_t)src[pos] & Key<BitsT>::kMask) > t_key));
+  }
+  const uint32_t need = (uint32_t)(k - c_gt);
+
+  BitsT* __restrict__ out_vals = vals + grp * (int64_t)k_full;
+  uint32_t* __restrict__ out_idx = WITH_IDX ? idx + grp * (int64_t)k_full : nullptr;
+  uint32_t run = 0, eq_run = 0;
+  for (int base = 0; base < len; base += 64) {
+    const int pos = base + lane;
+    const bool valid = pos < len;
+    const BitsT bits = valid ? src[pos] : (BitsT)0;
+    const uint32_t key = (uint32_t)bits & Key<BitsT>::kMask;
+    const bool gt = valid && key > t_key;
+    const bool eq = valid && key == t_key;
+    const uint64_t beq = ballot64(eq);
+    const bool keep = gt || (eq && lane_rank(beq, eq_run) < need);
+    const uint64_t b = ballot64(keep);
+    if (keep) {
+      const uint32_t o = lane_rank(b, run);
+      out_vals[o] = bits;
+      if (WITH_IDX) out_idx[o] = (uint32_t)pos;
+    }
+    or_into_mask(mask, gstart + base, b, lane);
+    run += (uint32_t)__popcll(b);
+    eq_run += (uint32_t)__popcll(beq);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// path 3: groups larger than one wavefront can hold -- radix select over HBM with workspace state
+// ---------------------------------------------------------------------------------------------------------
+struct GroupState {
+  uint32_t prefix;  // digits of the threshold key fixed so far
+  uint32_t k_rem;   // rank still to resolve among elements matching the prefix
+  uint32_t t_key;   // final threshold key
+  uint32_t need;    // elements equal to t_key that are kept
+};
+
+__global__ void gsel_init_kernel(GroupState* __restrict__ st, uint32_t* __restrict__ hist, int64_t n_groups,
+                                 uint32_t k_full, uint32_t k_last) {
+  const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = tid; i < n_groups * 256; i += stride) hist[i] = 0;
+  for (int64_t i = tid; i < n_groups; i += stride) {
+    GroupState s;
+    s.prefix = 0;
+    s.k_rem = (i == n_groups - 1) ? k_last : k_full;
+    s.t_key = 0;
+    s.need = 0;
+    st[i] = s;
+  }
+}
+
+// one digit pass: histogram of the digit at `shift` over the elements whose higher bits match the prefix
+template <typename BitsT>
+__global__ __launch_bounds__(256) void gsel_hist_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
+                                                        int64_t blocks_per_group, int shift, int nbits,
+                                                        const GroupState* __restrict__ st,
+                                                        uint32_t* __restrict__ hist) {
+  __shared__ uint32_t lh[256];
+  const int64_t grp = blockIdx.x / blocks_per_group;
+  const int64_t blk = blockIdx.x % blocks_per_group;
+  lh[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t gstart = grp * g;
+  const int64_t gend = min(gstart + g, n);
+  const int64_t e0 = gstart + blk * kGlobalHistChunk;
+  const int hshift = shift + nbits;
+  const uint32_t want = st[grp].prefix >> hshift;
+  const uint32_t dmask = (1u << nbits) - 1u;
+  for (int t = threadIdx.x; t < kGlobalHistChunk; t += 256) {
+    const int64_t e = e0 + t;
+    if (e < gend) {
+      const uint32_t key = (uint32_t)A[e] & Key<BitsT>::kMask;
+      if ((key >> hshift) == want) atomicAdd(&lh[(key >> shift) & dmask], 1u);
+    }
+  }
+  __syncthreads();
+  const uint32_t c = lh[threadIdx.x];
+  if (c) atomicAdd(&hist[grp * 256 + threadIdx.x], c);
+}
+
+// picks the digit holding the k_rem-th largest matching element, clears the histogram for the next pass
+__global__ __launch_bounds__(256) void gsel_resolve_kernel(GroupState* __restrict__ st, uint32_t* __restrict__ hist,
+                                                           int shift, int last) {
+  __shared__ uint32_t c[256];
+  const int64_t grp = blockIdx.x;
+  const int tid = threadIdx.x;
+  c[tid] = hist[grp * 256 + tid];
+  hist[grp * 256 + tid] = 0;
+  const GroupState s = st[grp];
+  __syncthreads();
+  uint32_t above = 0;
+  for (int b = tid + 1; b < 256; ++b) above += c[b];
+  if (above < s.k_rem && s.k_rem <= above + c[tid]) {  // exactly one digit satisfies this
+    GroupState o = s;
+    o.prefix = s.prefix | ((uint32_t)tid << shift);
+    o.k_rem = s.k_rem - above;
+    if (last) {
+      o.t_key = o.prefix;
+      o.need = o.k_rem;
+    }
+    st[grp] = o;
+  }
+}
+
+template <typename BitsT>
+__global__ __launch_bounds__(256) void gsel_count_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
+                                                         int64_t chunks_per_group, int64_t n_chunks,
+                                                         const GroupState* __restrict__ st,
+                                                         uint2* __restrict__ ccount) {
+  const int lane = threadIdx.x & 63;
+  const int64_t id = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (id >= n_chunks) return;
+  const int64_t grp = id / chunks_per_group, chunk = id % chunks_per_group;
+  const int64_t gstart = grp * g;
+  const int64_t gend = min(gstart + g, n);
+  const int64_t e0 = gstart + chunk * kGlobalWaveChunk;
+  const uint32_t t_key = st[grp].t_key;
+  uint32_t gt = 0, eq = 0;
+  for (int r = 0; r < kGlobalWaveChunk / 64; ++r) {
+    const int64_t e = e0 + r * 64 + lane;
+    const bool valid = e < gend;
+    const uint32_t key = valid ? ((uint32_t)A[e] & Key<BitsT>::kMask) : 0u;
+    gt += (uint32_t)__popcll(ballot64(valid && key > t_key));
+    eq += (uint32_t)__popcll(ballot64(valid && key == t_key));
+  }
+  if (lane == 0) ccount[id] = make_uint2(gt, eq);
+}
+
+// per group: exclusive prefix over its chunks of (equal elements seen, values written)
+__global__ __launch_bounds__(256) void gsel_scan_kernel(const GroupState* __restrict__ st,
+                                                        const uint2* __restrict__ ccount, uint2* __restrict__ cbase,
+                                                        int64_t chunks_per_group) {
+  __shared__ uint32_t part[256];
+  const int64_t grp = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int64_t per = (chunks_per_group + 255) / 256;
+  const int64_t c_begin = min((int64_t)tid * per, chunks_per_group);
+  const int64_t c_end = min(c_begin + per, chunks_per_group);
+  const uint2* __restrict__ cc = ccount + grp * chunks_per_group;
+  uint2* __restrict__ cb = cbase + grp * chunks_per_group;
+  const uint32_t need = st[grp].need;
+
+  uint32_t s = 0;
+  for (int64_t c = c_begin; c < c_end; ++c) s += cc[c].y;
+  part[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t acc = 0;
+    for (int t = 0; t < 256; ++t) {
+      const uint32_t v = part[t];
+      part[t] = acc;
+      acc += v;
+    }
+  }
+  __syncthreads();
+  uint32_t eq_before = part[tid];
+  uint32_t kept_sum = 0;
+  for (int64_t c = c_begin; c < c_end; ++c) {
+    const uint2 v = cc[c];
+    const uint32_t take = eq_before >= need ? 0u : min(need - eq_before, v.y);
+    cb[c].x = eq_before;
+    kept_sum += v.x + take;
+    eq_before += v.y;
+  }
+  __syncthreads();
+  part[tid] = kept_sum;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t acc = 0;
+    for (int t = 0; t < 256; ++t) {
+      const uint32_t v = part[t];
+      part[t] = acc;
+      acc += v;
+    }
+  }
+  __syncthreads();
+  uint32_t out_before = part[tid];
+  for (int64_t c = c_begin; c < c_end; ++c) {
+    const uint2 v = cc[c];
+    const uint32_t eqb = cb[c].x;
+    const uint32_t take = eqb >= need ? 0u : min(need - eqb, v.y);
+    cb[c].y = out_before;
+    out_before += v.x + take;
+  }
+}
+
+template <typename BitsT, bool WITH_IDX>
+__global__ __launch_bounds__(256) void gsel_pack_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
+                                                        int64_t chunks_per_group, int64_t n_chunks,
+                                                        const GroupState* __restrict__ st,
+                                                        const uint2* __restrict__ cbase, int64_t k_full,
+                                                        BitsT* __restrict__ vals, uint64_t* __restrict__ mask,
+                                                        uint32_t* __restrict__ idx) {
+  const int lane = threadIdx.x & 63;
+  const int64_t id = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (id >= n_chunks) return;
+  const int64_t grp = id / chunks_per_group, chunk = id % chunks_per_group;
+  const int64_t gstart = grp * g;
+  const int64_t gend = min(gstart + g, n);
+  const int64_t e0 = gstart + chunk * kGlobalWaveChunk;
+  const GroupState s = st[grp];
+  const uint2 base = cbase[id];
+  uint32_t eq_run = base.x, run = base.y;
+  BitsT* __restrict__ out_vals = vals + grp * k_full;
+  uint32_t* __restrict__ out_idx = WITH_IDX ? idx + grp * k_full : nullptr;
+  for (int r = 0; r < kGlobalWaveChunk / 64; ++r) {
+    const int64_t e_first = e0 + r * 64;
+    if (e_first >= gend) break;
+    const int64_t e = e_first + lane;
+    const bool valid = e < gend;
+    const BitsT bits = valid ? A[e] : (BitsT)0;
+    const uint32_t key = (uint32_t)bits & Key<BitsT>::kMask;
+    const bool gt = valid && key > s.t_key;
+    const bool eq = valid && key == s.t_key;
+    const uint64_t beq = ballot64(eq);
+    const bool keep = gt || (eq && lane_rank(beq, eq_run) < s.need);
+    const uint64_t b = ballot64(keep);
+    if (keep) {
+      const uint32_t o = lane_rank(b, run);
+      out_vals[o] = bits;
+      if (WITH_IDX) out_idx[o] = (uint32_t)(e - gstart);
+    }
+    or_into_mask(mask, e_first, b, lane);
+    run += (uint32_t)__popcll(b);
+    eq_run += (uint32_t)__popcll(beq);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// host dispatch
+// ---------------------------------------------------------------------------------------------------------
+static int zero_mask(uint64_t* mask, int64_t n_words, hipStream_t st) {
+  if (n_words == 0) return SURGEON_OK;
+  const int blocks = (int)std::min<int64_t>(ceil_div(n_words, 256), 4096);
+  hipLaunchKernelGGL(fill_zero_u64_kernel, dim3(blocks), dim3(256), 0, st, mask, n_words);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+template <int E, typename BitsT>
+static int launch_wave_reg(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx,
+                           hipStream_t st) {
+  const dim3 grid((unsigned)ceil_div(p.n_groups, 4)), block(256);
+  if (idx)
+    hipLaunchKernelGGL((select_pack_wave_reg_kernel<E, BitsT, true>), grid, block, 0, st, (const BitsT*)A, (BitsT*)vals,
+                       mask, idx, p.n_groups, (int)p.g, (int)p.len_last, (int)p.k_full, (int)p.k_last);
+  else
+    hipLaunchKernelGGL((select_pack_wave_reg_kernel<E, BitsT, false>), grid, block, 0, st, (const BitsT*)A,
+                       (BitsT*)vals, mask, idx, p.n_groups, (int)p.g, (int)p.len_last, (int)p.k_full, (int)p.k_last);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+template <typename BitsT>
+static int run_wave_reg(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx, hipStream_t st) {
+  const int slots = (int)(p.g / 64);
+  if (slots <= 1) return launch_wave_reg<1, BitsT>(p, A, vals, mask, idx, st);
+  if (slots <= 2) return launch_wave_reg<2, BitsT>(p, A, vals, mask, idx, st);
+  if (slots <= 4) return launch_wave_reg<4, BitsT>(p, A, vals, mask, idx, st);
+  if (slots <= 8) return launch_wave_reg<8, BitsT>(p, A, vals, mask, idx, st);
+  if (slots <= 12) return launch_wave_reg<12, BitsT>(p, A, vals, mask, idx, st);
+  if (slots <= 16) return launch_wave_reg<16, BitsT>(p, A, vals, mask, idx, st);
+  if (slots <= 24) return launch_wave_reg<24, BitsT>(p, A, vals, mask, idx, st);
+  if (slots <= 32) return launch_wave_reg<32, BitsT>(p, A, vals, mask, idx, st);
+  if (slots <= 48) return launch_wave_reg<48, BitsT>(p, A, vals, mask, idx, st);
+  return launch_wave_reg<64, BitsT>(p, A, vals, mask, idx, st);
+}
+
+template <typename BitsT>
+static int run_wave_mem(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx, hipStream_t st) {
+  const dim3 grid((unsigned)ceil_div(p.n_groups, 4)), block(256);
+  if (idx)
+    hipLaunchKernelGGL((select_pack_wave_mem_kernel<BitsT, true>), grid, block, 0, st, (const BitsT*)A, (BitsT*)vals,
+                       mask, idx, p.n_groups, (int)p.g, (int)p.len_last, (int)p.k_full, (int)p.k_last);
+  else
+    hipLaunchKernelGGL((select_pack_wave_mem_kernel<BitsT, false>), grid, block, 0, st, (const BitsT*)A, (BitsT*)vals,
+                       mask, idx, p.n_groups, (int)p.g, (int)p.len_last, (int)p.k_full, (int)p.k_last);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+template <typename BitsT>
+static int run_global(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx, void* ws,
+                      hipStream_t st) {
+  const int64_t cpg = ceil_div(p.g, kGlobalWaveChunk);
+  const int64_t n_chunks = p.n_groups * cpg;
+  const int64_t bpg = ceil_div(p.g, kGlobalHistChunk);
+  if (p.n_groups * bpg > 0x7fffffffLL || n_chunks > 0x7fffffffLL)
+    return fail(SURGEON_EUNSUPPORTED, "prune_pack: too many chunks");
+  char* w = (char*)ws;
+  GroupState* state = (GroupState*)w;
+  w += align_up((size_t)p.n_groups * 16, 256);
+  uint32_t* hist = (uint32_t*)w;
+  w += align_up((size_t)p.n_groups * 256 * 4, 256);
+  uint2* ccount = (uint2*)w;
+  w += align_up((size_t)n_chunks * 8, 256);
+  uint2* cbase = (uint2*)w;
+
+  const int init_blocks = (int)std::min<int64_t>(ceil_div(p.n_groups * 256, 256), 4096);
+  hipLaunchKernelGGL(gsel_init_kernel, dim3(init_blocks), dim3(256), 0, st, state, hist, p.n_groups,
+                     (uint32_t)p.k_full, (uint32_t)p.k_last);
+  SURGEON_LAUNCH_CHECK();
+  // digits from the top: 8,8,8,7 bits for the 31-bit fp32 key; 8,7 for the 15-bit bf16 key
+  int shift = Key<BitsT>::kBits;
+  while (shift > 0) {
+    const int nbits = shift >= 8 ? 8 : shift;
+    shift -= nbits;
+    hipLaunchKernelGGL((gsel_hist_kernel<BitsT>), dim3((unsigned)(p.n_groups * bpg)), dim3(256), 0, st,
+                       (const BitsT*)A, p.n, p.g, bpg, shift, nbits, (const GroupState*)state, hist);
+    SURGEON_LAUNCH_CHECK();
+    hipLaunchKernelGGL(gsel_resolve_kernel, dim3((unsigned)p.n_groups), dim3(256), 0, st, state, hist, shift,
+                       shift == 0 ? 1 : 0);
+    SURGEON_LAUNCH_CHECK();
+  }
+  const dim3 wgrid((unsigned)ceil_div(n_chunks, 4)), block(256);
+  hipLaunchKernelGGL((gsel_count_kernel<BitsT>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
+                     (const GroupState*)state, ccount);
+  SURGEON_LAUNCH_CHECK();
+  hipLaunchKernelGGL(gsel_scan_kernel, dim3((unsigned)p.n_groups), block, 0, st, (const GroupState*)state,
+                     (const uint2*)ccount, cbase, cpg);
+  SURGEON_LAUNCH_CHECK();
+  if (idx)
+    hipLaunchKernelGGL((gsel_pack_kernel<BitsT, true>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
+                       (const GroupState*)state, (const uint2*)cbase, p.k_full, (BitsT*)vals, mask, idx);
+  else
+    hipLaunchKernelGGL((gsel_pack_kernel<BitsT, false>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
+                       (const GroupState*)state, (const uint2*)cbase, p.k_full, (BitsT*)vals, mask, idx);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+template <typename BitsT>
+static int run_prune_pack(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx, void* ws,
+                          hipStream_t st) {
+  const int64_t n_words = ceil_div(p.n, 64);
+  if (p.k_total == 0) return zero_mask(mask, n_words, st);
+  switch (choose_prune_path(p)) {
+    case PATH_WAVE_REG:
+      return run_wave_reg<BitsT>(p, A, vals, mask, idx, st);
+    case PATH_WAVE_MEM: {
+      const int rc = zero_mask(mask, n_words, st);
+      if (rc != SURGEON_OK) return rc;
+      return run_wave_mem<BitsT>(p, A, vals, mask, idx, st);
+    }
+    default: {
+      const int rc = zero_mask(mask, n_words, st);
+      if (rc != SURGEON_OK) return rc;
+      return run_global<BitsT>(p, A, vals, mask, idx, ws, st);
+    }
+  }
+}
+
+}  // namespace surgeon
+
+using namespace surgeon;
+
+extern "C" int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, float r, int dt, void* vals,
+                                  uint64_t* mask, uint32_t* idx, void* ws, size_t ws_bytes, void* stream) {
+  if (dt != SURGEON_F32 && dt != SURGEON_BF16) return fail(SURGEON_EINVAL, "prune_pack: bad dtype %d", dt);
+  GroupPlan p;
+  if (!make_group_plan(n, group_len, r, &p))
+    return fail(SURGEON_EINVAL, "prune_pack: need n >= 0, group_len >= 1, 0 <= r <= 1 (n=%lld group_len=%lld r=%g)",
+                (long long)n, (long long)group_len, (double)r);
+  if (n > ((int64_t)1 << 31)) return fail(SURGEON_EUNSUPPORTED, "prune_pack: n = %lld exceeds 2^31", (long long)n);
+  if (n == 0) return SURGEON_OK;
+  if (!A || !mask || (p.k_total > 0 && !vals)) return fail(SURGEON_EINVAL, "prune_pack: null pointer");
+  const size_t es = dt == SURGEON_F32 ? 4 : 2;
+  if (((uintptr_t)A % es) || ((uintptr_t)vals % es) || ((uintptr_t)mask % 8) || ((uintptr_t)idx % 4))
+    return fail(SURGEON_EINVAL, "prune_pack: misaligned pointer");
+  const size_t need = prune_pack_ws_bytes(p);
+  if (need > 0 && (!ws || ws_bytes < need))
+    return fail(SURGEON_ESIZE, "prune_pack: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+  if (need > 0 && ((uintptr_t)ws % 16)) return fail(SURGEON_EINVAL, "prune_pack: workspace not 16-byte aligned");
+  hipStream_t st = (hipStream_t)stream;
+  if (dt == SURGEON_F32) return run_prune_pack<uint32_t>(p, A, vals, mask, idx, ws, st);
+  return run_prune_pack<uint16_t>(p, A, vals, mask, idx, ws, st);
+}

@@ -1,0 +1,130 @@
+// Host-only part of libsurgeon: size rules, the ratio rule of Eq. 5-7, error text.
+#include <math.h>
+#include <stdarg.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.hpp"
+
+namespace surgeon {
+
+static thread_local char g_err[512] = "no error";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int fail(int status, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return status;
+}
+
+bool make_group_plan(int64_t n, int64_t group_len, float r, GroupPlan* p) {
+  if (n < 0 || group_len < 1 || !(r >= 0.0f && r <= 1.0f)) return false;
+  if (n > 0 && group_len > n) group_len = n;
+  p->n = n;
+  p->g = group_len;
+  p->n_groups = n == 0 ? 0 : ceil_div(n, group_len);
+  p->len_last = n == 0 ? 0 : n - (p->n_groups - 1) * group_len;
+  p->k_full = surgeon_keep_count(group_len, r);
+  p->k_last = surgeon_keep_count(p->len_last, r);
+  p->k_total = n == 0 ? 0 : (p->n_groups - 1) * p->k_full + p->k_last;
+  return true;
+}
+
+PrunePath choose_prune_path(const GroupPlan& p) {
+  if (p.g > kWaveRegMaxGroup) return PATH_GLOBAL;
+  if (p.g % 64 == 0) return PATH_WAVE_REG;
+  return PATH_WAVE_MEM;
+}
+
+size_t prune_pack_ws_bytes(const GroupPlan& p) {
+  if (p.n == 0 || choose_prune_path(p) != PATH_GLOBAL) return 0;
+  const int64_t chunks_per_group = ceil_div(p.g, kGlobalWaveChunk);
+  const int64_t n_chunks = p.n_groups * chunks_per_group;
+  size_t bytes = 0;
+  bytes += align_up((size_t)p.n_groups * 16, 256);       // per-group select state
+  bytes += align_up((size_t)p.n_groups * 256 * 4, 256);  // per-group digit histogram
+  bytes += align_up((size_t)n_chunks * 8, 256);          // per-chunk (greater, equal) counts
+  bytes += align_up((size_t)n_chunks * 8, 256);          // per-chunk (equal-before, out-before) bases
+  return bytes;
+}
+
+}  // namespace surgeon
+
+using namespace surgeon;
+
+extern "C" {
+
+const char* surgeon_last_error(void) { return g_err; }
+
+const char* surgeon_version(void) { return "surgeon-gfx950 0.1"; }
+
+int64_t surgeon_keep_count(int64_t len, float r) {
+  if (len < 0 || !(r >= 0.0f && r <= 1.0f)) return -1;
+  // two separately rounded double operations: the subtraction must not fuse into the product
+  volatile double keep_fraction = 1.0 - (double)r;
+  volatile double product = keep_fraction * (double)len;
+  int64_t k = (int64_t)ceil(product);
+  if (k < 0) k = 0;
+  if (k > len) k = len;
+  return k;
+}
+
+int surgeon_packed_sizes(int64_t n, int64_t group_len, float r, int dt, int64_t* k_total, size_t* vals_bytes,
+                         size_t* mask_bytes, size_t* ws_bytes) {
+  if (dt != SURGEON_F32 && dt != SURGEON_BF16) return fail(SURGEON_EINVAL, "packed_sizes: bad dtype %d", dt);
+  GroupPlan p;
+  if (!make_group_plan(n, group_len, r, &p))
+    return fail(SURGEON_EINVAL, "packed_sizes: need n >= 0, group_len >= 1, 0 <= r <= 1 (n=%lld group_len=%lld r=%g)",
+                (long long)n, (long long)group_len, (double)r);
+  if (n > ((int64_t)1 << 31)) return fail(SURGEON_EUNSUPPORTED, "packed_sizes: n = %lld exceeds 2^31", (long long)n);
+  if (k_total) *k_total = p.k_total;
+  if (vals_bytes) *vals_bytes = (size_t)p.k_total * (dt == SURGEON_F32 ? 4 : 2);
+  if (mask_bytes) *mask_bytes = (size_t)ceil_div(n, 64) * 8;
+  if (ws_bytes) *ws_bytes = prune_pack_ws_bytes(p);
+  return SURGEON_OK;
+}
+
+int surgeon_layer_ratios(const float* G, const uint64_t* m, int l, float r_lo, float r_hi, float* r_out) {
+  if (!G || !m || !r_out) return fail(SURGEON_EINVAL, "layer_ratios: null pointer");
+  if (l < 1) return fail(SURGEON_EINVAL, "layer_ratios: l = %d", l);
+  if (!(r_lo >= 0.0f && r_hi <= 1.0f && r_lo <= r_hi))
+    return fail(SURGEON_EINVAL, "layer_ratios: need 0 <= r_lo <= r_hi <= 1 (got %g, %g)", (double)r_lo, (double)r_hi);
+  double total = 0.0;
+  for (int i = 0; i < l; ++i) {
+    if (m[i] == 0) return fail(SURGEON_EINVAL, "layer_ratios: m[%d] == 0", i);
+    if (!(G[i] >= 0.0f) || isinf(G[i])) return fail(SURGEON_EINVAL, "layer_ratios: G[%d] = %g", i, (double)G[i]);
+    total += (double)m[i];
+  }
+  // Eq. 5: memory score; Eq. 6: product of the two max-normalised scores; Eq. 7: ratio
+  std::vector<double> score(l);
+  double mem_max = 0.0, grad_max = 0.0;
+  for (int i = 0; i < l; ++i) {
+    score[i] = -log((double)m[i] / total);
+    mem_max = fmax(mem_max, score[i]);
+    grad_max = fmax(grad_max, (double)G[i]);
+  }
+  double ind_max = 0.0;
+  for (int i = 0; i < l; ++i) {
+    const double mem_n = mem_max > 0.0 ? score[i] / mem_max : 1.0;
+    const double grad_n = grad_max > 0.0 ? (double)G[i] / grad_max : 1.0;
+    score[i] = mem_n * grad_n;
+    ind_max = fmax(ind_max, score[i]);
+  }
+  const double span = (double)r_hi - (double)r_lo;
+  for (int i = 0; i < l; ++i) {
+    const double p = ind_max > 0.0 ? 1.0 - score[i] / ind_max : 0.0;
+    r_out[i] = (float)((double)r_lo + span * p);
+  }
+  return SURGEON_OK;
+}
+
+}  // extern "C"

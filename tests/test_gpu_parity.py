@@ -1,0 +1,275 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
+
+Bars: masks, values, indices and counts bit-exact; dW and Gradient Importance within rel-L2 1e-5 for fp32
+inputs and 2e-2 for bf16 inputs (the kernels accumulate exact bf16 products in fp32, so they sit far below it).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_20354_amd as surgeon
+import surgeon_workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def rel_l2(got, ref):
+    got, ref = np.asarray(got, np.float64).ravel(), np.asarray(ref, np.float64).ravel()
+    den = np.linalg.norm(ref)
+    return np.linalg.norm(got - ref) / den if den > 0 else np.linalg.norm(got)
+
+
+def host_bits(t):
+    return wl.to_numpy_bits(t)
+
+
+def draw(shape, dist, dtype, seed):
+    if dist == "few":  # a handful of distinct magnitudes: almost everything ties
+        g = torch.Generator().manual_seed(seed)
+        t = torch.randint(-3, 4, shape, generator=g).to(torch.float32) * 0.5
+        return t.to(torch.float32 if dtype == "f32" else torch.bfloat16)
+    if dist == "const":
+        return torch.full(shape, -1.25, dtype=torch.float32 if dtype == "f32" else torch.bfloat16)
+    return wl.draw(shape, dist, dtype, seed)
+
+
+def check_pack(A, g, r, want_idx=True, tag=""):
+    print("prune_pack", tag, tuple(A.shape), A.dtype, "g=%d r=%g" % (g, r), flush=True)
+    p = surgeon.prune_pack(A.to(DEV), g, r, want_idx=want_idx)
+    torch.cuda.synchronize()
+    o_vals, o_mask, o_idx, o_k = oracle.prune_pack(host_bits(A).reshape(-1), g, r)
+    assert p.k_total == o_k
+    assert np.array_equal(p.mask.cpu().numpy().view(np.uint64), o_mask), "mask"
+    got_vals = host_bits(p.vals)
+    assert np.array_equal(got_vals.view(np.uint8), o_vals.view(np.uint8)), "vals"
+    if want_idx:
+        assert np.array_equal(p.idx.cpu().numpy().view(np.uint32), o_idx), "idx"
+    return p, (o_vals, o_mask)
+
+
+# ------------------------------------------------------------------------------------------------
+# Gradient Importance (Eq. 4)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n", [0, 1, 5, 255, 4096, 4097, 65539, 1_000_003, 5_000_000])
+def test_grad_importance(n):
+    print("grad_importance n =", n, flush=True)
+    x = wl.draw((n,), "normal", "f32", 100 + n % 97) * 3.0
+    got = surgeon.grad_importance(x.to(DEV)).item()
+    ref = oracle.grad_importance(x.numpy())
+    assert abs(got - ref) <= 1e-5 * max(ref, 1e-30)
+    if n > 8:  # a view that is only 4-byte aligned takes the scalar-load kernel
+        got = surgeon.grad_importance(x.to(DEV)[1:]).item()
+        ref = oracle.grad_importance(x.numpy()[1:])
+        assert abs(got - ref) <= 1e-5 * ref
+
+
+def test_grad_importance_closed_forms():
+    c = torch.full((123457,), -2.5, device=DEV)
+    assert surgeon.grad_importance(c).item() == pytest.approx(2.5, rel=1e-6)
+    one_hot = torch.zeros(1 << 20, device=DEV)
+    one_hot[12345] = 1.0
+    assert surgeon.grad_importance(one_hot).item() == pytest.approx(2.0 ** -10, rel=1e-6)
+
+
+# ------------------------------------------------------------------------------------------------
+# prune + pack (Alg. 1 lines 6-7): the three selection paths
+# ------------------------------------------------------------------------------------------------
+REG_CASES = [(32768, 512), (4096 * 5 + 1000, 4096), (768 * 50, 768), (3072 * 9, 3072), (64 * 100, 64),
+             (128 * 33 + 64, 128), (320 * 20, 320), (1280 * 7 + 5, 1280), (2048 * 3, 2048), (4096, 4096), (64, 64)]
+MEM_CASES = [(1000, 100), (5000, 1000), (777, 777), (4095 * 3, 4095), (10, 3), (130, 65), (1, 1), (63, 63)]
+GLOBAL_CASES = [(100000, 100000), (300000, 50000), (20000, 5000), (1 << 20, 1 << 20), (70001, 70001), (12345, 4097)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n,g", REG_CASES + MEM_CASES + GLOBAL_CASES)
+def test_prune_pack_matches_oracle(dtype, n, g):
+    seed = n * 7 + g
+    for dist in ("normal", "relu", "few"):
+        for r in (0.0, 0.3, 0.5, 0.9, 0.95, 1.0):
+            A = draw((n,), dist, dtype, seed)
+            check_pack(A, g, r, want_idx=(r != 0.3), tag=dist)
+    check_pack(draw((n,), "const", dtype, seed), g, 0.7, tag="const")
+
+
+def test_prune_pack_signed_zero_and_non_finite():
+    a = torch.zeros(4096)
+    a[::3] = -0.0
+    a[5], a[70], a[900], a[901] = float("inf"), float("-inf"), float("nan"), 1e38
+    for g in (4096, 1000, 512):
+        p, _ = check_pack(a, g, 0.9)
+    A = a.clone()
+    A[1000:3000] = torch.randn(2000)
+    check_pack(A, 4096, 0.5)
+    check_pack(A.to(torch.bfloat16), 4096, 0.5)
+
+
+def test_prune_pack_empty_and_determinism():
+    p = surgeon.prune_pack(torch.zeros(0, device=DEV), 64, 0.5)
+    assert p.k_total == 0 and p.mask.numel() == 0
+    A = wl.draw((4096 * 300 + 77,), "relu", "f32", 5).to(DEV)
+    first = surgeon.prune_pack(A, 4096, 0.4, want_idx=True)
+    with torch.cuda.stream(torch.cuda.Stream()):
+        second = surgeon.prune_pack(A, 4096, 0.4, want_idx=True)
+    torch.cuda.synchronize()
+    assert torch.equal(first.mask, second.mask) and torch.equal(first.vals, second.vals)
+    assert torch.equal(first.idx, second.idx)
+
+
+# ------------------------------------------------------------------------------------------------
+# dW from the packed activation (Eq. 2, Alg. 1 lines 11-12)
+# ------------------------------------------------------------------------------------------------
+def run_linear(M, K, N, dtype, r, g=None, seed=0):
+    print("dw linear", (M, K, N), dtype, "r=%g" % r, flush=True)
+    A = wl.draw((M, K), "normal", dtype, seed + 1)
+    dY = wl.draw((M, N), "normal", dtype, seed + 2)
+    p, (o_vals, o_mask) = check_pack(A, g or K, r, want_idx=False)
+    desc = surgeon.linear_desc(M, K, N, surgeon.F32 if dtype == "f32" else surgeon.BF16, p.k_total)
+    dW = surgeon.dw_from_packed(desc, p, dY.to(DEV))
+    torch.cuda.synchronize()
+    ref = oracle.dw_linear(o_vals, o_mask, host_bits(dY), M, K, N)
+    return dW.cpu().numpy(), ref
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,K,N", [(64, 512, 256), (100, 70, 50), (300, 129, 257), (33, 64, 64), (1000, 768, 96),
+                                   (1, 64, 64), (517, 320, 1280)])
+def test_dw_linear(dtype, M, K, N):
+    for r in (0.0, 0.5, 0.9):
+        got, ref = run_linear(M, K, N, dtype, r, seed=M + K + N)
+        assert got.shape == ref.shape == (N, K)
+        assert rel_l2(got, ref) <= TOL[dtype]
+    got, _ = run_linear(M, K, N, dtype, 1.0)
+    assert not got.any()  # nothing cached: the gradient is exactly zero
+
+
+def test_dw_linear_ratio0_is_dense_gradient():
+    M, K, N = 200, 256, 192
+    A = wl.draw((M, K), "normal", "f32", 11)
+    dY = wl.draw((M, N), "normal", "f32", 12)
+    p = surgeon.prune_pack(A.to(DEV), K, 0.0)
+    dW = surgeon.dw_from_packed(surgeon.linear_desc(M, K, N, surgeon.F32, p.k_total), p, dY.to(DEV))
+    dense = dY.double().T @ A.double()
+    assert rel_l2(dW.cpu().numpy(), dense.numpy()) <= 1e-5
+
+
+def run_conv(shape, dtype, r, dist="relu", seed=0):
+    Nb, Ci, H, W, Co, k, st = shape
+    pad = k // 2
+    print("dw conv", shape, dtype, "r=%g" % r, flush=True)
+    OH, OW = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+    A = wl.draw((Nb, Ci, H, W), dist, dtype, seed + 1)
+    dY = wl.draw((Nb, Co, OH, OW), "normal", dtype, seed + 2)
+    p, (o_vals, o_mask) = check_pack(A, 4096, r, want_idx=False)
+    desc = surgeon.conv2d_desc(Nb, Ci, H, W, Co, k, k, st, pad, surgeon.F32 if dtype == "f32" else surgeon.BF16, p.k_total)
+    dW = surgeon.dw_from_packed(desc, p, dY.to(DEV))
+    torch.cuda.synchronize()
+    ref = oracle.dw_conv2d(o_vals, o_mask, host_bits(dY), Nb, Ci, H, W, Co, k, k, st, pad)
+    return dW.cpu().numpy(), ref
+
+
+CONV_SHAPES = [
+    # Nb, Ci, H, W, Co, k, stride
+    (4, 16, 32, 32, 160, 3, 1), (3, 160, 16, 16, 160, 3, 1), (2, 160, 32, 32, 320, 3, 2), (2, 16, 32, 32, 160, 1, 1),
+    (2, 160, 32, 32, 320, 1, 2), (2, 3, 32, 32, 16, 3, 1), (2, 3, 64, 64, 64, 7, 2), (1, 3, 224, 224, 64, 7, 2),
+    (2, 64, 56, 56, 64, 3, 1), (2, 64, 56, 56, 256, 1, 1), (2, 128, 56, 56, 128, 3, 2), (2, 512, 7, 7, 512, 3, 1),
+    (2, 5, 9, 9, 7, 5, 1), (3, 6, 12, 12, 20, 3, 1), (2, 256, 14, 14, 1024, 1, 1), (2, 40, 13, 13, 24, 3, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_dw_conv(dtype, shape):
+    for r in (0.0, 0.7):
+        got, ref = run_conv(shape, dtype, r, seed=sum(shape))
+        assert got.shape == ref.shape
+        assert rel_l2(got, ref) <= TOL[dtype]
+    got, _ = run_conv(shape, dtype, 1.0)
+    assert not got.any()
+
+
+def test_dw_is_deterministic():
+    shape = (8, 160, 32, 32, 160, 3, 1)
+    Nb, Ci, H, W, Co, k, st = shape
+    A = wl.draw((Nb, Ci, H, W), "relu", "f32", 1).to(DEV)
+    dY = wl.draw((Nb, Co, H, W), "normal", "f32", 2).to(DEV)
+    p = surgeon.prune_pack(A, 4096, 0.6)
+    desc = surgeon.conv2d_desc(Nb, Ci, H, W, Co, k, k, st, 1, surgeon.F32, p.k_total)
+    a = surgeon.dw_from_packed(desc, p, dY).clone()
+    b = surgeon.dw_from_packed(desc, p, dY)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------------------------------------------
+# the five workloads at reduced batch: the whole path per distinct layer shape
+# ------------------------------------------------------------------------------------------------
+def whole_path_layer(cfg, li, layer, r):
+    """select + pack + dW + Gradient Importance for one layer; returns (G_gpu, G_oracle)."""
+    A, dY = wl.layer_tensors(cfg, li, layer)
+    p, (o_vals, o_mask) = check_pack(A, layer.group_len, r, want_idx=False, tag=layer.name)
+    dt = surgeon.F32 if layer.dtype == "f32" else surgeon.BF16
+    if layer.kind == "linear":
+        desc = surgeon.linear_desc(layer.M, layer.K, layer.N, dt, p.k_total)
+        ref = oracle.dw_linear(o_vals, o_mask, host_bits(dY), layer.M, layer.K, layer.N)
+    else:
+        desc = surgeon.conv2d_desc(layer.Nb, layer.Ci, layer.H, layer.W, layer.Co, layer.kh, layer.kw, layer.stride,
+                                   layer.pad, dt, p.k_total)
+        ref = oracle.dw_conv2d(o_vals, o_mask, host_bits(dY), layer.Nb, layer.Ci, layer.H, layer.W, layer.Co,
+                               layer.kh, layer.kw, layer.stride, layer.pad)
+    dW = surgeon.dw_from_packed(desc, p, dY.to(DEV))
+    G = surgeon.grad_importance(dW)
+    torch.cuda.synchronize()
+    assert rel_l2(dW.cpu().numpy(), ref) <= TOL[layer.dtype], layer.name
+    o_G = oracle.grad_importance(ref)
+    assert abs(G.item() - o_G) <= TOL[layer.dtype] * max(o_G, 1e-30), layer.name
+    return G.item(), o_G
+
+
+@pytest.mark.parametrize("cfg,batch_div", [(0, 1), (1, 100), (2, 64), (3, 197), (4, 64)])
+def test_workload_shapes_reduced(cfg, batch_div):
+    layers = [wl.shrink(l, batch_div) for l in wl.distinct_shapes(wl.config_layers(cfg))]
+    lo, hi = wl.RATIO_RANGE[cfg]
+    # importance pass at the static ratio, then the ratio rule (Eq. 5-7), then the adaptation pass
+    G_gpu, G_ref = [], []
+    for li, layer in enumerate(layers):
+        g, o = whole_path_layer(cfg, li, layer, wl.IMPORTANCE_PASS_RATIO if cfg else 0.5)
+        G_gpu.append(g)
+        G_ref.append(o)
+    if cfg == 0:
+        return
+    m = [l.n * l.elem_bytes for l in layers]
+    ratios = surgeon.surgeon_layer_ratios(G_gpu, m, lo, hi).numpy()
+    assert np.allclose(ratios, oracle.layer_ratios(np.array(G_ref, np.float32), np.array(m, np.uint64), lo, hi), atol=1e-5)
+    assert ratios.min() == pytest.approx(lo, abs=1e-6) and ratios.max() <= hi + 1e-6
+    for li, layer in enumerate(layers):
+        whole_path_layer(cfg, li, layer, float(ratios[li]))
+
+
+# ------------------------------------------------------------------------------------------------
+# the benchmark workload at full size (WideResNet-28-10, batch 200): complete select/pack parity,
+# dW on sampled entries evaluated one by one from the definition
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,r", [("s1b2.conv1", 0.9), ("s2b1.conv1", 0.45), ("s3b2.conv2", 0.3), ("s2b1.shortcut", 0.6),
+                                    ("stem", 0.5)])
+def test_benchmark_workload_full_size_sampled(name, r):
+    layers = wl.config_layers(1)
+    li = [l.name for l in layers].index(name)
+    layer = layers[li]
+    A, dY = wl.layer_tensors(1, li, layer)
+    p, (o_vals, o_mask) = check_pack(A, layer.group_len, r, want_idx=False, tag=name)
+    desc = surgeon.conv2d_desc(layer.Nb, layer.Ci, layer.H, layer.W, layer.Co, layer.kh, layer.kw, layer.stride,
+                               layer.pad, surgeon.F32, p.k_total)
+    dW = surgeon.dw_from_packed(desc, p, dY.to(DEV))
+    G = surgeon.grad_importance(dW)
+    torch.cuda.synchronize()
+    where = np.random.default_rng(li).integers(0, layer.n_w, 2048)
+    ref = oracle.dw_conv2d_at(o_vals, o_mask, host_bits(dY), layer.Nb, layer.Ci, layer.H, layer.W, layer.Co, layer.kh,
+                              layer.kw, layer.stride, layer.pad, where)
+    got = dW.cpu().numpy().reshape(-1)
+    assert rel_l2(got[where], ref) <= 1e-5
+    # Gradient Importance of the full gradient the GPU produced, against the oracle on the same values
+    assert abs(G.item() - oracle.grad_importance(got)) <= 1e-5 * G.item()
