@@ -137,6 +137,24 @@ size_t surgeon_grad_importance_ws_bytes(int64_t n_w);
 int surgeon_grad_importance(const float* dW, int64_t n_w, float* G_out,
                             void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Kernel timing aid for benchmarks (not part of the method).  Between surgeon_profile_begin() and
+ * surgeon_profile_end() every kernel launch of the library is bracketed by two HIP events recorded on the
+ * caller's stream.  surgeon_profile_end() waits for the recorded events and returns, per kernel class,
+ * the summed device time in milliseconds and the number of launches, then discards the events:
+ *   class 0 SURGEON_PROF_SELECT_PACK  fused select+pack kernel (group_len % 64 == 0, <= 4096)
+ *   class 1 SURGEON_PROF_DW           the MFMA weight-gradient kernel (conv or linear)
+ *   class 2 SURGEON_PROF_IMPORTANCE   sum-of-squares kernels of Eq. 4
+ *   class 3 SURGEON_PROF_DW_AUX       rank-table pre-pass and split reduction around class 1
+ *   class 4 SURGEON_PROF_SELECT_OTHER kernels of the other two selection paths, mask clearing
+ * ms / launches are host arrays of n_classes entries (at most SURGEON_PROF_CLASSES are filled).
+ * Not thread-safe; intended for one benchmarking thread.  Event objects are created by the HIP runtime.
+ */
+enum { SURGEON_PROF_SELECT_PACK = 0, SURGEON_PROF_DW = 1, SURGEON_PROF_IMPORTANCE = 2, SURGEON_PROF_DW_AUX = 3,
+       SURGEON_PROF_SELECT_OTHER = 4, SURGEON_PROF_CLASSES = 5 };
+int surgeon_profile_begin(void);
+int surgeon_profile_end(int n_classes, double* ms, int64_t* launches);
+
 /* Description of the last error on the calling thread (static storage, never NULL). */
 const char* surgeon_last_error(void);
 

@@ -25,5 +25,7 @@ from .binding import (  # noqa: F401
     surgeon_layer_ratios,
     surgeon_packed_sizes,
     surgeon_prune_pack,
+    surgeon_profile_begin,
+    surgeon_profile_end,
     surgeon_version,
 )

@@ -64,6 +64,10 @@ def load_library():
     L.surgeon_grad_importance_ws_bytes.argtypes = [i64]
     L.surgeon_grad_importance.restype = ci
     L.surgeon_grad_importance.argtypes = [vp, i64, vp, vp, sz, vp]
+    L.surgeon_profile_begin.restype = ci
+    L.surgeon_profile_begin.argtypes = []
+    L.surgeon_profile_end.restype = ci
+    L.surgeon_profile_end.argtypes = [ci, vp, vp]
     L.surgeon_last_error.restype = ctypes.c_char_p
     L.surgeon_version.restype = ctypes.c_char_p
     _lib = L
@@ -165,6 +169,22 @@ def surgeon_grad_importance(dW, G_out, ws=None):
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(load_library().surgeon_grad_importance(_ptr(dW), dW.numel(), _ptr(G_out), _ptr(ws), ws_bytes,
                                                   _stream(dW.device)))
+
+
+PROF_CLASSES = ("select_pack", "dw", "importance", "dw_aux", "select_other")
+
+
+def surgeon_profile_begin():
+    _check(load_library().surgeon_profile_begin())
+
+
+def surgeon_profile_end():
+    """Returns {class name: (milliseconds, launches)} for the kernels launched since surgeon_profile_begin()."""
+    n = len(PROF_CLASSES)
+    ms = (ctypes.c_double * n)()
+    launches = (ctypes.c_int64 * n)()
+    _check(load_library().surgeon_profile_end(n, ms, launches))
+    return {name: (ms[i], launches[i]) for i, name in enumerate(PROF_CLASSES)}
 
 
 # ----------------------------------------------------------------------------------------------------

@@ -23,6 +23,14 @@ int fail(int status, const char* fmt, ...);
 // launch check: catches bad launch configurations without synchronising
 #define SURGEON_LAUNCH_CHECK() SURGEON_HIP_CHECK(hipGetLastError())
 
+// brackets the launches inside its scope with HIP events while profiling is on (surgeon_profile_begin/end)
+struct ProfScope {
+  ProfScope(int kind, hipStream_t stream);
+  ~ProfScope();
+  int slot_;
+  hipStream_t stream_;
+};
+
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 

@@ -162,31 +162,170 @@ struct ConvGeom {
                         // the pixels a strided 1x1 filter touches are staged), fill_step = stride / lds_step
   int fill_step;
   int ci_tiles;         // output tiles along ci (blockIdx.x = co_tile * ci_tiles + ci_tile)
+  int n_patch;          // tile_ci * PR * PW: patch elements staged per K-tile
+  uint32_t magic_pw, magic_pr;  // ceil(2^32 / PW), ceil(2^32 / PR) (0 when the divisor is 1)
+  int dy_vec;           // dY rows of a K-tile start 4-element aligned and hold a multiple of 4 positions
+  int n_buf;            // 2: staging overlaps the MFMA work of the previous K-tile; 1: LDS holds one K-tile only
   int64_t n_w;          // Co*Ci*KH*KW
 };
 
-// Workgroup = 4 wavefronts as 2 (co) x 2 (ci); wavefront tile = MT x NT MFMA 16x16 tiles for KHC*KW taps.
+// n / d for n*d < 2^32 with magic = ceil(2^32 / d); magic == 0 encodes d == 1
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t magic) { return magic ? __umulhi(n, magic) : n; }
+
+template <typename InT>
+struct Vec4;
+template <>
+struct Vec4<float> {
+  typedef float type __attribute__((ext_vector_type(4)));
+};
+template <>
+struct Vec4<uint16_t> {
+  typedef uint16_t type __attribute__((ext_vector_type(4)));
+};
+
+constexpr int kConvLoaders = 256;  // threads of the four staging wavefronts
+constexpr int kConvChunk = 20;     // patch elements a staging thread has in flight at once
+
+// Stages K-tile `tile` (dY rows + un-packed input patch) into one LDS buffer.  Called by the 256 staging
+// threads only.  All loads of a chunk are issued before the first dependent use: per chunk there are two
+// memory round trips (mask word + rank, then the value), not two per element.
+template <typename InT, int KHC, int MT, int NT, int P>
+__device__ __forceinline__ void conv_stage_tile(const ConvGeom& gm, const Packed<InT>& pk, const InT* __restrict__ dY,
+                                                float* __restrict__ buf, int tile, int ltid, int co0, int ci0, int u0) {
+  constexpr int TCO = 2 * MT * 16, SY = P + 4, NY = TCO * P / 4 / kConvLoaders;
+  typedef typename Vec4<InT>::type vec_t;
+  float* __restrict__ dYs = buf;
+  float* __restrict__ As = buf + TCO * SY;
+  const int b = tile / gm.tiles_per_img;
+  const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
+  const int valid_pos = gm.R * gm.OW;
+  const int PW = gm.PW, PS = gm.PS;
+
+  // ---- dY[b, co0.., oh0..oh0+R, :]: R*OW contiguous elements per output channel
+  vec_t y[NY];
+  if (gm.dy_vec) {
+#pragma unroll
+    for (int j = 0; j < NY; ++j) {
+      const int q = ltid + kConvLoaders * j;
+      const int c = q / (P / 4), k4 = q % (P / 4);
+      const bool ok = co0 + c < gm.Co && 4 * k4 < valid_pos;
+      const int64_t off = ok ? (((int64_t)b * gm.Co + co0 + c) * gm.OH + oh0) * gm.OW + 4 * k4 : 0;
+      y[j] = *reinterpret_cast<const vec_t*>(dY + off);
+      if (!ok) y[j] = vec_t{0, 0, 0, 0};
+    }
+  } else {
+    for (int idx = ltid; idx < TCO * P; idx += kConvLoaders) {
+      const int c = idx / P, k = idx - c * P;
+      float v = 0.0f;
+      if (co0 + c < gm.Co && k < valid_pos)
+        v = widen<InT>(dY[(((int64_t)b * gm.Co + co0 + c) * gm.OH + oh0) * gm.OW + k]);
+      dYs[c * SY + k] = v;
+    }
+  }
+
+  // ---- un-packed input patch: PR rows from ih0 and PW columns from -pad, every fill_step-th pixel
+  const int ih0 = oh0 * gm.stride + u0 - gm.pad;
+  for (int base = 0; base < gm.n_patch; base += kConvLoaders * kConvChunk) {
+    uint64_t word[kConvChunk];
+    uint32_t rank0[kConvChunk];
+    int where[kConvChunk];  // LDS offset, or -1 past the end of the patch; bit position in the top 6 bits
+#pragma unroll
+    for (int j = 0; j < kConvChunk; ++j) {
+      const uint32_t idx = (uint32_t)(base + j * kConvLoaders + ltid);
+      const bool in_patch = idx < (uint32_t)gm.n_patch;
+      const uint32_t row = fast_div(idx, gm.magic_pw), col = idx - row * PW;
+      const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
+      const int ci = ci0 + (int)c, ih = ih0 + (int)pr * gm.fill_step, iw = (int)col * gm.fill_step - gm.pad;
+      const bool ok = in_patch && ci < gm.Ci && ih >= 0 && ih < gm.H && iw >= 0 && iw < gm.W;
+      const int64_t e = ok ? (((int64_t)b * gm.Ci + ci) * gm.H + ih) * gm.W + iw : 0;
+      const uint64_t m = pk.mask[e >> 6];
+      rank0[j] = pk.word_rank[e >> 6];
+      word[j] = ok ? m : 0ull;
+      where[j] = in_patch ? (int)((c * PS + pr * PW + col) | ((uint32_t)(e & 63) << 26)) : -1;
+    }
+    InT raw[kConvChunk];
+#pragma unroll
+    for (int j = 0; j < kConvChunk; ++j) {
+      const int bit = (int)((uint32_t)where[j] >> 26);
+      const bool has = (word[j] >> bit) & 1ull;
+      int64_t r = (int64_t)rank0[j] + __popcll(word[j] & ((1ull << bit) - 1ull));
+      r = r > pk.k_last ? pk.k_last : r;
+      raw[j] = pk.vals[has ? r : 0];
+    }
+#pragma unroll
+    for (int j = 0; j < kConvChunk; ++j) {
+      if (where[j] != -1) {
+        const int bit = (int)((uint32_t)where[j] >> 26);
+        const bool has = (word[j] >> bit) & 1ull;
+        As[where[j] & 0x3ffffff] = has ? widen<InT>(raw[j]) : 0.0f;
+      }
+    }
+  }
+  if (gm.dy_vec) {
+#pragma unroll
+    for (int j = 0; j < NY; ++j) {
+      const int q = ltid + kConvLoaders * j;
+      const int c = q / (P / 4), k4 = q % (P / 4);
+      typedef float f4 __attribute__((ext_vector_type(4)));
+      f4 v = {widen<InT>(y[j][0]), widen<InT>(y[j][1]), widen<InT>(y[j][2]), widen<InT>(y[j][3])};
+      *reinterpret_cast<f4*>(&dYs[c * SY + 4 * k4]) = v;
+    }
+  }
+}
+
+// Workgroup = 8 wavefronts.  Wavefronts 0-3 are the MFMA wavefronts, arranged 2 (co) x 2 (ci), each owning
+// MT x NT MFMA 16x16 tiles for KHC*KW taps.  Wavefronts 4-7 stage the next K-tile into the other LDS buffer
+// while the MFMA wavefronts work on the current one; one barrier per K-tile hands the buffers over.
 // blockIdx.y = split along the contraction, blockIdx.z = first filter row handled (u0 = z * KHC).
 template <typename InT, int KHC, int KW, int MT, int NT, int P>
-__global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) void dw_conv_kernel(ConvGeom gm, Packed<InT> pk,
+__global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_kernel(ConvGeom gm, Packed<InT> pk,
                                                                                       const InT* __restrict__ dY,
                                                                                       float* __restrict__ out) {
   constexpr int TCO = 2 * MT * 16, TCI = 2 * NT * 16, SY = P + 4, TAPS = KHC * KW, STEPS = P / 4;
   extern __shared__ float smem[];
-  float* __restrict__ dYs = smem;            // [TCO][SY]
-  float* __restrict__ As = smem + TCO * SY;  // [TCI][PS]: PR patch rows followed by KHC rows of zeros
-
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
-  const int i16 = lane & 15, kk = lane >> 4;
   const int co_tile = blockIdx.x / gm.ci_tiles, ci_tile = blockIdx.x % gm.ci_tiles;
   const int co0 = co_tile * TCO, ci0 = ci_tile * TCI;
   const int u0 = blockIdx.z * KHC;
   const int PW = gm.PW, PS = gm.PS;
+  const int buf_floats = TCO * SY + TCI * PS;
+  const int t_begin = blockIdx.y * gm.tiles_per_split;
+  const int t_end = min(t_begin + gm.tiles_per_split, gm.n_ktiles);
 
-  // LDS offset of the input pixel under tap (0,0) for each contraction position this lane feeds;
-  // positions past R*OW point at the zero rows (their dY is zero as well)
+  // KHC rows of zeros after every channel's patch in both buffers (written once): contraction positions past
+  // R*OW point there, and their dY is zero as well
+  for (int t = tid; t < gm.n_buf * TCI * KHC * PW; t += 512) {
+    const int bsel = t / (TCI * KHC * PW), rem = t - bsel * (TCI * KHC * PW);
+    const int c = rem / (KHC * PW), x = rem - c * (KHC * PW);
+    smem[bsel * buf_floats + TCO * SY + c * PS + gm.PR * PW + x] = 0.0f;
+  }
+
+  if (wave >= 4) {
+    // ------------------------------ staging wavefronts ------------------------------
+    const int ltid = tid - 256;
+    if (gm.n_buf == 1) {
+      for (int tile = t_begin; tile < t_end; ++tile) {
+        conv_stage_tile<InT, KHC, MT, NT, P>(gm, pk, dY, smem, tile, ltid, co0, ci0, u0);
+        __syncthreads();  // the tile is staged
+        __syncthreads();  // the MFMA wavefronts are done with it
+      }
+      return;
+    }
+    if (t_begin < t_end) conv_stage_tile<InT, KHC, MT, NT, P>(gm, pk, dY, smem, t_begin, ltid, co0, ci0, u0);
+    for (int tile = t_begin; tile < t_end; ++tile) {
+      __syncthreads();  // buffer (tile - t_begin) & 1 is complete; the other one is no longer being read
+      if (tile + 1 < t_end)
+        conv_stage_tile<InT, KHC, MT, NT, P>(gm, pk, dY, smem + ((tile + 1 - t_begin) & 1) * buf_floats, tile + 1, ltid,
+                                             co0, ci0, u0);
+    }
+    return;
+  }
+
+  // ------------------------------ MFMA wavefronts ------------------------------
+  const int wm = wave >> 1, wn = wave & 1;
+  const int i16 = lane & 15, kk = lane >> 4;
+  // LDS offset of the input pixel under tap (0,0) for each contraction position this lane feeds
   int aoff[STEPS];
 #pragma unroll
   for (int s = 0; s < STEPS; ++s) {
@@ -194,10 +333,6 @@ __global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) void dw_conv_k
     const int r = k / gm.OW, ow = k - r * gm.OW;
     aoff[s] = (r < gm.R) ? (r * gm.lds_step) * PW + ow * gm.lds_step : gm.PR * PW;
   }
-  // zero rows at the end of every channel's patch (written once)
-  for (int c = 0; c < TCI; ++c)
-    for (int t = tid; t < KHC * PW; t += 256) As[c * PS + gm.PR * PW + t] = 0.0f;
-
   floatx4 acc[MT][NT][TAPS];
 #pragma unroll
   for (int a = 0; a < MT; ++a)
@@ -206,52 +341,25 @@ __global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) void dw_conv_k
 #pragma unroll
       for (int t = 0; t < TAPS; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  const int t_begin = blockIdx.y * gm.tiles_per_split;
-  const int t_end = min(t_begin + gm.tiles_per_split, gm.n_ktiles);
-  const int valid_pos = gm.R * gm.OW;
-
   for (int tile = t_begin; tile < t_end; ++tile) {
-    const int b = tile / gm.tiles_per_img;
-    const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
-    __syncthreads();  // the previous tile's MFMA reads are done
-    // ---- stage dY[b, co0.., oh0..oh0+R, :] : R*OW contiguous elements per output channel
-    for (int idx = tid; idx < TCO * P; idx += 256) {
-      const int c = idx / P, k = idx - c * P;
-      float v = 0.0f;
-      if (co0 + c < gm.Co && k < valid_pos)
-        v = widen<InT>(dY[(((int64_t)b * gm.Co + co0 + c) * gm.OH + oh0) * gm.OW + k]);
-      dYs[c * SY + k] = v;
-    }
-    // ---- stage the un-packed input patch: PR rows from ih0 and PW columns from -pad, every fill_step-th pixel
-    const int ih0 = oh0 * gm.stride + u0 - gm.pad;
-    for (int c = wave * (TCI / 4); c < (wave + 1) * (TCI / 4); ++c) {
-      const int ci = ci0 + c;
-      for (int pr = 0; pr < gm.PR; ++pr) {
-        const int ih = ih0 + pr * gm.fill_step;
-        const bool row_ok = ci < gm.Ci && ih >= 0 && ih < gm.H;
-        const int64_t e_row = (((int64_t)b * gm.Ci + ci) * gm.H + ih) * gm.W;
-        for (int col = lane; col < PW; col += 64) {
-          const int iw = col * gm.fill_step - gm.pad;
-          float v = 0.0f;
-          if (row_ok && iw >= 0 && iw < gm.W) v = unpack_at<InT>(pk, e_row + iw);
-          As[c * PS + pr * PW + col] = v;
-        }
-      }
-    }
     __syncthreads();
-    // ---- MFMA over the positions of this tile; taps are shifted reads of the same patch
+    const float* __restrict__ dYs = smem + ((tile - t_begin) & (gm.n_buf - 1)) * buf_floats;
+    const float* __restrict__ As = dYs + TCO * SY;
+    const float* __restrict__ a_base = dYs + (wm * MT * 16 + i16) * SY + kk;
+    const float* __restrict__ b_base = As + (wn * NT * 16 + i16) * PS;
+    // taps are shifted reads of the same patch
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
       float av[MT];
 #pragma unroll
-      for (int a = 0; a < MT; ++a) av[a] = dYs[(wm * MT * 16 + a * 16 + i16) * SY + 4 * s + kk];
+      for (int a = 0; a < MT; ++a) av[a] = a_base[a * 16 * SY + 4 * s];
 #pragma unroll
       for (int du = 0; du < KHC; ++du) {
 #pragma unroll
         for (int v = 0; v < KW; ++v) {
 #pragma unroll
           for (int bn = 0; bn < NT; ++bn) {
-            const float bv = As[(wn * NT * 16 + bn * 16 + i16) * PS + aoff[s] + du * PW + v];
+            const float bv = b_base[bn * 16 * PS + aoff[s] + du * PW + v];
 #pragma unroll
             for (int a = 0; a < MT; ++a)
               acc[a][bn][du * KW + v] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv, acc[a][bn][du * KW + v], 0, 0, 0);
@@ -259,6 +367,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) void dw_conv_k
         }
       }
     }
+    if (gm.n_buf == 1) __syncthreads();
   }
 
   // ---- write this split's partial tile: lane holds rows 4*kk..4*kk+3 (co), column i16 (ci) of each 16x16 tile
@@ -372,8 +481,10 @@ __global__ void fill_zero_f32_kernel(float* __restrict__ p, int64_t n) {
 // ---------------------------------------------------------------------------------------------------------
 // host planning
 // ---------------------------------------------------------------------------------------------------------
-constexpr int kSplitSlots = 512;   // two workgroups on each of the 256 compute units
+constexpr int kConvSlots = 256;    // the conv kernel keeps one 8-wavefront workgroup per compute unit
+constexpr int kLinSlots = 512;     // the linear kernel fits two workgroups per compute unit
 constexpr int kMaxSplits = 256;
+constexpr double kFlopsPerCuPerUs = 0.6e6;  // fp32 MFMA rate of one compute unit (157.3 TFLOP/s / 256), per microsecond
 constexpr size_t kMaxLds = 160 * 1024;
 
 struct ConvPlan {
@@ -398,10 +509,26 @@ struct DwPlan {
   size_t off_rank, off_blocks, off_part, ws_bytes;
 };
 
-static int choose_splits(int64_t k_tiles, int64_t out_tiles, int64_t* tiles_per_split) {
-  int64_t s = std::max<int64_t>(1, std::min<int64_t>(k_tiles, kSplitSlots / std::max<int64_t>(1, out_tiles)));
-  s = std::min<int64_t>(s, kMaxSplits);
-  const int64_t per = ceil_div(k_tiles, s);
+// Splits along the contraction.  Modelled time of a launch with s splits:
+//   rounds(s) * (tiles_per_split * tile_us + fixed_us)  +  time to write and re-read s partial copies of dW,
+// rounds = ceil(out_tiles * s / slots).  The smallest s with the least modelled time wins.
+static int choose_splits(int64_t k_tiles, int64_t out_tiles, int slots, double tile_us, int64_t n_w,
+                         int64_t* tiles_per_split) {
+  const double fixed_us = 15.0, partial_us_per_split = (double)n_w * 8.0 / 4.0e6;  // 8 bytes per element at 4 TB/s
+  int64_t best_s = 1;
+  double best_cost = -1.0;
+  const int64_t s_max = std::min<int64_t>(k_tiles, kMaxSplits);
+  for (int64_t s = 1; s <= s_max; ++s) {
+    const int64_t per = ceil_div(k_tiles, s);
+    const int64_t s_eff = ceil_div(k_tiles, per);
+    const double rounds = (double)ceil_div(out_tiles * s_eff, slots);
+    const double cost = rounds * ((double)per * tile_us + fixed_us) + (s_eff > 1 ? s_eff * partial_us_per_split : 0.0);
+    if (best_cost < 0.0 || cost < best_cost) {
+      best_cost = cost;
+      best_s = s_eff;
+    }
+  }
+  const int64_t per = ceil_div(k_tiles, best_s);
   *tiles_per_split = per;
   return (int)ceil_div(k_tiles, per);
 }
@@ -430,7 +557,6 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
   }
   cp->z = g.KH / cp->khc;
   if (g.OW > 128) return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: output width %d > 128 not implemented", g.OW);
-  cp->p = g.OW <= 64 ? 64 : 128;
   g.lds_step = (g.KH == 1 && g.KW == 1) ? 1 : g.stride;
   g.fill_step = g.stride / g.lds_step;
   // tile shape
@@ -447,23 +573,48 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
   const int tco = 2 * cp->mt * 16, tci = 2 * cp->nt * 16;
   cp->co_tiles = (int)ceil_div(g.Co, tco);
   g.ci_tiles = (int)ceil_div(g.Ci, tci);
-  // R: the largest divisor of OH whose rows fit one K-tile and whose patch fits LDS
-  bool fits = false;
-  for (int r = g.OH; r >= 1 && !fits; --r) {
-    if (g.OH % r != 0 || r * g.OW > cp->p) continue;
-    g.R = r;
-    g.PR = (r - 1) * g.lds_step + cp->khc;
-    g.PW = (g.OW - 1) * g.lds_step + g.KW;
-    g.PS = (g.PR + cp->khc) * g.PW;
-    g.PS += (4 - g.PS % 32 + 32) % 32;  // per-channel stride = 4 (mod 32) floats: spreads channels over LDS banks
-    cp->lds_bytes = ((size_t)tco * (cp->p + 4) + (size_t)tci * g.PS) * sizeof(float);
-    fits = cp->lds_bytes <= kMaxLds;
+  // K-tile: P contraction positions = R whole output rows of one image (R divides OH).  Among the implemented
+  // P, take the one whose rows fill it best and whose two LDS buffers fit; 64 is preferred on a near tie.
+  double best_score = -1.0;
+  const int p_options[3] = {64, 32, 128};
+  for (int n_buf = 2; n_buf >= 1 && best_score < 0.0; --n_buf) {
+    for (int pi = 0; pi < 3; ++pi) {
+      const int p = p_options[pi];
+      for (int r = g.OH; r >= 1; --r) {
+        if (g.OH % r != 0 || r * g.OW > p) continue;
+        const int pr = (r - 1) * g.lds_step + cp->khc;
+        const int pw = (g.OW - 1) * g.lds_step + g.KW;
+        int ps = (pr + cp->khc) * pw;
+        ps += (4 - ps % 32 + 32) % 32;  // per-channel stride = 4 (mod 32) floats: spreads channels over LDS banks
+        const size_t lds = n_buf * ((size_t)tco * (p + 4) + (size_t)tci * ps) * sizeof(float);
+        if (lds > kMaxLds) continue;
+        const double score = (double)(r * g.OW) / p - (p == 64 ? 0.0 : 0.05);
+        if (score > best_score) {
+          best_score = score;
+          cp->p = p;
+          g.R = r;
+          g.PR = pr;
+          g.PW = pw;
+          g.PS = ps;
+          g.n_buf = n_buf;
+          cp->lds_bytes = lds;
+        }
+        break;  // smaller r only lowers the fill of this P
+      }
+    }
   }
-  if (!fits) return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv tile needs %zu bytes of LDS", cp->lds_bytes);
+  if (best_score < 0.0) return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv tile does not fit LDS (OW = %d)", g.OW);
   g.tiles_per_img = g.OH / g.R;
   g.n_ktiles = g.Nb * g.tiles_per_img;
+  g.n_patch = tci * g.PR * g.PW;
+  g.magic_pw = g.PW > 1 ? (uint32_t)(0xffffffffu / (uint32_t)g.PW) + 1u : 0u;
+  g.magic_pr = g.PR > 1 ? (uint32_t)(0xffffffffu / (uint32_t)g.PR) + 1u : 0u;
+  if ((int64_t)g.n_patch * std::max(g.PW, g.PR) >= ((int64_t)1 << 32) || g.n_patch >= (1 << 26))
+    return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv patch too large");
+  g.dy_vec = ((g.R * g.OW) % 4 == 0 && ((int64_t)g.OH * g.OW) % 4 == 0) ? 1 : 0;
   int64_t per;
-  cp->splits = choose_splits(g.n_ktiles, (int64_t)cp->co_tiles * g.ci_tiles * cp->z, &per);
+  const double tile_us = 2.0 * tco * tci * cp->khc * cp->kw_t * cp->p / kFlopsPerCuPerUs;
+  cp->splits = choose_splits(g.n_ktiles, (int64_t)cp->co_tiles * g.ci_tiles * cp->z, kConvSlots, tile_us, g.n_w, &per);
   g.tiles_per_split = (int)per;
   return SURGEON_OK;
 }
@@ -485,7 +636,8 @@ static int plan_linear(const surgeon_layer_desc* d, LinPlan* lp) {
   g.i_tiles = (int)ceil_div(d->K, ti);
   int64_t per;
   const int64_t k_tiles = std::max<int64_t>(1, ceil_div(d->M, lp->tm));
-  lp->splits = choose_splits(k_tiles, (int64_t)lp->o_tiles * g.i_tiles, &per);
+  const double tile_us = 2.0 * to * ti * lp->tm / kFlopsPerCuPerUs;
+  lp->splits = choose_splits(k_tiles, (int64_t)lp->o_tiles * g.i_tiles, kLinSlots, tile_us, g.n_w, &per);
   g.rows_per_split = per * lp->tm;
   return SURGEON_OK;
 }
@@ -537,13 +689,15 @@ static int launch_conv_variant(const ConvPlan& cp, const Packed<InT>& pk, const 
   const int rc = allow_lds(kernel, cp.lds_bytes);
   if (rc != SURGEON_OK) return rc;
   const dim3 grid((unsigned)(cp.co_tiles * cp.g.ci_tiles), (unsigned)cp.splits, (unsigned)cp.z);
-  hipLaunchKernelGGL(kernel, grid, dim3(256), cp.lds_bytes, st, cp.g, pk, (const InT*)dY, out);
+  ProfScope prof(SURGEON_PROF_DW, st);
+  hipLaunchKernelGGL(kernel, grid, dim3(512), cp.lds_bytes, st, cp.g, pk, (const InT*)dY, out);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }
 
 template <typename InT, int KHC, int KW, int MT, int NT>
 static int launch_conv_p(const ConvPlan& cp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
+  if (cp.p == 32) return launch_conv_variant<InT, KHC, KW, MT, NT, 32>(cp, pk, dY, out, st);
   if (cp.p == 64) return launch_conv_variant<InT, KHC, KW, MT, NT, 64>(cp, pk, dY, out, st);
   return launch_conv_variant<InT, KHC, KW, MT, NT, 128>(cp, pk, dY, out, st);
 }
@@ -574,6 +728,7 @@ static int launch_conv(const ConvPlan& cp, const Packed<InT>& pk, const void* dY
 template <typename InT>
 static int launch_linear(const LinPlan& lp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
   const dim3 grid((unsigned)(lp.o_tiles * lp.g.i_tiles), (unsigned)lp.splits);
+  ProfScope prof(SURGEON_PROF_DW, st);
   if (lp.mt == 4)
     hipLaunchKernelGGL((dw_linear_kernel<InT, 4, 4, 32>), grid, dim3(256), 0, st, lp.g, pk, (const InT*)dY, out);
   else
@@ -592,12 +747,15 @@ static int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals
 
   // nothing kept (or no tokens): the gradient is exactly zero
   if (d->k_total == 0 || p.n == 0) {
+    ProfScope prof(SURGEON_PROF_DW_AUX, st);
     const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 4096);
     hipLaunchKernelGGL(fill_zero_f32_kernel, dim3(blocks), dim3(256), 0, st, dW, p.n_w);
     SURGEON_LAUNCH_CHECK();
     return SURGEON_OK;
   }
   // rank table
+  {
+  ProfScope prof(SURGEON_PROF_DW_AUX, st);
   hipLaunchKernelGGL(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
                      block_sum);
   SURGEON_LAUNCH_CHECK();
@@ -606,6 +764,7 @@ static int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals
   hipLaunchKernelGGL(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
                      (const uint32_t*)block_sum, word_rank);
   SURGEON_LAUNCH_CHECK();
+  }
 
   Packed<InT> pk;
   pk.vals = (const InT*)vals;
@@ -617,6 +776,7 @@ static int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals
   if (rc != SURGEON_OK) return rc;
   if (p.splits > 1) {
     const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 8192);
+    ProfScope prof(SURGEON_PROF_DW_AUX, st);
     hipLaunchKernelGGL(dw_reduce_splits_kernel, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w, dW);
     SURGEON_LAUNCH_CHECK();
   }

@@ -117,6 +117,7 @@ extern "C" int surgeon_grad_importance(const float* dW, int64_t n_w, float* G_ou
   hipStream_t st = (hipStream_t)stream;
   const bool vec4 = ((uintptr_t)dW & 15) == 0;
   const int nb = importance_blocks(n_w);
+  ProfScope prof(SURGEON_PROF_IMPORTANCE, st);
   if (nb == 1) {
     if (vec4)
       hipLaunchKernelGGL(sumsq_single_kernel<true>, dim3(1), dim3(kImpBlock), 0, st, dW, n_w, G_out);

@@ -490,6 +490,7 @@ template <int E, typename BitsT>
 static int launch_wave_reg(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx,
                            hipStream_t st) {
   const dim3 grid((unsigned)ceil_div(p.n_groups, 4)), block(256);
+  ProfScope prof(SURGEON_PROF_SELECT_PACK, st);
   if (idx)
     hipLaunchKernelGGL((select_pack_wave_reg_kernel<E, BitsT, true>), grid, block, 0, st, (const BitsT*)A, (BitsT*)vals,
                        mask, idx, p.n_groups, (int)p.g, (int)p.len_last, (int)p.k_full, (int)p.k_last);
@@ -582,8 +583,11 @@ template <typename BitsT>
 static int run_prune_pack(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx, void* ws,
                           hipStream_t st) {
   const int64_t n_words = ceil_div(p.n, 64);
+  const PrunePath path = choose_prune_path(p);
+  if (p.k_total > 0 && path == PATH_WAVE_REG) return run_wave_reg<BitsT>(p, A, vals, mask, idx, st);
+  ProfScope prof(SURGEON_PROF_SELECT_OTHER, st);
   if (p.k_total == 0) return zero_mask(mask, n_words, st);
-  switch (choose_prune_path(p)) {
+  switch (path) {
     case PATH_WAVE_REG:
       return run_wave_reg<BitsT>(p, A, vals, mask, idx, st);
     case PATH_WAVE_MEM: {

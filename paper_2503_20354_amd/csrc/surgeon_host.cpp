@@ -57,9 +57,69 @@ size_t prune_pack_ws_bytes(const GroupPlan& p) {
   return bytes;
 }
 
+// ---- kernel timing aid -------------------------------------------------------------------------
+struct ProfRecord {
+  int kind;
+  hipEvent_t start, stop;
+};
+static bool g_prof_on = false;
+static std::vector<ProfRecord> g_prof;
+
+ProfScope::ProfScope(int kind, hipStream_t stream) : slot_(-1), stream_(stream) {
+  if (!g_prof_on) return;
+  ProfRecord r;
+  r.kind = kind;
+  if (hipEventCreate(&r.start) != hipSuccess) return;
+  if (hipEventCreate(&r.stop) != hipSuccess) {
+    (void)hipEventDestroy(r.start);
+    return;
+  }
+  (void)hipEventRecord(r.start, stream);
+  g_prof.push_back(r);
+  slot_ = (int)g_prof.size() - 1;
+}
+
+ProfScope::~ProfScope() {
+  if (slot_ >= 0) (void)hipEventRecord(g_prof[slot_].stop, stream_);
+}
+
 }  // namespace surgeon
 
 using namespace surgeon;
+
+extern "C" int surgeon_profile_begin(void) {
+  for (auto& r : g_prof) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_prof.clear();
+  g_prof_on = true;
+  return SURGEON_OK;
+}
+
+extern "C" int surgeon_profile_end(int n_classes, double* ms, int64_t* launches) {
+  g_prof_on = false;
+  if (n_classes < 0 || (n_classes > 0 && (!ms || !launches))) return fail(SURGEON_EINVAL, "profile_end: bad arguments");
+  for (int i = 0; i < n_classes; ++i) {
+    ms[i] = 0.0;
+    launches[i] = 0;
+  }
+  int rc = SURGEON_OK;
+  for (auto& r : g_prof) {
+    float t = 0.0f;
+    hipError_t e = hipEventSynchronize(r.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
+    if (e != hipSuccess) rc = fail(SURGEON_EHIP, "profile_end: %s", hipGetErrorString(e));
+    if (e == hipSuccess && r.kind >= 0 && r.kind < n_classes) {
+      ms[r.kind] += (double)t;
+      launches[r.kind] += 1;
+    }
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  g_prof.clear();
+  return rc;
+}
 
 extern "C" {
 
