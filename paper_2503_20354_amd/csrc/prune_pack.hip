@@ -41,23 +41,89 @@ __device__ __forceinline__ uint64_t ballot64(bool p) { return __builtin_amdgcn_b
 __device__ __forceinline__ uint32_t lane_rank(uint64_t b, uint32_t base) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, base));
 }
+// total += popcount(b) on the vector ALU (b is wave-uniform), keeping running totals off the scalar ALU, whose
+// reads of vector-compare results stall the wavefront.  The leading s_nop covers the two wait states gfx940+
+// needs between a vector instruction writing an SGPR and a vector instruction reading it: the compiler cannot
+// see inside inline asm, so it does not insert them itself.
+__device__ __forceinline__ void add_popcount(uint64_t b, uint32_t& total) {
+  asm("s_nop 1\n\tv_bcnt_u32_b32 %0, %1, %0\n\tv_bcnt_u32_b32 %0, %2, %0"
+      : "+v"(total)
+      : "s"((uint32_t)b), "s"((uint32_t)(b >> 32)));
+}
+// the same, and lane J of (lo, hi) receives the two halves of b
+template <int J>
+__device__ __forceinline__ void add_popcount_set_lane(uint64_t b, uint32_t& total, uint32_t& lo, uint32_t& hi) {
+  asm("s_nop 1\n\tv_bcnt_u32_b32 %0, %3, %0\n\tv_bcnt_u32_b32 %0, %4, %0\n\t"
+      "v_writelane_b32 %1, %3, %5\n\tv_writelane_b32 %2, %4, %5"
+      : "+v"(total), "+v"(lo), "+v"(hi)
+      : "s"((uint32_t)b), "s"((uint32_t)(b >> 32)), "n"(J));
+}
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, off, 64));
   return v;
 }
+// sum over the 64 lanes (wave-uniform result): prefix sums inside each row of 16 lanes with DPP shifts,
+// then the four row totals
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);  // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);  // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);  // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);  // row_shr:8
+  return (uint32_t)(__builtin_amdgcn_readlane((int)v, 15) + __builtin_amdgcn_readlane((int)v, 31) +
+                    __builtin_amdgcn_readlane((int)v, 47) + __builtin_amdgcn_readlane((int)v, 63));
+}
 
+// number of slots-times-lanes with rot key >= thr2: per-lane counters on the vector ALU, one wave sum at the end
 template <int E>
 __device__ __forceinline__ int count_ge(const uint32_t (&kr)[E], uint32_t thr2) {
-  int c = 0;
+  uint32_t c = 0;
 #pragma unroll
-  for (int j = 0; j < E; ++j) c += __popcll(ballot64(kr[j] >= thr2));
-  return c;
+  for (int j = 0; j < E; ++j) c += kr[j] >= thr2 ? 1u : 0u;
+  return (int)wave_sum_u32(c);
 }
+
+// stores that drop out-of-range lanes in hardware: lanes that keep nothing pass offset 0xffffffff
+__device__ __forceinline__ void store_or_drop(__amdgpu_buffer_rsrc_t rsrc, uint32_t v, uint32_t byte_off) {
+  __builtin_amdgcn_raw_buffer_store_b32(v, rsrc, byte_off, 0, 0);
+}
+__device__ __forceinline__ void store_or_drop(__amdgpu_buffer_rsrc_t rsrc, uint16_t v, uint32_t byte_off) {
+  __builtin_amdgcn_raw_buffer_store_b16(v, rsrc, byte_off, 0, 0);
+}
+constexpr int kBufferRsrcWord3 = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
 
 // ---------------------------------------------------------------------------------------------------------
 // path 1: one wavefront per group, group in registers
 // ---------------------------------------------------------------------------------------------------------
+template <int J, int E, typename BitsT, bool WITH_IDX, int MODE>
+struct PackSlots {
+  // emits slot J and recurses: MODE 0 = keep everything in range, 1 = keep rot >= thr2, 2 = threshold with ties
+  __device__ static __forceinline__ void run(const uint32_t (&kr)[E], int lane, int len, uint32_t thr2, uint32_t need,
+                                             __amdgpu_buffer_rsrc_t r_vals, __amdgpu_buffer_rsrc_t r_idx, uint32_t& run_v,
+                                             uint32_t& eq_run_v, uint32_t& w_lo, uint32_t& w_hi) {
+    if constexpr (J < E) {
+      bool keep;
+      if constexpr (MODE == 0) {
+        keep = J * 64 + lane < len;
+      } else if constexpr (MODE == 1) {
+        keep = kr[J] >= thr2;
+      } else {
+        const bool gt = kr[J] > (thr2 | 1u);  // thr2 = 2 * threshold key: strictly larger magnitude
+        const bool eq = !gt && kr[J] >= thr2;
+        const uint64_t beq = ballot64(eq);
+        keep = gt || (eq && lane_rank(beq, eq_run_v) < need);
+        add_popcount(beq, eq_run_v);
+      }
+      const uint64_t b = ballot64(keep);
+      const uint32_t pos = lane_rank(b, run_v);
+      store_or_drop(r_vals, Key<BitsT>::unrot(kr[J]), keep ? pos * (uint32_t)sizeof(BitsT) : 0xffffffffu);
+      if constexpr (WITH_IDX) store_or_drop(r_idx, (uint32_t)(J * 64 + lane), keep ? pos * 4u : 0xffffffffu);
+      add_popcount_set_lane<J>(b, run_v, w_lo, w_hi);
+      PackSlots<J + 1, E, BitsT, WITH_IDX, MODE>::run(kr, lane, len, thr2, need, r_vals, r_idx, run_v, eq_run_v, w_lo, w_hi);
+    }
+  }
+};
+
 template <int E, typename BitsT, bool WITH_IDX>
 __global__ __launch_bounds__(256) void select_pack_wave_reg_kernel(const BitsT* __restrict__ A,
                                                                    BitsT* __restrict__ vals,
@@ -74,61 +140,75 @@ __global__ __launch_bounds__(256) void select_pack_wave_reg_kernel(const BitsT* 
   const int64_t gstart = grp * (int64_t)g;
   const BitsT* __restrict__ src = A + gstart;
 
+  // all loads are issued unconditionally (out-of-range slots re-read the group's last element) so that they
+  // are in flight together; padding slots then become magnitude 0 at the highest indices
   uint32_t kr[E];
+  {
+    BitsT raw[E];
 #pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const int pos = j * 64 + lane;
-    kr[j] = pos < len ? Key<BitsT>::rot(src[pos]) : 0u;  // padding: magnitude 0 at the highest indices
+    for (int j = 0; j < E; ++j) raw[j] = src[min(j * 64 + lane, len - 1)];
+#pragma unroll
+    for (int j = 0; j < E; ++j) kr[j] = (j * 64 + lane < len) ? Key<BitsT>::rot(raw[j]) : 0u;
   }
 
-  BitsT* __restrict__ out_vals = vals + grp * (int64_t)k_full;
-  uint32_t* __restrict__ out_idx = WITH_IDX ? idx + grp * (int64_t)k_full : nullptr;
-  uint64_t* __restrict__ out_mask = mask + (gstart >> 6);
-  const int n_words = (len + 63) >> 6;
-  uint64_t my_word = 0;  // lane j ends up holding mask word j of this group
-
-  enum { MODE_ALL, MODE_THRESHOLD, MODE_TIE };
+  enum { MODE_ALL = 0, MODE_THRESHOLD = 1, MODE_TIE = 2 };
   int mode;
-  uint32_t thr2 = 0;          // MODE_THRESHOLD: keep rot >= thr2
-  uint32_t t_key = 0;         // MODE_TIE: threshold magnitude key
-  uint32_t need = 0;          // MODE_TIE: how many elements equal to t_key are kept (lowest index first)
+  uint32_t thr2 = 0;  // MODE_THRESHOLD: keep rot >= thr2; MODE_TIE: 2 * threshold key
+  uint32_t need = 0;  // MODE_TIE: how many elements equal to the threshold key are kept (lowest index first)
 
   if (k >= len) {
     mode = MODE_ALL;
   } else {
-    // invariant: count(key >= lo) >= k (c_lo) and count(key >= hi) < k (c_hi); the k-th largest key is in [lo, hi)
+    // invariant: count(key >= lo) >= k and count(key >= hi) < k, so the k-th largest key is in [lo, hi).
+    // f_lo = count(lo) - k >= 0 and f_hi = count(hi) - k < 0 drive a regula-falsi search on the integer key;
+    // when one end moves twice in a row the other end's weight is halved (Illinois rule), so the bracket
+    // shrinks super-linearly on smooth distributions and at least geometrically on plateaus of ties.
     uint32_t m = 0;
 #pragma unroll
     for (int j = 0; j < E; ++j) m = max(m, kr[j]);
     m = wave_max_u32(m);
     uint32_t lo = 0, hi = (m >> 1) + 1;
-    int c_lo = E * 64, c_hi = 0;
+    float f_lo = (float)(E * 64 - k), f_hi = (float)(-k);
+    int c_hi = 0;
     bool found = false;
-    // first probe: the non-zero count settles post-ReLU groups whose threshold is the tie at zero
-    if (hi > 1) {
+    // first guess: 16 octaves below the largest magnitude (covers the populated range of typical activations)
+    constexpr uint32_t kSixteenOctaves = 16u << (Key<BitsT>::kBits - 8);
+    bool probe_nonzero = true;
+    if (hi > kSixteenOctaves + 1u) {
+      const uint32_t guess = hi - 1u - kSixteenOctaves;
+      const int c = count_ge<E>(kr, guess << 1);
+      if (c == k) {
+        found = true;
+        thr2 = guess << 1;
+      } else if (c > k) {
+        lo = guess;
+        f_lo = (float)(c - k);
+        probe_nonzero = false;
+      } else {
+        hi = guess;
+        c_hi = c;
+        f_hi = (float)(c - k);
+      }
+    }
+    // the non-zero count settles post-ReLU groups whose threshold is the tie at zero in one probe
+    if (!found && probe_nonzero && hi > 1) {
       const int c = count_ge<E>(kr, 2u);
       if (c == k) {
         found = true;
         thr2 = 2u;
       } else if (c > k) {
         lo = 1;
-        c_lo = c;
+        f_lo = (float)(c - k);
       } else {
         hi = 1;
         c_hi = c;
+        f_hi = (float)(c - k);
       }
     }
-    int streak = 0;  // >0: lo moved that many times in a row, <0: hi did
+    int last_side = 0;  // +1: lo moved last, -1: hi moved last
     while (!found && hi - lo > 1) {
       const uint32_t span = hi - lo;
-      uint32_t d;
-      if (streak >= 2 || streak <= -2) {
-        d = span >> 1;  // the other end is stuck: halve instead of interpolating
-        streak = 0;
-      } else {
-        const float f = (float)(c_lo - k) / (float)(c_lo - c_hi);
-        d = (uint32_t)(f * (float)span);
-      }
+      uint32_t d = (uint32_t)(f_lo / (f_lo - f_hi) * (float)span);
       d = min(max(d, 1u), span - 1u);
       const uint32_t mid = lo + d;
       const int c = count_ge<E>(kr, mid << 1);
@@ -137,58 +217,40 @@ __global__ __launch_bounds__(256) void select_pack_wave_reg_kernel(const BitsT* 
         thr2 = mid << 1;
       } else if (c > k) {
         lo = mid;
-        c_lo = c;
-        streak = streak > 0 ? streak + 1 : 1;
+        f_lo = (float)(c - k);
+        if (last_side > 0) f_hi *= 0.5f;
+        last_side = 1;
       } else {
         hi = mid;
         c_hi = c;
-        streak = streak < 0 ? streak - 1 : -1;
+        f_hi = (float)(c - k);
+        if (last_side < 0) f_lo *= 0.5f;
+        last_side = -1;
       }
     }
     if (found) {
       mode = MODE_THRESHOLD;
     } else {
       mode = MODE_TIE;  // hi == lo + 1: more than k keys are >= lo, fewer than k are > lo
-      t_key = lo;
+      thr2 = lo << 1;
       need = (uint32_t)(k - c_hi);
     }
   }
 
-  uint32_t run = 0;  // kept elements in slots before j
-  if (mode == MODE_TIE) {
-    const uint32_t eq_lo = t_key << 1, gt_lo = (t_key << 1) | 1u;
-    uint32_t eq_run = 0;
-#pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const bool gt = kr[j] > gt_lo;
-      const bool eq = !gt && kr[j] >= eq_lo;
-      const uint64_t beq = ballot64(eq);
-      const bool keep = gt || (eq && lane_rank(beq, eq_run) < need);
-      const uint64_t b = ballot64(keep);
-      if (lane == j) my_word = b;
-      if (keep) {
-        const uint32_t pos = lane_rank(b, run);
-        out_vals[pos] = Key<BitsT>::unrot(kr[j]);
-        if (WITH_IDX) out_idx[pos] = (uint32_t)(j * 64 + lane);
-      }
-      run += (uint32_t)__popcll(b);
-      eq_run += (uint32_t)__popcll(beq);
-    }
-  } else {
-#pragma unroll
-    for (int j = 0; j < E; ++j) {
-      const bool keep = mode == MODE_ALL ? (j * 64 + lane < len) : (kr[j] >= thr2);
-      const uint64_t b = ballot64(keep);
-      if (lane == j) my_word = b;
-      if (keep) {
-        const uint32_t pos = lane_rank(b, run);
-        out_vals[pos] = Key<BitsT>::unrot(kr[j]);
-        if (WITH_IDX) out_idx[pos] = (uint32_t)(j * 64 + lane);
-      }
-      run += (uint32_t)__popcll(b);
-    }
-  }
-  if (lane < n_words) out_mask[lane] = my_word;
+  const __amdgpu_buffer_rsrc_t r_vals = __builtin_amdgcn_make_buffer_rsrc(
+      vals + grp * (int64_t)k_full, 0, k * (int)sizeof(BitsT), kBufferRsrcWord3);
+  const __amdgpu_buffer_rsrc_t r_idx = __builtin_amdgcn_make_buffer_rsrc(
+      WITH_IDX ? idx + grp * (int64_t)k_full : (uint32_t*)nullptr, 0, WITH_IDX ? k * 4 : 0, kBufferRsrcWord3);
+  uint32_t run_v = 0, eq_run_v = 0;  // kept / tied elements in earlier slots (same value in every lane)
+  uint32_t w_lo = 0, w_hi = 0;       // lane j ends up holding mask word j of this group
+  if (mode == MODE_TIE)
+    PackSlots<0, E, BitsT, WITH_IDX, 2>::run(kr, lane, len, thr2, need, r_vals, r_idx, run_v, eq_run_v, w_lo, w_hi);
+  else if (mode == MODE_THRESHOLD)
+    PackSlots<0, E, BitsT, WITH_IDX, 1>::run(kr, lane, len, thr2, need, r_vals, r_idx, run_v, eq_run_v, w_lo, w_hi);
+  else
+    PackSlots<0, E, BitsT, WITH_IDX, 0>::run(kr, lane, len, thr2, need, r_vals, r_idx, run_v, eq_run_v, w_lo, w_hi);
+  const int n_words = (len + 63) >> 6;
+  if (lane < n_words) mask[(gstart >> 6) + lane] = ((uint64_t)w_hi << 32) | w_lo;
 }
 
 // ---------------------------------------------------------------------------------------------------------
