@@ -41,47 +41,100 @@ __device__ __forceinline__ uint64_t ballot64(bool p) { return __builtin_amdgcn_b
 __device__ __forceinline__ uint32_t lane_rank(uint64_t b, uint32_t base) {
   return __builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, base));
 }
-// total += popcount(b) on the vector ALU (b is wave-uniform), keeping running totals off the scalar ALU, whose
-// reads of vector-compare results stall the wavefront.  The leading s_nop covers the two wait states gfx940+
-// needs between a vector instruction writing an SGPR and a vector instruction reading it: the compiler cannot
-// see inside inline asm, so it does not insert them itself.
-__device__ __forceinline__ void add_popcount(uint64_t b, uint32_t& total) {
-  asm("s_nop 1\n\tv_bcnt_u32_b32 %0, %1, %0\n\tv_bcnt_u32_b32 %0, %2, %0"
-      : "+v"(total)
-      : "s"((uint32_t)b), "s"((uint32_t)(b >> 32)));
-}
-// the same, and lane J of (lo, hi) receives the two halves of b
-template <int J>
-__device__ __forceinline__ void add_popcount_set_lane(uint64_t b, uint32_t& total, uint32_t& lo, uint32_t& hi) {
-  asm("s_nop 1\n\tv_bcnt_u32_b32 %0, %3, %0\n\tv_bcnt_u32_b32 %0, %4, %0\n\t"
-      "v_writelane_b32 %1, %3, %5\n\tv_writelane_b32 %2, %4, %5"
-      : "+v"(total), "+v"(lo), "+v"(hi)
-      : "s"((uint32_t)b), "s"((uint32_t)(b >> 32)), "n"(J));
-}
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v = max(v, (uint32_t)__shfl_xor((int)v, off, 64));
   return v;
 }
-// sum over the 64 lanes (wave-uniform result): prefix sums inside each row of 16 lanes with DPP shifts,
-// then the four row totals
-__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+// inclusive prefix sum inside each row of 16 lanes (DPP shifts, zero fill)
+__device__ __forceinline__ uint32_t row_incl_scan_u32(uint32_t v) {
   v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);  // row_shr:1
   v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);  // row_shr:2
   v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);  // row_shr:4
   v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);  // row_shr:8
+  return v;
+}
+// sum over the 64 lanes (wave-uniform result)
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+  v = row_incl_scan_u32(v);
   return (uint32_t)(__builtin_amdgcn_readlane((int)v, 15) + __builtin_amdgcn_readlane((int)v, 31) +
                     __builtin_amdgcn_readlane((int)v, 47) + __builtin_amdgcn_readlane((int)v, 63));
 }
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
+  v = row_incl_scan_u32(v);
+  const uint32_t t0 = (uint32_t)__builtin_amdgcn_readlane((int)v, 15), t1 = (uint32_t)__builtin_amdgcn_readlane((int)v, 31),
+                 t2 = (uint32_t)__builtin_amdgcn_readlane((int)v, 47);
+  return v + (lane >= 16 ? t0 : 0u) + (lane >= 32 ? t1 : 0u) + (lane >= 48 ? t2 : 0u);
+}
+__device__ __forceinline__ uint64_t low_bits64(int q) { return q >= 64 ? ~0ull : (q <= 0 ? 0ull : ((1ull << q) - 1ull)); }
 
-// number of slots-times-lanes with rot key >= thr2: per-lane counters on the vector ALU, one wave sum at the end
+// Number of (slot, lane) pairs with rot key >= thr2.  Per-lane counters on the vector ALU, four independent
+// compare -> add-with-carry chains per block so that no instruction waits for its predecessor; each compare
+// result sits in its own SGPR pair and is consumed three instructions later (gfx940+ needs two wait states
+// between a vector write of an SGPR and a vector read of it, which the compiler cannot add inside inline asm).
 template <int E>
 __device__ __forceinline__ int count_ge(const uint32_t (&kr)[E], uint32_t thr2) {
-  uint32_t c = 0;
+  if constexpr (E % 4 == 0) {
+    uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
-  for (int j = 0; j < E; ++j) c += kr[j] >= thr2 ? 1u : 0u;
-  return (int)wave_sum_u32(c);
+    for (int j = 0; j < E; j += 4) {
+      uint64_t s0, s1, s2, s3;
+      asm("v_cmp_ge_u32_e64 %[s0], %[k0], %[t]\n\t"
+          "v_cmp_ge_u32_e64 %[s1], %[k1], %[t]\n\t"
+          "v_cmp_ge_u32_e64 %[s2], %[k2], %[t]\n\t"
+          "v_cmp_ge_u32_e64 %[s3], %[k3], %[t]\n\t"
+          "v_addc_co_u32_e64 %[c0], %[s0], 0, %[c0], %[s0]\n\t"
+          "v_addc_co_u32_e64 %[c1], %[s1], 0, %[c1], %[s1]\n\t"
+          "v_addc_co_u32_e64 %[c2], %[s2], 0, %[c2], %[s2]\n\t"
+          "v_addc_co_u32_e64 %[c3], %[s3], 0, %[c3], %[s3]"
+          : [c0] "+v"(c0), [c1] "+v"(c1), [c2] "+v"(c2), [c3] "+v"(c3), [s0] "=&s"(s0), [s1] "=&s"(s1),
+            [s2] "=&s"(s2), [s3] "=&s"(s3)
+          : [k0] "v"(kr[j]), [k1] "v"(kr[j + 1]), [k2] "v"(kr[j + 2]), [k3] "v"(kr[j + 3]), [t] "v"(thr2));
+    }
+    return (int)wave_sum_u32((c0 + c1) + (c2 + c3));
+  } else {
+    int c = 0;
+#pragma unroll
+    for (int j = 0; j < E; ++j) c += __popcll(ballot64(kr[j] >= thr2));
+    return c;
+  }
 }
+
+// Lane J of (lo, hi) receives the ballot of slot J under the predicate (rot key >= thr), or > thr if STRICT.
+template <int J, int E, bool STRICT>
+struct CollectWords {
+  __device__ static __forceinline__ void run(const uint32_t (&kr)[E], uint32_t thr, uint32_t& lo, uint32_t& hi) {
+    if constexpr (J + 4 <= E) {
+      uint64_t s0, s1, s2, s3;
+      if constexpr (STRICT)
+        asm volatile("v_cmp_gt_u32_e64 %0, %4, %8\n\tv_cmp_gt_u32_e64 %1, %5, %8\n\t"
+                     "v_cmp_gt_u32_e64 %2, %6, %8\n\tv_cmp_gt_u32_e64 %3, %7, %8"
+                     : "=&s"(s0), "=&s"(s1), "=&s"(s2), "=&s"(s3)
+                     : "v"(kr[J]), "v"(kr[J + 1]), "v"(kr[J + 2]), "v"(kr[J + 3]), "v"(thr));
+      else
+        asm volatile("v_cmp_ge_u32_e64 %0, %4, %8\n\tv_cmp_ge_u32_e64 %1, %5, %8\n\t"
+                     "v_cmp_ge_u32_e64 %2, %6, %8\n\tv_cmp_ge_u32_e64 %3, %7, %8"
+                     : "=&s"(s0), "=&s"(s1), "=&s"(s2), "=&s"(s3)
+                     : "v"(kr[J]), "v"(kr[J + 1]), "v"(kr[J + 2]), "v"(kr[J + 3]), "v"(thr));
+      // volatile keeps these in order right behind the compares: each result is read >= 3 instructions after its write
+      asm volatile("v_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+                   : "+v"(lo), "+v"(hi) : "s"((uint32_t)s0), "s"((uint32_t)(s0 >> 32)), "n"(J));
+      asm volatile("v_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+                   : "+v"(lo), "+v"(hi) : "s"((uint32_t)s1), "s"((uint32_t)(s1 >> 32)), "n"(J + 1));
+      asm volatile("v_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+                   : "+v"(lo), "+v"(hi) : "s"((uint32_t)s2), "s"((uint32_t)(s2 >> 32)), "n"(J + 2));
+      asm volatile("v_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+                   : "+v"(lo), "+v"(hi) : "s"((uint32_t)s3), "s"((uint32_t)(s3 >> 32)), "n"(J + 3));
+      CollectWords<J + 4, E, STRICT>::run(kr, thr, lo, hi);
+    } else if constexpr (J < E) {
+      const uint64_t b = ballot64(STRICT ? kr[J] > thr : kr[J] >= thr);
+      asm volatile("s_nop 1\n\tv_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+                   : "+v"(lo), "+v"(hi) : "s"((uint32_t)b), "s"((uint32_t)(b >> 32)), "n"(J));
+      CollectWords<J + 1, E, STRICT>::run(kr, thr, lo, hi);
+    }
+  }
+};
 
 // stores that drop out-of-range lanes in hardware: lanes that keep nothing pass offset 0xffffffff
 __device__ __forceinline__ void store_or_drop(__amdgpu_buffer_rsrc_t rsrc, uint32_t v, uint32_t byte_off) {
@@ -92,38 +145,28 @@ __device__ __forceinline__ void store_or_drop(__amdgpu_buffer_rsrc_t rsrc, uint1
 }
 constexpr int kBufferRsrcWord3 = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
 
-// ---------------------------------------------------------------------------------------------------------
-// path 1: one wavefront per group, group in registers
-// ---------------------------------------------------------------------------------------------------------
-template <int J, int E, typename BitsT, bool WITH_IDX, int MODE>
-struct PackSlots {
-  // emits slot J and recurses: MODE 0 = keep everything in range, 1 = keep rot >= thr2, 2 = threshold with ties
-  __device__ static __forceinline__ void run(const uint32_t (&kr)[E], int lane, int len, uint32_t thr2, uint32_t need,
-                                             __amdgpu_buffer_rsrc_t r_vals, __amdgpu_buffer_rsrc_t r_idx, uint32_t& run_v,
-                                             uint32_t& eq_run_v, uint32_t& w_lo, uint32_t& w_hi) {
+// Emits slot J: lane l stores its element at base(J) + (kept lanes below l) if bit l of keep word J is set.
+// Every slot is independent of the others, so the stores stream at issue rate.
+template <int J, int E, typename BitsT, bool WITH_IDX>
+struct EmitSlots {
+  __device__ static __forceinline__ void run(const uint32_t (&kr)[E], int lane, uint32_t w_lo, uint32_t w_hi, uint32_t base,
+                                             __amdgpu_buffer_rsrc_t r_vals, __amdgpu_buffer_rsrc_t r_idx) {
     if constexpr (J < E) {
-      bool keep;
-      if constexpr (MODE == 0) {
-        keep = J * 64 + lane < len;
-      } else if constexpr (MODE == 1) {
-        keep = kr[J] >= thr2;
-      } else {
-        const bool gt = kr[J] > (thr2 | 1u);  // thr2 = 2 * threshold key: strictly larger magnitude
-        const bool eq = !gt && kr[J] >= thr2;
-        const uint64_t beq = ballot64(eq);
-        keep = gt || (eq && lane_rank(beq, eq_run_v) < need);
-        add_popcount(beq, eq_run_v);
-      }
-      const uint64_t b = ballot64(keep);
-      const uint32_t pos = lane_rank(b, run_v);
+      const uint32_t b_lo = (uint32_t)__builtin_amdgcn_readlane((int)w_lo, J);
+      const uint32_t b_hi = (uint32_t)__builtin_amdgcn_readlane((int)w_hi, J);
+      const uint32_t base_j = (uint32_t)__builtin_amdgcn_readlane((int)base, J);
+      const bool keep = __builtin_amdgcn_inverse_ballot_w64(((uint64_t)b_hi << 32) | b_lo);
+      const uint32_t pos = __builtin_amdgcn_mbcnt_hi(b_hi, __builtin_amdgcn_mbcnt_lo(b_lo, base_j));
       store_or_drop(r_vals, Key<BitsT>::unrot(kr[J]), keep ? pos * (uint32_t)sizeof(BitsT) : 0xffffffffu);
       if constexpr (WITH_IDX) store_or_drop(r_idx, (uint32_t)(J * 64 + lane), keep ? pos * 4u : 0xffffffffu);
-      add_popcount_set_lane<J>(b, run_v, w_lo, w_hi);
-      PackSlots<J + 1, E, BitsT, WITH_IDX, MODE>::run(kr, lane, len, thr2, need, r_vals, r_idx, run_v, eq_run_v, w_lo, w_hi);
+      EmitSlots<J + 1, E, BitsT, WITH_IDX>::run(kr, lane, w_lo, w_hi, base, r_vals, r_idx);
     }
   }
 };
 
+// ---------------------------------------------------------------------------------------------------------
+// path 1: one wavefront per group, group in registers
+// ---------------------------------------------------------------------------------------------------------
 template <int E, typename BitsT, bool WITH_IDX>
 __global__ __launch_bounds__(256) void select_pack_wave_reg_kernel(const BitsT* __restrict__ A,
                                                                    BitsT* __restrict__ vals,
@@ -140,24 +183,27 @@ __global__ __launch_bounds__(256) void select_pack_wave_reg_kernel(const BitsT* 
   const int64_t gstart = grp * (int64_t)g;
   const BitsT* __restrict__ src = A + gstart;
 
-  // all loads are issued unconditionally (out-of-range slots re-read the group's last element) so that they
-  // are in flight together; padding slots then become magnitude 0 at the highest indices
+  // lane l, slot j <-> element 64*j + l.  All loads are issued before the first use.  A short group re-reads
+  // its last element for the missing slots, which then become magnitude 0 at the highest indices.
   uint32_t kr[E];
-  {
-    BitsT raw[E];
+  if (len == E * 64) {
 #pragma unroll
-    for (int j = 0; j < E; ++j) raw[j] = src[min(j * 64 + lane, len - 1)];
+    for (int j = 0; j < E; ++j) kr[j] = (uint32_t)src[j * 64 + lane];
 #pragma unroll
-    for (int j = 0; j < E; ++j) kr[j] = (j * 64 + lane < len) ? Key<BitsT>::rot(raw[j]) : 0u;
+    for (int j = 0; j < E; ++j) kr[j] = Key<BitsT>::rot((BitsT)kr[j]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < E; ++j) kr[j] = (uint32_t)src[min(j * 64 + lane, len - 1)];
+#pragma unroll
+    for (int j = 0; j < E; ++j) kr[j] = (j * 64 + lane < len) ? Key<BitsT>::rot((BitsT)kr[j]) : 0u;
   }
 
-  enum { MODE_ALL = 0, MODE_THRESHOLD = 1, MODE_TIE = 2 };
-  int mode;
-  uint32_t thr2 = 0;  // MODE_THRESHOLD: keep rot >= thr2; MODE_TIE: 2 * threshold key
-  uint32_t need = 0;  // MODE_TIE: how many elements equal to the threshold key are kept (lowest index first)
-
+  // ---- the keep words: lane j of (w_lo, w_hi) = mask word j of this group
+  uint32_t w_lo = 0, w_hi = 0;
   if (k >= len) {
-    mode = MODE_ALL;
+    const uint64_t w = lane < E ? low_bits64(len - 64 * lane) : 0ull;
+    w_lo = (uint32_t)w;
+    w_hi = (uint32_t)(w >> 32);
   } else {
     // invariant: count(key >= lo) >= k and count(key >= hi) < k, so the k-th largest key is in [lo, hi).
     // f_lo = count(lo) - k >= 0 and f_hi = count(hi) - k < 0 drive a regula-falsi search on the integer key;
@@ -171,6 +217,7 @@ __global__ __launch_bounds__(256) void select_pack_wave_reg_kernel(const BitsT* 
     float f_lo = (float)(E * 64 - k), f_hi = (float)(-k);
     int c_hi = 0;
     bool found = false;
+    uint32_t thr2 = 0;
     // first guess: 16 octaves below the largest magnitude (covers the populated range of typical activations)
     constexpr uint32_t kSixteenOctaves = 16u << (Key<BitsT>::kBits - 8);
     bool probe_nonzero = true;
@@ -208,7 +255,7 @@ __global__ __launch_bounds__(256) void select_pack_wave_reg_kernel(const BitsT* 
     int last_side = 0;  // +1: lo moved last, -1: hi moved last
     while (!found && hi - lo > 1) {
       const uint32_t span = hi - lo;
-      uint32_t d = (uint32_t)(f_lo / (f_lo - f_hi) * (float)span);
+      uint32_t d = (uint32_t)(f_lo * __builtin_amdgcn_rcpf(f_lo - f_hi) * (float)span);
       d = min(max(d, 1u), span - 1u);
       const uint32_t mid = lo + d;
       const int c = count_ge<E>(kr, mid << 1);
@@ -229,26 +276,42 @@ __global__ __launch_bounds__(256) void select_pack_wave_reg_kernel(const BitsT* 
       }
     }
     if (found) {
-      mode = MODE_THRESHOLD;
+      CollectWords<0, E, false>::run(kr, thr2, w_lo, w_hi);
     } else {
-      mode = MODE_TIE;  // hi == lo + 1: more than k keys are >= lo, fewer than k are > lo
+      // hi == lo + 1: more than k keys are >= lo, fewer than k are > lo.  Keep everything above the threshold key
+      // and the first `need` elements equal to it in index order.
       thr2 = lo << 1;
-      need = (uint32_t)(k - c_hi);
+      const uint32_t need = (uint32_t)(k - c_hi);
+      uint32_t gt_lo = 0, gt_hi = 0;
+      CollectWords<0, E, false>::run(kr, thr2, w_lo, w_hi);      // >= threshold
+      CollectWords<0, E, true>::run(kr, thr2 | 1u, gt_lo, gt_hi);  // >  threshold (both signs share thr2 | 1)
+      const uint64_t eq = (((uint64_t)w_hi << 32) | w_lo) & ~(((uint64_t)gt_hi << 32) | gt_lo);
+      const uint32_t ce = (uint32_t)__popcll(eq);
+      const uint32_t e_incl = wave_incl_scan_u32(ce, lane), e_base = e_incl - ce;  // tied elements in earlier slots
+      if (e_incl > need) {  // not all of this slot's tied elements are kept
+        uint64_t keep_eq = 0;
+        if (e_base < need) {  // the cut falls inside this slot (at most one lane): its lowest need - e_base tied bits
+          const uint32_t want = need - e_base;
+          int p = 0;
+#pragma unroll
+          for (int step = 32; step >= 1; step >>= 1)
+            if ((uint32_t)__popcll(eq & low_bits64(p + step)) < want) p += step;
+          keep_eq = eq & low_bits64(p + 1);
+        }
+        w_lo = gt_lo | (uint32_t)keep_eq;
+        w_hi = gt_hi | (uint32_t)(keep_eq >> 32);
+      }
     }
   }
 
+  // ---- pack: slot bases from a prefix sum over the lanes holding the words, then independent slot stores
+  const uint32_t kept = (uint32_t)__builtin_popcount(w_lo) + (uint32_t)__builtin_popcount(w_hi);
+  const uint32_t base = wave_incl_scan_u32(kept, lane) - kept;
   const __amdgpu_buffer_rsrc_t r_vals = __builtin_amdgcn_make_buffer_rsrc(
       vals + grp * (int64_t)k_full, 0, k * (int)sizeof(BitsT), kBufferRsrcWord3);
   const __amdgpu_buffer_rsrc_t r_idx = __builtin_amdgcn_make_buffer_rsrc(
       WITH_IDX ? idx + grp * (int64_t)k_full : (uint32_t*)nullptr, 0, WITH_IDX ? k * 4 : 0, kBufferRsrcWord3);
-  uint32_t run_v = 0, eq_run_v = 0;  // kept / tied elements in earlier slots (same value in every lane)
-  uint32_t w_lo = 0, w_hi = 0;       // lane j ends up holding mask word j of this group
-  if (mode == MODE_TIE)
-    PackSlots<0, E, BitsT, WITH_IDX, 2>::run(kr, lane, len, thr2, need, r_vals, r_idx, run_v, eq_run_v, w_lo, w_hi);
-  else if (mode == MODE_THRESHOLD)
-    PackSlots<0, E, BitsT, WITH_IDX, 1>::run(kr, lane, len, thr2, need, r_vals, r_idx, run_v, eq_run_v, w_lo, w_hi);
-  else
-    PackSlots<0, E, BitsT, WITH_IDX, 0>::run(kr, lane, len, thr2, need, r_vals, r_idx, run_v, eq_run_v, w_lo, w_hi);
+  EmitSlots<0, E, BitsT, WITH_IDX>::run(kr, lane, w_lo, w_hi, base, r_vals, r_idx);
   const int n_words = (len + 63) >> 6;
   if (lane < n_words) mask[(gstart >> 6) + lane] = ((uint64_t)w_hi << 32) | w_lo;
 }
