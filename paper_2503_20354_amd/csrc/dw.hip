@@ -134,7 +134,8 @@ struct Packed {
   const InT* __restrict__ vals;
   const uint64_t* __restrict__ mask;
   const uint32_t* __restrict__ word_rank;
-  int64_t k_last;  // k_total - 1: every read of vals is clamped to it
+  int64_t k_last;   // k_total - 1: every read of vals is clamped to it
+  int64_t n_words;  // mask words
 };
 
 template <typename InT>
@@ -165,6 +166,10 @@ struct ConvGeom {
   int n_patch;          // tile_ci * PR * PW: patch elements staged per K-tile
   uint32_t magic_pw, magic_pr;  // ceil(2^32 / PW), ceil(2^32 / PR) (0 when the divisor is 1)
   int dy_vec;           // dY rows of a K-tile start 4-element aligned and hold a multiple of 4 positions
+  int run_mode;         // 1: the patch is staged as runs of 16 consecutive elements with metadata prefetch
+  int Wv;               // input columns of a row that fall inside the patch
+  int runs_per_row, n_runs;
+  uint32_t magic_rpr;   // ceil(2^32 / runs_per_row)
   int n_buf;            // 2: staging overlaps the MFMA work of the previous K-tile; 1: LDS holds one K-tile only
   int64_t n_w;          // Co*Ci*KH*KW
 };
@@ -273,6 +278,106 @@ __device__ __forceinline__ void conv_stage_tile(const ConvGeom& gm, const Packed
   }
 }
 
+// ---- run-based staging: each staging thread un-packs runs of 16 consecutive elements of a patch row --------
+constexpr int kRunLen = 16;
+constexpr int kRunsPerThread = 2;
+
+// Raw loads describing one run of K-tile `tile`: the two mask words its 16 bits may straddle and the rank of the
+// first word.  They are issued one K-tile ahead, so that per K-tile only one memory round trip (the values and
+// dY) sits on the staging wavefronts' critical path.
+struct RunLoad {
+  uint64_t m0, m1;
+  uint32_t r0;
+  int info;  // bit offset in m0 (6 bits) | elements of the run inside the image << 6 (5 bits) | row valid << 11
+};
+
+template <typename InT>
+__device__ __forceinline__ RunLoad conv_run_issue(const ConvGeom& gm, const Packed<InT>& pk, int tile, int q, int ci0,
+                                                  int u0) {
+  const uint32_t row = fast_div((uint32_t)q, gm.magic_rpr), rr = (uint32_t)q - row * gm.runs_per_row;
+  const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
+  const int b = tile / gm.tiles_per_img;
+  const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
+  const int ih = oh0 * gm.stride + u0 - gm.pad + (int)pr, ci = ci0 + (int)c, iw0 = (int)rr * kRunLen;
+  const bool ok = q < gm.n_runs && ci < gm.Ci && ih >= 0 && ih < gm.H;
+  const int64_t e0 = ok ? (((int64_t)b * gm.Ci + ci) * gm.H + ih) * gm.W + iw0 : 0;
+  const int64_t w = e0 >> 6;
+  RunLoad L;
+  L.m0 = pk.mask[w];
+  L.m1 = pk.mask[min(w + 1, pk.n_words - 1)];
+  L.r0 = pk.word_rank[w];
+  L.info = (int)(e0 & 63) | (min(kRunLen, gm.Wv - iw0) << 6) | (ok ? (1 << 11) : 0);
+  return L;
+}
+
+// Stages K-tile `tile` from the run metadata in `cur` (loaded earlier), and replaces `cur` by the metadata of
+// K-tile tile + 1 when prefetch_next is set.  Requires gm.dy_vec and gm.run_mode.
+template <typename InT, int KHC, int MT, int NT, int P>
+__device__ __forceinline__ void conv_stage_runs(const ConvGeom& gm, const Packed<InT>& pk, const InT* __restrict__ dY,
+                                                float* __restrict__ buf, int tile, int ltid, int co0, int ci0, int u0,
+                                                RunLoad (&cur)[kRunsPerThread], bool prefetch_next) {
+  constexpr int TCO = 2 * MT * 16, SY = P + 4, NY = TCO * P / 4 / kConvLoaders;
+  typedef typename Vec4<InT>::type vec_t;
+  float* __restrict__ dYs = buf;
+  float* __restrict__ As = buf + TCO * SY;
+  const int b = tile / gm.tiles_per_img;
+  const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
+  const int valid_pos = gm.R * gm.OW;
+
+  vec_t y[NY];
+#pragma unroll
+  for (int j = 0; j < NY; ++j) {
+    const int q = ltid + kConvLoaders * j;
+    const int c = q / (P / 4), k4 = q % (P / 4);
+    const bool ok = co0 + c < gm.Co && 4 * k4 < valid_pos;
+    const int64_t off = ok ? (((int64_t)b * gm.Co + co0 + c) * gm.OH + oh0) * gm.OW + 4 * k4 : 0;
+    y[j] = *reinterpret_cast<const vec_t*>(dY + off);
+    if (!ok) y[j] = vec_t{0, 0, 0, 0};
+  }
+
+  uint32_t bits[kRunsPerThread];
+  InT raw[kRunsPerThread][kRunLen];
+#pragma unroll
+  for (int r = 0; r < kRunsPerThread; ++r) {
+    const int sh = cur[r].info & 63, nvalid = (cur[r].info >> 6) & 31;
+    const uint64_t window = (cur[r].m0 >> sh) | (sh ? cur[r].m1 << (64 - sh) : 0ull);
+    bits[r] = (cur[r].info >> 11) ? ((uint32_t)window & ((1u << nvalid) - 1u)) : 0u;
+    const int64_t rank = (int64_t)cur[r].r0 + __popcll(cur[r].m0 & ((1ull << sh) - 1ull));
+#pragma unroll
+    for (int t = 0; t < kRunLen; ++t) {
+      int64_t i = rank + __builtin_popcount(bits[r] & ((1u << t) - 1u));
+      i = i > pk.k_last ? pk.k_last : i;
+      raw[r][t] = pk.vals[i];
+    }
+  }
+  if (prefetch_next) {
+#pragma unroll
+    for (int r = 0; r < kRunsPerThread; ++r)
+      cur[r] = conv_run_issue<InT>(gm, pk, tile + 1, ltid + kConvLoaders * r, ci0, u0);
+  }
+#pragma unroll
+  for (int r = 0; r < kRunsPerThread; ++r) {
+    const int q = ltid + kConvLoaders * r;
+    if (q < gm.n_runs) {
+      const uint32_t row = fast_div((uint32_t)q, gm.magic_rpr), rr = (uint32_t)q - row * gm.runs_per_row;
+      const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
+      const int nvalid = min(kRunLen, gm.Wv - (int)rr * kRunLen);
+      float* __restrict__ dst = As + c * gm.PS + pr * gm.PW + rr * kRunLen + gm.pad;
+#pragma unroll
+      for (int t = 0; t < kRunLen; ++t)
+        if (t < nvalid) dst[t] = ((bits[r] >> t) & 1u) ? widen<InT>(raw[r][t]) : 0.0f;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NY; ++j) {
+    const int q = ltid + kConvLoaders * j;
+    const int c = q / (P / 4), k4 = q % (P / 4);
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    f4 v = {widen<InT>(y[j][0]), widen<InT>(y[j][1]), widen<InT>(y[j][2]), widen<InT>(y[j][3])};
+    *reinterpret_cast<f4*>(&dYs[c * SY + 4 * k4]) = v;
+  }
+}
+
 // Workgroup = 8 wavefronts.  Wavefronts 0-3 are the MFMA wavefronts, arranged 2 (co) x 2 (ci), each owning
 // MT x NT MFMA 16x16 tiles for KHC*KW taps.  Wavefronts 4-7 stage the next K-tile into the other LDS buffer
 // while the MFMA wavefronts work on the current one; one barrier per K-tile hands the buffers over.
@@ -300,6 +405,12 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
     const int c = rem / (KHC * PW), x = rem - c * (KHC * PW);
     smem[bsel * buf_floats + TCO * SY + c * PS + gm.PR * PW + x] = 0.0f;
   }
+  if (gm.run_mode) {  // halo columns are never written by the run-based staging: clear both patches once
+    for (int t = tid; t < gm.n_buf * TCI * PS; t += 512) {
+      const int bsel = t / (TCI * PS);
+      smem[bsel * buf_floats + TCO * SY + (t - bsel * (TCI * PS))] = 0.0f;
+    }
+  }
 
   if (wave >= 4) {
     // ------------------------------ staging wavefronts ------------------------------
@@ -309,6 +420,25 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
         conv_stage_tile<InT, KHC, MT, NT, P>(gm, pk, dY, smem, tile, ltid, co0, ci0, u0);
         __syncthreads();  // the tile is staged
         __syncthreads();  // the MFMA wavefronts are done with it
+      }
+      return;
+    }
+    if (gm.run_mode) {
+      RunLoad meta[kRunsPerThread];
+      if (t_begin < t_end) {
+#pragma unroll
+        for (int r = 0; r < kRunsPerThread; ++r)
+          meta[r] = conv_run_issue<InT>(gm, pk, t_begin, ltid + kConvLoaders * r, ci0, u0);
+        __syncthreads();  // the patches are cleared before the first run is written
+        conv_stage_runs<InT, KHC, MT, NT, P>(gm, pk, dY, smem, t_begin, ltid, co0, ci0, u0, meta, t_begin + 1 < t_end);
+      } else {
+        __syncthreads();
+      }
+      for (int tile = t_begin; tile < t_end; ++tile) {
+        __syncthreads();
+        if (tile + 1 < t_end)
+          conv_stage_runs<InT, KHC, MT, NT, P>(gm, pk, dY, smem + ((tile + 1 - t_begin) & 1) * buf_floats, tile + 1, ltid,
+                                               co0, ci0, u0, meta, tile + 2 < t_end);
       }
       return;
     }
@@ -341,6 +471,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
 #pragma unroll
       for (int t = 0; t < TAPS; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+  if (gm.run_mode) __syncthreads();  // pairs with the staging wavefronts' barrier after the patches are cleared
   for (int tile = t_begin; tile < t_end; ++tile) {
     __syncthreads();
     const float* __restrict__ dYs = smem + ((tile - t_begin) & (gm.n_buf - 1)) * buf_floats;
@@ -612,6 +743,11 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
   if ((int64_t)g.n_patch * std::max(g.PW, g.PR) >= ((int64_t)1 << 32) || g.n_patch >= (1 << 26))
     return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv patch too large");
   g.dy_vec = ((g.R * g.OW) % 4 == 0 && ((int64_t)g.OH * g.OW) % 4 == 0) ? 1 : 0;
+  g.Wv = std::min(g.W, g.PW - g.pad);
+  g.runs_per_row = (int)ceil_div(std::max(g.Wv, 1), kRunLen);
+  g.n_runs = tci * g.PR * g.runs_per_row;
+  g.magic_rpr = g.runs_per_row > 1 ? (uint32_t)(0xffffffffu / (uint32_t)g.runs_per_row) + 1u : 0u;
+  g.run_mode = (g.fill_step == 1 && g.n_buf == 2 && g.dy_vec && g.Wv >= 1 && g.n_runs <= kRunsPerThread * kConvLoaders) ? 1 : 0;
   int64_t per;
   const double tile_us = 2.0 * tco * tci * cp->khc * cp->kw_t * cp->p / kFlopsPerCuPerUs;
   cp->splits = choose_splits(g.n_ktiles, (int64_t)cp->co_tiles * g.ci_tiles * cp->z, kConvSlots, tile_us, g.n_w, &per);
@@ -771,6 +907,7 @@ static int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals
   pk.mask = mask;
   pk.word_rank = word_rank;
   pk.k_last = d->k_total - 1;
+  pk.n_words = p.n_words;
   float* out = p.splits > 1 ? part : dW;
   int rc = p.conv ? launch_conv<InT>(p.c, pk, dY, out, st) : launch_linear<InT>(p.l, pk, dY, out, st);
   if (rc != SURGEON_OK) return rc;
@@ -805,7 +942,8 @@ extern "C" int surgeon_dw_from_packed(const surgeon_layer_desc* desc, const void
   if (p.n > 0 && desc->k_total > 0 && (!vals || !mask || !dY)) return fail(SURGEON_EINVAL, "dw_from_packed: null pointer");
   if (p.ws_bytes > 0 && (!ws || ws_bytes < p.ws_bytes))
     return fail(SURGEON_ESIZE, "dw_from_packed: workspace of %zu bytes needed, %zu given", p.ws_bytes, ws_bytes);
-  if (((uintptr_t)ws % 16) || ((uintptr_t)mask % 8) || ((uintptr_t)dW % 4))
+  if (((uintptr_t)ws % 16) || ((uintptr_t)mask % 8) || ((uintptr_t)dW % 4) || ((uintptr_t)dY % 16) ||
+      ((uintptr_t)vals % (desc->dtype == SURGEON_F32 ? 4 : 2)))
     return fail(SURGEON_EINVAL, "dw_from_packed: misaligned pointer");
   hipStream_t st = (hipStream_t)stream;
   if (desc->dtype == SURGEON_F32) return run_dw<float>(p, desc, vals, mask, dY, dW, ws, st);
