@@ -41,8 +41,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--cfg", type=int, default=1, help="workload (default 1 = the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (used under rocprofv3)")
-    ap.add_argument("--traffic-json", default=None, help="JSON file with HBM bytes per launch of the dominant kernel "
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "dw_conv_wrn28_hbm_traffic.txt"),
+                    help="text file whose line starting with '{' holds the HBM bytes per launch of the dominant kernel "
                     "(from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs); reported as roofline.traffic")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain elementwise kernel reading and writing 1 GiB, as the known-size reference "
+                    "for scaling FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -124,6 +128,12 @@ def main():
         backward_half(False, count)
         return ratios
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)  # 1 GiB read + 1 GiB written by one add kernel
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -148,8 +158,10 @@ def main():
     sp_gbps = rate(acct["sp_bytes"], sp_ms) / 1e9
     imp_gbps = rate(acct["imp_bytes"], imp_ms) / 1e9
     traffic = None
-    if args.traffic_json and os.path.exists(args.traffic_json):
-        traffic = json.load(open(args.traffic_json)).get("dw_bytes_per_launch")
+    if cfg == 1 and args.traffic_file and os.path.exists(args.traffic_file):
+        for line in open(args.traffic_file):
+            if line.startswith("{"):
+                traffic = json.loads(line).get("dw_hbm_bytes_per_launch")
     peak = PEAK_MFMA_TFLOPS[dtype]
     out = {
         "metric": METRIC, "value": round(act_bytes_per_step * args.steps / sec / 1e9, 3), "unit": "GB/s",
