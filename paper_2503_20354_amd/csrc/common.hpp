@@ -1,6 +1,7 @@
 // Internal helpers shared by the translation units of libsurgeon (gfx950 only; not part of the C ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <stdint.h>
 #include <stdio.h>
 
@@ -47,6 +48,13 @@ size_t prune_pack_ws_bytes(const GroupPlan& p);
 // selection paths of prune_pack
 enum PrunePath { PATH_WAVE_REG = 0, PATH_WAVE_MEM = 1, PATH_GLOBAL = 2 };
 PrunePath choose_prune_path(const GroupPlan& p);
+
+// bf16 linear weight gradient: un-pack to a dense transient copy, then a dense bf16-MFMA contraction (dw_bf16.hip)
+int launch_unpack_dense(int dtype, const void* vals, const uint64_t* mask, const uint32_t* word_rank, int64_t n,
+                        int64_t k_total, void* dense, hipStream_t st);
+int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,
+                       int64_t rows_per_split, hipStream_t st);
+constexpr int kBf16LinearTile = 128, kBf16LinearTokens = 64;
 
 constexpr int kWaveRegMaxGroup = 4096;  // largest group one wavefront keeps in registers (64 lanes x 64)
 constexpr int kGlobalHistChunk = 4096;  // elements per block in the histogram passes of the global path

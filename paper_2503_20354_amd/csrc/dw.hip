@@ -615,6 +615,7 @@ __global__ void fill_zero_f32_kernel(float* __restrict__ p, int64_t n) {
 constexpr int kConvSlots = 256;    // the conv kernel keeps one 8-wavefront workgroup per compute unit
 constexpr int kLinSlots = 512;     // the linear kernel fits two workgroups per compute unit
 constexpr int kMaxSplits = 256;
+constexpr double kBf16FlopsPerCuPerUs = 9.8e6;  // bf16 MFMA rate of one compute unit (2.5 PFLOP/s / 256)
 constexpr double kFlopsPerCuPerUs = 0.6e6;  // fp32 MFMA rate of one compute unit (157.3 TFLOP/s / 256), per microsecond
 constexpr size_t kMaxLds = 160 * 1024;
 
@@ -629,6 +630,7 @@ struct LinPlan {
   LinGeom g;
   int mt, nt, tm;
   int o_tiles, splits;
+  bool bf16_mfma;  // dense bf16-MFMA path: un-pack to the workspace, then contract
 };
 
 struct DwPlan {
@@ -637,7 +639,7 @@ struct DwPlan {
   LinPlan l;
   int64_t n, n_words, n_rank_blocks, n_w;
   int splits;
-  size_t off_rank, off_blocks, off_part, ws_bytes;
+  size_t off_rank, off_blocks, off_part, off_dense, ws_bytes;
 };
 
 // Splits along the contraction.  Modelled time of a launch with s splits:
@@ -763,6 +765,19 @@ static int plan_linear(const surgeon_layer_desc* d, LinPlan* lp) {
   LinGeom& g = lp->g;
   g.M = d->M; g.K = d->K; g.N = d->N;
   g.n_w = d->N * d->K;
+  lp->bf16_mfma = d->dtype == SURGEON_BF16 && d->N % 8 == 0 && d->K % 8 == 0 && d->M > 0;
+  if (lp->bf16_mfma) {
+    lp->mt = lp->nt = 0;
+    lp->tm = kBf16LinearTokens;
+    lp->o_tiles = (int)ceil_div(d->N, kBf16LinearTile);
+    g.i_tiles = (int)ceil_div(d->K, kBf16LinearTile);
+    int64_t per;
+    const int64_t k_tiles = ceil_div(d->M, lp->tm);
+    const double tile_us = 2.0 * kBf16LinearTile * kBf16LinearTile * lp->tm / (0.35 * kBf16FlopsPerCuPerUs);
+    lp->splits = choose_splits(k_tiles, (int64_t)lp->o_tiles * g.i_tiles, kLinSlots, tile_us, g.n_w, &per);
+    g.rows_per_split = per * lp->tm;
+    return SURGEON_OK;
+  }
   const bool small = d->N <= 64 && d->K <= 64;
   lp->mt = small ? 2 : 4;
   lp->nt = small ? 2 : 4;
@@ -808,6 +823,8 @@ static int plan_dw(const surgeon_layer_desc* d, DwPlan* p) {
   off += align_up((size_t)p->n_rank_blocks * 4, 256);
   p->off_part = off;
   if (p->splits > 1) off += align_up((size_t)p->splits * (size_t)p->n_w * 4, 256);
+  p->off_dense = off;
+  if (!p->conv && p->l.bf16_mfma) off += align_up((size_t)p->n * 2, 256);  // transient dense activation
   p->ws_bytes = off;
   return SURGEON_OK;
 }
@@ -909,7 +926,15 @@ static int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals
   pk.k_last = d->k_total - 1;
   pk.n_words = p.n_words;
   float* out = p.splits > 1 ? part : dW;
-  int rc = p.conv ? launch_conv<InT>(p.c, pk, dY, out, st) : launch_linear<InT>(p.l, pk, dY, out, st);
+  int rc;
+  if (!p.conv && p.l.bf16_mfma) {
+    void* dense = w + p.off_dense;
+    rc = launch_unpack_dense(SURGEON_BF16, vals, mask, word_rank, p.n, d->k_total, dense, st);
+    if (rc == SURGEON_OK)
+      rc = launch_linear_bf16(p.l.g.M, p.l.g.K, p.l.g.N, dense, dY, out, p.l.splits, p.l.g.rows_per_split, st);
+  } else {
+    rc = p.conv ? launch_conv<InT>(p.c, pk, dY, out, st) : launch_linear<InT>(p.l, pk, dY, out, st);
+  }
   if (rc != SURGEON_OK) return rc;
   if (p.splits > 1) {
     const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 8192);

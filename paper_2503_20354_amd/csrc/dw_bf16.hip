@@ -1,0 +1,198 @@
+// bf16 weight gradient of linear layers (Eq. 2, Alg. 1 lines 11-12) on the bf16 matrix cores.
+//
+// At bf16 MFMA rates (16x the fp32 rate) un-packing inside the GEMM's tile loads would cost more vector-ALU time
+// than the contraction itself, so this path does what Alg. 1 line 11 says literally: un-pack the cached activation
+// to a dense, transient bf16 copy in the workspace (an HBM-bound kernel: reads k*2 + n/8 bytes, writes 2n), then
+// run a dense contraction  dW[o][i] = sum_m dY[m][o] * A[m][i]  with v_mfma_f32_32x32x16_bf16, fp32 accumulation.
+//
+// Both operands have the contraction index m (tokens) as their slow index.  The MFMA wants, per lane, 8 consecutive
+// contraction values of one row.  Tiles are staged into LDS exactly as they sit in memory ([token][feature]) and read
+// back with ds_read_b64_tr_b16, gfx950's transposing LDS read: within a block of 16 lanes, lane i receives in element
+// r the value source lane 4r + i/4 pointed at, element i%4.  Pointing source lane s at [token t0 + s/4][feature
+// f0 + 4*(s%4)] therefore gives lane i the 4 consecutive tokens t0..t0+3 of feature f0 + i.
+#include "common.hpp"
+
+namespace surgeon {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------------------------
+// Alg. 1 line 11: dense pruned activation from (vals, mask); 8 elements per thread
+// ---------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void unpack_dense_kernel(const T* __restrict__ vals, const uint64_t* __restrict__ mask,
+                                                           const uint32_t* __restrict__ word_rank, int64_t n,
+                                                           int64_t k_last, T* __restrict__ dense) {
+  const int64_t n8 = (n + 7) >> 3;
+  for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < n8; t += (int64_t)gridDim.x * 256) {
+    const int64_t e0 = t << 3;
+    const int sh = (int)(e0 & 63);
+    const uint64_t word = mask[e0 >> 6];
+    const uint32_t bits = (uint32_t)(word >> sh) & 0xffu;
+    const int64_t rank = (int64_t)word_rank[e0 >> 6] + __popcll(word & ((1ull << sh) - 1ull));
+    T v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      int64_t i = rank + __builtin_popcount(bits & ((1u << j) - 1u));
+      i = i > k_last ? k_last : i;
+      v[j] = vals[i];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (!((bits >> j) & 1u)) v[j] = (T)0;
+    if (e0 + 8 <= n) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dense[e0 + j] = v[j];  // contiguous: merged into 16-byte stores by the compiler
+    } else {
+      for (int j = 0; j < 8 && e0 + j < n; ++j) dense[e0 + j] = v[j];
+    }
+  }
+}
+
+int launch_unpack_dense(int dtype, const void* vals, const uint64_t* mask, const uint32_t* word_rank, int64_t n,
+                        int64_t k_total, void* dense, hipStream_t st) {
+  if (n == 0) return SURGEON_OK;
+  const int blocks = (int)std::min<int64_t>(ceil_div(ceil_div(n, 8), 256), 65536);
+  ProfScope prof(SURGEON_PROF_DW_AUX, st);
+  if (dtype == SURGEON_F32)
+    hipLaunchKernelGGL(unpack_dense_kernel<uint32_t>, dim3(blocks), dim3(256), 0, st, (const uint32_t*)vals, mask, word_rank,
+                       n, k_total - 1, (uint32_t*)dense);
+  else
+    hipLaunchKernelGGL(unpack_dense_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)vals, mask, word_rank,
+                       n, k_total - 1, (uint16_t*)dense);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// dense TN contraction on bf16 MFMA
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kBfTile = 128;               // workgroup tile: 128 out-features x 128 in-features
+constexpr int kBfTokens = 64;              // tokens per K-tile
+constexpr int kBfStride = kBfTile + 16;    // LDS row stride in elements: 288 bytes, 4 consecutive rows hit distinct banks
+
+// one 16-byte chunk (8 bf16) of row `row`, columns col0..col0+7, zero outside the matrix
+__device__ __forceinline__ u32x4 load_chunk(const uint16_t* __restrict__ src, int64_t row, int64_t row_end, int64_t col0,
+                                            int64_t n_cols, int64_t ld) {
+  const bool ok = row < row_end && col0 < n_cols;  // n_cols is a multiple of 8: a chunk is inside or outside as a whole
+  const int64_t off = ok ? row * ld + col0 : 0;
+  u32x4 v = *reinterpret_cast<const u32x4*>(src + off);
+  if (!ok) v = u32x4{0, 0, 0, 0};
+  return v;
+}
+
+// 8 consecutive tokens (t0..t0+7) of feature (f0 + lane%16) as one MFMA operand register set
+__device__ __forceinline__ bf16x8 read_operand(const uint16_t* tile, int t0, int f0, int lane) {
+  const int s = lane & 15;
+  const uint16_t* p = tile + (t0 + (s >> 2)) * kBfStride + f0 + 4 * (s & 3);
+  typedef shortx4 __attribute__((address_space(3))) * lds_ptr;
+  const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p);
+  const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * kBfStride));
+  typedef short shortx8 __attribute__((ext_vector_type(8)));
+  const shortx8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+// Workgroup = 4 wavefronts as 2 (out) x 2 (in); wavefront tile 64 x 64 = 2 x 2 MFMA 32x32 tiles.
+// blockIdx.x = o_tile * i_tiles + i_tile, blockIdx.y = split along the tokens.
+__global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t K, int64_t N, int i_tiles,
+                                                             int64_t rows_per_split, const uint16_t* __restrict__ A,
+                                                             const uint16_t* __restrict__ dY, float* __restrict__ out) {
+  __shared__ __attribute__((aligned(16))) uint16_t Ys[2][kBfTokens * kBfStride];
+  __shared__ __attribute__((aligned(16))) uint16_t As[2][kBfTokens * kBfStride];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t o0 = (int64_t)(blockIdx.x / i_tiles) * kBfTile, i0 = (int64_t)(blockIdx.x % i_tiles) * kBfTile;
+  const int64_t m_begin = (int64_t)blockIdx.y * rows_per_split;
+  const int64_t m_end = min(m_begin + rows_per_split, M);
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.0f;
+
+  // staging: thread t moves chunks t, t+256, t+512, t+768 of each operand tile (64 rows x 16 chunks of 8 elements)
+  u32x4 ry[4], ra[4];
+  auto load_tile = [&](int64_t m0) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = tid + 256 * j, row = c >> 4, col = (c & 15) * 8;
+      ry[j] = load_chunk(dY, m0 + row, m_end, o0 + col, N, N);
+      ra[j] = load_chunk(A, m0 + row, m_end, i0 + col, K, K);
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = tid + 256 * j, row = c >> 4, col = (c & 15) * 8;
+      *reinterpret_cast<u32x4*>(&Ys[buf][row * kBfStride + col]) = ry[j];
+      *reinterpret_cast<u32x4*>(&As[buf][row * kBfStride + col]) = ra[j];
+    }
+  };
+
+  if (m_begin < m_end) {
+    load_tile(m_begin);
+    store_tile(0);
+  }
+  __syncthreads();
+  int buf = 0;
+  for (int64_t m0 = m_begin; m0 < m_end; m0 += kBfTokens) {
+    const bool more = m0 + kBfTokens < m_end;
+    if (more) load_tile(m0 + kBfTokens);  // in flight while the matrix cores work on the current tile
+    const uint16_t* ys = Ys[buf];
+    const uint16_t* as = As[buf];
+    const int blk = lane >> 4;  // 16-lane block: rows 16*(blk&1).., contraction half blk>>1
+#pragma unroll
+    for (int ks = 0; ks < kBfTokens; ks += 16) {
+      const int t0 = ks + 8 * (blk >> 1);
+      bf16x8 a[2], b[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        a[q] = read_operand(ys, t0, wm * 64 + q * 32 + 16 * (blk & 1), lane);
+        b[q] = read_operand(as, t0, wn * 64 + q * 32 + 16 * (blk & 1), lane);
+      }
+#pragma unroll
+      for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) acc[p][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[p], b[q], acc[p][q], 0, 0, 0);
+    }
+    if (more) store_tile(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // 32x32 result tile: lane holds column lane%32 and rows 8*(v/4) + 4*(lane/32) + v%4, v = 0..15
+  float* __restrict__ dst = out + (int64_t)blockIdx.y * N * K;
+  const int col = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int p = 0; p < 2; ++p)
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int64_t i = i0 + wn * 64 + q * 32 + col;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t o = o0 + wm * 64 + p * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+        if (o < N && i < K) dst[o * K + i] = acc[p][q][v];
+      }
+    }
+}
+
+int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,
+                       int64_t rows_per_split, hipStream_t st) {
+  const int i_tiles = (int)ceil_div(K, kBfTile), o_tiles = (int)ceil_div(N, kBfTile);
+  const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
+  ProfScope prof(SURGEON_PROF_DW, st);
+  hipLaunchKernelGGL(dw_linear_bf16_kernel, grid, dim3(256), 0, st, M, K, N, i_tiles, rows_per_split,
+                     (const uint16_t*)A_dense, (const uint16_t*)dY, out);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+}  // namespace surgeon

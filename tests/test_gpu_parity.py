@@ -146,6 +146,15 @@ def test_dw_linear(dtype, M, K, N):
     assert not got.any()  # nothing cached: the gradient is exactly zero
 
 
+@pytest.mark.parametrize("M,K,N", [(130, 136, 264), (1000, 768, 384), (77, 8, 8), (4096, 320, 1280), (257, 1032, 72)])
+def test_dw_linear_bf16_matrix_core_path(M, K, N):
+    """bf16 linears with in/out features that are multiples of 8 take the dense bf16-MFMA path."""
+    for r in (0.5, 0.93):
+        got, ref = run_linear(M, K, N, "bf16", r, seed=3 * M + K)
+        assert rel_l2(got, ref) <= TOL["bf16"]
+        assert rel_l2(got, ref) <= 1e-5  # exact bf16 products, fp32 accumulation: far inside the bar
+
+
 def test_dw_linear_ratio0_is_dense_gradient():
     M, K, N = 200, 256, 192
     A = wl.draw((M, K), "normal", "f32", 11)
