@@ -87,6 +87,7 @@ def main():
         ws_bytes = max(ws_bytes, surgeon.surgeon_dw_ws_bytes(e["desc"]), surgeon.surgeon_grad_importance_ws_bytes(L.n_w),
                        surgeon.surgeon_packed_sizes(L.n, L.group_len, 0.5, dt)[3])
         st.append(e)
+    ws_bytes = max(ws_bytes, surgeon.surgeon_grad_importance_batched_ws_bytes([e["dW"] for e in st]))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     G_dev = torch.zeros(len(layers), dtype=torch.float32, device=dev)
     G_host = torch.zeros(len(layers), dtype=torch.float32).pin_memory()
@@ -103,16 +104,18 @@ def main():
                 acct["sp_bytes"] += L.n * L.elem_bytes + k * L.elem_bytes + 8 * ((L.n + 63) // 64)
                 acct["nnz_flops"] += L.dense_flops * (k / L.n)
 
+    dW_list = [e["dW"] for e in st]
+
     def backward_half(with_importance, count):
         for li in range(len(st) - 1, -1, -1):
             e = st[li]
             surgeon.surgeon_dw_from_packed(e["desc"], e["vals"], e["mask"], e["dY"], e["dW"], ws)
-            if with_importance:
-                surgeon.surgeon_grad_importance(e["dW"], G_dev[li:li + 1], ws)
             if count:
                 acct["dw_flops"] += e["L"].dense_flops
-                if with_importance:
-                    acct["imp_bytes"] += 4 * e["L"].n_w
+        if with_importance:  # Eq. 4 for every layer in one call, once all weight gradients of the pass exist
+            surgeon.surgeon_grad_importance_batched(dW_list, G_dev, ws)
+            if count:
+                acct["imp_bytes"] += 4 * sum(e["L"].n_w for e in st)
 
     def step(count=False):
         # extra forward-backward at a static ratio to obtain the layer importances (Alg. 1 line 2)

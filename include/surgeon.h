@@ -138,6 +138,19 @@ int surgeon_grad_importance(const float* dW, int64_t n_w, float* G_out,
                             void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Eq. 4 for l layers in one call (one pair of launches per 64 layers instead of one per layer: the layers of a
+ * network are small, so per-layer launches are latency-bound).  dW and n_w are HOST arrays of l device pointers /
+ * element counts; G_out is a DEVICE array of l floats, G_out[i] for layer i.  Same arithmetic as
+ * surgeon_grad_importance (fp64 accumulation, fixed order, deterministic); the two entry points agree to
+ * fp32 rounding but not necessarily bit for bit, because partial sums are grouped differently.
+ * ws/ws_bytes as reported by surgeon_grad_importance_batched_ws_bytes (host only).  Consecutive batches of a call
+ * reuse the workspace in stream order.
+ */
+size_t surgeon_grad_importance_batched_ws_bytes(const int64_t* n_w, int l);
+int surgeon_grad_importance_batched(const float* const* dW, const int64_t* n_w, int l, float* G_out,
+                                    void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Kernel timing aid for benchmarks (not part of the method).  Between surgeon_profile_begin() and
  * surgeon_profile_end() every kernel launch of the library is bracketed by two HIP events recorded on the
  * caller's stream.  surgeon_profile_end() waits for the recorded events and returns, per kernel class,

@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     surgeon_dw_from_packed,
     surgeon_dw_ws_bytes,
     surgeon_grad_importance,
+    surgeon_grad_importance_batched,
+    surgeon_grad_importance_batched_ws_bytes,
     surgeon_grad_importance_ws_bytes,
     surgeon_keep_count,
     surgeon_last_error,

@@ -64,6 +64,10 @@ def load_library():
     L.surgeon_grad_importance_ws_bytes.argtypes = [i64]
     L.surgeon_grad_importance.restype = ci
     L.surgeon_grad_importance.argtypes = [vp, i64, vp, vp, sz, vp]
+    L.surgeon_grad_importance_batched_ws_bytes.restype = sz
+    L.surgeon_grad_importance_batched_ws_bytes.argtypes = [vp, ci]
+    L.surgeon_grad_importance_batched.restype = ci
+    L.surgeon_grad_importance_batched.argtypes = [vp, vp, ci, vp, vp, sz, vp]
     L.surgeon_profile_begin.restype = ci
     L.surgeon_profile_begin.argtypes = []
     L.surgeon_profile_end.restype = ci
@@ -169,6 +173,33 @@ def surgeon_grad_importance(dW, G_out, ws=None):
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(load_library().surgeon_grad_importance(_ptr(dW), dW.numel(), _ptr(G_out), _ptr(ws), ws_bytes,
                                                   _stream(dW.device)))
+
+
+def _batched_args(dWs):
+    l = len(dWs)
+    ptrs = (ctypes.c_void_p * l)(*[t.data_ptr() for t in dWs])
+    sizes = (ctypes.c_int64 * l)(*[t.numel() for t in dWs])
+    return l, ptrs, sizes
+
+
+def surgeon_grad_importance_batched_ws_bytes(dWs) -> int:
+    l, _, sizes = _batched_args(dWs)
+    return int(load_library().surgeon_grad_importance_batched_ws_bytes(sizes, l))
+
+
+def surgeon_grad_importance_batched(dWs, G_out, ws):
+    """Eq. 4 for a list of per-layer dW tensors in one call; G_out: float32 device tensor of len(dWs)."""
+    for t in dWs:
+        _dev(t, "dW")
+        if t.dtype != torch.float32:
+            raise TypeError("dW is float32")
+    _dev(G_out, "G_out")
+    if G_out.numel() < len(dWs):
+        raise ValueError("G_out is too short")
+    l, ptrs, sizes = _batched_args(dWs)
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(load_library().surgeon_grad_importance_batched(ptrs, sizes, l, _ptr(G_out), _ptr(ws), ws_bytes,
+                                                          _stream(G_out.device)))
 
 
 PROF_CLASSES = ("select_pack", "dw", "importance", "dw_aux", "select_other")

@@ -2,6 +2,8 @@
 //
 // One pass over dW with 16-byte loads; squares are accumulated in fp64 (full-rate on CDNA) so the result
 // does not depend on n_w's size; partial sums are combined in a fixed order, so the result is reproducible.
+#include <algorithm>
+
 #include "common.hpp"
 
 namespace surgeon {
@@ -96,6 +98,66 @@ static int importance_blocks(int64_t n_w) {
   return (int)b;
 }
 
+// ---- all layers in one launch --------------------------------------------------------------------------
+constexpr int kImpBatch = 64;           // layers per launch (their descriptors travel as kernel arguments)
+constexpr int kImpChunk = 16384;        // elements per workgroup
+
+struct ImpBatch {
+  const float* ptr[kImpBatch];
+  int64_t n[kImpBatch];
+  int first_block[kImpBatch + 1];  // workgroups [first_block[i], first_block[i+1]) belong to layer i
+  int layers;
+};
+
+template <bool VEC4>
+__global__ __launch_bounds__(kImpBlock) void sumsq_batched_partial_kernel(ImpBatch bt, double* __restrict__ partial) {
+  __shared__ double lds[kImpBlock / 64];
+  int layer = 0;
+  while (layer + 1 < bt.layers && (int)blockIdx.x >= bt.first_block[layer + 1]) ++layer;
+  const float* __restrict__ x = bt.ptr[layer];
+  const int64_t begin = (int64_t)((int)blockIdx.x - bt.first_block[layer]) * kImpChunk;
+  const int64_t end = min(begin + kImpChunk, bt.n[layer]);
+  double acc0 = 0.0, acc1 = 0.0;
+  if (VEC4) {
+    // begin is a multiple of 4 and x is 16-byte aligned: whole float4s, then the tail
+    const f32x4* x4 = reinterpret_cast<const f32x4*>(x + begin);
+    const int64_t n4 = (end - begin) >> 2;
+    // a full chunk is 16 float4 per thread: all of them are in flight before the first is consumed
+    constexpr int kInFlight = kImpChunk / 4 / kImpBlock;
+    f32x4 v[kInFlight];
+#pragma unroll
+    for (int q = 0; q < kInFlight; ++q) {
+      const int64_t i = threadIdx.x + (int64_t)q * kImpBlock;
+      v[q] = __builtin_nontemporal_load(&x4[i < n4 ? i : 0]);  // unconditional: loads must not serialise
+      if (i >= n4) v[q] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int q = 0; q < kInFlight; q += 2) {
+      acc0 += (double)v[q].x * v[q].x + (double)v[q].y * v[q].y + (double)v[q].z * v[q].z + (double)v[q].w * v[q].w;
+      acc1 += (double)v[q + 1].x * v[q + 1].x + (double)v[q + 1].y * v[q + 1].y + (double)v[q + 1].z * v[q + 1].z +
+              (double)v[q + 1].w * v[q + 1].w;
+    }
+    for (int64_t j = begin + (n4 << 2) + threadIdx.x; j < end; j += kImpBlock) acc0 += (double)x[j] * x[j];
+  } else {
+    for (int64_t j = begin + threadIdx.x; j < end; j += kImpBlock) acc0 += (double)x[j] * x[j];
+  }
+  const double total = block_sum(acc0 + acc1, lds);
+  if (threadIdx.x == 0) partial[blockIdx.x] = total;
+}
+
+// one workgroup per layer: adds that layer's partials in index order and finishes Eq. 4
+__global__ __launch_bounds__(kImpBlock) void sumsq_batched_final_kernel(ImpBatch bt, const double* __restrict__ partial,
+                                                                        float* __restrict__ out) {
+  __shared__ double lds[kImpBlock / 64];
+  const int layer = blockIdx.x;
+  double acc = 0.0;
+  for (int i = bt.first_block[layer] + threadIdx.x; i < bt.first_block[layer + 1]; i += kImpBlock) acc += partial[i];
+  const double total = block_sum(acc, lds);
+  if (threadIdx.x == 0) out[layer] = bt.n[layer] > 0 ? (float)sqrt(total / (double)bt.n[layer]) : 0.0f;
+}
+
+static int64_t batched_blocks(int64_t n_w) { return n_w > 0 ? ceil_div(n_w, kImpChunk) : 0; }
+
 }  // namespace surgeon
 
 using namespace surgeon;
@@ -134,5 +196,59 @@ extern "C" int surgeon_grad_importance(const float* dW, int64_t n_w, float* G_ou
   SURGEON_LAUNCH_CHECK();
   hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(kImpBlock), 0, st, (const double*)partial, nb, n_w, G_out);
   SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+extern "C" size_t surgeon_grad_importance_batched_ws_bytes(const int64_t* n_w, int l) {
+  if (!n_w || l < 1) return 0;
+  int64_t most = 0;
+  for (int i0 = 0; i0 < l; i0 += kImpBatch) {
+    int64_t blocks = 0;
+    for (int i = i0; i < l && i < i0 + kImpBatch; ++i) blocks += batched_blocks(n_w[i]);
+    most = std::max(most, blocks);
+  }
+  return align_up((size_t)std::max<int64_t>(most, 1) * sizeof(double), 256);
+}
+
+extern "C" int surgeon_grad_importance_batched(const float* const* dW, const int64_t* n_w, int l, float* G_out, void* ws,
+                                               size_t ws_bytes, void* stream) {
+  if (!dW || !n_w || !G_out) return fail(SURGEON_EINVAL, "grad_importance_batched: null pointer");
+  if (l < 1) return fail(SURGEON_EINVAL, "grad_importance_batched: l = %d", l);
+  bool vec4 = true;
+  for (int i = 0; i < l; ++i) {
+    if (n_w[i] < 0 || (n_w[i] > 0 && !dW[i])) return fail(SURGEON_EINVAL, "grad_importance_batched: bad layer %d", i);
+    if ((uintptr_t)dW[i] & 3) return fail(SURGEON_EINVAL, "grad_importance_batched: dW[%d] is not 4-byte aligned", i);
+    if ((uintptr_t)dW[i] & 15) vec4 = false;
+  }
+  const size_t need = surgeon_grad_importance_batched_ws_bytes(n_w, l);
+  if (!ws || ws_bytes < need)
+    return fail(SURGEON_ESIZE, "grad_importance_batched: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+  hipStream_t st = (hipStream_t)stream;
+  ProfScope prof(SURGEON_PROF_IMPORTANCE, st);
+  for (int i0 = 0; i0 < l; i0 += kImpBatch) {
+    ImpBatch bt;
+    bt.layers = std::min(kImpBatch, l - i0);
+    int64_t blocks = 0;
+    for (int i = 0; i < kImpBatch; ++i) {
+      bt.first_block[i] = (int)blocks;
+      bt.ptr[i] = i < bt.layers ? dW[i0 + i] : nullptr;
+      bt.n[i] = i < bt.layers ? n_w[i0 + i] : 0;
+      blocks += batched_blocks(bt.n[i]);
+      if (blocks > 0x7fffffff) return fail(SURGEON_EUNSUPPORTED, "grad_importance_batched: too many elements");
+    }
+    bt.first_block[kImpBatch] = (int)blocks;
+    for (int i = bt.layers; i <= kImpBatch; ++i) bt.first_block[i] = (int)blocks;
+    double* partial = (double*)ws;
+    if (blocks > 0) {
+      if (vec4)
+        hipLaunchKernelGGL(sumsq_batched_partial_kernel<true>, dim3((unsigned)blocks), dim3(kImpBlock), 0, st, bt, partial);
+      else
+        hipLaunchKernelGGL(sumsq_batched_partial_kernel<false>, dim3((unsigned)blocks), dim3(kImpBlock), 0, st, bt, partial);
+      SURGEON_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(sumsq_batched_final_kernel, dim3((unsigned)bt.layers), dim3(kImpBlock), 0, st, bt,
+                       (const double*)partial, G_out + i0);
+    SURGEON_LAUNCH_CHECK();
+  }
   return SURGEON_OK;
 }

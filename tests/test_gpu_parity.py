@@ -67,6 +67,25 @@ def test_grad_importance(n):
         assert abs(got - ref) <= 1e-5 * ref
 
 
+@pytest.mark.parametrize("n_layers", [1, 3, 28, 70, 266])
+def test_grad_importance_batched(n_layers):
+    """One call for all layers (also more than 64, which takes several launches) against the oracle per layer."""
+    rng = np.random.default_rng(n_layers)
+    sizes = [int(s) for s in rng.choice([0, 1, 7, 432, 4096, 16384, 16385, 51200, 230400, 1_000_003], n_layers)]
+    sizes[0] = 1_000_003
+    layers = [wl.draw((s,), "normal", "f32", 1000 + i) * (1.0 + i % 5) for i, s in enumerate(sizes)]
+    dev_layers = [x.to(DEV) for x in layers]
+    if n_layers >= 3:
+        dev_layers[2] = torch.cat([torch.zeros(1, device=DEV), dev_layers[2]])[1:]  # one pointer only 4-byte aligned
+    G = torch.full((n_layers,), -1.0, device=DEV)
+    ws = torch.empty(surgeon.surgeon_grad_importance_batched_ws_bytes(dev_layers), dtype=torch.uint8, device=DEV)
+    surgeon.surgeon_grad_importance_batched(dev_layers, G, ws)
+    got = G.cpu().numpy()
+    for i, x in enumerate(layers):
+        ref = oracle.grad_importance(x.numpy())
+        assert abs(got[i] - ref) <= 1e-5 * max(ref, 1e-30), (i, sizes[i])
+
+
 def test_grad_importance_closed_forms():
     c = torch.full((123457,), -2.5, device=DEV)
     assert surgeon.grad_importance(c).item() == pytest.approx(2.5, rel=1e-6)
