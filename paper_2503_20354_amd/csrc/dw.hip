@@ -15,12 +15,26 @@
 // kernel adds the splits in index order (no floating-point atomics: results are reproducible bit for bit).
 // Inputs in bf16 are widened to fp32 while staging (exact), so all products and sums are fp32 MFMA.
 #include <algorithm>
+#include <type_traits>
 
 #include "common.hpp"
 
 namespace surgeon {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx4_a4 __attribute__((ext_vector_type(4), aligned(4)));  // LDS vector read at 4-byte alignment
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// the high halves (= the bf16 values) of 8 floats that hold exactly widened bf16 numbers, as one MFMA operand
+__device__ __forceinline__ bf16x8 pack_bf16x8(floatx4 lo, floatx4 hi) {
+  u32x4 d;
+  d[0] = __builtin_amdgcn_perm(__float_as_uint(lo[1]), __float_as_uint(lo[0]), 0x07060302u);
+  d[1] = __builtin_amdgcn_perm(__float_as_uint(lo[3]), __float_as_uint(lo[2]), 0x07060302u);
+  d[2] = __builtin_amdgcn_perm(__float_as_uint(hi[1]), __float_as_uint(hi[0]), 0x07060302u);
+  d[3] = __builtin_amdgcn_perm(__float_as_uint(hi[3]), __float_as_uint(hi[2]), 0x07060302u);
+  return __builtin_bit_cast(bf16x8, d);
+}
 
 template <typename InT>
 __device__ __forceinline__ float widen(InT v);
@@ -166,6 +180,7 @@ struct ConvGeom {
   int n_patch;          // tile_ci * PR * PW: patch elements staged per K-tile
   uint32_t magic_pw, magic_pr;  // ceil(2^32 / PW), ceil(2^32 / PR) (0 when the divisor is 1)
   int dy_vec;           // dY rows of a K-tile start 4-element aligned and hold a multiple of 4 positions
+  int bf16_mfma;        // 1: bf16 inputs go through v_mfma_f32_16x16x32_bf16 (stride-1 LDS patch, OW % 8 == 0)
   int run_mode;         // 1: the patch is staged as runs of 16 consecutive elements with metadata prefetch
   int Wv;               // input columns of a row that fall inside the patch
   int runs_per_row, n_runs;
@@ -382,7 +397,7 @@ __device__ __forceinline__ void conv_stage_runs(const ConvGeom& gm, const Packed
 // MT x NT MFMA 16x16 tiles for KHC*KW taps.  Wavefronts 4-7 stage the next K-tile into the other LDS buffer
 // while the MFMA wavefronts work on the current one; one barrier per K-tile hands the buffers over.
 // blockIdx.y = split along the contraction, blockIdx.z = first filter row handled (u0 = z * KHC).
-template <typename InT, int KHC, int KW, int MT, int NT, int P>
+template <typename InT, bool BF, int KHC, int KW, int MT, int NT, int P>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_kernel(ConvGeom gm, Packed<InT> pk,
                                                                                       const InT* __restrict__ dY,
                                                                                       float* __restrict__ out) {
@@ -400,9 +415,10 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
 
   // KHC rows of zeros after every channel's patch in both buffers (written once): contraction positions past
   // R*OW point there, and their dY is zero as well
-  for (int t = tid; t < gm.n_buf * TCI * KHC * PW; t += 512) {
-    const int bsel = t / (TCI * KHC * PW), rem = t - bsel * (TCI * KHC * PW);
-    const int c = rem / (KHC * PW), x = rem - c * (KHC * PW);
+  const int zero_len = KHC * PW + 8;  // 8 more floats: the bf16 path reads 8 consecutive positions per lane
+  for (int t = tid; t < gm.n_buf * TCI * zero_len; t += 512) {
+    const int bsel = t / (TCI * zero_len), rem = t - bsel * (TCI * zero_len);
+    const int c = rem / zero_len, x = rem - c * zero_len;
     smem[bsel * buf_floats + TCO * SY + c * PS + gm.PR * PW + x] = 0.0f;
   }
   if (gm.run_mode) {  // halo columns are never written by the run-based staging: clear both patches once
@@ -463,6 +479,17 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
     const int r = k / gm.OW, ow = k - r * gm.OW;
     aoff[s] = (r < gm.R) ? (r * gm.lds_step) * PW + ow * gm.lds_step : gm.PR * PW;
   }
+  // bf16 matrix-core path: each lane feeds 8 consecutive positions (32*s + 8*kk ...), which never straddle an
+  // output row because OW is a multiple of 8 there
+  static_assert(!BF || std::is_same<InT, uint16_t>::value, "the bf16 matrix-core loop needs bf16 inputs");
+  constexpr int STEPS_B = BF ? P / 32 : 1;
+  int aoff_b[STEPS_B];
+#pragma unroll
+  for (int s = 0; s < STEPS_B; ++s) {
+    const int k = 32 * s + 8 * kk;
+    const int r = k / gm.OW, ow = k - r * gm.OW;
+    aoff_b[s] = (r < gm.R) ? r * PW + ow : gm.PR * PW;
+  }
   floatx4 acc[MT][NT][TAPS];
 #pragma unroll
   for (int a = 0; a < MT; ++a)
@@ -478,6 +505,33 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
     const float* __restrict__ As = dYs + TCO * SY;
     const float* __restrict__ a_base = dYs + (wm * MT * 16 + i16) * SY + kk;
     const float* __restrict__ b_base = As + (wn * NT * 16 + i16) * PS;
+    if constexpr (BF) {
+      const float* __restrict__ ya = dYs + (wm * MT * 16 + i16) * SY + 8 * kk;
+#pragma unroll
+      for (int s = 0; s < STEPS_B; ++s) {
+        bf16x8 av[MT];
+#pragma unroll
+        for (int a = 0; a < MT; ++a) {
+          const float* y = ya + a * 16 * SY + 32 * s;
+          av[a] = pack_bf16x8(*reinterpret_cast<const floatx4*>(y), *reinterpret_cast<const floatx4*>(y + 4));
+        }
+#pragma unroll
+        for (int du = 0; du < KHC; ++du) {
+#pragma unroll
+          for (int v = 0; v < KW; ++v) {
+#pragma unroll
+            for (int bn = 0; bn < NT; ++bn) {
+              const float* q = b_base + bn * 16 * PS + aoff_b[s] + du * PW + v;
+              const bf16x8 bv = pack_bf16x8(*reinterpret_cast<const floatx4_a4*>(q), *reinterpret_cast<const floatx4_a4*>(q + 4));
+#pragma unroll
+              for (int a = 0; a < MT; ++a)
+                acc[a][bn][du * KW + v] =
+                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[a], bv, acc[a][bn][du * KW + v], 0, 0, 0);
+            }
+          }
+        }
+      }
+    } else {
     // taps are shifted reads of the same patch
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
@@ -497,6 +551,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
           }
         }
       }
+    }
     }
     if (gm.n_buf == 1) __syncthreads();
   }
@@ -717,7 +772,7 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
         if (g.OH % r != 0 || r * g.OW > p) continue;
         const int pr = (r - 1) * g.lds_step + cp->khc;
         const int pw = (g.OW - 1) * g.lds_step + g.KW;
-        int ps = (pr + cp->khc) * pw;
+        int ps = (pr + cp->khc) * pw + 8;
         ps += (4 - ps % 32 + 32) % 32;  // per-channel stride = 4 (mod 32) floats: spreads channels over LDS banks
         const size_t lds = n_buf * ((size_t)tco * (p + 4) + (size_t)tci * ps) * sizeof(float);
         if (lds > kMaxLds) continue;
@@ -745,6 +800,7 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
   if ((int64_t)g.n_patch * std::max(g.PW, g.PR) >= ((int64_t)1 << 32) || g.n_patch >= (1 << 26))
     return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv patch too large");
   g.dy_vec = ((g.R * g.OW) % 4 == 0 && ((int64_t)g.OH * g.OW) % 4 == 0) ? 1 : 0;
+  g.bf16_mfma = (d->dtype == SURGEON_BF16 && g.lds_step == 1 && g.OW % 8 == 0) ? 1 : 0;
   g.Wv = std::min(g.W, g.PW - g.pad);
   g.runs_per_row = (int)ceil_div(std::max(g.Wv, 1), kRunLen);
   g.n_runs = tci * g.PR * g.runs_per_row;
@@ -836,9 +892,9 @@ static int allow_lds(K kernel, size_t bytes) {
   return SURGEON_OK;
 }
 
-template <typename InT, int KHC, int KW, int MT, int NT, int P>
+template <typename InT, bool BF, int KHC, int KW, int MT, int NT, int P>
 static int launch_conv_variant(const ConvPlan& cp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
-  auto kernel = dw_conv_kernel<InT, KHC, KW, MT, NT, P>;
+  auto kernel = dw_conv_kernel<InT, BF, KHC, KW, MT, NT, P>;
   const int rc = allow_lds(kernel, cp.lds_bytes);
   if (rc != SURGEON_OK) return rc;
   const dim3 grid((unsigned)(cp.co_tiles * cp.g.ci_tiles), (unsigned)cp.splits, (unsigned)cp.z);
@@ -850,9 +906,16 @@ static int launch_conv_variant(const ConvPlan& cp, const Packed<InT>& pk, const 
 
 template <typename InT, int KHC, int KW, int MT, int NT>
 static int launch_conv_p(const ConvPlan& cp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
-  if (cp.p == 32) return launch_conv_variant<InT, KHC, KW, MT, NT, 32>(cp, pk, dY, out, st);
-  if (cp.p == 64) return launch_conv_variant<InT, KHC, KW, MT, NT, 64>(cp, pk, dY, out, st);
-  return launch_conv_variant<InT, KHC, KW, MT, NT, 128>(cp, pk, dY, out, st);
+  if constexpr (std::is_same<InT, uint16_t>::value) {
+    if (cp.g.bf16_mfma) {
+      if (cp.p == 32) return launch_conv_variant<InT, true, KHC, KW, MT, NT, 32>(cp, pk, dY, out, st);
+      if (cp.p == 64) return launch_conv_variant<InT, true, KHC, KW, MT, NT, 64>(cp, pk, dY, out, st);
+      return launch_conv_variant<InT, true, KHC, KW, MT, NT, 128>(cp, pk, dY, out, st);
+    }
+  }
+  if (cp.p == 32) return launch_conv_variant<InT, false, KHC, KW, MT, NT, 32>(cp, pk, dY, out, st);
+  if (cp.p == 64) return launch_conv_variant<InT, false, KHC, KW, MT, NT, 64>(cp, pk, dY, out, st);
+  return launch_conv_variant<InT, false, KHC, KW, MT, NT, 128>(cp, pk, dY, out, st);
 }
 
 template <typename InT>
