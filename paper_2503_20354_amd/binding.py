@@ -15,7 +15,7 @@ import torch
 F32, BF16 = 0, 1
 _STATUS = {0: "SURGEON_OK", 1: "SURGEON_EINVAL", 2: "SURGEON_ESIZE", 3: "SURGEON_EUNSUPPORTED", 4: "SURGEON_EHIP"}
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libsurgeon.so")
+_LIB_PATH = os.environ.get("SURGEON_LIBRARY", os.path.join(_HERE, "libsurgeon.so"))  # override: another build of the same ABI
 _lib = None
 
 

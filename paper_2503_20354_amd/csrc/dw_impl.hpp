@@ -1,0 +1,1016 @@
+#pragma once
+// Weight gradient from the packed activation (Alg. 1 lines 11-12, Eq. 2): dW = dY^T . A_pruned.
+//
+// The dense pruned activation is never written to memory: every workgroup rebuilds the tile it needs from
+// (vals, mask) straight into LDS -- element e is vals[rank(e)] if bit e of the mask is set, else 0, where
+// rank(e) = (set bits before e) comes from a per-64-element prefix table built by a small pre-pass over the
+// mask -- and feeds MFMA from there.  This is the only dense contraction of the path, hence the only MFMA user.
+//
+//   conv2d : implicit GEMM with the output positions (b, oh, ow) as the contraction dimension.  A workgroup
+//            owns a [co x ci] tile for ALL taps (u, v) of the filter (or one filter row for large filters): a
+//            K-tile is R output rows of one image; its dY rows and the matching input patch (with halo) sit in
+//            LDS, and the taps are just shifted LDS reads of the same patch, so every un-packed activation
+//            element is reused kh*kw*tile_co times.
+//   linear : dW[o][i] = sum_m dY[m][o] * A[m][i]; K-tiles of TM tokens.
+// Long contractions are split over workgroups; each split writes its partial tile to the workspace and a last
+// kernel adds the splits in index order (no floating-point atomics: results are reproducible bit for bit).
+// Inputs in bf16 are widened to fp32 while staging (exact), so all products and sums are fp32 MFMA.
+#include <algorithm>
+#include <type_traits>
+
+#include "common.hpp"
+
+namespace surgeon {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx4_a4 __attribute__((ext_vector_type(4), aligned(4)));  // LDS vector read at 4-byte alignment
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// the high halves (= the bf16 values) of 8 floats that hold exactly widened bf16 numbers, as one MFMA operand
+__device__ __forceinline__ bf16x8 pack_bf16x8(floatx4 lo, floatx4 hi) {
+  u32x4 d;
+  d[0] = __builtin_amdgcn_perm(__float_as_uint(lo[1]), __float_as_uint(lo[0]), 0x07060302u);
+  d[1] = __builtin_amdgcn_perm(__float_as_uint(lo[3]), __float_as_uint(lo[2]), 0x07060302u);
+  d[2] = __builtin_amdgcn_perm(__float_as_uint(hi[1]), __float_as_uint(hi[0]), 0x07060302u);
+  d[3] = __builtin_amdgcn_perm(__float_as_uint(hi[3]), __float_as_uint(hi[2]), 0x07060302u);
+  return __builtin_bit_cast(bf16x8, d);
+}
+
+template <typename InT>
+__device__ __forceinline__ float widen(InT v);
+template <>
+__device__ __forceinline__ float widen<float>(float v) {
+  return v;
+}
+template <>
+__device__ __forceinline__ float widen<uint16_t>(uint16_t v) {
+  return __uint_as_float((uint32_t)v << 16);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// rank table: word_rank[w] = number of set mask bits before word w
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kRankBlock = 256;
+constexpr int kRankWordsPerBlock = 1024;  // 4 words per thread
+
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t v, int lane) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t t = (uint32_t)__shfl_up((int)v, off, 64);
+    if (lane >= off) v += t;
+  }
+  return v;
+}
+
+// exclusive prefix of `v` over the 256 threads of the block (and the block total in *total)
+__device__ __forceinline__ uint32_t block_excl_scan_u32(uint32_t v, uint32_t* lds4, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t incl = wave_incl_scan_u32(v, lane);
+  if (lane == 63) lds4[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kRankBlock / 64; ++w) {
+    const uint32_t s = lds4[w];
+    if (w < wave) base += s;
+    tot += s;
+  }
+  *total = tot;
+  return base + incl - v;
+}
+
+static __global__ __launch_bounds__(kRankBlock) void rank_block_sum_kernel(const uint64_t* __restrict__ mask, int64_t n_words,
+                                                                    uint32_t* __restrict__ block_sum) {
+  __shared__ uint32_t lds4[kRankBlock / 64];
+  const int64_t w0 = (int64_t)blockIdx.x * kRankWordsPerBlock + threadIdx.x * 4;
+  uint32_t s = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if (w0 + q < n_words) s += (uint32_t)__popcll(mask[w0 + q]);
+  uint32_t total;
+  block_excl_scan_u32(s, lds4, &total);
+  if (threadIdx.x == 0) block_sum[blockIdx.x] = total;
+}
+
+// single block: in-place exclusive scan of the block sums
+static __global__ __launch_bounds__(1024) void rank_scan_kernel(uint32_t* __restrict__ block_sum, int n_blocks) {
+  __shared__ uint32_t part[1024];
+  const int tid = threadIdx.x;
+  const int per = (n_blocks + 1023) / 1024;
+  const int begin = min(tid * per, n_blocks), end = min(begin + per, n_blocks);
+  uint32_t s = 0;
+  for (int i = begin; i < end; ++i) s += block_sum[i];
+  part[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t acc = 0;
+    for (int t = 0; t < 1024; ++t) {
+      const uint32_t v = part[t];
+      part[t] = acc;
+      acc += v;
+    }
+  }
+  __syncthreads();
+  uint32_t acc = part[tid];
+  for (int i = begin; i < end; ++i) {
+    const uint32_t v = block_sum[i];
+    block_sum[i] = acc;
+    acc += v;
+  }
+}
+
+static __global__ __launch_bounds__(kRankBlock) void rank_write_kernel(const uint64_t* __restrict__ mask, int64_t n_words,
+                                                                const uint32_t* __restrict__ block_base,
+                                                                uint32_t* __restrict__ word_rank) {
+  __shared__ uint32_t lds4[kRankBlock / 64];
+  const int64_t w0 = (int64_t)blockIdx.x * kRankWordsPerBlock + threadIdx.x * 4;
+  uint32_t c[4];
+  uint32_t s = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    c[q] = (w0 + q < n_words) ? (uint32_t)__popcll(mask[w0 + q]) : 0u;
+    s += c[q];
+  }
+  uint32_t total;
+  uint32_t base = block_base[blockIdx.x] + block_excl_scan_u32(s, lds4, &total);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if (w0 + q < n_words) word_rank[w0 + q] = base;
+    base += c[q];
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// un-pack of one element (Alg. 1 line 11)
+// ---------------------------------------------------------------------------------------------------------
+template <typename InT>
+struct Packed {
+  const InT* __restrict__ vals;
+  const uint64_t* __restrict__ mask;
+  const uint32_t* __restrict__ word_rank;
+  int64_t k_last;   // k_total - 1: every read of vals is clamped to it
+  int64_t n_words;  // mask words
+};
+
+template <typename InT>
+__device__ __forceinline__ float unpack_at(const Packed<InT>& p, int64_t e) {
+  const int64_t w = e >> 6;
+  const int bit = (int)(e & 63);
+  const uint64_t word = p.mask[w];
+  if (!((word >> bit) & 1ull)) return 0.0f;
+  int64_t r = (int64_t)p.word_rank[w] + __popcll(word & ((1ull << bit) - 1ull));
+  r = r > p.k_last ? p.k_last : r;
+  return widen<InT>(p.vals[r]);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// conv2d
+// ---------------------------------------------------------------------------------------------------------
+struct ConvGeom {
+  int Nb, Ci, H, W, Co, OH, OW, KH, KW, stride, pad;
+  int R;                // output rows per K-tile (divides OH)
+  int tiles_per_img;    // OH / R
+  int n_ktiles;         // Nb * tiles_per_img
+  int tiles_per_split;  // K-tiles per workgroup along the contraction
+  int PR, PW, PS;       // patch rows / cols kept in LDS per input channel, and the per-channel stride (floats)
+  int lds_step;         // LDS distance between horizontally adjacent output positions (1 for 1x1 filters: only
+                        // the pixels a strided 1x1 filter touches are staged), fill_step = stride / lds_step
+  int fill_step;
+  int ci_tiles;         // output tiles along ci (blockIdx.x = co_tile * ci_tiles + ci_tile)
+  int n_patch;          // tile_ci * PR * PW: patch elements staged per K-tile
+  uint32_t magic_pw, magic_pr;  // ceil(2^32 / PW), ceil(2^32 / PR) (0 when the divisor is 1)
+  int dy_vec;           // dY rows of a K-tile start 4-element aligned and hold a multiple of 4 positions
+  int bf16_mfma;        // 1: bf16 inputs go through v_mfma_f32_16x16x32_bf16 (stride-1 LDS patch, OW % 8 == 0)
+  int run_mode;         // 1: the patch is staged as runs of 16 consecutive elements with metadata prefetch
+  int Wv;               // input columns of a row that fall inside the patch
+  int runs_per_row, n_runs;
+  uint32_t magic_rpr;   // ceil(2^32 / runs_per_row)
+  int n_buf;            // 2: staging overlaps the MFMA work of the previous K-tile; 1: LDS holds one K-tile only
+  int64_t n_w;          // Co*Ci*KH*KW
+};
+
+// n / d for n*d < 2^32 with magic = ceil(2^32 / d); magic == 0 encodes d == 1
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t magic) { return magic ? __umulhi(n, magic) : n; }
+
+template <typename InT>
+struct Vec4;
+template <>
+struct Vec4<float> {
+  typedef float type __attribute__((ext_vector_type(4)));
+};
+template <>
+struct Vec4<uint16_t> {
+  typedef uint16_t type __attribute__((ext_vector_type(4)));
+};
+
+constexpr int kConvLoaders = 256;  // threads of the four staging wavefronts
+constexpr int kConvChunk = 20;     // patch elements a staging thread has in flight at once
+
+// Stages K-tile `tile` (dY rows + un-packed input patch) into one LDS buffer.  Called by the 256 staging
+// threads only.  All loads of a chunk are issued before the first dependent use: per chunk there are two
+// memory round trips (mask word + rank, then the value), not two per element.
+template <typename InT, int KHC, int MT, int NT, int P>
+__device__ __forceinline__ void conv_stage_tile(const ConvGeom& gm, const Packed<InT>& pk, const InT* __restrict__ dY,
+                                                float* __restrict__ buf, int tile, int ltid, int co0, int ci0, int u0) {
+  constexpr int TCO = 2 * MT * 16, SY = P + 4, NY = TCO * P / 4 / kConvLoaders;
+  typedef typename Vec4<InT>::type vec_t;
+  float* __restrict__ dYs = buf;
+  float* __restrict__ As = buf + TCO * SY;
+  const int b = tile / gm.tiles_per_img;
+  const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
+  const int valid_pos = gm.R * gm.OW;
+  const int PW = gm.PW, PS = gm.PS;
+
+  // ---- dY[b, co0.., oh0..oh0+R, :]: R*OW contiguous elements per output channel
+  vec_t y[NY];
+  if (gm.dy_vec) {
+#pragma unroll
+    for (int j = 0; j < NY; ++j) {
+      const int q = ltid + kConvLoaders * j;
+      const int c = q / (P / 4), k4 = q % (P / 4);
+      const bool ok = co0 + c < gm.Co && 4 * k4 < valid_pos;
+      const int64_t off = ok ? (((int64_t)b * gm.Co + co0 + c) * gm.OH + oh0) * gm.OW + 4 * k4 : 0;
+      y[j] = *reinterpret_cast<const vec_t*>(dY + off);
+      if (!ok) y[j] = vec_t{0, 0, 0, 0};
+    }
+  } else {
+    for (int idx = ltid; idx < TCO * P; idx += kConvLoaders) {
+      const int c = idx / P, k = idx - c * P;
+      float v = 0.0f;
+      if (co0 + c < gm.Co && k < valid_pos)
+        v = widen<InT>(dY[(((int64_t)b * gm.Co + co0 + c) * gm.OH + oh0) * gm.OW + k]);
+      dYs[c * SY + k] = v;
+    }
+  }
+
+  // ---- un-packed input patch: PR rows from ih0 and PW columns from -pad, every fill_step-th pixel
+  const int ih0 = oh0 * gm.stride + u0 - gm.pad;
+  for (int base = 0; base < gm.n_patch; base += kConvLoaders * kConvChunk) {
+    uint64_t word[kConvChunk];
+    uint32_t rank0[kConvChunk];
+    int where[kConvChunk];  // LDS offset, or -1 past the end of the patch; bit position in the top 6 bits
+#pragma unroll
+    for (int j = 0; j < kConvChunk; ++j) {
+      const uint32_t idx = (uint32_t)(base + j * kConvLoaders + ltid);
+      const bool in_patch = idx < (uint32_t)gm.n_patch;
+      const uint32_t row = fast_div(idx, gm.magic_pw), col = idx - row * PW;
+      const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
+      const int ci = ci0 + (int)c, ih = ih0 + (int)pr * gm.fill_step, iw = (int)col * gm.fill_step - gm.pad;
+      const bool ok = in_patch && ci < gm.Ci && ih >= 0 && ih < gm.H && iw >= 0 && iw < gm.W;
+      const int64_t e = ok ? (((int64_t)b * gm.Ci + ci) * gm.H + ih) * gm.W + iw : 0;
+      const uint64_t m = pk.mask[e >> 6];
+      rank0[j] = pk.word_rank[e >> 6];
+      word[j] = ok ? m : 0ull;
+      where[j] = in_patch ? (int)((c * PS + pr * PW + col) | ((uint32_t)(e & 63) << 26)) : -1;
+    }
+    InT raw[kConvChunk];
+#pragma unroll
+    for (int j = 0; j < kConvChunk; ++j) {
+      const int bit = (int)((uint32_t)where[j] >> 26);
+      const bool has = (word[j] >> bit) & 1ull;
+      int64_t r = (int64_t)rank0[j] + __popcll(word[j] & ((1ull << bit) - 1ull));
+      r = r > pk.k_last ? pk.k_last : r;
+      raw[j] = pk.vals[has ? r : 0];
+    }
+#pragma unroll
+    for (int j = 0; j < kConvChunk; ++j) {
+      if (where[j] != -1) {
+        const int bit = (int)((uint32_t)where[j] >> 26);
+        const bool has = (word[j] >> bit) & 1ull;
+        As[where[j] & 0x3ffffff] = has ? widen<InT>(raw[j]) : 0.0f;
+      }
+    }
+  }
+  if (gm.dy_vec) {
+#pragma unroll
+    for (int j = 0; j < NY; ++j) {
+      const int q = ltid + kConvLoaders * j;
+      const int c = q / (P / 4), k4 = q % (P / 4);
+      typedef float f4 __attribute__((ext_vector_type(4)));
+      f4 v = {widen<InT>(y[j][0]), widen<InT>(y[j][1]), widen<InT>(y[j][2]), widen<InT>(y[j][3])};
+      *reinterpret_cast<f4*>(&dYs[c * SY + 4 * k4]) = v;
+    }
+  }
+}
+
+// ---- run-based staging: each staging thread un-packs runs of 16 consecutive elements of a patch row --------
+constexpr int kRunLen = 16;
+constexpr int kRunsPerThread = 2;
+
+// Raw loads describing one run of K-tile `tile`: the two mask words its 16 bits may straddle and the rank of the
+// first word.  They are issued one K-tile ahead, so that per K-tile only one memory round trip (the values and
+// dY) sits on the staging wavefronts' critical path.
+struct RunLoad {
+  uint64_t m0, m1;
+  uint32_t r0;
+  int info;  // bit offset in m0 (6 bits) | elements of the run inside the image << 6 (5 bits) | row valid << 11
+};
+
+template <typename InT>
+__device__ __forceinline__ RunLoad conv_run_issue(const ConvGeom& gm, const Packed<InT>& pk, int tile, int q, int ci0,
+                                                  int u0) {
+  const uint32_t row = fast_div((uint32_t)q, gm.magic_rpr), rr = (uint32_t)q - row * gm.runs_per_row;
+  const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
+  const int b = tile / gm.tiles_per_img;
+  const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
+  const int ih = oh0 * gm.stride + u0 - gm.pad + (int)pr, ci = ci0 + (int)c, iw0 = (int)rr * kRunLen;
+  const bool ok = q < gm.n_runs && ci < gm.Ci && ih >= 0 && ih < gm.H;
+  const int64_t e0 = ok ? (((int64_t)b * gm.Ci + ci) * gm.H + ih) * gm.W + iw0 : 0;
+  const int64_t w = e0 >> 6;
+  RunLoad L;
+  L.m0 = pk.mask[w];
+  L.m1 = pk.mask[min(w + 1, pk.n_words - 1)];
+  L.r0 = pk.word_rank[w];
+  L.info = (int)(e0 & 63) | (min(kRunLen, gm.Wv - iw0) << 6) | (ok ? (1 << 11) : 0);
+  return L;
+}
+
+// Stages K-tile `tile` from the run metadata in `cur` (loaded earlier), and replaces `cur` by the metadata of
+// K-tile tile + 1 when prefetch_next is set.  Requires gm.dy_vec and gm.run_mode.
+template <typename InT, int KHC, int MT, int NT, int P>
+__device__ __forceinline__ void conv_stage_runs(const ConvGeom& gm, const Packed<InT>& pk, const InT* __restrict__ dY,
+                                                float* __restrict__ buf, int tile, int ltid, int co0, int ci0, int u0,
+                                                RunLoad (&cur)[kRunsPerThread], bool prefetch_next) {
+  constexpr int TCO = 2 * MT * 16, SY = P + 4, NY = TCO * P / 4 / kConvLoaders;
+  typedef typename Vec4<InT>::type vec_t;
+  float* __restrict__ dYs = buf;
+  float* __restrict__ As = buf + TCO * SY;
+  const int b = tile / gm.tiles_per_img;
+  const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
+  const int valid_pos = gm.R * gm.OW;
+
+  vec_t y[NY];
+#pragma unroll
+  for (int j = 0; j < NY; ++j) {
+    const int q = ltid + kConvLoaders * j;
+    const int c = q / (P / 4), k4 = q % (P / 4);
+    const bool ok = co0 + c < gm.Co && 4 * k4 < valid_pos;
+    const int64_t off = ok ? (((int64_t)b * gm.Co + co0 + c) * gm.OH + oh0) * gm.OW + 4 * k4 : 0;
+    y[j] = *reinterpret_cast<const vec_t*>(dY + off);
+    if (!ok) y[j] = vec_t{0, 0, 0, 0};
+  }
+
+  uint32_t bits[kRunsPerThread];
+  InT raw[kRunsPerThread][kRunLen];
+#pragma unroll
+  for (int r = 0; r < kRunsPerThread; ++r) {
+    if (kConvLoaders * r >= gm.n_runs) continue;  // uniform: no thread has an r-th run in this geometry
+    const int sh = cur[r].info & 63, nvalid = (cur[r].info >> 6) & 31;
+    const uint64_t window = (cur[r].m0 >> sh) | (sh ? cur[r].m1 << (64 - sh) : 0ull);
+    bits[r] = (cur[r].info >> 11) ? ((uint32_t)window & ((1u << nvalid) - 1u)) : 0u;
+    const int64_t rank = (int64_t)cur[r].r0 + __popcll(cur[r].m0 & ((1ull << sh) - 1ull));
+#pragma unroll
+    for (int t = 0; t < kRunLen; ++t) {
+      int64_t i = rank + __builtin_popcount(bits[r] & ((1u << t) - 1u));
+      i = i > pk.k_last ? pk.k_last : i;
+      raw[r][t] = pk.vals[i];
+    }
+  }
+  if (prefetch_next) {
+#pragma unroll
+    for (int r = 0; r < kRunsPerThread; ++r)
+      if (kConvLoaders * r < gm.n_runs) cur[r] = conv_run_issue<InT>(gm, pk, tile + 1, ltid + kConvLoaders * r, ci0, u0);
+  }
+#pragma unroll
+  for (int r = 0; r < kRunsPerThread; ++r) {
+    const int q = ltid + kConvLoaders * r;
+    if (q < gm.n_runs) {
+      const uint32_t row = fast_div((uint32_t)q, gm.magic_rpr), rr = (uint32_t)q - row * gm.runs_per_row;
+      const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
+      const int nvalid = min(kRunLen, gm.Wv - (int)rr * kRunLen);
+      float* __restrict__ dst = As + c * gm.PS + pr * gm.PW + rr * kRunLen + gm.pad;
+#pragma unroll
+      for (int t = 0; t < kRunLen; ++t)
+        if (t < nvalid) dst[t] = ((bits[r] >> t) & 1u) ? widen<InT>(raw[r][t]) : 0.0f;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NY; ++j) {
+    const int q = ltid + kConvLoaders * j;
+    const int c = q / (P / 4), k4 = q % (P / 4);
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    f4 v = {widen<InT>(y[j][0]), widen<InT>(y[j][1]), widen<InT>(y[j][2]), widen<InT>(y[j][3])};
+    *reinterpret_cast<f4*>(&dYs[c * SY + 4 * k4]) = v;
+  }
+}
+
+// Workgroup = 8 wavefronts.  Wavefronts 0-3 are the MFMA wavefronts, arranged 2 (co) x 2 (ci), each owning
+// MT x NT MFMA 16x16 tiles for KHC*KW taps.  Wavefronts 4-7 stage the next K-tile into the other LDS buffer
+// while the MFMA wavefronts work on the current one; one barrier per K-tile hands the buffers over.
+// blockIdx.y = split along the contraction, blockIdx.z = first filter row handled (u0 = z * KHC).
+template <typename InT, bool BF, int KHC, int KW, int MT, int NT, int P>
+__global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_kernel(ConvGeom gm, Packed<InT> pk,
+                                                                                      const InT* __restrict__ dY,
+                                                                                      float* __restrict__ out) {
+  constexpr int TCO = 2 * MT * 16, TCI = 2 * NT * 16, SY = P + 4, TAPS = KHC * KW, STEPS = P / 4;
+  extern __shared__ float smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int co_tile = blockIdx.x / gm.ci_tiles, ci_tile = blockIdx.x % gm.ci_tiles;
+  const int co0 = co_tile * TCO, ci0 = ci_tile * TCI;
+  const int u0 = blockIdx.z * KHC;
+  const int PW = gm.PW, PS = gm.PS;
+  const int buf_floats = TCO * SY + TCI * PS;
+  const int t_begin = blockIdx.y * gm.tiles_per_split;
+  const int t_end = min(t_begin + gm.tiles_per_split, gm.n_ktiles);
+
+  // KHC rows of zeros after every channel's patch in both buffers (written once): contraction positions past
+  // R*OW point there, and their dY is zero as well
+  const int zero_len = KHC * PW + 8;  // 8 more floats: the bf16 path reads 8 consecutive positions per lane
+  for (int t = tid; t < gm.n_buf * TCI * zero_len; t += 512) {
+    const int bsel = t / (TCI * zero_len), rem = t - bsel * (TCI * zero_len);
+    const int c = rem / zero_len, x = rem - c * zero_len;
+    smem[bsel * buf_floats + TCO * SY + c * PS + gm.PR * PW + x] = 0.0f;
+  }
+  if (gm.run_mode) {  // halo columns are never written by the run-based staging: clear both patches once
+    for (int t = tid; t < gm.n_buf * TCI * PS; t += 512) {
+      const int bsel = t / (TCI * PS);
+      smem[bsel * buf_floats + TCO * SY + (t - bsel * (TCI * PS))] = 0.0f;
+    }
+  }
+
+  if (wave >= 4) {
+    // ------------------------------ staging wavefronts ------------------------------
+    // their few vector instructions win arbitration against the MFMA wavefront sharing the SIMD, so that a tile is
+    // staged promptly instead of in whatever issue slots the matrix pipeline leaves free
+    __builtin_amdgcn_s_setprio(3);
+    const int ltid = tid - 256;
+    if (gm.n_buf == 1) {
+      for (int tile = t_begin; tile < t_end; ++tile) {
+        conv_stage_tile<InT, KHC, MT, NT, P>(gm, pk, dY, smem, tile, ltid, co0, ci0, u0);
+        __syncthreads();  // the tile is staged
+        __syncthreads();  // the MFMA wavefronts are done with it
+      }
+      return;
+    }
+    if (gm.run_mode) {
+      RunLoad meta[kRunsPerThread];
+      if (t_begin < t_end) {
+#pragma unroll
+        for (int r = 0; r < kRunsPerThread; ++r)
+          if (kConvLoaders * r < gm.n_runs) meta[r] = conv_run_issue<InT>(gm, pk, t_begin, ltid + kConvLoaders * r, ci0, u0);
+        __syncthreads();  // the patches are cleared before the first run is written
+        conv_stage_runs<InT, KHC, MT, NT, P>(gm, pk, dY, smem, t_begin, ltid, co0, ci0, u0, meta, t_begin + 1 < t_end);
+      } else {
+        __syncthreads();
+      }
+      for (int tile = t_begin; tile < t_end; ++tile) {
+        __syncthreads();
+        if (tile + 1 < t_end)
+          conv_stage_runs<InT, KHC, MT, NT, P>(gm, pk, dY, smem + ((tile + 1 - t_begin) & 1) * buf_floats, tile + 1, ltid,
+                                               co0, ci0, u0, meta, tile + 2 < t_end);
+      }
+      return;
+    }
+    if (t_begin < t_end) conv_stage_tile<InT, KHC, MT, NT, P>(gm, pk, dY, smem, t_begin, ltid, co0, ci0, u0);
+    for (int tile = t_begin; tile < t_end; ++tile) {
+      __syncthreads();  // buffer (tile - t_begin) & 1 is complete; the other one is no longer being read
+      if (tile + 1 < t_end)
+        conv_stage_tile<InT, KHC, MT, NT, P>(gm, pk, dY, smem + ((tile + 1 - t_begin) & 1) * buf_floats, tile + 1, ltid,
+                                             co0, ci0, u0);
+    }
+    return;
+  }
+
+  // ------------------------------ MFMA wavefronts ------------------------------
+  const int wm = wave >> 1, wn = wave & 1;
+  const int i16 = lane & 15, kk = lane >> 4;
+  // LDS offset of the input pixel under tap (0,0) for each contraction position this lane feeds
+  int aoff[STEPS];
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+    const int k = 4 * s + kk;
+    const int r = k / gm.OW, ow = k - r * gm.OW;
+    aoff[s] = (r < gm.R) ? (r * gm.lds_step) * PW + ow * gm.lds_step : gm.PR * PW;
+  }
+  // bf16 matrix-core path: each lane feeds 8 consecutive positions (32*s + 8*kk ...), which never straddle an
+  // output row because OW is a multiple of 8 there
+  static_assert(!BF || std::is_same<InT, uint16_t>::value, "the bf16 matrix-core loop needs bf16 inputs");
+  constexpr int STEPS_B = BF ? P / 32 : 1;
+  int aoff_b[STEPS_B];
+#pragma unroll
+  for (int s = 0; s < STEPS_B; ++s) {
+    const int k = 32 * s + 8 * kk;
+    const int r = k / gm.OW, ow = k - r * gm.OW;
+    aoff_b[s] = (r < gm.R) ? r * PW + ow : gm.PR * PW;
+  }
+  floatx4 acc[MT][NT][TAPS];
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int b = 0; b < NT; ++b)
+#pragma unroll
+      for (int t = 0; t < TAPS; ++t) acc[a][b][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  if (gm.run_mode) __syncthreads();  // pairs with the staging wavefronts' barrier after the patches are cleared
+  for (int tile = t_begin; tile < t_end; ++tile) {
+    __syncthreads();
+    const float* __restrict__ dYs = smem + ((tile - t_begin) & (gm.n_buf - 1)) * buf_floats;
+    const float* __restrict__ As = dYs + TCO * SY;
+    const float* __restrict__ a_base = dYs + (wm * MT * 16 + i16) * SY + kk;
+    const float* __restrict__ b_base = As + (wn * NT * 16 + i16) * PS;
+    if constexpr (BF) {
+      const float* __restrict__ ya = dYs + (wm * MT * 16 + i16) * SY + 8 * kk;
+#pragma unroll
+      for (int s = 0; s < STEPS_B; ++s) {
+        bf16x8 av[MT];
+#pragma unroll
+        for (int a = 0; a < MT; ++a) {
+          const float* y = ya + a * 16 * SY + 32 * s;
+          av[a] = pack_bf16x8(*reinterpret_cast<const floatx4*>(y), *reinterpret_cast<const floatx4*>(y + 4));
+        }
+#pragma unroll
+        for (int du = 0; du < KHC; ++du) {
+#pragma unroll
+          for (int v = 0; v < KW; ++v) {
+#pragma unroll
+            for (int bn = 0; bn < NT; ++bn) {
+              const float* q = b_base + bn * 16 * PS + aoff_b[s] + du * PW + v;
+              const bf16x8 bv = pack_bf16x8(*reinterpret_cast<const floatx4_a4*>(q), *reinterpret_cast<const floatx4_a4*>(q + 4));
+#pragma unroll
+              for (int a = 0; a < MT; ++a)
+                acc[a][bn][du * KW + v] =
+                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[a], bv, acc[a][bn][du * KW + v], 0, 0, 0);
+            }
+          }
+        }
+      }
+    } else {
+    // taps are shifted reads of the same patch
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      float av[MT];
+#pragma unroll
+      for (int a = 0; a < MT; ++a) av[a] = a_base[a * 16 * SY + 4 * s];
+#pragma unroll
+      for (int du = 0; du < KHC; ++du) {
+#pragma unroll
+        for (int v = 0; v < KW; ++v) {
+#pragma unroll
+          for (int bn = 0; bn < NT; ++bn) {
+            const float bv = b_base[bn * 16 * PS + aoff[s] + du * PW + v];
+#pragma unroll
+            for (int a = 0; a < MT; ++a)
+              acc[a][bn][du * KW + v] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv, acc[a][bn][du * KW + v], 0, 0, 0);
+          }
+        }
+      }
+    }
+    }
+    if (gm.n_buf == 1) __syncthreads();
+  }
+
+  // ---- write this split's partial tile: lane holds rows 4*kk..4*kk+3 (co), column i16 (ci) of each 16x16 tile
+  float* __restrict__ dst = out + (int64_t)blockIdx.y * gm.n_w;
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+#pragma unroll
+    for (int bn = 0; bn < NT; ++bn) {
+      const int ci = ci0 + wn * NT * 16 + bn * 16 + i16;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int co = co0 + wm * MT * 16 + a * 16 + 4 * kk + r;
+        if (co < gm.Co && ci < gm.Ci) {
+          const int64_t base = (((int64_t)co * gm.Ci + ci) * gm.KH + u0) * gm.KW;
+#pragma unroll
+          for (int du = 0; du < KHC; ++du)
+#pragma unroll
+            for (int v = 0; v < KW; ++v) dst[base + du * gm.KW + v] = acc[a][bn][du * KW + v][r];
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// linear
+// ---------------------------------------------------------------------------------------------------------
+struct LinGeom {
+  int64_t M, K, N;
+  int i_tiles;            // tiles along in-features (blockIdx.x = o_tile * i_tiles + i_tile)
+  int64_t rows_per_split; // tokens per workgroup along the contraction (multiple of TM)
+  int64_t n_w;
+};
+
+template <typename InT, int MT, int NT, int TM>
+__global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) void dw_linear_kernel(LinGeom gm, Packed<InT> pk,
+                                                                                        const InT* __restrict__ dY,
+                                                                                        float* __restrict__ out) {
+  constexpr int TO = 2 * MT * 16, TI = 2 * NT * 16, SO = TO + 16, SI = TI + 16, STEPS = TM / 4;
+  __shared__ float dYs[TM * SO];
+  __shared__ float As[TM * SI];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int i16 = lane & 15, kk = lane >> 4;
+  const int o_tile = blockIdx.x / gm.i_tiles, i_tile = blockIdx.x % gm.i_tiles;
+  const int64_t o0 = (int64_t)o_tile * TO, i0 = (int64_t)i_tile * TI;
+
+  floatx4 acc[MT][NT];
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int b = 0; b < NT; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const int64_t m_begin = (int64_t)blockIdx.y * gm.rows_per_split;
+  const int64_t m_end = min(m_begin + gm.rows_per_split, gm.M);
+  for (int64_t m0 = m_begin; m0 < m_end; m0 += TM) {
+    __syncthreads();
+    for (int idx = tid; idx < TM * TO; idx += 256) {
+      const int r = idx / TO, c = idx - r * TO;
+      const int64_t m = m0 + r, o = o0 + c;
+      dYs[r * SO + c] = (m < m_end && o < gm.N) ? widen<InT>(dY[m * gm.N + o]) : 0.0f;
+    }
+    for (int idx = tid; idx < TM * TI; idx += 256) {
+      const int r = idx / TI, c = idx - r * TI;
+      const int64_t m = m0 + r, i = i0 + c;
+      As[r * SI + c] = (m < m_end && i < gm.K) ? unpack_at<InT>(pk, m * gm.K + i) : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      float av[MT], bv[NT];
+#pragma unroll
+      for (int a = 0; a < MT; ++a) av[a] = dYs[(4 * s + kk) * SO + wm * MT * 16 + a * 16 + i16];
+#pragma unroll
+      for (int b = 0; b < NT; ++b) bv[b] = As[(4 * s + kk) * SI + wn * NT * 16 + b * 16 + i16];
+#pragma unroll
+      for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int b = 0; b < NT; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+    }
+  }
+  float* __restrict__ dst = out + (int64_t)blockIdx.y * gm.n_w;
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int b = 0; b < NT; ++b) {
+      const int64_t i = i0 + wn * NT * 16 + b * 16 + i16;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int64_t o = o0 + wm * MT * 16 + a * 16 + 4 * kk + r;
+        if (o < gm.N && i < gm.K) dst[o * gm.K + i] = acc[a][b][r];
+      }
+    }
+}
+
+// adds the split partials in index order
+static __global__ __launch_bounds__(256) void dw_reduce_splits_kernel(const float* __restrict__ part, int n_splits, int64_t n_w,
+                                                               float* __restrict__ dW) {
+  for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n_w; x += (int64_t)gridDim.x * 256) {
+    float s = part[x];
+    for (int k = 1; k < n_splits; ++k) s += part[(int64_t)k * n_w + x];
+    dW[x] = s;
+  }
+}
+
+static __global__ void fill_zero_f32_kernel(float* __restrict__ p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// host planning
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kConvSlots = 256;    // the conv kernel keeps one 8-wavefront workgroup per compute unit
+constexpr int kLinSlots = 512;     // the linear kernel fits two workgroups per compute unit
+constexpr int kMaxSplits = 256;
+constexpr double kBf16FlopsPerCuPerUs = 9.8e6;  // bf16 MFMA rate of one compute unit (2.5 PFLOP/s / 256)
+constexpr double kFlopsPerCuPerUs = 0.6e6;  // fp32 MFMA rate of one compute unit (157.3 TFLOP/s / 256), per microsecond
+constexpr size_t kMaxLds = 160 * 1024;
+
+struct ConvPlan {
+  ConvGeom g;
+  int khc, kw_t, mt, nt, p;  // kernel variant
+  int co_tiles, z, splits;
+  size_t lds_bytes;
+};
+
+struct LinPlan {
+  LinGeom g;
+  int mt, nt, tm;
+  int o_tiles, splits;
+  bool bf16_mfma;  // dense bf16-MFMA path: un-pack to the workspace, then contract
+};
+
+struct DwPlan {
+  bool conv;
+  ConvPlan c;
+  LinPlan l;
+  int64_t n, n_words, n_rank_blocks, n_w;
+  int splits;
+  size_t off_rank, off_blocks, off_part, off_dense, ws_bytes;
+};
+
+// Splits along the contraction.  Modelled time of a launch with s splits:
+//   rounds(s) * (tiles_per_split * tile_us + fixed_us)  +  time to write and re-read s partial copies of dW,
+// rounds = ceil(out_tiles * s / slots).  The smallest s with the least modelled time wins.
+static int choose_splits(int64_t k_tiles, int64_t out_tiles, int slots, double tile_us, int64_t n_w,
+                         int64_t* tiles_per_split) {
+  const double fixed_us = 15.0, partial_us_per_split = (double)n_w * 8.0 / 4.0e6;  // 8 bytes per element at 4 TB/s
+  int64_t best_s = 1;
+  double best_cost = -1.0;
+  const int64_t s_max = std::min<int64_t>(k_tiles, kMaxSplits);
+  for (int64_t s = 1; s <= s_max; ++s) {
+    const int64_t per = ceil_div(k_tiles, s);
+    const int64_t s_eff = ceil_div(k_tiles, per);
+    const double rounds = (double)ceil_div(out_tiles * s_eff, slots);
+    const double cost = rounds * ((double)per * tile_us + fixed_us) + (s_eff > 1 ? s_eff * partial_us_per_split : 0.0);
+    if (best_cost < 0.0 || cost < best_cost) {
+      best_cost = cost;
+      best_s = s_eff;
+    }
+  }
+  const int64_t per = ceil_div(k_tiles, best_s);
+  *tiles_per_split = per;
+  return (int)ceil_div(k_tiles, per);
+}
+
+static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
+  if (d->Nb < 1 || d->Ci < 1 || d->H < 1 || d->W < 1 || d->Co < 1 || d->kh < 1 || d->kw < 1 || d->stride < 1 ||
+      d->pad < 0)
+    return fail(SURGEON_EINVAL, "dw_from_packed: bad conv shape");
+  if (d->H + 2 * d->pad < d->kh || d->W + 2 * d->pad < d->kw)
+    return fail(SURGEON_EINVAL, "dw_from_packed: filter larger than the padded input");
+  const int64_t big = (int64_t)1 << 31;
+  if (d->Nb * d->Ci * d->H * d->W > big || d->Nb >= (1 << 24) || d->Co * d->Ci * d->kh * d->kw > big)
+    return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv tensor too large");
+  ConvGeom& g = cp->g;
+  g.Nb = (int)d->Nb; g.Ci = (int)d->Ci; g.H = (int)d->H; g.W = (int)d->W; g.Co = (int)d->Co;
+  g.KH = (int)d->kh; g.KW = (int)d->kw; g.stride = (int)d->stride; g.pad = (int)d->pad;
+  g.OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1;
+  g.OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
+  g.n_w = (int64_t)g.Co * g.Ci * g.KH * g.KW;
+  if (g.KH == 3 && g.KW == 3) {
+    cp->khc = 3; cp->kw_t = 3;
+  } else if (g.KW == 1 || g.KW == 3 || g.KW == 5 || g.KW == 7) {
+    cp->khc = 1; cp->kw_t = g.KW;
+  } else {
+    return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: filter width %d not implemented (1, 3, 5, 7)", g.KW);
+  }
+  cp->z = g.KH / cp->khc;
+  if (g.OW > 128) return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: output width %d > 128 not implemented", g.OW);
+  g.lds_step = (g.KH == 1 && g.KW == 1) ? 1 : g.stride;
+  g.fill_step = g.stride / g.lds_step;
+  // tile shape
+  if (cp->kw_t == 1 && cp->khc == 1) {
+    cp->mt = (g.Co > 64 || g.Ci > 64) ? 4 : 2;  // implemented pairs: (4,4) and (2,2)
+    cp->nt = cp->mt;
+  } else if (cp->khc == 3) {
+    cp->nt = 1;
+    cp->mt = (g.Co % 160 == 0) ? 5 : (g.Co > 64 ? 4 : 2);
+  } else {
+    cp->nt = 1;
+    cp->mt = g.Co > 64 ? 4 : 2;
+  }
+  const int tco = 2 * cp->mt * 16, tci = 2 * cp->nt * 16;
+  cp->co_tiles = (int)ceil_div(g.Co, tco);
+  g.ci_tiles = (int)ceil_div(g.Ci, tci);
+  // K-tile: P contraction positions = R whole output rows of one image (R divides OH).  Among the implemented
+  // P, take the one whose rows fill it best and whose two LDS buffers fit; 64 is preferred on a near tie.
+  double best_score = -1.0;
+  const int p_options[3] = {64, 32, 128};
+  for (int n_buf = 2; n_buf >= 1 && best_score < 0.0; --n_buf) {
+    for (int pi = 0; pi < 3; ++pi) {
+      const int p = p_options[pi];
+      for (int r = g.OH; r >= 1; --r) {
+        if (g.OH % r != 0 || r * g.OW > p) continue;
+        const int pr = (r - 1) * g.lds_step + cp->khc;
+        const int pw = (g.OW - 1) * g.lds_step + g.KW;
+        int ps = (pr + cp->khc) * pw + 8;
+        ps += (4 - ps % 32 + 32) % 32;  // per-channel stride = 4 (mod 32) floats: spreads channels over LDS banks
+        const size_t lds = n_buf * ((size_t)tco * (p + 4) + (size_t)tci * ps) * sizeof(float);
+        if (lds > kMaxLds) continue;
+        const double score = (double)(r * g.OW) / p - (p == 64 ? 0.0 : 0.05);
+        if (score > best_score) {
+          best_score = score;
+          cp->p = p;
+          g.R = r;
+          g.PR = pr;
+          g.PW = pw;
+          g.PS = ps;
+          g.n_buf = n_buf;
+          cp->lds_bytes = lds;
+        }
+        break;  // smaller r only lowers the fill of this P
+      }
+    }
+  }
+  if (best_score < 0.0) return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv tile does not fit LDS (OW = %d)", g.OW);
+  g.tiles_per_img = g.OH / g.R;
+  g.n_ktiles = g.Nb * g.tiles_per_img;
+  g.n_patch = tci * g.PR * g.PW;
+  g.magic_pw = g.PW > 1 ? (uint32_t)(0xffffffffu / (uint32_t)g.PW) + 1u : 0u;
+  g.magic_pr = g.PR > 1 ? (uint32_t)(0xffffffffu / (uint32_t)g.PR) + 1u : 0u;
+  if ((int64_t)g.n_patch * std::max(g.PW, g.PR) >= ((int64_t)1 << 32) || g.n_patch >= (1 << 26))
+    return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv patch too large");
+  g.dy_vec = ((g.R * g.OW) % 4 == 0 && ((int64_t)g.OH * g.OW) % 4 == 0) ? 1 : 0;
+  g.bf16_mfma = (d->dtype == SURGEON_BF16 && g.lds_step == 1 && g.OW % 8 == 0) ? 1 : 0;
+  g.Wv = std::min(g.W, g.PW - g.pad);
+  g.runs_per_row = (int)ceil_div(std::max(g.Wv, 1), kRunLen);
+  g.n_runs = tci * g.PR * g.runs_per_row;
+  g.magic_rpr = g.runs_per_row > 1 ? (uint32_t)(0xffffffffu / (uint32_t)g.runs_per_row) + 1u : 0u;
+  g.run_mode = (g.fill_step == 1 && g.n_buf == 2 && g.dy_vec && g.Wv >= 1 && g.n_runs <= kRunsPerThread * kConvLoaders) ? 1 : 0;
+  int64_t per;
+  const double tile_us = 2.0 * tco * tci * cp->khc * cp->kw_t * cp->p / kFlopsPerCuPerUs;
+  cp->splits = choose_splits(g.n_ktiles, (int64_t)cp->co_tiles * g.ci_tiles * cp->z, kConvSlots, tile_us, g.n_w, &per);
+  g.tiles_per_split = (int)per;
+  return SURGEON_OK;
+}
+
+static int plan_linear(const surgeon_layer_desc* d, LinPlan* lp) {
+  if (d->M < 0 || d->K < 1 || d->N < 1) return fail(SURGEON_EINVAL, "dw_from_packed: bad linear shape");
+  const int64_t big = (int64_t)1 << 31;
+  if (d->M * d->K > big || d->N * d->K > big || d->M * d->N > ((int64_t)1 << 40))
+    return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: linear tensor too large");
+  LinGeom& g = lp->g;
+  g.M = d->M; g.K = d->K; g.N = d->N;
+  g.n_w = d->N * d->K;
+  lp->bf16_mfma = d->dtype == SURGEON_BF16 && d->N % 8 == 0 && d->K % 8 == 0 && d->M > 0;
+  if (lp->bf16_mfma) {
+    lp->mt = lp->nt = 0;
+    lp->tm = kBf16LinearTokens;
+    lp->o_tiles = (int)ceil_div(d->N, kBf16LinearTile);
+    g.i_tiles = (int)ceil_div(d->K, kBf16LinearTile);
+    int64_t per;
+    const int64_t k_tiles = ceil_div(d->M, lp->tm);
+    const double tile_us = 2.0 * kBf16LinearTile * kBf16LinearTile * lp->tm / (0.35 * kBf16FlopsPerCuPerUs);
+    lp->splits = choose_splits(k_tiles, (int64_t)lp->o_tiles * g.i_tiles, kLinSlots, tile_us, g.n_w, &per);
+    g.rows_per_split = per * lp->tm;
+    return SURGEON_OK;
+  }
+  const bool small = d->N <= 64 && d->K <= 64;
+  lp->mt = small ? 2 : 4;
+  lp->nt = small ? 2 : 4;
+  lp->tm = 32;
+  const int to = 2 * lp->mt * 16, ti = 2 * lp->nt * 16;
+  lp->o_tiles = (int)ceil_div(d->N, to);
+  g.i_tiles = (int)ceil_div(d->K, ti);
+  int64_t per;
+  const int64_t k_tiles = std::max<int64_t>(1, ceil_div(d->M, lp->tm));
+  const double tile_us = 2.0 * to * ti * lp->tm / kFlopsPerCuPerUs;
+  lp->splits = choose_splits(k_tiles, (int64_t)lp->o_tiles * g.i_tiles, kLinSlots, tile_us, g.n_w, &per);
+  g.rows_per_split = per * lp->tm;
+  return SURGEON_OK;
+}
+
+static int plan_dw(const surgeon_layer_desc* d, DwPlan* p) {
+  if (!d) return fail(SURGEON_EINVAL, "dw_from_packed: null descriptor");
+  if (d->dtype != SURGEON_F32 && d->dtype != SURGEON_BF16) return fail(SURGEON_EINVAL, "dw_from_packed: bad dtype");
+  if (d->k_total < 0) return fail(SURGEON_EINVAL, "dw_from_packed: k_total < 0");
+  int rc;
+  if (d->kind == SURGEON_CONV2D) {
+    p->conv = true;
+    if ((rc = plan_conv(d, &p->c)) != SURGEON_OK) return rc;
+    p->n = d->Nb * d->Ci * d->H * d->W;
+    p->n_w = p->c.g.n_w;
+    p->splits = p->c.splits;
+  } else if (d->kind == SURGEON_LINEAR) {
+    p->conv = false;
+    if ((rc = plan_linear(d, &p->l)) != SURGEON_OK) return rc;
+    p->n = d->M * d->K;
+    p->n_w = p->l.g.n_w;
+    p->splits = p->l.splits;
+  } else {
+    return fail(SURGEON_EINVAL, "dw_from_packed: bad layer kind %d", d->kind);
+  }
+  if (d->k_total > p->n) return fail(SURGEON_EINVAL, "dw_from_packed: k_total exceeds the activation size");
+  p->n_words = ceil_div(p->n, 64);
+  p->n_rank_blocks = ceil_div(p->n_words, kRankWordsPerBlock);
+  size_t off = 0;
+  p->off_rank = off;
+  off += align_up((size_t)p->n_words * 4, 256);
+  p->off_blocks = off;
+  off += align_up((size_t)p->n_rank_blocks * 4, 256);
+  p->off_part = off;
+  if (p->splits > 1) off += align_up((size_t)p->splits * (size_t)p->n_w * 4, 256);
+  p->off_dense = off;
+  if (!p->conv && p->l.bf16_mfma) off += align_up((size_t)p->n * 2, 256);  // transient dense activation
+  p->ws_bytes = off;
+  return SURGEON_OK;
+}
+
+template <typename K>
+static int allow_lds(K kernel, size_t bytes) {
+  if (bytes > 48 * 1024)
+    SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  return SURGEON_OK;
+}
+
+template <typename InT, bool BF, int KHC, int KW, int MT, int NT, int P>
+static int launch_conv_variant(const ConvPlan& cp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
+  auto kernel = dw_conv_kernel<InT, BF, KHC, KW, MT, NT, P>;
+  const int rc = allow_lds(kernel, cp.lds_bytes);
+  if (rc != SURGEON_OK) return rc;
+  const dim3 grid((unsigned)(cp.co_tiles * cp.g.ci_tiles), (unsigned)cp.splits, (unsigned)cp.z);
+  ProfScope prof(SURGEON_PROF_DW, st);
+  hipLaunchKernelGGL(kernel, grid, dim3(512), cp.lds_bytes, st, cp.g, pk, (const InT*)dY, out);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+template <typename InT, int KHC, int KW, int MT, int NT>
+static int launch_conv_p(const ConvPlan& cp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
+  if constexpr (std::is_same<InT, uint16_t>::value) {
+    if (cp.g.bf16_mfma) {
+      if (cp.p == 32) return launch_conv_variant<InT, true, KHC, KW, MT, NT, 32>(cp, pk, dY, out, st);
+      if (cp.p == 64) return launch_conv_variant<InT, true, KHC, KW, MT, NT, 64>(cp, pk, dY, out, st);
+      return launch_conv_variant<InT, true, KHC, KW, MT, NT, 128>(cp, pk, dY, out, st);
+    }
+  }
+  if (cp.p == 32) return launch_conv_variant<InT, false, KHC, KW, MT, NT, 32>(cp, pk, dY, out, st);
+  if (cp.p == 64) return launch_conv_variant<InT, false, KHC, KW, MT, NT, 64>(cp, pk, dY, out, st);
+  return launch_conv_variant<InT, false, KHC, KW, MT, NT, 128>(cp, pk, dY, out, st);
+}
+
+template <typename InT>
+static int launch_conv(const ConvPlan& cp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
+  if (cp.khc == 3) {
+    if (cp.mt == 5) return launch_conv_p<InT, 3, 3, 5, 1>(cp, pk, dY, out, st);
+    if (cp.mt == 4) return launch_conv_p<InT, 3, 3, 4, 1>(cp, pk, dY, out, st);
+    return launch_conv_p<InT, 3, 3, 2, 1>(cp, pk, dY, out, st);
+  }
+  if (cp.kw_t == 1) {
+    if (cp.mt == 4) return launch_conv_p<InT, 1, 1, 4, 4>(cp, pk, dY, out, st);
+    return launch_conv_p<InT, 1, 1, 2, 2>(cp, pk, dY, out, st);
+  }
+  if (cp.kw_t == 3) {
+    if (cp.mt == 4) return launch_conv_p<InT, 1, 3, 4, 1>(cp, pk, dY, out, st);
+    return launch_conv_p<InT, 1, 3, 2, 1>(cp, pk, dY, out, st);
+  }
+  if (cp.kw_t == 5) {
+    if (cp.mt == 4) return launch_conv_p<InT, 1, 5, 4, 1>(cp, pk, dY, out, st);
+    return launch_conv_p<InT, 1, 5, 2, 1>(cp, pk, dY, out, st);
+  }
+  if (cp.mt == 4) return launch_conv_p<InT, 1, 7, 4, 1>(cp, pk, dY, out, st);
+  return launch_conv_p<InT, 1, 7, 2, 1>(cp, pk, dY, out, st);
+}
+
+template <typename InT>
+static int launch_linear(const LinPlan& lp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
+  const dim3 grid((unsigned)(lp.o_tiles * lp.g.i_tiles), (unsigned)lp.splits);
+  ProfScope prof(SURGEON_PROF_DW, st);
+  if (lp.mt == 4)
+    hipLaunchKernelGGL((dw_linear_kernel<InT, 4, 4, 32>), grid, dim3(256), 0, st, lp.g, pk, (const InT*)dY, out);
+  else
+    hipLaunchKernelGGL((dw_linear_kernel<InT, 2, 2, 32>), grid, dim3(256), 0, st, lp.g, pk, (const InT*)dY, out);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+template <typename InT>
+int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const uint64_t* mask, const void* dY,
+                  float* dW, void* ws, hipStream_t st) {
+  char* w = (char*)ws;
+  uint32_t* word_rank = (uint32_t*)(w + p.off_rank);
+  uint32_t* block_sum = (uint32_t*)(w + p.off_blocks);
+  float* part = (float*)(w + p.off_part);
+
+  // nothing kept (or no tokens): the gradient is exactly zero
+  if (d->k_total == 0 || p.n == 0) {
+    ProfScope prof(SURGEON_PROF_DW_AUX, st);
+    const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 4096);
+    hipLaunchKernelGGL(fill_zero_f32_kernel, dim3(blocks), dim3(256), 0, st, dW, p.n_w);
+    SURGEON_LAUNCH_CHECK();
+    return SURGEON_OK;
+  }
+  // rank table
+  {
+  ProfScope prof(SURGEON_PROF_DW_AUX, st);
+  hipLaunchKernelGGL(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
+                     block_sum);
+  SURGEON_LAUNCH_CHECK();
+  hipLaunchKernelGGL(rank_scan_kernel, dim3(1), dim3(1024), 0, st, block_sum, (int)p.n_rank_blocks);
+  SURGEON_LAUNCH_CHECK();
+  hipLaunchKernelGGL(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
+                     (const uint32_t*)block_sum, word_rank);
+  SURGEON_LAUNCH_CHECK();
+  }
+
+  Packed<InT> pk;
+  pk.vals = (const InT*)vals;
+  pk.mask = mask;
+  pk.word_rank = word_rank;
+  pk.k_last = d->k_total - 1;
+  pk.n_words = p.n_words;
+  float* out = p.splits > 1 ? part : dW;
+  int rc;
+  if (!p.conv && p.l.bf16_mfma) {
+    void* dense = w + p.off_dense;
+    rc = launch_unpack_dense(SURGEON_BF16, vals, mask, word_rank, p.n, d->k_total, dense, st);
+    if (rc == SURGEON_OK)
+      rc = launch_linear_bf16(p.l.g.M, p.l.g.K, p.l.g.N, dense, dY, out, p.l.splits, p.l.g.rows_per_split, st);
+  } else {
+    rc = p.conv ? launch_conv<InT>(p.c, pk, dY, out, st) : launch_linear<InT>(p.l, pk, dY, out, st);
+  }
+  if (rc != SURGEON_OK) return rc;
+  if (p.splits > 1) {
+    const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 8192);
+    ProfScope prof(SURGEON_PROF_DW_AUX, st);
+    hipLaunchKernelGGL(dw_reduce_splits_kernel, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w, dW);
+    SURGEON_LAUNCH_CHECK();
+  }
+  return SURGEON_OK;
+}
+
+}  // namespace surgeon
