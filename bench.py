@@ -99,6 +99,7 @@ def main():
             L = e["L"]
             k = surgeon.surgeon_packed_sizes(L.n, L.group_len, r, dt)[0]
             e["desc"].k_total = k
+            e["desc"].group_len, e["desc"].r = L.group_len, r
             surgeon.surgeon_prune_pack(e["A"], L.group_len, r, e["vals"], e["mask"], None, ws)
             if count:
                 acct["sp_bytes"] += L.n * L.elem_bytes + k * L.elem_bytes + 8 * ((L.n + 63) // 64)

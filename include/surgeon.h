@@ -56,6 +56,11 @@ typedef enum { SURGEON_LINEAR = 0, SURGEON_CONV2D = 1 } surgeon_layer_kind;
  * dtype is the element type of vals and dY; dW is always fp32.
  * k_total is the number of values in the packed stream (as returned by surgeon_packed_sizes);
  * it bounds every read of `vals`.
+ * group_len / r (optional hint): the arguments surgeon_prune_pack was called with for this (vals, mask); the
+ * caller vouches for them.  When group_len is a multiple of 64 and at most 4096, and k_total equals the count
+ * those arguments imply, every group's position in `vals` is known in closed form and a cheaper pre-pass is
+ * used; the result is the same as without the hint.  A hint that does not describe the packing gives wrong
+ * values (never an out-of-bounds access).  group_len = 0 means "unknown".
  */
 typedef struct {
   int32_t kind;  /* surgeon_layer_kind */
@@ -63,6 +68,8 @@ typedef struct {
   int64_t M, K, N;                                   /* LINEAR */
   int64_t Nb, Ci, H, W, Co, kh, kw, stride, pad;     /* CONV2D */
   int64_t k_total;
+  int64_t group_len; /* 0 = unknown */
+  float r;
 } surgeon_layer_desc;
 
 /*

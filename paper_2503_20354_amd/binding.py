@@ -31,7 +31,8 @@ class LayerDesc(ctypes.Structure):
                 ("M", ctypes.c_int64), ("K", ctypes.c_int64), ("N", ctypes.c_int64),
                 ("Nb", ctypes.c_int64), ("Ci", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64),
                 ("Co", ctypes.c_int64), ("kh", ctypes.c_int64), ("kw", ctypes.c_int64),
-                ("stride", ctypes.c_int64), ("pad", ctypes.c_int64), ("k_total", ctypes.c_int64)]
+                ("stride", ctypes.c_int64), ("pad", ctypes.c_int64), ("k_total", ctypes.c_int64),
+                ("group_len", ctypes.c_int64), ("r", ctypes.c_float)]
 
 
 def library_path():
@@ -247,15 +248,17 @@ def prune_pack(A: torch.Tensor, group_len: int, r: float, want_idx: bool = False
     return PackedActivation(vals, mask, idx, k, n, group_len, r)
 
 
-def linear_desc(M, K, N, dtype, k_total) -> LayerDesc:
+def linear_desc(M, K, N, dtype, k_total, group_len=0, r=0.0) -> LayerDesc:
     d = LayerDesc()
     d.kind, d.dtype, d.M, d.K, d.N, d.k_total = 0, dtype, M, K, N, k_total
+    d.group_len, d.r = group_len, r  # optional hint: the arguments the packing used
     return d
 
 
-def conv2d_desc(Nb, Ci, H, W, Co, kh, kw, stride, pad, dtype, k_total) -> LayerDesc:
+def conv2d_desc(Nb, Ci, H, W, Co, kh, kw, stride, pad, dtype, k_total, group_len=0, r=0.0) -> LayerDesc:
     d = LayerDesc()
     d.kind, d.dtype, d.k_total = 1, dtype, k_total
+    d.group_len, d.r = group_len, r
     d.Nb, d.Ci, d.H, d.W, d.Co, d.kh, d.kw, d.stride, d.pad = Nb, Ci, H, W, Co, kh, kw, stride, pad
     return d
 
@@ -270,6 +273,8 @@ def dw_from_packed(desc: LayerDesc, packed: PackedActivation, dY: torch.Tensor, 
         dW = torch.empty(shape, dtype=torch.float32, device=dY.device)
     if ws is None:
         ws = _workspace(surgeon_dw_ws_bytes(desc), dY.device)
+    if desc.group_len == 0:  # pass the packing's arguments along as the hint
+        desc.group_len, desc.r = packed.group_len, packed.r
     surgeon_dw_from_packed(desc, packed.vals, packed.mask, dY, dW, ws)
     return dW
 

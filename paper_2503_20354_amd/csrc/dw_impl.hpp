@@ -141,6 +141,21 @@ static __global__ __launch_bounds__(kRankBlock) void rank_write_kernel(const uin
   }
 }
 
+// Rank table when every group of `words_per_group` mask words is known to hold exactly k_full kept elements
+// (the packing's group length is a multiple of 64, at most 4096): one wavefront per group, no cross-group pass.
+static __global__ __launch_bounds__(kRankBlock) void rank_grouped_kernel(const uint64_t* __restrict__ mask, int64_t n_words,
+                                                                         int words_per_group, int64_t n_groups,
+                                                                         uint32_t k_full, uint32_t* __restrict__ word_rank) {
+  const int lane = threadIdx.x & 63;
+  const int64_t grp = (int64_t)blockIdx.x * (kRankBlock / 64) + (threadIdx.x >> 6);
+  if (grp >= n_groups) return;
+  const int64_t w = grp * words_per_group + lane;
+  const bool ok = lane < words_per_group && w < n_words;
+  const uint32_t c = ok ? (uint32_t)__popcll(mask[w]) : 0u;
+  const uint32_t incl = wave_incl_scan_u32(c, lane);
+  if (ok) word_rank[w] = (uint32_t)grp * k_full + incl - c;
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // un-pack of one element (Alg. 1 line 11)
 // ---------------------------------------------------------------------------------------------------------
@@ -698,6 +713,8 @@ struct DwPlan {
   ConvPlan c;
   LinPlan l;
   int64_t n, n_words, n_rank_blocks, n_w;
+  int rank_words_per_group;  // > 0: closed-form group positions (rank_grouped_kernel)
+  int64_t rank_groups, rank_k_full;
   int splits;
   size_t off_rank, off_blocks, off_part, off_dense, ws_bytes;
 };
@@ -876,6 +893,16 @@ static int plan_dw(const surgeon_layer_desc* d, DwPlan* p) {
   }
   if (d->k_total > p->n) return fail(SURGEON_EINVAL, "dw_from_packed: k_total exceeds the activation size");
   p->n_words = ceil_div(p->n, 64);
+  p->rank_words_per_group = 0;
+  if (d->group_len > 0 && d->group_len % 64 == 0 && d->group_len <= kWaveRegMaxGroup && p->n > 0) {
+    GroupPlan gp;
+    if (make_group_plan(p->n, d->group_len, d->r, &gp) && gp.g % 64 == 0 && gp.k_total == d->k_total &&
+        gp.n_groups * gp.k_full < ((int64_t)1 << 32)) {  // gp.g: the group length after clamping to n
+      p->rank_words_per_group = (int)(gp.g / 64);
+      p->rank_groups = gp.n_groups;
+      p->rank_k_full = gp.k_full;
+    }
+  }
   p->n_rank_blocks = ceil_div(p->n_words, kRankWordsPerBlock);
   size_t off = 0;
   p->off_rank = off;
@@ -977,6 +1004,11 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   // rank table
   {
   ProfScope prof(SURGEON_PROF_DW_AUX, st);
+  if (p.rank_words_per_group > 0) {
+    hipLaunchKernelGGL(rank_grouped_kernel, dim3((unsigned)ceil_div(p.rank_groups, kRankBlock / 64)), dim3(kRankBlock), 0, st,
+                       mask, p.n_words, p.rank_words_per_group, p.rank_groups, (uint32_t)p.rank_k_full, word_rank);
+    SURGEON_LAUNCH_CHECK();
+  } else {
   hipLaunchKernelGGL(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
                      block_sum);
   SURGEON_LAUNCH_CHECK();
@@ -985,6 +1017,7 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   hipLaunchKernelGGL(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
                      (const uint32_t*)block_sum, word_rank);
   SURGEON_LAUNCH_CHECK();
+  }
   }
 
   Packed<InT> pk;

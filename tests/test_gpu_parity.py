@@ -219,6 +219,23 @@ def test_dw_conv(dtype, shape):
     assert not got.any()
 
 
+def test_dw_group_hint_changes_nothing():
+    """The optional (group_len, r) hint only selects a cheaper pre-pass: same bits with and without it."""
+    Nb, Ci, H, W, Co = 4, 160, 32, 32, 160
+    A = wl.draw((Nb, Ci, H, W), "relu", "f32", 21).to(DEV)
+    dY = wl.draw((Nb, Co, H, W), "normal", "f32", 22).to(DEV)
+    for g, r in ((4096, 0.45), (512, 0.9), (4096 * 3, 0.5)):  # the last one is not eligible for the closed form
+        p = surgeon.prune_pack(A, g, r)
+        plain = surgeon.conv2d_desc(Nb, Ci, H, W, Co, 3, 3, 1, 1, surgeon.F32, p.k_total)
+        hinted = surgeon.conv2d_desc(Nb, Ci, H, W, Co, 3, 3, 1, 1, surgeon.F32, p.k_total, group_len=g, r=r)
+        ws = torch.empty(surgeon.surgeon_dw_ws_bytes(plain), dtype=torch.uint8, device=DEV)
+        a, b = torch.empty(Co, Ci, 3, 3, device=DEV), torch.empty(Co, Ci, 3, 3, device=DEV)
+        surgeon.surgeon_dw_from_packed(plain, p.vals, p.mask, dY, a, ws)
+        surgeon.surgeon_dw_from_packed(hinted, p.vals, p.mask, dY, b, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)
+
+
 def test_dw_is_deterministic():
     shape = (8, 160, 32, 32, 160, 3, 1)
     Nb, Ci, H, W, Co, k, st = shape
