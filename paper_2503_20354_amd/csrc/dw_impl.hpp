@@ -310,105 +310,172 @@ __device__ __forceinline__ void conv_stage_tile(const ConvGeom& gm, const Packed
 }
 
 // ---- run-based staging: each staging thread un-packs runs of 16 consecutive elements of a patch row --------
+// All global reads of this path are buffer loads: 32-bit byte offsets (no 64-bit address arithmetic on the vector
+// ALU, which the staging wavefronts share with the matrix instructions of the wavefront on the same SIMD), a
+// per-K-tile scalar offset for everything that is uniform, and the hardware range check instead of clamps and
+// selects: an offset at or beyond the buffer size returns 0.  The host enables the path only when every buffer is
+// smaller than 2 GiB, so kOutOfRange is out of range for all of them.
 constexpr int kRunLen = 16;
 constexpr int kRunsPerThread = 2;
+constexpr uint32_t kOutOfRange = 0x80000000u;
+constexpr int kRawBufferWord3 = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
 
-// Raw loads describing one run of K-tile `tile`: the two mask words its 16 bits may straddle and the rank of the
-// first word.  They are issued one K-tile ahead, so that per K-tile only one memory round trip (the values and
-// dY) sits on the staging wavefronts' critical path.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Raw loads describing one run of a K-tile: the mask word holding the run's first element (d0, d1), the low half
+// of the next word (d2), and the rank of the first word.  They are issued one K-tile ahead, so that per K-tile only
+// one memory round trip (the values and dY) sits on the staging wavefronts' critical path.  A run outside the image
+// (padding rows, channels past Ci) loads from kOutOfRange and sees an empty mask.
 struct RunLoad {
-  uint64_t m0, m1;
-  uint32_t r0;
-  int info;  // bit offset in m0 (6 bits) | elements of the run inside the image << 6 (5 bits) | row valid << 11
+  uint32_t d0, d1, d2, r0, sh;  // sh: bit offset of the run in (d1:d0), 0..63
 };
 
 template <typename InT>
-__device__ __forceinline__ RunLoad conv_run_issue(const ConvGeom& gm, const Packed<InT>& pk, int tile, int q, int ci0,
-                                                  int u0) {
-  const uint32_t row = fast_div((uint32_t)q, gm.magic_rpr), rr = (uint32_t)q - row * gm.runs_per_row;
-  const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
-  const int b = tile / gm.tiles_per_img;
-  const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
-  const int ih = oh0 * gm.stride + u0 - gm.pad + (int)pr, ci = ci0 + (int)c, iw0 = (int)rr * kRunLen;
-  const bool ok = q < gm.n_runs && ci < gm.Ci && ih >= 0 && ih < gm.H;
-  const int64_t e0 = ok ? (((int64_t)b * gm.Ci + ci) * gm.H + ih) * gm.W + iw0 : 0;
-  const int64_t w = e0 >> 6;
-  RunLoad L;
-  L.m0 = pk.mask[w];
-  L.m1 = pk.mask[min(w + 1, pk.n_words - 1)];
-  L.r0 = pk.word_rank[w];
-  L.info = (int)(e0 & 63) | (min(kRunLen, gm.Wv - iw0) << 6) | (ok ? (1 << 11) : 0);
-  return L;
+struct DyVec;
+template <>
+struct DyVec<float> {
+  typedef u32x4 raw_t;
+  static __device__ __forceinline__ raw_t load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+  }
+  static __device__ __forceinline__ floatx4 widen4(raw_t v) { return __builtin_bit_cast(floatx4, v); }
+};
+template <>
+struct DyVec<uint16_t> {
+  typedef u32x2 raw_t;
+  static __device__ __forceinline__ raw_t load(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+  }
+  static __device__ __forceinline__ floatx4 widen4(raw_t v) {
+    u32x4 w = {v.x << 16, v.x & 0xffff0000u, v.y << 16, v.y & 0xffff0000u};
+    return __builtin_bit_cast(floatx4, w);
+  }
+};
+__device__ __forceinline__ uint32_t load_val_bits(__amdgpu_buffer_rsrc_t r, uint32_t voff, float) {
+  return __builtin_amdgcn_raw_buffer_load_b32(r, voff, 0, 0);
+}
+__device__ __forceinline__ uint32_t load_val_bits(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint16_t) {
+  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, voff, 0, 0) << 16;  // bf16 -> the fp32 with the same value
 }
 
-// Stages K-tile `tile` from the run metadata in `cur` (loaded earlier), and replaces `cur` by the metadata of
-// K-tile tile + 1 when prefetch_next is set.  Requires gm.dy_vec and gm.run_mode.
-template <typename InT, int KHC, int MT, int NT, int P>
-__device__ __forceinline__ void conv_stage_runs(const ConvGeom& gm, const Packed<InT>& pk, const InT* __restrict__ dY,
-                                                float* __restrict__ buf, int tile, int ltid, int co0, int ci0, int u0,
-                                                RunLoad (&cur)[kRunsPerThread], bool prefetch_next) {
-  constexpr int TCO = 2 * MT * 16, SY = P + 4, NY = TCO * P / 4 / kConvLoaders;
-  typedef typename Vec4<InT>::type vec_t;
-  float* __restrict__ dYs = buf;
-  float* __restrict__ As = buf + TCO * SY;
-  const int b = tile / gm.tiles_per_img;
-  const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
-  const int valid_pos = gm.R * gm.OW;
+// Per-thread state of the run-based staging: everything that does not change from K-tile to K-tile is computed once.
+template <typename InT, int MT, int P>
+struct RunStager {
+  static constexpr int TCO = 2 * MT * 16, SY = P + 4, NY = TCO * P / 4 / kConvLoaders;
+  static constexpr uint32_t ES = sizeof(InT);
+  __amdgpu_buffer_rsrc_t r_mask, r_rank, r_vals, r_dy;
+  uint32_t e_const[kRunsPerThread];  // flat element index of the run minus the K-tile's uniform part (mod 2^32)
+  int ih_const[kRunsPerThread];      // input row of the run minus the K-tile's first row; hugely negative: no run
+  uint32_t nv_mask[kRunsPerThread];  // low `elements of the run inside the row` bits
+  int lds_dst[kRunsPerThread];       // float offset of the run inside the patch area
+  uint32_t y_voff[NY];               // byte offset of this thread's j-th dY vector inside the K-tile's dY block
+  int y_lds;                         // float offset of the first of them in the dY area (the j-th is 16*SY*j... further)
 
-  vec_t y[NY];
+  __device__ __forceinline__ void init(const ConvGeom& gm, const Packed<InT>& pk, const InT* __restrict__ dY, int ltid,
+                                       int co0, int ci0, int u0) {
+    r_mask = __builtin_amdgcn_make_buffer_rsrc((void*)pk.mask, 0, (int)(pk.n_words * 8), kRawBufferWord3);
+    r_rank = __builtin_amdgcn_make_buffer_rsrc((void*)pk.word_rank, 0, (int)(pk.n_words * 4), kRawBufferWord3);
+    r_vals = __builtin_amdgcn_make_buffer_rsrc((void*)pk.vals, 0, (int)((pk.k_last + 1) * (int64_t)ES), kRawBufferWord3);
+    r_dy = __builtin_amdgcn_make_buffer_rsrc((void*)dY, 0, (int)((int64_t)gm.Nb * gm.Co * gm.OH * gm.OW * ES),
+                                             kRawBufferWord3);
 #pragma unroll
-  for (int j = 0; j < NY; ++j) {
-    const int q = ltid + kConvLoaders * j;
-    const int c = q / (P / 4), k4 = q % (P / 4);
-    const bool ok = co0 + c < gm.Co && 4 * k4 < valid_pos;
-    const int64_t off = ok ? (((int64_t)b * gm.Co + co0 + c) * gm.OH + oh0) * gm.OW + 4 * k4 : 0;
-    y[j] = *reinterpret_cast<const vec_t*>(dY + off);
-    if (!ok) y[j] = vec_t{0, 0, 0, 0};
-  }
-
-  uint32_t bits[kRunsPerThread];
-  InT raw[kRunsPerThread][kRunLen];
-#pragma unroll
-  for (int r = 0; r < kRunsPerThread; ++r) {
-    if (kConvLoaders * r >= gm.n_runs) continue;  // uniform: no thread has an r-th run in this geometry
-    const int sh = cur[r].info & 63, nvalid = (cur[r].info >> 6) & 31;
-    const uint64_t window = (cur[r].m0 >> sh) | (sh ? cur[r].m1 << (64 - sh) : 0ull);
-    bits[r] = (cur[r].info >> 11) ? ((uint32_t)window & ((1u << nvalid) - 1u)) : 0u;
-    const int64_t rank = (int64_t)cur[r].r0 + __popcll(cur[r].m0 & ((1ull << sh) - 1ull));
-#pragma unroll
-    for (int t = 0; t < kRunLen; ++t) {
-      int64_t i = rank + __builtin_popcount(bits[r] & ((1u << t) - 1u));
-      i = i > pk.k_last ? pk.k_last : i;
-      raw[r][t] = pk.vals[i];
-    }
-  }
-  if (prefetch_next) {
-#pragma unroll
-    for (int r = 0; r < kRunsPerThread; ++r)
-      if (kConvLoaders * r < gm.n_runs) cur[r] = conv_run_issue<InT>(gm, pk, tile + 1, ltid + kConvLoaders * r, ci0, u0);
-  }
-#pragma unroll
-  for (int r = 0; r < kRunsPerThread; ++r) {
-    const int q = ltid + kConvLoaders * r;
-    if (q < gm.n_runs) {
+    for (int r = 0; r < kRunsPerThread; ++r) {
+      const int q = ltid + kConvLoaders * r;
       const uint32_t row = fast_div((uint32_t)q, gm.magic_rpr), rr = (uint32_t)q - row * gm.runs_per_row;
       const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
-      const int nvalid = min(kRunLen, gm.Wv - (int)rr * kRunLen);
-      float* __restrict__ dst = As + c * gm.PS + pr * gm.PW + rr * kRunLen + gm.pad;
+      const int ci = ci0 + (int)c, dih = u0 - gm.pad + (int)pr, iw0 = (int)rr * kRunLen;
+      const bool has_run = q < gm.n_runs && ci < gm.Ci;
+      e_const[r] = (uint32_t)((ci * gm.H + dih) * gm.W + iw0);
+      ih_const[r] = has_run ? dih : -(1 << 30);
+      const int nvalid = min(kRunLen, gm.Wv - iw0);
+      nv_mask[r] = (q < gm.n_runs) ? ((1u << nvalid) - 1u) : 0u;
+      lds_dst[r] = (int)(c * gm.PS + pr * gm.PW) + iw0 + gm.pad;
+    }
+    const int valid_pos = gm.R * gm.OW;
 #pragma unroll
-      for (int t = 0; t < kRunLen; ++t)
-        if (t < nvalid) dst[t] = ((bits[r] >> t) & 1u) ? widen<InT>(raw[r][t]) : 0.0f;
+    for (int j = 0; j < NY; ++j) {
+      const int q = ltid + kConvLoaders * j;
+      const int c = q / (P / 4), k4 = q % (P / 4);
+      const bool ok = co0 + c < gm.Co && 4 * k4 < valid_pos;
+      y_voff[j] = ok ? (uint32_t)(c * gm.OH * gm.OW + 4 * k4) * ES : kOutOfRange;
+    }
+    y_lds = (ltid / (P / 4)) * SY + 4 * (ltid % (P / 4));
+  }
+
+  // the metadata loads of K-tile `tile`
+  __device__ __forceinline__ void issue(const ConvGeom& gm, int tile, RunLoad (&m)[kRunsPerThread]) const {
+    const int b = tile / gm.tiles_per_img;
+    const int ih_base = (tile - b * gm.tiles_per_img) * gm.R * gm.stride;
+    const uint32_t e_base = (uint32_t)(b * gm.Ci * gm.H + ih_base) * (uint32_t)gm.W;
+#pragma unroll
+    for (int r = 0; r < kRunsPerThread; ++r) {
+      if (kConvLoaders * r >= gm.n_runs) continue;  // uniform: no thread has an r-th run in this geometry
+      const bool ok = (uint32_t)(ih_base + ih_const[r]) < (uint32_t)gm.H;
+      const uint32_t e0 = e_base + e_const[r];
+      const uint32_t off8 = ok ? (e0 >> 6) * 8u : kOutOfRange;
+      const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(r_mask, off8, 0, 0);
+      m[r].d0 = w.x;
+      m[r].d1 = w.y;
+      m[r].d2 = __builtin_amdgcn_raw_buffer_load_b32(r_mask, off8 + 8u, 0, 0);
+      m[r].r0 = __builtin_amdgcn_raw_buffer_load_b32(r_rank, off8 >> 1, 0, 0);
+      m[r].sh = e0 & 63u;
     }
   }
+
+  // Stages K-tile `tile` from the metadata in `cur`; replaces `cur` by the metadata of K-tile tile + 1 when
+  // prefetch_next is set.  NV = 16 / 8: every run of this geometry has exactly NV elements; 0: they vary.
+  template <int NV>
+  __device__ __forceinline__ void stage(const ConvGeom& gm, float* __restrict__ buf, int tile, int co0,
+                                        RunLoad (&cur)[kRunsPerThread], bool prefetch_next) const {
+    constexpr int LEN = NV ? NV : kRunLen;
+    float* __restrict__ dYs = buf;
+    float* __restrict__ As = buf + TCO * SY;
+    const int b = tile / gm.tiles_per_img;
+    const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
+    const uint32_t y_soff = (uint32_t)(((b * gm.Co + co0) * gm.OH + oh0) * gm.OW) * ES;
+    typename DyVec<InT>::raw_t y[NY];
 #pragma unroll
-  for (int j = 0; j < NY; ++j) {
-    const int q = ltid + kConvLoaders * j;
-    const int c = q / (P / 4), k4 = q % (P / 4);
-    typedef float f4 __attribute__((ext_vector_type(4)));
-    f4 v = {widen<InT>(y[j][0]), widen<InT>(y[j][1]), widen<InT>(y[j][2]), widen<InT>(y[j][3])};
-    *reinterpret_cast<f4*>(&dYs[c * SY + 4 * k4]) = v;
+    for (int j = 0; j < NY; ++j) y[j] = DyVec<InT>::load(r_dy, y_voff[j], y_soff);
+
+    uint32_t bits[kRunsPerThread], raw[kRunsPerThread][LEN];
+#pragma unroll
+    for (int r = 0; r < kRunsPerThread; ++r) {
+      if (kConvLoaders * r >= gm.n_runs) continue;
+      const uint32_t sh = cur[r].sh, s5 = sh & 31u;
+      const bool upper = sh >= 32u;
+      const uint32_t below5 = (1u << s5) - 1u;
+      // the run's bits: 32 bits of (d2:d1:d0) starting at sh, cut to the run's length
+      bits[r] = __builtin_amdgcn_alignbit(upper ? cur[r].d2 : cur[r].d1, upper ? cur[r].d1 : cur[r].d0, s5) & nv_mask[r];
+      // kept elements of the word before the run
+      const uint32_t before = (uint32_t)__builtin_popcount(upper ? cur[r].d0 : (cur[r].d0 & below5)) +
+                              (uint32_t)__builtin_popcount(upper ? (cur[r].d1 & below5) : 0u);
+      uint32_t off = (cur[r].r0 + before) * ES;  // byte offset in vals of the run's first kept element
+#pragma unroll
+      for (int t = 0; t < LEN; ++t) {
+        // a dropped element reads the next kept value (or 0 past the end) and is masked when it is stored
+        raw[r][t] = load_val_bits(r_vals, off, InT());
+        off += ((bits[r] >> t) & 1u) * ES;
+      }
+    }
+    if (prefetch_next) issue(gm, tile + 1, cur);
+#pragma unroll
+    for (int r = 0; r < kRunsPerThread; ++r) {
+      if (kConvLoaders * r >= gm.n_runs) continue;
+      if (nv_mask[r]) {
+        float* __restrict__ dst = As + lds_dst[r];
+#pragma unroll
+        for (int t = 0; t < LEN; ++t) {
+          const uint32_t keep = (uint32_t)(((int32_t)(bits[r] << (31 - t))) >> 31);  // all ones if bit t is set
+          if (NV || ((nv_mask[r] >> t) & 1u)) dst[t] = __uint_as_float(raw[r][t] & keep);
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NY; ++j)
+      *reinterpret_cast<floatx4*>(&dYs[y_lds + j * (kConvLoaders / (P / 4)) * SY]) = DyVec<InT>::widen4(y[j]);
   }
-}
+};
 
 // Workgroup = 8 wavefronts.  Wavefronts 0-3 are the MFMA wavefronts, arranged 2 (co) x 2 (ci), each owning
 // MT x NT MFMA 16x16 tiles for KHC*KW taps.  Wavefronts 4-7 stage the next K-tile into the other LDS buffer
@@ -460,21 +527,20 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
       return;
     }
     if (gm.run_mode) {
+      RunStager<InT, MT, P> rs;
+      rs.init(gm, pk, dY, ltid, co0, ci0, u0);
       RunLoad meta[kRunsPerThread];
-      if (t_begin < t_end) {
-#pragma unroll
-        for (int r = 0; r < kRunsPerThread; ++r)
-          if (kConvLoaders * r < gm.n_runs) meta[r] = conv_run_issue<InT>(gm, pk, t_begin, ltid + kConvLoaders * r, ci0, u0);
-        __syncthreads();  // the patches are cleared before the first run is written
-        conv_stage_runs<InT, KHC, MT, NT, P>(gm, pk, dY, smem, t_begin, ltid, co0, ci0, u0, meta, t_begin + 1 < t_end);
-      } else {
-        __syncthreads();
-      }
+      if (t_begin < t_end) rs.issue(gm, t_begin, meta);
+      __syncthreads();  // the patches are cleared before the first run is written
+      // uniform choice of the run length handling: all runs full (W a multiple of 16), all of 8 elements, or mixed
+      const int nv = (gm.Wv % kRunLen == 0) ? kRunLen : (gm.Wv == 8 ? 8 : 0);
       for (int tile = t_begin; tile < t_end; ++tile) {
-        __syncthreads();
-        if (tile + 1 < t_end)
-          conv_stage_runs<InT, KHC, MT, NT, P>(gm, pk, dY, smem + ((tile + 1 - t_begin) & 1) * buf_floats, tile + 1, ltid,
-                                               co0, ci0, u0, meta, tile + 2 < t_end);
+        float* __restrict__ buf = smem + ((tile - t_begin) & 1) * buf_floats;
+        const bool more = tile + 1 < t_end;
+        if (nv == kRunLen) rs.template stage<kRunLen>(gm, buf, tile, co0, meta, more);
+        else if (nv == 8) rs.template stage<8>(gm, buf, tile, co0, meta, more);
+        else rs.template stage<0>(gm, buf, tile, co0, meta, more);
+        __syncthreads();  // this buffer is complete; the other one is no longer being read
       }
       return;
     }
@@ -827,7 +893,11 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
   g.runs_per_row = (int)ceil_div(std::max(g.Wv, 1), kRunLen);
   g.n_runs = tci * g.PR * g.runs_per_row;
   g.magic_rpr = g.runs_per_row > 1 ? (uint32_t)(0xffffffffu / (uint32_t)g.runs_per_row) + 1u : 0u;
-  g.run_mode = (g.fill_step == 1 && g.n_buf == 2 && g.dy_vec && g.Wv >= 1 && g.n_runs <= kRunsPerThread * kConvLoaders) ? 1 : 0;
+  // the run-based staging addresses vals and dY with 32-bit byte offsets whose top bit marks "no access"
+  const int64_t es = d->dtype == SURGEON_F32 ? 4 : 2;
+  const bool small_buffers = d->k_total * es < big && (int64_t)g.Nb * g.Co * g.OH * g.OW * es < big;
+  g.run_mode = (g.fill_step == 1 && g.n_buf == 2 && g.dy_vec && g.Wv >= 1 && small_buffers &&
+                g.n_runs <= kRunsPerThread * kConvLoaders) ? 1 : 0;
   int64_t per;
   const double tile_us = 2.0 * tco * tci * cp->khc * cp->kw_t * cp->p / kFlopsPerCuPerUs;
   cp->splits = choose_splits(g.n_ktiles, (int64_t)cp->co_tiles * g.ci_tiles * cp->z, kConvSlots, tile_us, g.n_w, &per);
