@@ -740,8 +740,17 @@ __global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) void dw_linear
 static __global__ __launch_bounds__(256) void dw_reduce_splits_kernel(const float* __restrict__ part, int n_splits, int64_t n_w,
                                                                float* __restrict__ dW) {
   for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n_w; x += (int64_t)gridDim.x * 256) {
-    float s = part[x];
-    for (int k = 1; k < n_splits; ++k) s += part[(int64_t)k * n_w + x];
+    // eight loads in flight at a time; the additions stay in split order, so the result does not depend on the batching
+    float s = 0.0f;
+    int k = 0;
+    for (; k + 8 <= n_splits; k += 8) {
+      float v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = part[(int64_t)(k + q) * n_w + x];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) s += v[q];
+    }
+    for (; k < n_splits; ++k) s += part[(int64_t)k * n_w + x];
     dW[x] = s;
   }
 }
