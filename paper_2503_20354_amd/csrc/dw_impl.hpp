@@ -384,13 +384,15 @@ struct RunStager {
       const int q = ltid + kConvLoaders * r;
       const uint32_t row = fast_div((uint32_t)q, gm.magic_rpr), rr = (uint32_t)q - row * gm.runs_per_row;
       const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
-      const int ci = ci0 + (int)c, dih = u0 - gm.pad + (int)pr, iw0 = (int)rr * kRunLen;
+      // a run is kRunLen LDS columns = kRunLen * fill_step input pixels (fill_step 2: a strided 1x1 filter, pad 0)
+      const int fs = gm.fill_step;
+      const int ci = ci0 + (int)c, dih = u0 - gm.pad + (int)pr * fs, col0 = (int)rr * kRunLen, iw0 = col0 * fs;
       const bool has_run = q < gm.n_runs && ci < gm.Ci;
       e_const[r] = (uint32_t)((ci * gm.H + dih) * gm.W + iw0);
       ih_const[r] = has_run ? dih : -(1 << 30);
-      const int nvalid = min(kRunLen, gm.Wv - iw0);
-      nv_mask[r] = (q < gm.n_runs) ? ((1u << nvalid) - 1u) : 0u;
-      lds_dst[r] = (int)(c * gm.PS + pr * gm.PW) + iw0 + gm.pad;
+      const int in_valid = min(kRunLen * fs, gm.W - iw0);  // input pixels of the run that exist in the row (1..32)
+      nv_mask[r] = (q < gm.n_runs) ? (0xffffffffu >> (32 - in_valid)) : 0u;
+      lds_dst[r] = (int)(c * gm.PS + pr * gm.PW) + col0 + gm.pad;
     }
     const int valid_pos = gm.R * gm.OW;
 #pragma unroll
@@ -425,7 +427,8 @@ struct RunStager {
 
   // Stages K-tile `tile` from the metadata in `cur`; replaces `cur` by the metadata of K-tile tile + 1 when
   // prefetch_next is set.  NV = 16 / 8: every run of this geometry has exactly NV elements; 0: they vary.
-  template <int NV>
+  // FS = fill_step (1 or 2): LDS column t of a run is input pixel t * FS of it.
+  template <int NV, int FS>
   __device__ __forceinline__ void stage(const ConvGeom& gm, float* __restrict__ buf, int tile, int co0,
                                         RunLoad (&cur)[kRunsPerThread], bool prefetch_next) const {
     constexpr int LEN = NV ? NV : kRunLen;
@@ -454,8 +457,13 @@ struct RunStager {
 #pragma unroll
       for (int t = 0; t < LEN; ++t) {
         // a dropped element reads the next kept value (or 0 past the end) and is masked when it is stored
-        raw[r][t] = load_val_bits(r_vals, off, InT());
-        off += ((bits[r] >> t) & 1u) * ES;
+        if (FS == 1) {
+          raw[r][t] = load_val_bits(r_vals, off, InT());
+          off += ((bits[r] >> t) & 1u) * ES;
+        } else {
+          const uint32_t kept_before = (uint32_t)__builtin_popcount(bits[r] & ((1u << (t * FS)) - 1u));
+          raw[r][t] = load_val_bits(r_vals, off + kept_before * ES, InT());
+        }
       }
     }
     if (prefetch_next) issue(gm, tile + 1, cur);
@@ -466,8 +474,8 @@ struct RunStager {
         float* __restrict__ dst = As + lds_dst[r];
 #pragma unroll
         for (int t = 0; t < LEN; ++t) {
-          const uint32_t keep = (uint32_t)(((int32_t)(bits[r] << (31 - t))) >> 31);  // all ones if bit t is set
-          if (NV || ((nv_mask[r] >> t) & 1u)) dst[t] = __uint_as_float(raw[r][t] & keep);
+          const uint32_t keep = (uint32_t)(((int32_t)(bits[r] << (31 - t * FS))) >> 31);  // all ones if the pixel's bit is set
+          if (NV || ((nv_mask[r] >> (t * FS)) & 1u)) dst[t] = __uint_as_float(raw[r][t] & keep);
         }
       }
     }
@@ -533,13 +541,20 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
       if (t_begin < t_end) rs.issue(gm, t_begin, meta);
       __syncthreads();  // the patches are cleared before the first run is written
       // uniform choice of the run length handling: all runs full (W a multiple of 16), all of 8 elements, or mixed
-      const int nv = (gm.Wv % kRunLen == 0) ? kRunLen : (gm.Wv == 8 ? 8 : 0);
+      const int nv = (gm.Wv % kRunLen == 0 && gm.W % (kRunLen * gm.fill_step) == 0) ? kRunLen
+                     : ((gm.Wv == 8 && gm.W == 8 * gm.fill_step) ? 8 : 0);
       for (int tile = t_begin; tile < t_end; ++tile) {
         float* __restrict__ buf = smem + ((tile - t_begin) & 1) * buf_floats;
         const bool more = tile + 1 < t_end;
-        if (nv == kRunLen) rs.template stage<kRunLen>(gm, buf, tile, co0, meta, more);
-        else if (nv == 8) rs.template stage<8>(gm, buf, tile, co0, meta, more);
-        else rs.template stage<0>(gm, buf, tile, co0, meta, more);
+        if (gm.fill_step == 1) {
+          if (nv == kRunLen) rs.template stage<kRunLen, 1>(gm, buf, tile, co0, meta, more);
+          else if (nv == 8) rs.template stage<8, 1>(gm, buf, tile, co0, meta, more);
+          else rs.template stage<0, 1>(gm, buf, tile, co0, meta, more);
+        } else {
+          if (nv == kRunLen) rs.template stage<kRunLen, 2>(gm, buf, tile, co0, meta, more);
+          else if (nv == 8) rs.template stage<8, 2>(gm, buf, tile, co0, meta, more);
+          else rs.template stage<0, 2>(gm, buf, tile, co0, meta, more);
+        }
         __syncthreads();  // this buffer is complete; the other one is no longer being read
       }
       return;
@@ -873,7 +888,11 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
         ps += (4 - ps % 32 + 32) % 32;  // per-channel stride = 4 (mod 32) floats: spreads channels over LDS banks
         const size_t lds = n_buf * ((size_t)tco * (p + 4) + (size_t)tci * ps) * sizeof(float);
         if (lds > kMaxLds) continue;
-        const double score = (double)(r * g.OW) / p - (p == 64 ? 0.0 : 0.05);
+        // the run-based staging (far cheaper per element) needs at most kRunsPerThread runs per staging thread
+        const int wv = g.fill_step == 1 ? std::min(g.W, pw - g.pad) : std::min(pw, (g.W + g.fill_step - 1) / g.fill_step);
+        const bool runs_fit = (int64_t)tci * pr * ceil_div(std::max(wv, 1), kRunLen) <= kRunsPerThread * kConvLoaders &&
+                              n_buf == 2 && (r * g.OW) % 4 == 0;
+        const double score = (double)(r * g.OW) / p - (p == 64 ? 0.0 : 0.05) + (runs_fit ? 0.5 : 0.0);
         if (score > best_score) {
           best_score = score;
           cp->p = p;
@@ -898,14 +917,15 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
     return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv patch too large");
   g.dy_vec = ((g.R * g.OW) % 4 == 0 && ((int64_t)g.OH * g.OW) % 4 == 0) ? 1 : 0;
   g.bf16_mfma = (d->dtype == SURGEON_BF16 && g.lds_step == 1 && g.OW % 8 == 0) ? 1 : 0;
-  g.Wv = std::min(g.W, g.PW - g.pad);
+  // LDS columns of a patch row that hold an input pixel: column c is pixel c * fill_step - pad
+  g.Wv = g.fill_step == 1 ? std::min(g.W, g.PW - g.pad) : std::min(g.PW, (g.W + g.fill_step - 1) / g.fill_step);
   g.runs_per_row = (int)ceil_div(std::max(g.Wv, 1), kRunLen);
   g.n_runs = tci * g.PR * g.runs_per_row;
   g.magic_rpr = g.runs_per_row > 1 ? (uint32_t)(0xffffffffu / (uint32_t)g.runs_per_row) + 1u : 0u;
   // the run-based staging addresses vals and dY with 32-bit byte offsets whose top bit marks "no access"
   const int64_t es = d->dtype == SURGEON_F32 ? 4 : 2;
   const bool small_buffers = d->k_total * es < big && (int64_t)g.Nb * g.Co * g.OH * g.OW * es < big;
-  g.run_mode = (g.fill_step == 1 && g.n_buf == 2 && g.dy_vec && g.Wv >= 1 && small_buffers &&
+  g.run_mode = ((g.fill_step == 1 || (g.fill_step == 2 && g.pad == 0)) && g.n_buf == 2 && g.dy_vec && g.Wv >= 1 && small_buffers &&
                 g.n_runs <= kRunsPerThread * kConvLoaders) ? 1 : 0;
   int64_t per;
   const double tile_us = 2.0 * tco * tci * cp->khc * cp->kw_t * cp->p / kFlopsPerCuPerUs;

@@ -205,6 +205,7 @@ CONV_SHAPES = [
     (2, 160, 32, 32, 320, 1, 2), (2, 3, 32, 32, 16, 3, 1), (2, 3, 64, 64, 64, 7, 2), (1, 3, 224, 224, 64, 7, 2),
     (2, 64, 56, 56, 64, 3, 1), (2, 64, 56, 56, 256, 1, 1), (2, 128, 56, 56, 128, 3, 2), (2, 512, 7, 7, 512, 3, 1),
     (2, 5, 9, 9, 7, 5, 1), (3, 6, 12, 12, 20, 3, 1), (2, 256, 14, 14, 1024, 1, 1), (2, 40, 13, 13, 24, 3, 1),
+    (3, 64, 8, 8, 160, 3, 1), (2, 48, 24, 24, 32, 3, 2), (2, 33, 40, 40, 20, 3, 1),
 ]
 
 
