@@ -168,7 +168,7 @@ struct EmitSlots {
 // path 1: one wavefront per group, group in registers
 // ---------------------------------------------------------------------------------------------------------
 template <int E, typename BitsT, bool WITH_IDX>
-__global__ __launch_bounds__(256) void select_pack_wave_reg_kernel(const BitsT* __restrict__ A,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void select_pack_wave_reg_kernel(const BitsT* __restrict__ A,
                                                                    BitsT* __restrict__ vals,
                                                                    uint64_t* __restrict__ mask,
                                                                    uint32_t* __restrict__ idx, int64_t n_groups,
