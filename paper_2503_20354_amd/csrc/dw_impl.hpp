@@ -203,6 +203,12 @@ struct ConvGeom {
   uint32_t magic_rpr;   // ceil(2^32 / runs_per_row)
   int n_buf;            // 2: staging overlaps the MFMA work of the previous K-tile; 1: LDS holds one K-tile only
   int64_t n_w;          // Co*Ci*KH*KW
+  // Filter rows folded into the channel dimension (layers with few input channels, e.g. a network's first conv):
+  // Ci and KH above are then the VIRTUAL sizes (Ci_in * fold channels, one filter row); virtual channel cv reads
+  // input channel cv / fold shifted down by cv % fold rows, and [Co][cv][kw] is the same memory as
+  // [Co][ci][kh][kw].  fold == 0: no folding, Ci_in == Ci.
+  int Ci_in, fold;
+  uint32_t magic_fold;  // ceil(2^32 / fold)
 };
 
 // n / d for n*d < 2^32 with magic = ceil(2^32 / d); magic == 0 encodes d == 1
@@ -271,9 +277,12 @@ __device__ __forceinline__ void conv_stage_tile(const ConvGeom& gm, const Packed
       const bool in_patch = idx < (uint32_t)gm.n_patch;
       const uint32_t row = fast_div(idx, gm.magic_pw), col = idx - row * PW;
       const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
-      const int ci = ci0 + (int)c, ih = ih0 + (int)pr * gm.fill_step, iw = (int)col * gm.fill_step - gm.pad;
-      const bool ok = in_patch && ci < gm.Ci && ih >= 0 && ih < gm.H && iw >= 0 && iw < gm.W;
-      const int64_t e = ok ? (((int64_t)b * gm.Ci + ci) * gm.H + ih) * gm.W + iw : 0;
+      const int cv = ci0 + (int)c;
+      const int ci = gm.fold ? (int)fast_div((uint32_t)cv, gm.magic_fold) : cv;
+      const int kh = gm.fold ? cv - ci * gm.fold : 0;  // filter row folded into this virtual channel
+      const int ih = ih0 + (int)pr * gm.fill_step + kh, iw = (int)col * gm.fill_step - gm.pad;
+      const bool ok = in_patch && cv < gm.Ci && ih >= 0 && ih < gm.H && iw >= 0 && iw < gm.W;
+      const int64_t e = ok ? (((int64_t)b * gm.Ci_in + ci) * gm.H + ih) * gm.W + iw : 0;
       const uint64_t m = pk.mask[e >> 6];
       rank0[j] = pk.word_rank[e >> 6];
       word[j] = ok ? m : 0ull;
@@ -386,8 +395,11 @@ struct RunStager {
       const uint32_t c = fast_div(row, gm.magic_pr), pr = row - c * gm.PR;
       // a run is kRunLen LDS columns = kRunLen * fill_step input pixels (fill_step 2: a strided 1x1 filter, pad 0)
       const int fs = gm.fill_step;
-      const int ci = ci0 + (int)c, dih = u0 - gm.pad + (int)pr * fs, col0 = (int)rr * kRunLen, iw0 = col0 * fs;
-      const bool has_run = q < gm.n_runs && ci < gm.Ci;
+      const int cv = ci0 + (int)c;
+      const int ci = gm.fold ? (int)fast_div((uint32_t)cv, gm.magic_fold) : cv;
+      const int kh = gm.fold ? cv - ci * gm.fold : 0;  // filter row folded into this virtual channel
+      const int dih = u0 - gm.pad + (int)pr * fs + kh, col0 = (int)rr * kRunLen, iw0 = col0 * fs;
+      const bool has_run = q < gm.n_runs && cv < gm.Ci;
       e_const[r] = (uint32_t)((ci * gm.H + dih) * gm.W + iw0);
       ih_const[r] = has_run ? dih : -(1 << 30);
       const int in_valid = min(kRunLen * fs, gm.W - iw0);  // input pixels of the run that exist in the row (1..32)
@@ -409,7 +421,7 @@ struct RunStager {
   __device__ __forceinline__ void issue(const ConvGeom& gm, int tile, RunLoad (&m)[kRunsPerThread]) const {
     const int b = tile / gm.tiles_per_img;
     const int ih_base = (tile - b * gm.tiles_per_img) * gm.R * gm.stride;
-    const uint32_t e_base = (uint32_t)(b * gm.Ci * gm.H + ih_base) * (uint32_t)gm.W;
+    const uint32_t e_base = (uint32_t)(b * gm.Ci_in * gm.H + ih_base) * (uint32_t)gm.W;
 #pragma unroll
     for (int r = 0; r < kRunsPerThread; ++r) {
       if (kConvLoaders * r >= gm.n_runs) continue;  // uniform: no thread has an r-th run in this geometry
@@ -859,6 +871,27 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
   if (g.OW > 128) return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: output width %d > 128 not implemented", g.OW);
   g.lds_step = (g.KH == 1 && g.KW == 1) ? 1 : g.stride;
   g.fill_step = g.stride / g.lds_step;
+  g.Ci_in = g.Ci;
+  g.fold = 0;
+  g.magic_fold = 0;
+  if (g.KH > 1) {
+    // Folding the filter rows into the channels pays when the channel tile (32) is mostly padding: compare the
+    // matrix work (padded tile sizes x taps x filter-row slices) of both forms.
+    auto padded = [](int64_t x, int64_t t) { return ceil_div(x, t) * t; };
+    const int mt_plain = cp->khc == 3 ? ((g.Co % 160 == 0) ? 5 : (g.Co > 64 ? 4 : 2)) : (g.Co > 64 ? 4 : 2);
+    const int mt_fold = g.Co > 64 ? 4 : 2;
+    const int64_t work_plain = padded(g.Co, 32 * mt_plain) * padded(g.Ci, 32) * cp->khc * g.KW * cp->z;
+    const int64_t work_fold = padded(g.Co, 32 * mt_fold) * padded((int64_t)g.Ci * g.KH, 32) * g.KW;
+    if (work_fold < work_plain) {
+      g.fold = g.KH;
+      g.magic_fold = (uint32_t)(0xffffffffu / (uint32_t)g.fold) + 1u;
+      g.Ci = g.Ci_in * g.KH;
+      g.KH = 1;
+      cp->khc = 1;
+      cp->kw_t = g.KW;
+      cp->z = 1;
+    }
+  }
   // tile shape
   if (cp->kw_t == 1 && cp->khc == 1) {
     cp->mt = (g.Co > 64 || g.Ci > 64) ? 4 : 2;  // implemented pairs: (4,4) and (2,2)
