@@ -517,9 +517,10 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
   const int t_begin = blockIdx.y * gm.tiles_per_split;
   const int t_end = min(t_begin + gm.tiles_per_split, gm.n_ktiles);
 
-  // KHC rows of zeros after every channel's patch in both buffers (written once): contraction positions past
-  // R*OW point there, and their dY is zero as well
-  const int zero_len = KHC * PW + 8;  // 8 more floats: the bf16 path reads 8 consecutive positions per lane
+  // A zero area after every channel's patch in both buffers (written once): contraction positions past R*OW point
+  // at its start, and their dY is zero as well.  Reads of such a position reach KHC - 1 rows and KW - 1 columns
+  // further, the bf16 path 7 more floats.
+  const int zero_len = (KHC - 1) * PW + KW + 7;
   for (int t = tid; t < gm.n_buf * TCI * zero_len; t += 512) {
     const int bsel = t / (TCI * zero_len), rem = t - bsel * (TCI * zero_len);
     const int c = rem / zero_len, x = rem - c * zero_len;
@@ -917,7 +918,7 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
         if (g.OH % r != 0 || r * g.OW > p) continue;
         const int pr = (r - 1) * g.lds_step + cp->khc;
         const int pw = (g.OW - 1) * g.lds_step + g.KW;
-        int ps = (pr + cp->khc) * pw + 8;
+        int ps = (pr + cp->khc - 1) * pw + cp->kw_t + 7;  // patch + the zero area behind it
         ps += (4 - ps % 32 + 32) % 32;  // per-channel stride = 4 (mod 32) floats: spreads channels over LDS banks
         const size_t lds = n_buf * ((size_t)tco * (p + 4) + (size_t)tci * ps) * sizeof(float);
         if (lds > kMaxLds) continue;
