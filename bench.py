@@ -205,7 +205,7 @@ def cpu_baseline(cfg, wl):
     import oracle
 
     layers = wl.config_layers(cfg)
-    div = {0: 1, 1: 50, 2: 64, 3: 197, 4: 64}[cfg]
+    div = {0: 1, 1: 8, 2: 64, 3: 197, 4: 64}[cfg]  # sized for roughly 10-30 s of CPU work on a 16-core host
     sample = [wl.shrink(L, div) for L in layers]
     tensors = [tuple(wl.to_numpy_bits(t) for t in wl.layer_tensors(cfg, li, L)) for li, L in enumerate(sample)]
     r_lo, r_hi = wl.RATIO_RANGE[cfg]
