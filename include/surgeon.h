@@ -159,16 +159,18 @@ int surgeon_grad_importance_batched(const float* const* dW, const int64_t* n_w, 
 
 /*
  * Kernel timing aid for benchmarks (not part of the method).  Between surgeon_profile_begin() and
- * surgeon_profile_end() every kernel launch of the library is bracketed by two HIP events recorded on the
- * caller's stream.  surgeon_profile_end() waits for the recorded events and returns, per kernel class,
- * the summed device time in milliseconds and the number of launches, then discards the events:
+ * surgeon_profile_end() every kernel the library launches carries a start and a stop HIP event on the caller's
+ * stream (attached to the kernel's own dispatch, so no extra work is queued between kernels).
+ * surgeon_profile_end() waits for the events and returns, per kernel class, the summed kernel time in
+ * milliseconds and the number of kernels launched, then discards the events:
  *   class 0 SURGEON_PROF_SELECT_PACK  fused select+pack kernel (group_len % 64 == 0, <= 4096)
  *   class 1 SURGEON_PROF_DW           the MFMA weight-gradient kernel (conv or linear)
  *   class 2 SURGEON_PROF_IMPORTANCE   sum-of-squares kernels of Eq. 4
  *   class 3 SURGEON_PROF_DW_AUX       rank-table pre-pass and split reduction around class 1
  *   class 4 SURGEON_PROF_SELECT_OTHER kernels of the other two selection paths, mask clearing
  * ms / launches are host arrays of n_classes entries (at most SURGEON_PROF_CLASSES are filled).
- * Not thread-safe; intended for one benchmarking thread.  Event objects are created by the HIP runtime.
+ * Not thread-safe; intended for one benchmarking thread.  Event objects are created by the HIP runtime, kept in a
+ * pool and reused by later profiling sessions of the process.
  */
 enum { SURGEON_PROF_SELECT_PACK = 0, SURGEON_PROF_DW = 1, SURGEON_PROF_IMPORTANCE = 2, SURGEON_PROF_DW_AUX = 3,
        SURGEON_PROF_SELECT_OTHER = 4, SURGEON_PROF_CLASSES = 5 };

@@ -1,6 +1,7 @@
 // Internal helpers shared by the translation units of libsurgeon (gfx950 only; not part of the C ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <algorithm>
 #include <stdint.h>
 #include <stdio.h>
@@ -24,13 +25,25 @@ int fail(int status, const char* fmt, ...);
 // launch check: catches bad launch configurations without synchronising
 #define SURGEON_LAUNCH_CHECK() SURGEON_HIP_CHECK(hipGetLastError())
 
-// brackets the launches inside its scope with HIP events while profiling is on (surgeon_profile_begin/end)
+// Kernel timing aid (surgeon_profile_begin/end).  A ProfScope names the kernel class of the launches inside its
+// scope; while profiling is on, SURGEON_LAUNCH attaches a start and a stop event to each kernel it launches (the
+// events ride on the kernel's own dispatch packet: no extra packets between kernels), else it is a plain launch.
 struct ProfScope {
   ProfScope(int kind, hipStream_t stream);
   ~ProfScope();
-  int slot_;
-  hipStream_t stream_;
+  int prev_;
 };
+// true while profiling is on and a class is current: hands out the two events of the next kernel
+bool prof_next_events(hipEvent_t* start, hipEvent_t* stop);
+
+#define SURGEON_LAUNCH(kernel, grid, block, shmem, st, ...)                                              \
+  do {                                                                                                    \
+    hipEvent_t prof_e0_, prof_e1_;                                                                        \
+    if (surgeon::prof_next_events(&prof_e0_, &prof_e1_))                                                  \
+      hipExtLaunchKernelGGL(kernel, grid, block, shmem, st, prof_e0_, prof_e1_, 0, __VA_ARGS__);         \
+    else                                                                                                  \
+      hipLaunchKernelGGL(kernel, grid, block, shmem, st, __VA_ARGS__);                                    \
+  } while (0)
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

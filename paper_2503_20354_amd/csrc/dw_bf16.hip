@@ -58,10 +58,10 @@ int launch_unpack_dense(int dtype, const void* vals, const uint64_t* mask, const
   const int blocks = (int)std::min<int64_t>(ceil_div(ceil_div(n, 8), 256), 65536);
   ProfScope prof(SURGEON_PROF_DW_AUX, st);
   if (dtype == SURGEON_F32)
-    hipLaunchKernelGGL(unpack_dense_kernel<uint32_t>, dim3(blocks), dim3(256), 0, st, (const uint32_t*)vals, mask, word_rank,
+    SURGEON_LAUNCH(unpack_dense_kernel<uint32_t>, dim3(blocks), dim3(256), 0, st, (const uint32_t*)vals, mask, word_rank,
                        n, k_total - 1, (uint32_t*)dense);
   else
-    hipLaunchKernelGGL(unpack_dense_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)vals, mask, word_rank,
+    SURGEON_LAUNCH(unpack_dense_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (const uint16_t*)vals, mask, word_rank,
                        n, k_total - 1, (uint16_t*)dense);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
@@ -189,7 +189,7 @@ int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, con
   const int i_tiles = (int)ceil_div(K, kBfTile), o_tiles = (int)ceil_div(N, kBfTile);
   const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
   ProfScope prof(SURGEON_PROF_DW, st);
-  hipLaunchKernelGGL(dw_linear_bf16_kernel, grid, dim3(256), 0, st, M, K, N, i_tiles, rows_per_split,
+  SURGEON_LAUNCH(dw_linear_bf16_kernel, grid, dim3(256), 0, st, M, K, N, i_tiles, rows_per_split,
                      (const uint16_t*)A_dense, (const uint16_t*)dY, out);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;

@@ -1064,7 +1064,7 @@ static int launch_conv_variant(const ConvPlan& cp, const Packed<InT>& pk, const 
   if (rc != SURGEON_OK) return rc;
   const dim3 grid((unsigned)(cp.co_tiles * cp.g.ci_tiles), (unsigned)cp.splits, (unsigned)cp.z);
   ProfScope prof(SURGEON_PROF_DW, st);
-  hipLaunchKernelGGL(kernel, grid, dim3(512), cp.lds_bytes, st, cp.g, pk, (const InT*)dY, out);
+  SURGEON_LAUNCH(kernel, grid, dim3(512), cp.lds_bytes, st, cp.g, pk, (const InT*)dY, out);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }
@@ -1111,9 +1111,9 @@ static int launch_linear(const LinPlan& lp, const Packed<InT>& pk, const void* d
   const dim3 grid((unsigned)(lp.o_tiles * lp.g.i_tiles), (unsigned)lp.splits);
   ProfScope prof(SURGEON_PROF_DW, st);
   if (lp.mt == 4)
-    hipLaunchKernelGGL((dw_linear_kernel<InT, 4, 4, 32>), grid, dim3(256), 0, st, lp.g, pk, (const InT*)dY, out);
+    SURGEON_LAUNCH((dw_linear_kernel<InT, 4, 4, 32>), grid, dim3(256), 0, st, lp.g, pk, (const InT*)dY, out);
   else
-    hipLaunchKernelGGL((dw_linear_kernel<InT, 2, 2, 32>), grid, dim3(256), 0, st, lp.g, pk, (const InT*)dY, out);
+    SURGEON_LAUNCH((dw_linear_kernel<InT, 2, 2, 32>), grid, dim3(256), 0, st, lp.g, pk, (const InT*)dY, out);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }
@@ -1130,7 +1130,7 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   if (d->k_total == 0 || p.n == 0) {
     ProfScope prof(SURGEON_PROF_DW_AUX, st);
     const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 4096);
-    hipLaunchKernelGGL(fill_zero_f32_kernel, dim3(blocks), dim3(256), 0, st, dW, p.n_w);
+    SURGEON_LAUNCH(fill_zero_f32_kernel, dim3(blocks), dim3(256), 0, st, dW, p.n_w);
     SURGEON_LAUNCH_CHECK();
     return SURGEON_OK;
   }
@@ -1138,16 +1138,16 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   {
   ProfScope prof(SURGEON_PROF_DW_AUX, st);
   if (p.rank_words_per_group > 0) {
-    hipLaunchKernelGGL(rank_grouped_kernel, dim3((unsigned)ceil_div(p.rank_groups, kRankBlock / 64)), dim3(kRankBlock), 0, st,
+    SURGEON_LAUNCH(rank_grouped_kernel, dim3((unsigned)ceil_div(p.rank_groups, kRankBlock / 64)), dim3(kRankBlock), 0, st,
                        mask, p.n_words, p.rank_words_per_group, p.rank_groups, (uint32_t)p.rank_k_full, word_rank);
     SURGEON_LAUNCH_CHECK();
   } else {
-  hipLaunchKernelGGL(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
+  SURGEON_LAUNCH(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
                      block_sum);
   SURGEON_LAUNCH_CHECK();
-  hipLaunchKernelGGL(rank_scan_kernel, dim3(1), dim3(1024), 0, st, block_sum, (int)p.n_rank_blocks);
+  SURGEON_LAUNCH(rank_scan_kernel, dim3(1), dim3(1024), 0, st, block_sum, (int)p.n_rank_blocks);
   SURGEON_LAUNCH_CHECK();
-  hipLaunchKernelGGL(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
+  SURGEON_LAUNCH(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
                      (const uint32_t*)block_sum, word_rank);
   SURGEON_LAUNCH_CHECK();
   }
@@ -1173,7 +1173,7 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   if (p.splits > 1) {
     const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 8192);
     ProfScope prof(SURGEON_PROF_DW_AUX, st);
-    hipLaunchKernelGGL(dw_reduce_splits_kernel, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w, dW);
+    SURGEON_LAUNCH(dw_reduce_splits_kernel, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w, dW);
     SURGEON_LAUNCH_CHECK();
   }
   return SURGEON_OK;

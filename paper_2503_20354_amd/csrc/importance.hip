@@ -186,19 +186,19 @@ extern "C" int surgeon_grad_importance(const float* dW, int64_t n_w, float* G_ou
   ProfScope prof(SURGEON_PROF_IMPORTANCE, st);
   if (nb == 1) {
     if (vec4)
-      hipLaunchKernelGGL(sumsq_single_kernel<true>, dim3(1), dim3(kImpBlock), 0, st, dW, n_w, G_out);
+      SURGEON_LAUNCH(sumsq_single_kernel<true>, dim3(1), dim3(kImpBlock), 0, st, dW, n_w, G_out);
     else
-      hipLaunchKernelGGL(sumsq_single_kernel<false>, dim3(1), dim3(kImpBlock), 0, st, dW, n_w, G_out);
+      SURGEON_LAUNCH(sumsq_single_kernel<false>, dim3(1), dim3(kImpBlock), 0, st, dW, n_w, G_out);
     SURGEON_LAUNCH_CHECK();
     return SURGEON_OK;
   }
   double* partial = (double*)ws;
   if (vec4)
-    hipLaunchKernelGGL(sumsq_partial_kernel<true>, dim3(nb), dim3(kImpBlock), 0, st, dW, n_w, partial);
+    SURGEON_LAUNCH(sumsq_partial_kernel<true>, dim3(nb), dim3(kImpBlock), 0, st, dW, n_w, partial);
   else
-    hipLaunchKernelGGL(sumsq_partial_kernel<false>, dim3(nb), dim3(kImpBlock), 0, st, dW, n_w, partial);
+    SURGEON_LAUNCH(sumsq_partial_kernel<false>, dim3(nb), dim3(kImpBlock), 0, st, dW, n_w, partial);
   SURGEON_LAUNCH_CHECK();
-  hipLaunchKernelGGL(sumsq_final_kernel, dim3(1), dim3(kImpBlock), 0, st, (const double*)partial, nb, n_w, G_out);
+  SURGEON_LAUNCH(sumsq_final_kernel, dim3(1), dim3(kImpBlock), 0, st, (const double*)partial, nb, n_w, G_out);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }
@@ -245,12 +245,12 @@ extern "C" int surgeon_grad_importance_batched(const float* const* dW, const int
     double* partial = (double*)ws;
     if (blocks > 0) {
       if (vec4)
-        hipLaunchKernelGGL(sumsq_batched_partial_kernel<true>, dim3((unsigned)blocks), dim3(kImpBlock), 0, st, bt, partial);
+        SURGEON_LAUNCH(sumsq_batched_partial_kernel<true>, dim3((unsigned)blocks), dim3(kImpBlock), 0, st, bt, partial);
       else
-        hipLaunchKernelGGL(sumsq_batched_partial_kernel<false>, dim3((unsigned)blocks), dim3(kImpBlock), 0, st, bt, partial);
+        SURGEON_LAUNCH(sumsq_batched_partial_kernel<false>, dim3((unsigned)blocks), dim3(kImpBlock), 0, st, bt, partial);
       SURGEON_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(sumsq_batched_final_kernel, dim3((unsigned)bt.layers), dim3(kImpBlock), 0, st, bt,
+    SURGEON_LAUNCH(sumsq_batched_final_kernel, dim3((unsigned)bt.layers), dim3(kImpBlock), 0, st, bt,
                        (const double*)partial, G_out + i0);
     SURGEON_LAUNCH_CHECK();
   }

@@ -606,7 +606,7 @@ __global__ __launch_bounds__(256) void gsel_pack_kernel(const BitsT* __restrict_
 static int zero_mask(uint64_t* mask, int64_t n_words, hipStream_t st) {
   if (n_words == 0) return SURGEON_OK;
   const int blocks = (int)std::min<int64_t>(ceil_div(n_words, 256), 4096);
-  hipLaunchKernelGGL(fill_zero_u64_kernel, dim3(blocks), dim3(256), 0, st, mask, n_words);
+  SURGEON_LAUNCH(fill_zero_u64_kernel, dim3(blocks), dim3(256), 0, st, mask, n_words);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }
@@ -617,10 +617,10 @@ static int launch_wave_reg(const GroupPlan& p, const void* A, void* vals, uint64
   const dim3 grid((unsigned)ceil_div(p.n_groups, 4)), block(256);
   ProfScope prof(SURGEON_PROF_SELECT_PACK, st);
   if (idx)
-    hipLaunchKernelGGL((select_pack_wave_reg_kernel<E, BitsT, true>), grid, block, 0, st, (const BitsT*)A, (BitsT*)vals,
+    SURGEON_LAUNCH((select_pack_wave_reg_kernel<E, BitsT, true>), grid, block, 0, st, (const BitsT*)A, (BitsT*)vals,
                        mask, idx, p.n_groups, (int)p.g, (int)p.len_last, (int)p.k_full, (int)p.k_last);
   else
-    hipLaunchKernelGGL((select_pack_wave_reg_kernel<E, BitsT, false>), grid, block, 0, st, (const BitsT*)A,
+    SURGEON_LAUNCH((select_pack_wave_reg_kernel<E, BitsT, false>), grid, block, 0, st, (const BitsT*)A,
                        (BitsT*)vals, mask, idx, p.n_groups, (int)p.g, (int)p.len_last, (int)p.k_full, (int)p.k_last);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
@@ -645,10 +645,10 @@ template <typename BitsT>
 static int run_wave_mem(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx, hipStream_t st) {
   const dim3 grid((unsigned)ceil_div(p.n_groups, 4)), block(256);
   if (idx)
-    hipLaunchKernelGGL((select_pack_wave_mem_kernel<BitsT, true>), grid, block, 0, st, (const BitsT*)A, (BitsT*)vals,
+    SURGEON_LAUNCH((select_pack_wave_mem_kernel<BitsT, true>), grid, block, 0, st, (const BitsT*)A, (BitsT*)vals,
                        mask, idx, p.n_groups, (int)p.g, (int)p.len_last, (int)p.k_full, (int)p.k_last);
   else
-    hipLaunchKernelGGL((select_pack_wave_mem_kernel<BitsT, false>), grid, block, 0, st, (const BitsT*)A, (BitsT*)vals,
+    SURGEON_LAUNCH((select_pack_wave_mem_kernel<BitsT, false>), grid, block, 0, st, (const BitsT*)A, (BitsT*)vals,
                        mask, idx, p.n_groups, (int)p.g, (int)p.len_last, (int)p.k_full, (int)p.k_last);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
@@ -672,7 +672,7 @@ static int run_global(const GroupPlan& p, const void* A, void* vals, uint64_t* m
   uint2* cbase = (uint2*)w;
 
   const int init_blocks = (int)std::min<int64_t>(ceil_div(p.n_groups * 256, 256), 4096);
-  hipLaunchKernelGGL(gsel_init_kernel, dim3(init_blocks), dim3(256), 0, st, state, hist, p.n_groups,
+  SURGEON_LAUNCH(gsel_init_kernel, dim3(init_blocks), dim3(256), 0, st, state, hist, p.n_groups,
                      (uint32_t)p.k_full, (uint32_t)p.k_last);
   SURGEON_LAUNCH_CHECK();
   // digits from the top: 8,8,8,7 bits for the 31-bit fp32 key; 8,7 for the 15-bit bf16 key
@@ -680,25 +680,25 @@ static int run_global(const GroupPlan& p, const void* A, void* vals, uint64_t* m
   while (shift > 0) {
     const int nbits = shift >= 8 ? 8 : shift;
     shift -= nbits;
-    hipLaunchKernelGGL((gsel_hist_kernel<BitsT>), dim3((unsigned)(p.n_groups * bpg)), dim3(256), 0, st,
+    SURGEON_LAUNCH((gsel_hist_kernel<BitsT>), dim3((unsigned)(p.n_groups * bpg)), dim3(256), 0, st,
                        (const BitsT*)A, p.n, p.g, bpg, shift, nbits, (const GroupState*)state, hist);
     SURGEON_LAUNCH_CHECK();
-    hipLaunchKernelGGL(gsel_resolve_kernel, dim3((unsigned)p.n_groups), dim3(256), 0, st, state, hist, shift,
+    SURGEON_LAUNCH(gsel_resolve_kernel, dim3((unsigned)p.n_groups), dim3(256), 0, st, state, hist, shift,
                        shift == 0 ? 1 : 0);
     SURGEON_LAUNCH_CHECK();
   }
   const dim3 wgrid((unsigned)ceil_div(n_chunks, 4)), block(256);
-  hipLaunchKernelGGL((gsel_count_kernel<BitsT>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
+  SURGEON_LAUNCH((gsel_count_kernel<BitsT>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
                      (const GroupState*)state, ccount);
   SURGEON_LAUNCH_CHECK();
-  hipLaunchKernelGGL(gsel_scan_kernel, dim3((unsigned)p.n_groups), block, 0, st, (const GroupState*)state,
+  SURGEON_LAUNCH(gsel_scan_kernel, dim3((unsigned)p.n_groups), block, 0, st, (const GroupState*)state,
                      (const uint2*)ccount, cbase, cpg);
   SURGEON_LAUNCH_CHECK();
   if (idx)
-    hipLaunchKernelGGL((gsel_pack_kernel<BitsT, true>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
+    SURGEON_LAUNCH((gsel_pack_kernel<BitsT, true>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
                        (const GroupState*)state, (const uint2*)cbase, p.k_full, (BitsT*)vals, mask, idx);
   else
-    hipLaunchKernelGGL((gsel_pack_kernel<BitsT, false>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
+    SURGEON_LAUNCH((gsel_pack_kernel<BitsT, false>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
                        (const GroupState*)state, (const uint2*)cbase, p.k_full, (BitsT*)vals, mask, idx);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;

@@ -63,24 +63,40 @@ struct ProfRecord {
   hipEvent_t start, stop;
 };
 static bool g_prof_on = false;
+static int g_prof_kind = -1;  // class of the innermost live ProfScope
 static std::vector<ProfRecord> g_prof;
 
-ProfScope::ProfScope(int kind, hipStream_t stream) : slot_(-1), stream_(stream) {
-  if (!g_prof_on) return;
-  ProfRecord r;
-  r.kind = kind;
-  if (hipEventCreate(&r.start) != hipSuccess) return;
-  if (hipEventCreate(&r.stop) != hipSuccess) {
-    (void)hipEventDestroy(r.start);
-    return;
+ProfScope::ProfScope(int kind, hipStream_t) : prev_(g_prof_kind) { g_prof_kind = kind; }
+
+ProfScope::~ProfScope() { g_prof_kind = prev_; }
+
+// events are kept in a pool and reused by later profiling sessions: creating them costs host time per launch
+static std::vector<hipEvent_t> g_event_pool;
+static size_t g_events_used = 0;
+
+static bool pool_event(hipEvent_t* e) {
+  if (g_events_used == g_event_pool.size()) {
+    hipEvent_t fresh;
+    if (hipEventCreate(&fresh) != hipSuccess) return false;
+    g_event_pool.push_back(fresh);
   }
-  (void)hipEventRecord(r.start, stream);
-  g_prof.push_back(r);
-  slot_ = (int)g_prof.size() - 1;
+  *e = g_event_pool[g_events_used++];
+  return true;
 }
 
-ProfScope::~ProfScope() {
-  if (slot_ >= 0) (void)hipEventRecord(g_prof[slot_].stop, stream_);
+bool prof_next_events(hipEvent_t* start, hipEvent_t* stop) {
+  if (!g_prof_on || g_prof_kind < 0) return false;
+  ProfRecord r;
+  r.kind = g_prof_kind;
+  if (!pool_event(&r.start)) return false;
+  if (!pool_event(&r.stop)) {
+    --g_events_used;
+    return false;
+  }
+  g_prof.push_back(r);
+  *start = r.start;
+  *stop = r.stop;
+  return true;
 }
 
 }  // namespace surgeon
@@ -88,11 +104,8 @@ ProfScope::~ProfScope() {
 using namespace surgeon;
 
 extern "C" int surgeon_profile_begin(void) {
-  for (auto& r : g_prof) {
-    (void)hipEventDestroy(r.start);
-    (void)hipEventDestroy(r.stop);
-  }
   g_prof.clear();
+  g_events_used = 0;
   g_prof_on = true;
   return SURGEON_OK;
 }
@@ -114,10 +127,9 @@ extern "C" int surgeon_profile_end(int n_classes, double* ms, int64_t* launches)
       ms[r.kind] += (double)t;
       launches[r.kind] += 1;
     }
-    (void)hipEventDestroy(r.start);
-    (void)hipEventDestroy(r.stop);
   }
   g_prof.clear();
+  g_events_used = 0;
   return rc;
 }
 
