@@ -65,6 +65,8 @@ PrunePath choose_prune_path(const GroupPlan& p);
 // bf16 linear weight gradient: un-pack to a dense transient copy, then a dense bf16-MFMA contraction (dw_bf16.hip)
 int launch_unpack_dense(int dtype, const void* vals, const uint64_t* mask, const uint32_t* word_rank, int64_t n,
                         int64_t k_total, void* dense, hipStream_t st);
+int launch_unpack_grouped(const void* vals, const uint64_t* mask, int64_t n_words, int words_per_group, int64_t n_groups,
+                          int64_t k_full, int64_t n, int64_t k_total, void* dense, hipStream_t st);
 int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,
                        int64_t rows_per_split, hipStream_t st);
 constexpr int kBf16LinearTile = 128, kBf16LinearTokens = 64;

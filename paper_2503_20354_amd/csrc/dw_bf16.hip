@@ -52,6 +52,54 @@ __global__ __launch_bounds__(256) void unpack_dense_kernel(const T* __restrict__
   }
 }
 
+// The same un-pack when every group of `words_per_group` mask words is known to hold exactly k_full kept elements (the
+// packing's group length is a multiple of 64, at most 4096): one wavefront per group finds its words' positions with
+// a popcount and a prefix sum over the lanes, so no rank table is needed, and then expands word by word with all 64
+// lanes on the 64 elements of a word (reads of vals and writes of dense are contiguous).
+template <typename T>
+__global__ __launch_bounds__(256) void unpack_grouped_kernel(const T* __restrict__ vals, const uint64_t* __restrict__ mask,
+                                                             int64_t n_words, int words_per_group, int64_t n_groups,
+                                                             uint32_t k_full, int64_t k_last, int64_t n,
+                                                             T* __restrict__ dense) {
+  const int lane = threadIdx.x & 63;
+  const int64_t grp = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (grp >= n_groups) return;
+  const int64_t w0 = grp * words_per_group;
+  const bool has_word = lane < words_per_group && w0 + lane < n_words;
+  const uint64_t word = has_word ? mask[w0 + lane] : 0ull;
+  const uint32_t c = (uint32_t)__popcll(word);
+  uint32_t incl = c;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t up = (uint32_t)__shfl_up((int)incl, off, 64);
+    if (lane >= off) incl += up;
+  }
+  const uint32_t rank = (uint32_t)grp * k_full + incl - c;
+  const int n_here = (int)min((int64_t)words_per_group, n_words - w0);
+  for (int j = 0; j < n_here; ++j) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)word, j);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(word >> 32), j);
+    const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)rank, j);
+    const bool kept = (lane < 32 ? (lo >> lane) : (hi >> (lane - 32))) & 1u;
+    int64_t pos = (int64_t)__builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, r0));
+    pos = pos > k_last ? k_last : pos;
+    const T v = kept ? vals[pos] : (T)0;
+    const int64_t e = (w0 + j) * 64 + lane;
+    if (e < n) dense[e] = v;
+  }
+}
+
+int launch_unpack_grouped(const void* vals, const uint64_t* mask, int64_t n_words, int words_per_group, int64_t n_groups,
+                          int64_t k_full, int64_t n, int64_t k_total, void* dense, hipStream_t st) {
+  if (n == 0) return SURGEON_OK;
+  ProfScope prof(SURGEON_PROF_DW_AUX, st);
+  SURGEON_LAUNCH(unpack_grouped_kernel<uint16_t>, dim3((unsigned)ceil_div(n_groups, 4)), dim3(256), 0, st,
+                 (const uint16_t*)vals, mask, n_words, words_per_group, n_groups, (uint32_t)k_full, k_total - 1, n,
+                 (uint16_t*)dense);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
 int launch_unpack_dense(int dtype, const void* vals, const uint64_t* mask, const uint32_t* word_rank, int64_t n,
                         int64_t k_total, void* dense, hipStream_t st) {
   if (n == 0) return SURGEON_OK;

@@ -1134,8 +1134,10 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
     SURGEON_LAUNCH_CHECK();
     return SURGEON_OK;
   }
+  // the bf16 linear path un-packs whole groups when their positions are known in closed form: no rank table at all
+  const bool grouped_unpack = !p.conv && p.l.bf16_mfma && p.rank_words_per_group > 0;
   // rank table
-  {
+  if (!grouped_unpack) {
   ProfScope prof(SURGEON_PROF_DW_AUX, st);
   if (p.rank_words_per_group > 0) {
     SURGEON_LAUNCH(rank_grouped_kernel, dim3((unsigned)ceil_div(p.rank_groups, kRankBlock / 64)), dim3(kRankBlock), 0, st,
@@ -1163,7 +1165,9 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   int rc;
   if (!p.conv && p.l.bf16_mfma) {
     void* dense = w + p.off_dense;
-    rc = launch_unpack_dense(SURGEON_BF16, vals, mask, word_rank, p.n, d->k_total, dense, st);
+    rc = grouped_unpack ? launch_unpack_grouped(vals, mask, p.n_words, p.rank_words_per_group, p.rank_groups, p.rank_k_full,
+                                                p.n, d->k_total, dense, st)
+                        : launch_unpack_dense(SURGEON_BF16, vals, mask, word_rank, p.n, d->k_total, dense, st);
     if (rc == SURGEON_OK)
       rc = launch_linear_bf16(p.l.g.M, p.l.g.K, p.l.g.N, dense, dY, out, p.l.splits, p.l.g.rows_per_split, st);
   } else {
