@@ -72,7 +72,9 @@ int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, con
 constexpr int kBf16LinearTile = 128, kBf16LinearTokens = 64;
 
 constexpr int kWaveRegMaxGroup = 4096;  // largest group one wavefront keeps in registers (64 lanes x 64)
-constexpr int kGlobalHistChunk = 4096;  // elements per block in the histogram passes of the global path
-constexpr int kGlobalWaveChunk = 1024;  // elements per wavefront in the count / pack passes of the global path
+constexpr int kGlobalHistChunk = 16384;  // elements per block in the histogram passes of the global path
+constexpr int kGlobalWaveChunk = 4096;   // elements per wavefront in the count / pack passes of the global path
+constexpr int kGlobalDigitBits = 11;     // key bits resolved per histogram pass
+constexpr int kGlobalHistBins = 1 << kGlobalDigitBits;
 
 }  // namespace surgeon

@@ -412,7 +412,7 @@ __global__ void gsel_init_kernel(GroupState* __restrict__ st, uint32_t* __restri
                                  uint32_t k_full, uint32_t k_last) {
   const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = tid; i < n_groups * 256; i += stride) hist[i] = 0;
+  for (int64_t i = tid; i < n_groups * kGlobalHistBins; i += stride) hist[i] = 0;
   for (int64_t i = tid; i < n_groups; i += stride) {
     GroupState s;
     s.prefix = 0;
@@ -423,59 +423,91 @@ __global__ void gsel_init_kernel(GroupState* __restrict__ st, uint32_t* __restri
   }
 }
 
-// one digit pass: histogram of the digit at `shift` over the elements whose higher bits match the prefix
+// One digit pass: histogram of the digit at `shift` over the elements whose higher bits match the prefix.
+// A workgroup histograms kGlobalHistChunk elements in LDS and adds its non-empty bins to the group's histogram.
+// Lanes whose digit is 0 (in the first pass: every exact zero of a post-ReLU tensor) are counted with one ballot
+// per load instead of one LDS atomic each, which would all hit the same address.
 template <typename BitsT>
 __global__ __launch_bounds__(256) void gsel_hist_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
                                                         int64_t blocks_per_group, int shift, int nbits,
                                                         const GroupState* __restrict__ st,
                                                         uint32_t* __restrict__ hist) {
-  __shared__ uint32_t lh[256];
+  __shared__ uint32_t lh[kGlobalHistBins];
   const int64_t grp = blockIdx.x / blocks_per_group;
   const int64_t blk = blockIdx.x % blocks_per_group;
-  lh[threadIdx.x] = 0;
+  for (int b = threadIdx.x; b < kGlobalHistBins; b += 256) lh[b] = 0;
   __syncthreads();
   const int64_t gstart = grp * g;
   const int64_t gend = min(gstart + g, n);
   const int64_t e0 = gstart + blk * kGlobalHistChunk;
   const int hshift = shift + nbits;
-  const uint32_t want = st[grp].prefix >> hshift;
+  const uint32_t want = hshift >= 32 ? 0u : (st[grp].prefix >> hshift);
   const uint32_t dmask = (1u << nbits) - 1u;
-  for (int t = threadIdx.x; t < kGlobalHistChunk; t += 256) {
-    const int64_t e = e0 + t;
-    if (e < gend) {
-      const uint32_t key = (uint32_t)A[e] & Key<BitsT>::kMask;
-      if ((key >> hshift) == want) atomicAdd(&lh[(key >> shift) & dmask], 1u);
+  const int lane = threadIdx.x & 63;
+  uint32_t zeros = 0;  // elements of this wavefront with digit 0 (wave-uniform)
+  constexpr int kBatch = 8;
+  for (int t0 = 0; t0 < kGlobalHistChunk; t0 += 256 * kBatch) {
+    uint32_t key[kBatch];
+    bool ok[kBatch];
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int64_t e = e0 + t0 + q * 256 + threadIdx.x;
+      ok[q] = e < gend;
+      key[q] = (uint32_t)A[ok[q] ? e : gend - 1] & Key<BitsT>::kMask;
+    }
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const bool match = ok[q] && (hshift >= 32 || (key[q] >> hshift) == want);
+      const uint32_t digit = (key[q] >> shift) & dmask;
+      zeros += (uint32_t)__popcll(ballot64(match && digit == 0u));
+      if (match && digit != 0u) atomicAdd(&lh[digit], 1u);
     }
   }
+  if (lane == 0 && zeros) atomicAdd(&lh[0], zeros);
   __syncthreads();
-  const uint32_t c = lh[threadIdx.x];
-  if (c) atomicAdd(&hist[grp * 256 + threadIdx.x], c);
+  for (int b = threadIdx.x; b < kGlobalHistBins; b += 256) {
+    const uint32_t c = lh[b];
+    if (c) atomicAdd(&hist[grp * kGlobalHistBins + b], c);
+  }
 }
 
 // picks the digit holding the k_rem-th largest matching element, clears the histogram for the next pass
 __global__ __launch_bounds__(256) void gsel_resolve_kernel(GroupState* __restrict__ st, uint32_t* __restrict__ hist,
                                                            int shift, int last) {
-  __shared__ uint32_t c[256];
+  constexpr int kPer = kGlobalHistBins / 256;  // consecutive bins per thread
+  __shared__ uint32_t tot[256];
   const int64_t grp = blockIdx.x;
   const int tid = threadIdx.x;
-  c[tid] = hist[grp * 256 + tid];
-  hist[grp * 256 + tid] = 0;
+  uint32_t c[kPer];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
+    c[q] = hist[grp * kGlobalHistBins + tid * kPer + q];
+    hist[grp * kGlobalHistBins + tid * kPer + q] = 0;
+    sum += c[q];
+  }
+  tot[tid] = sum;
   const GroupState s = st[grp];
   __syncthreads();
-  uint32_t above = 0;
-  for (int b = tid + 1; b < 256; ++b) above += c[b];
-  if (above < s.k_rem && s.k_rem <= above + c[tid]) {  // exactly one digit satisfies this
-    GroupState o = s;
-    o.prefix = s.prefix | ((uint32_t)tid << shift);
-    o.k_rem = s.k_rem - above;
-    if (last) {
-      o.t_key = o.prefix;
-      o.need = o.k_rem;
+  uint32_t above = 0;  // matching elements in the bins above this thread's
+  for (int b = tid + 1; b < 256; ++b) above += tot[b];
+#pragma unroll
+  for (int q = kPer - 1; q >= 0; --q) {
+    if (above < s.k_rem && s.k_rem <= above + c[q]) {  // exactly one bin of one thread satisfies this
+      GroupState o = s;
+      o.prefix = s.prefix | ((uint32_t)(tid * kPer + q) << shift);
+      o.k_rem = s.k_rem - above;
+      if (last) {
+        o.t_key = o.prefix;
+        o.need = o.k_rem;
+      }
+      st[grp] = o;
     }
-    st[grp] = o;
+    above += c[q];
   }
 }
 
+// per wave chunk: elements above the threshold key and elements equal to it
 template <typename BitsT>
 __global__ __launch_bounds__(256) void gsel_count_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
                                                          int64_t chunks_per_group, int64_t n_chunks,
@@ -489,72 +521,90 @@ __global__ __launch_bounds__(256) void gsel_count_kernel(const BitsT* __restrict
   const int64_t gend = min(gstart + g, n);
   const int64_t e0 = gstart + chunk * kGlobalWaveChunk;
   const uint32_t t_key = st[grp].t_key;
-  uint32_t gt = 0, eq = 0;
-  for (int r = 0; r < kGlobalWaveChunk / 64; ++r) {
-    const int64_t e = e0 + r * 64 + lane;
-    const bool valid = e < gend;
-    const uint32_t key = valid ? ((uint32_t)A[e] & Key<BitsT>::kMask) : 0u;
-    gt += (uint32_t)__popcll(ballot64(valid && key > t_key));
-    eq += (uint32_t)__popcll(ballot64(valid && key == t_key));
+  uint32_t gt = 0, eq = 0;  // per-lane counts
+  constexpr int kBatch = 8;
+  for (int r0 = 0; r0 < kGlobalWaveChunk / 64; r0 += kBatch) {
+    uint32_t key[kBatch];
+    bool valid[kBatch];
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int64_t e = e0 + (r0 + q) * 64 + lane;
+      valid[q] = e < gend;
+      key[q] = (uint32_t)A[valid[q] ? e : gend - 1] & Key<BitsT>::kMask;
+    }
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      gt += (valid[q] && key[q] > t_key) ? 1u : 0u;
+      eq += (valid[q] && key[q] == t_key) ? 1u : 0u;
+    }
   }
+  gt = wave_sum_u32(gt);
+  eq = wave_sum_u32(eq);
   if (lane == 0) ccount[id] = make_uint2(gt, eq);
 }
 
-// per group: exclusive prefix over its chunks of (equal elements seen, values written)
-__global__ __launch_bounds__(256) void gsel_scan_kernel(const GroupState* __restrict__ st,
-                                                        const uint2* __restrict__ ccount, uint2* __restrict__ cbase,
-                                                        int64_t chunks_per_group) {
-  __shared__ uint32_t part[256];
+// Per group: exclusive prefix over its chunks of (equal elements seen, values written).  One workgroup of 1024
+// threads; a thread holds kScanPer consecutive chunks in registers, so a tile of 1024 * kScanPer chunks costs one
+// round of loads, two block-wide scans (ties first: how many tied elements a chunk may keep depends on the ties
+// before it) and one round of stores.
+constexpr int kScanPer = 8;
+__device__ __forceinline__ uint32_t block_excl_scan_1024(uint32_t v, uint32_t* lds17, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t incl = wave_incl_scan_u32(v, lane);
+  __syncthreads();  // lds17 may still be read from the previous call
+  if (lane == 63) lds17[wave] = incl;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t acc = 0;
+    for (int w = 0; w < 16; ++w) {
+      const uint32_t x = lds17[w];
+      lds17[w] = acc;
+      acc += x;
+    }
+    lds17[16] = acc;
+  }
+  __syncthreads();
+  *total = lds17[16];
+  return lds17[wave] + incl - v;
+}
+
+__global__ __launch_bounds__(1024) void gsel_scan_kernel(const GroupState* __restrict__ st,
+                                                         const uint2* __restrict__ ccount, uint2* __restrict__ cbase,
+                                                         int64_t chunks_per_group) {
+  __shared__ uint32_t lds17[17];
   const int64_t grp = blockIdx.x;
-  const int tid = threadIdx.x;
-  const int64_t per = (chunks_per_group + 255) / 256;
-  const int64_t c_begin = min((int64_t)tid * per, chunks_per_group);
-  const int64_t c_end = min(c_begin + per, chunks_per_group);
   const uint2* __restrict__ cc = ccount + grp * chunks_per_group;
   uint2* __restrict__ cb = cbase + grp * chunks_per_group;
   const uint32_t need = st[grp].need;
-
-  uint32_t s = 0;
-  for (int64_t c = c_begin; c < c_end; ++c) s += cc[c].y;
-  part[tid] = s;
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t acc = 0;
-    for (int t = 0; t < 256; ++t) {
-      const uint32_t v = part[t];
-      part[t] = acc;
-      acc += v;
+  uint32_t eq_carry = 0, out_carry = 0;
+  for (int64_t tile0 = 0; tile0 < chunks_per_group; tile0 += 1024 * kScanPer) {
+    const int64_t c0 = tile0 + (int64_t)threadIdx.x * kScanPer;
+    uint2 v[kScanPer];
+    uint32_t eq_sum = 0;
+#pragma unroll
+    for (int q = 0; q < kScanPer; ++q) {
+      v[q] = c0 + q < chunks_per_group ? cc[c0 + q] : make_uint2(0u, 0u);
+      eq_sum += v[q].y;
     }
-  }
-  __syncthreads();
-  uint32_t eq_before = part[tid];
-  uint32_t kept_sum = 0;
-  for (int64_t c = c_begin; c < c_end; ++c) {
-    const uint2 v = cc[c];
-    const uint32_t take = eq_before >= need ? 0u : min(need - eq_before, v.y);
-    cb[c].x = eq_before;
-    kept_sum += v.x + take;
-    eq_before += v.y;
-  }
-  __syncthreads();
-  part[tid] = kept_sum;
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t acc = 0;
-    for (int t = 0; t < 256; ++t) {
-      const uint32_t v = part[t];
-      part[t] = acc;
-      acc += v;
+    uint32_t eq_total, out_total;
+    uint32_t eq_before = eq_carry + block_excl_scan_1024(eq_sum, lds17, &eq_total);
+    uint32_t eqb[kScanPer], kept_sum = 0;
+#pragma unroll
+    for (int q = 0; q < kScanPer; ++q) {
+      eqb[q] = eq_before;
+      const uint32_t take = eq_before >= need ? 0u : min(need - eq_before, v[q].y);
+      v[q].x += take;  // values this chunk writes
+      kept_sum += v[q].x;
+      eq_before += v[q].y;
     }
-  }
-  __syncthreads();
-  uint32_t out_before = part[tid];
-  for (int64_t c = c_begin; c < c_end; ++c) {
-    const uint2 v = cc[c];
-    const uint32_t eqb = cb[c].x;
-    const uint32_t take = eqb >= need ? 0u : min(need - eqb, v.y);
-    cb[c].y = out_before;
-    out_before += v.x + take;
+    uint32_t out_before = out_carry + block_excl_scan_1024(kept_sum, lds17, &out_total);
+#pragma unroll
+    for (int q = 0; q < kScanPer; ++q) {
+      if (c0 + q < chunks_per_group) cb[c0 + q] = make_uint2(eqb[q], out_before);
+      out_before += v[q].x;
+    }
+    eq_carry += eq_total;
+    out_carry += out_total;
   }
 }
 
@@ -666,19 +716,19 @@ static int run_global(const GroupPlan& p, const void* A, void* vals, uint64_t* m
   GroupState* state = (GroupState*)w;
   w += align_up((size_t)p.n_groups * 16, 256);
   uint32_t* hist = (uint32_t*)w;
-  w += align_up((size_t)p.n_groups * 256 * 4, 256);
+  w += align_up((size_t)p.n_groups * kGlobalHistBins * 4, 256);
   uint2* ccount = (uint2*)w;
   w += align_up((size_t)n_chunks * 8, 256);
   uint2* cbase = (uint2*)w;
 
-  const int init_blocks = (int)std::min<int64_t>(ceil_div(p.n_groups * 256, 256), 4096);
+  const int init_blocks = (int)std::min<int64_t>(ceil_div(p.n_groups * kGlobalHistBins, 256), 4096);
   SURGEON_LAUNCH(gsel_init_kernel, dim3(init_blocks), dim3(256), 0, st, state, hist, p.n_groups,
                      (uint32_t)p.k_full, (uint32_t)p.k_last);
   SURGEON_LAUNCH_CHECK();
-  // digits from the top: 8,8,8,7 bits for the 31-bit fp32 key; 8,7 for the 15-bit bf16 key
+  // digits from the top: 11, 11, 9 bits for the 31-bit fp32 key; 11, 4 for the 15-bit bf16 key
   int shift = Key<BitsT>::kBits;
   while (shift > 0) {
-    const int nbits = shift >= 8 ? 8 : shift;
+    const int nbits = shift >= kGlobalDigitBits ? kGlobalDigitBits : shift;
     shift -= nbits;
     SURGEON_LAUNCH((gsel_hist_kernel<BitsT>), dim3((unsigned)(p.n_groups * bpg)), dim3(256), 0, st,
                        (const BitsT*)A, p.n, p.g, bpg, shift, nbits, (const GroupState*)state, hist);
@@ -691,7 +741,7 @@ static int run_global(const GroupPlan& p, const void* A, void* vals, uint64_t* m
   SURGEON_LAUNCH((gsel_count_kernel<BitsT>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
                      (const GroupState*)state, ccount);
   SURGEON_LAUNCH_CHECK();
-  SURGEON_LAUNCH(gsel_scan_kernel, dim3((unsigned)p.n_groups), block, 0, st, (const GroupState*)state,
+  SURGEON_LAUNCH(gsel_scan_kernel, dim3((unsigned)p.n_groups), dim3(1024), 0, st, (const GroupState*)state,
                      (const uint2*)ccount, cbase, cpg);
   SURGEON_LAUNCH_CHECK();
   if (idx)

@@ -51,7 +51,7 @@ size_t prune_pack_ws_bytes(const GroupPlan& p) {
   const int64_t n_chunks = p.n_groups * chunks_per_group;
   size_t bytes = 0;
   bytes += align_up((size_t)p.n_groups * 16, 256);       // per-group select state
-  bytes += align_up((size_t)p.n_groups * 256 * 4, 256);  // per-group digit histogram
+  bytes += align_up((size_t)p.n_groups * kGlobalHistBins * 4, 256);  // per-group digit histogram
   bytes += align_up((size_t)n_chunks * 8, 256);          // per-chunk (greater, equal) counts
   bytes += align_up((size_t)n_chunks * 8, 256);          // per-chunk (equal-before, out-before) bases
   return bytes;
