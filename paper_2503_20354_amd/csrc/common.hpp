@@ -57,6 +57,8 @@ bool make_group_plan(int64_t n, int64_t group_len, float r, GroupPlan* p);
 
 // workspace of the large-group (multi-kernel radix select) path of prune_pack; 0 for the in-register path
 size_t prune_pack_ws_bytes(const GroupPlan& p);
+// copies of a group's digit histogram in the large-group path (spreads the atomics of many workgroups)
+int global_hist_replicas(const GroupPlan& p);
 
 // selection paths of prune_pack
 enum PrunePath { PATH_WAVE_REG = 0, PATH_WAVE_MEM = 1, PATH_GLOBAL = 2 };

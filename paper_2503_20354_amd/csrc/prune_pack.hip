@@ -409,10 +409,10 @@ struct GroupState {
 };
 
 __global__ void gsel_init_kernel(GroupState* __restrict__ st, uint32_t* __restrict__ hist, int64_t n_groups,
-                                 uint32_t k_full, uint32_t k_last) {
+                                 uint32_t k_full, uint32_t k_last, int replicas) {
   const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = tid; i < n_groups * kGlobalHistBins; i += stride) hist[i] = 0;
+  for (int64_t i = tid; i < n_groups * replicas * kGlobalHistBins; i += stride) hist[i] = 0;
   for (int64_t i = tid; i < n_groups; i += stride) {
     GroupState s;
     s.prefix = 0;
@@ -431,7 +431,7 @@ template <typename BitsT>
 __global__ __launch_bounds__(256) void gsel_hist_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
                                                         int64_t blocks_per_group, int shift, int nbits,
                                                         const GroupState* __restrict__ st,
-                                                        uint32_t* __restrict__ hist) {
+                                                        uint32_t* __restrict__ hist, int replicas) {
   __shared__ uint32_t lh[kGlobalHistBins];
   const int64_t grp = blockIdx.x / blocks_per_group;
   const int64_t blk = blockIdx.x % blocks_per_group;
@@ -465,32 +465,61 @@ __global__ __launch_bounds__(256) void gsel_hist_kernel(const BitsT* __restrict_
   }
   if (lane == 0 && zeros) atomicAdd(&lh[0], zeros);
   __syncthreads();
+  uint32_t* __restrict__ h = hist + (grp * replicas + blk % replicas) * (int64_t)kGlobalHistBins;
   for (int b = threadIdx.x; b < kGlobalHistBins; b += 256) {
     const uint32_t c = lh[b];
-    if (c) atomicAdd(&hist[grp * kGlobalHistBins + b], c);
+    if (c) atomicAdd(&h[b], c);
   }
 }
 
-// picks the digit holding the k_rem-th largest matching element, clears the histogram for the next pass
+// exclusive prefix sum over the threads of a workgroup of up to 1024 threads (lds17: 17 words); *total = the sum
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* lds17, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = (blockDim.x + 63) >> 6;
+  const uint32_t incl = wave_incl_scan_u32(v, lane);
+  __syncthreads();  // lds17 may still be read from the previous call
+  if (lane == 63) lds17[wave] = incl;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t acc = 0;
+    for (int w = 0; w < n_waves; ++w) {
+      const uint32_t x = lds17[w];
+      lds17[w] = acc;
+      acc += x;
+    }
+    lds17[16] = acc;
+  }
+  __syncthreads();
+  *total = lds17[16];
+  return lds17[wave] + incl - v;
+}
+
+// Picks the digit holding the k_rem-th largest matching element and clears the histogram for the next pass.
+// The group's histogram exists in `replicas` copies (workgroups of the histogram pass spread their atomics over
+// them); they are summed here.
 __global__ __launch_bounds__(256) void gsel_resolve_kernel(GroupState* __restrict__ st, uint32_t* __restrict__ hist,
-                                                           int shift, int last) {
+                                                           int replicas, int shift, int last) {
   constexpr int kPer = kGlobalHistBins / 256;  // consecutive bins per thread
-  __shared__ uint32_t tot[256];
+  __shared__ uint32_t lds17[17];
   const int64_t grp = blockIdx.x;
   const int tid = threadIdx.x;
+  uint32_t* __restrict__ h = hist + grp * replicas * (int64_t)kGlobalHistBins;
   uint32_t c[kPer];
   uint32_t sum = 0;
 #pragma unroll
-  for (int q = 0; q < kPer; ++q) {
-    c[q] = hist[grp * kGlobalHistBins + tid * kPer + q];
-    hist[grp * kGlobalHistBins + tid * kPer + q] = 0;
-    sum += c[q];
+  for (int q = 0; q < kPer; ++q) c[q] = 0;
+  for (int rep = 0; rep < replicas; ++rep) {
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      c[q] += h[rep * kGlobalHistBins + tid * kPer + q];
+      h[rep * kGlobalHistBins + tid * kPer + q] = 0;
+    }
   }
-  tot[tid] = sum;
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) sum += c[q];
   const GroupState s = st[grp];
-  __syncthreads();
-  uint32_t above = 0;  // matching elements in the bins above this thread's
-  for (int b = tid + 1; b < 256; ++b) above += tot[b];
+  uint32_t total;
+  const uint32_t below = block_excl_scan(sum, lds17, &total);
+  uint32_t above = total - below - sum;  // matching elements in the bins above this thread's
 #pragma unroll
   for (int q = kPer - 1; q >= 0; --q) {
     if (above < s.k_rem && s.k_rem <= above + c[q]) {  // exactly one bin of one thread satisfies this
@@ -548,26 +577,6 @@ __global__ __launch_bounds__(256) void gsel_count_kernel(const BitsT* __restrict
 // round of loads, two block-wide scans (ties first: how many tied elements a chunk may keep depends on the ties
 // before it) and one round of stores.
 constexpr int kScanPer = 8;
-__device__ __forceinline__ uint32_t block_excl_scan_1024(uint32_t v, uint32_t* lds17, uint32_t* total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint32_t incl = wave_incl_scan_u32(v, lane);
-  __syncthreads();  // lds17 may still be read from the previous call
-  if (lane == 63) lds17[wave] = incl;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t acc = 0;
-    for (int w = 0; w < 16; ++w) {
-      const uint32_t x = lds17[w];
-      lds17[w] = acc;
-      acc += x;
-    }
-    lds17[16] = acc;
-  }
-  __syncthreads();
-  *total = lds17[16];
-  return lds17[wave] + incl - v;
-}
-
 __global__ __launch_bounds__(1024) void gsel_scan_kernel(const GroupState* __restrict__ st,
                                                          const uint2* __restrict__ ccount, uint2* __restrict__ cbase,
                                                          int64_t chunks_per_group) {
@@ -587,7 +596,7 @@ __global__ __launch_bounds__(1024) void gsel_scan_kernel(const GroupState* __res
       eq_sum += v[q].y;
     }
     uint32_t eq_total, out_total;
-    uint32_t eq_before = eq_carry + block_excl_scan_1024(eq_sum, lds17, &eq_total);
+    uint32_t eq_before = eq_carry + block_excl_scan(eq_sum, lds17, &eq_total);
     uint32_t eqb[kScanPer], kept_sum = 0;
 #pragma unroll
     for (int q = 0; q < kScanPer; ++q) {
@@ -597,7 +606,7 @@ __global__ __launch_bounds__(1024) void gsel_scan_kernel(const GroupState* __res
       kept_sum += v[q].x;
       eq_before += v[q].y;
     }
-    uint32_t out_before = out_carry + block_excl_scan_1024(kept_sum, lds17, &out_total);
+    uint32_t out_before = out_carry + block_excl_scan(kept_sum, lds17, &out_total);
 #pragma unroll
     for (int q = 0; q < kScanPer; ++q) {
       if (c0 + q < chunks_per_group) cb[c0 + q] = make_uint2(eqb[q], out_before);
@@ -627,26 +636,38 @@ __global__ __launch_bounds__(256) void gsel_pack_kernel(const BitsT* __restrict_
   uint32_t eq_run = base.x, run = base.y;
   BitsT* __restrict__ out_vals = vals + grp * k_full;
   uint32_t* __restrict__ out_idx = WITH_IDX ? idx + grp * k_full : nullptr;
-  for (int r = 0; r < kGlobalWaveChunk / 64; ++r) {
-    const int64_t e_first = e0 + r * 64;
-    if (e_first >= gend) break;
-    const int64_t e = e_first + lane;
-    const bool valid = e < gend;
-    const BitsT bits = valid ? A[e] : (BitsT)0;
-    const uint32_t key = (uint32_t)bits & Key<BitsT>::kMask;
-    const bool gt = valid && key > s.t_key;
-    const bool eq = valid && key == s.t_key;
-    const uint64_t beq = ballot64(eq);
-    const bool keep = gt || (eq && lane_rank(beq, eq_run) < s.need);
-    const uint64_t b = ballot64(keep);
-    if (keep) {
-      const uint32_t o = lane_rank(b, run);
-      out_vals[o] = bits;
-      if (WITH_IDX) out_idx[o] = (uint32_t)(e - gstart);
+  constexpr int kBatch = 8;  // rows of 64 elements requested together
+  for (int r0 = 0; r0 < kGlobalWaveChunk / 64; r0 += kBatch) {
+    if (e0 + r0 * 64 >= gend) break;
+    BitsT row[kBatch];
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int64_t e = e0 + (r0 + q) * 64 + lane;
+      row[q] = A[e < gend ? e : gend - 1];
     }
-    or_into_mask(mask, e_first, b, lane);
-    run += (uint32_t)__popcll(b);
-    eq_run += (uint32_t)__popcll(beq);
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int64_t e_first = e0 + (r0 + q) * 64;
+      if (e_first < gend) {
+        const int64_t e = e_first + lane;
+        const bool valid = e < gend;
+        const BitsT bits = row[q];
+        const uint32_t key = (uint32_t)bits & Key<BitsT>::kMask;
+        const bool gt = valid && key > s.t_key;
+        const bool eq = valid && key == s.t_key;
+        const uint64_t beq = ballot64(eq);
+        const bool keep = gt || (eq && lane_rank(beq, eq_run) < s.need);
+        const uint64_t b = ballot64(keep);
+        if (keep) {
+          const uint32_t o = lane_rank(b, run);
+          out_vals[o] = bits;
+          if (WITH_IDX) out_idx[o] = (uint32_t)(e - gstart);
+        }
+        or_into_mask(mask, e_first, b, lane);
+        run += (uint32_t)__popcll(b);
+        eq_run += (uint32_t)__popcll(beq);
+      }
+    }
   }
 }
 
@@ -716,14 +737,15 @@ static int run_global(const GroupPlan& p, const void* A, void* vals, uint64_t* m
   GroupState* state = (GroupState*)w;
   w += align_up((size_t)p.n_groups * 16, 256);
   uint32_t* hist = (uint32_t*)w;
-  w += align_up((size_t)p.n_groups * kGlobalHistBins * 4, 256);
+  const int replicas = global_hist_replicas(p);
+  w += align_up((size_t)p.n_groups * replicas * kGlobalHistBins * 4, 256);
   uint2* ccount = (uint2*)w;
   w += align_up((size_t)n_chunks * 8, 256);
   uint2* cbase = (uint2*)w;
 
-  const int init_blocks = (int)std::min<int64_t>(ceil_div(p.n_groups * kGlobalHistBins, 256), 4096);
+  const int init_blocks = (int)std::min<int64_t>(ceil_div(p.n_groups * replicas * kGlobalHistBins, 256), 4096);
   SURGEON_LAUNCH(gsel_init_kernel, dim3(init_blocks), dim3(256), 0, st, state, hist, p.n_groups,
-                     (uint32_t)p.k_full, (uint32_t)p.k_last);
+                     (uint32_t)p.k_full, (uint32_t)p.k_last, replicas);
   SURGEON_LAUNCH_CHECK();
   // digits from the top: 11, 11, 9 bits for the 31-bit fp32 key; 11, 4 for the 15-bit bf16 key
   int shift = Key<BitsT>::kBits;
@@ -731,9 +753,9 @@ static int run_global(const GroupPlan& p, const void* A, void* vals, uint64_t* m
     const int nbits = shift >= kGlobalDigitBits ? kGlobalDigitBits : shift;
     shift -= nbits;
     SURGEON_LAUNCH((gsel_hist_kernel<BitsT>), dim3((unsigned)(p.n_groups * bpg)), dim3(256), 0, st,
-                       (const BitsT*)A, p.n, p.g, bpg, shift, nbits, (const GroupState*)state, hist);
+                       (const BitsT*)A, p.n, p.g, bpg, shift, nbits, (const GroupState*)state, hist, replicas);
     SURGEON_LAUNCH_CHECK();
-    SURGEON_LAUNCH(gsel_resolve_kernel, dim3((unsigned)p.n_groups), dim3(256), 0, st, state, hist, shift,
+    SURGEON_LAUNCH(gsel_resolve_kernel, dim3((unsigned)p.n_groups), dim3(256), 0, st, state, hist, replicas, shift,
                        shift == 0 ? 1 : 0);
     SURGEON_LAUNCH_CHECK();
   }

@@ -45,13 +45,18 @@ PrunePath choose_prune_path(const GroupPlan& p) {
   return PATH_WAVE_MEM;
 }
 
+int global_hist_replicas(const GroupPlan& p) {
+  const int64_t blocks_per_group = ceil_div(p.g, kGlobalHistChunk);
+  return (int)std::min<int64_t>(std::max<int64_t>(blocks_per_group / 32, 1), 16);
+}
+
 size_t prune_pack_ws_bytes(const GroupPlan& p) {
   if (p.n == 0 || choose_prune_path(p) != PATH_GLOBAL) return 0;
   const int64_t chunks_per_group = ceil_div(p.g, kGlobalWaveChunk);
   const int64_t n_chunks = p.n_groups * chunks_per_group;
   size_t bytes = 0;
   bytes += align_up((size_t)p.n_groups * 16, 256);       // per-group select state
-  bytes += align_up((size_t)p.n_groups * kGlobalHistBins * 4, 256);  // per-group digit histogram
+  bytes += align_up((size_t)p.n_groups * global_hist_replicas(p) * kGlobalHistBins * 4, 256);  // per-group digit histograms
   bytes += align_up((size_t)n_chunks * 8, 256);          // per-chunk (greater, equal) counts
   bytes += align_up((size_t)n_chunks * 8, 256);          // per-chunk (equal-before, out-before) bases
   return bytes;
