@@ -118,9 +118,11 @@ int launch_unpack_dense(int dtype, const void* vals, const uint64_t* mask, const
 // ---------------------------------------------------------------------------------------------------------
 // dense TN contraction on bf16 MFMA
 // ---------------------------------------------------------------------------------------------------------
-constexpr int kBfTile = 128;               // workgroup tile: 128 out-features x 128 in-features
-constexpr int kBfTokens = 64;              // tokens per K-tile
-constexpr int kBfStride = kBfTile + 16;    // LDS row stride in elements: 288 bytes, 4 consecutive rows hit distinct banks
+// Workgroup = 4 wavefronts as 2 (out) x 2 (in); a wavefront owns PO x PI MFMA 32x32 tiles, so the workgroup tile is
+// 64*PO out-features x 64*PI in-features; TOK tokens per K-tile.  Two shapes are built: 128 x 128 with 64 tokens, and
+// 128 x 256 with 32 tokens, which issues 8 matrix instructions per 12 transposing LDS reads instead of 4 per 8 (the LDS
+// port is the limit of this kernel) and needs a quarter less L2 traffic per flop.
+constexpr int kBfPad = 16;  // LDS row padding in elements: 4 consecutive rows hit distinct banks
 
 // one 16-byte chunk (8 bf16) of row `row`, columns col0..col0+7, zero outside the matrix
 __device__ __forceinline__ u32x4 load_chunk(const uint16_t* __restrict__ src, int64_t row, int64_t row_end, int64_t col0,
@@ -133,55 +135,67 @@ __device__ __forceinline__ u32x4 load_chunk(const uint16_t* __restrict__ src, in
 }
 
 // 8 consecutive tokens (t0..t0+7) of feature (f0 + lane%16) as one MFMA operand register set
+template <int STRIDE>
 __device__ __forceinline__ bf16x8 read_operand(const uint16_t* tile, int t0, int f0, int lane) {
   const int s = lane & 15;
-  const uint16_t* p = tile + (t0 + (s >> 2)) * kBfStride + f0 + 4 * (s & 3);
+  const uint16_t* p = tile + (t0 + (s >> 2)) * STRIDE + f0 + 4 * (s & 3);
   typedef shortx4 __attribute__((address_space(3))) * lds_ptr;
   const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p);
-  const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * kBfStride));
+  const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * STRIDE));
   typedef short shortx8 __attribute__((ext_vector_type(8)));
   const shortx8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   return __builtin_bit_cast(bf16x8, both);
 }
 
-// Workgroup = 4 wavefronts as 2 (out) x 2 (in); wavefront tile 64 x 64 = 2 x 2 MFMA 32x32 tiles.
 // blockIdx.x = o_tile * i_tiles + i_tile, blockIdx.y = split along the tokens.
+template <int PO, int PI, int TOK>
 __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t K, int64_t N, int i_tiles,
                                                              int64_t rows_per_split, const uint16_t* __restrict__ A,
                                                              const uint16_t* __restrict__ dY, float* __restrict__ out) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ys[2][kBfTokens * kBfStride];
-  __shared__ __attribute__((aligned(16))) uint16_t As[2][kBfTokens * kBfStride];
+  constexpr int TO = 64 * PO, TI = 64 * PI, SO = TO + kBfPad, SI = TI + kBfPad;
+  constexpr int CY = TOK * TO / 8 / 256, CA = TOK * TI / 8 / 256;  // 16-byte chunks per thread and K-tile
+  static_assert(TOK * TO / 8 % 256 == 0 && TOK * TI / 8 % 256 == 0 && TOK % 16 == 0, "tile shape");
+  __shared__ __attribute__((aligned(16))) uint16_t Ys[2][TOK * SO];
+  __shared__ __attribute__((aligned(16))) uint16_t As[2][TOK * SI];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
-  const int64_t o0 = (int64_t)(blockIdx.x / i_tiles) * kBfTile, i0 = (int64_t)(blockIdx.x % i_tiles) * kBfTile;
+  const int64_t o0 = (int64_t)(blockIdx.x / i_tiles) * TO, i0 = (int64_t)(blockIdx.x % i_tiles) * TI;
   const int64_t m_begin = (int64_t)blockIdx.y * rows_per_split;
   const int64_t m_end = min(m_begin + rows_per_split, M);
 
-  floatx16 acc[2][2];
+  floatx16 acc[PO][PI];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < PO; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < PI; ++b)
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.0f;
 
-  // staging: thread t moves chunks t, t+256, t+512, t+768 of each operand tile (64 rows x 16 chunks of 8 elements)
-  u32x4 ry[4], ra[4];
+  // staging: thread t moves chunks t, t+256, ... of each operand tile (TOK rows x T/8 chunks of 8 elements)
+  u32x4 ry[CY], ra[CA];
   auto load_tile = [&](int64_t m0) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = tid + 256 * j, row = c >> 4, col = (c & 15) * 8;
+    for (int j = 0; j < CY; ++j) {
+      const int c = tid + 256 * j, row = c / (TO / 8), col = (c % (TO / 8)) * 8;
       ry[j] = load_chunk(dY, m0 + row, m_end, o0 + col, N, N);
+    }
+#pragma unroll
+    for (int j = 0; j < CA; ++j) {
+      const int c = tid + 256 * j, row = c / (TI / 8), col = (c % (TI / 8)) * 8;
       ra[j] = load_chunk(A, m0 + row, m_end, i0 + col, K, K);
     }
   };
   auto store_tile = [&](int buf) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = tid + 256 * j, row = c >> 4, col = (c & 15) * 8;
-      *reinterpret_cast<u32x4*>(&Ys[buf][row * kBfStride + col]) = ry[j];
-      *reinterpret_cast<u32x4*>(&As[buf][row * kBfStride + col]) = ra[j];
+    for (int j = 0; j < CY; ++j) {
+      const int c = tid + 256 * j, row = c / (TO / 8), col = (c % (TO / 8)) * 8;
+      *reinterpret_cast<u32x4*>(&Ys[buf][row * SO + col]) = ry[j];
+    }
+#pragma unroll
+    for (int j = 0; j < CA; ++j) {
+      const int c = tid + 256 * j, row = c / (TI / 8), col = (c % (TI / 8)) * 8;
+      *reinterpret_cast<u32x4*>(&As[buf][row * SI + col]) = ra[j];
     }
   };
 
@@ -191,25 +205,24 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
   }
   __syncthreads();
   int buf = 0;
-  for (int64_t m0 = m_begin; m0 < m_end; m0 += kBfTokens) {
-    const bool more = m0 + kBfTokens < m_end;
-    if (more) load_tile(m0 + kBfTokens);  // in flight while the matrix cores work on the current tile
+  for (int64_t m0 = m_begin; m0 < m_end; m0 += TOK) {
+    const bool more = m0 + TOK < m_end;
+    if (more) load_tile(m0 + TOK);  // in flight while the matrix cores work on the current tile
     const uint16_t* ys = Ys[buf];
     const uint16_t* as = As[buf];
     const int blk = lane >> 4;  // 16-lane block: rows 16*(blk&1).., contraction half blk>>1
 #pragma unroll
-    for (int ks = 0; ks < kBfTokens; ks += 16) {
+    for (int ks = 0; ks < TOK; ks += 16) {
       const int t0 = ks + 8 * (blk >> 1);
-      bf16x8 a[2], b[2];
+      bf16x8 a[PO], b[PI];
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        a[q] = read_operand(ys, t0, wm * 64 + q * 32 + 16 * (blk & 1), lane);
-        b[q] = read_operand(as, t0, wn * 64 + q * 32 + 16 * (blk & 1), lane);
-      }
+      for (int q = 0; q < PO; ++q) a[q] = read_operand<SO>(ys, t0, wm * 32 * PO + q * 32 + 16 * (blk & 1), lane);
 #pragma unroll
-      for (int p = 0; p < 2; ++p)
+      for (int q = 0; q < PI; ++q) b[q] = read_operand<SI>(as, t0, wn * 32 * PI + q * 32 + 16 * (blk & 1), lane);
 #pragma unroll
-        for (int q = 0; q < 2; ++q) acc[p][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[p], b[q], acc[p][q], 0, 0, 0);
+      for (int p = 0; p < PO; ++p)
+#pragma unroll
+        for (int q = 0; q < PI; ++q) acc[p][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[p], b[q], acc[p][q], 0, 0, 0);
     }
     if (more) store_tile(buf ^ 1);
     __syncthreads();
@@ -220,25 +233,30 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
   float* __restrict__ dst = out + (int64_t)blockIdx.y * N * K;
   const int col = lane & 31, half = lane >> 5;
 #pragma unroll
-  for (int p = 0; p < 2; ++p)
+  for (int p = 0; p < PO; ++p)
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int64_t i = i0 + wn * 64 + q * 32 + col;
+    for (int q = 0; q < PI; ++q) {
+      const int64_t i = i0 + wn * 32 * PI + q * 32 + col;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int64_t o = o0 + wm * 64 + p * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+        const int64_t o = o0 + wm * 32 * PO + p * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
         if (o < N && i < K) dst[o * K + i] = acc[p][q][v];
       }
     }
 }
 
 int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,
-                       int64_t rows_per_split, hipStream_t st) {
-  const int i_tiles = (int)ceil_div(K, kBfTile), o_tiles = (int)ceil_div(N, kBfTile);
+                       int64_t rows_per_split, int wide, hipStream_t st) {
+  const int tile_i = wide ? kBf16LinearTileWide : kBf16LinearTile;
+  const int i_tiles = (int)ceil_div(K, tile_i), o_tiles = (int)ceil_div(N, kBf16LinearTile);
   const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
   ProfScope prof(SURGEON_PROF_DW, st);
-  SURGEON_LAUNCH(dw_linear_bf16_kernel, grid, dim3(256), 0, st, M, K, N, i_tiles, rows_per_split,
-                     (const uint16_t*)A_dense, (const uint16_t*)dY, out);
+  if (wide)
+    SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 4, kBf16LinearTokensWide>), grid, dim3(256), 0, st, M, K, N, i_tiles,
+                   rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);
+  else
+    SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 2, kBf16LinearTokens>), grid, dim3(256), 0, st, M, K, N, i_tiles,
+                   rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }

@@ -809,6 +809,7 @@ struct LinPlan {
   int mt, nt, tm;
   int o_tiles, splits;
   bool bf16_mfma;  // dense bf16-MFMA path: un-pack to the workspace, then contract
+  int bf16_wide;   // 1: the 128 x 256 tile of the bf16 path
 };
 
 struct DwPlan {
@@ -977,14 +978,19 @@ static int plan_linear(const surgeon_layer_desc* d, LinPlan* lp) {
   g.M = d->M; g.K = d->K; g.N = d->N;
   g.n_w = d->N * d->K;
   lp->bf16_mfma = d->dtype == SURGEON_BF16 && d->N % 8 == 0 && d->K % 8 == 0 && d->M > 0;
+  lp->bf16_wide = 0;
   if (lp->bf16_mfma) {
     lp->mt = lp->nt = 0;
-    lp->tm = kBf16LinearTokens;
+    // the wide tile when the in-feature dimension fills it and the layer is large enough to keep the chip busy with it
+    lp->bf16_wide = (d->K % kBf16LinearTileWide == 0 &&
+                     ceil_div(d->N, kBf16LinearTile) * (d->K / kBf16LinearTileWide) >= 36) ? 1 : 0;
+    const int tile_i = lp->bf16_wide ? kBf16LinearTileWide : kBf16LinearTile;
+    lp->tm = lp->bf16_wide ? kBf16LinearTokensWide : kBf16LinearTokens;
     lp->o_tiles = (int)ceil_div(d->N, kBf16LinearTile);
-    g.i_tiles = (int)ceil_div(d->K, kBf16LinearTile);
+    g.i_tiles = (int)ceil_div(d->K, tile_i);
     int64_t per;
     const int64_t k_tiles = ceil_div(d->M, lp->tm);
-    const double tile_us = 2.0 * kBf16LinearTile * kBf16LinearTile * lp->tm / (0.35 * kBf16FlopsPerCuPerUs);
+    const double tile_us = 2.0 * kBf16LinearTile * tile_i * lp->tm / (0.35 * kBf16FlopsPerCuPerUs);
     lp->splits = choose_splits(k_tiles, (int64_t)lp->o_tiles * g.i_tiles, kLinSlots, tile_us, g.n_w, &per);
     g.rows_per_split = per * lp->tm;
     return SURGEON_OK;
@@ -1169,7 +1175,7 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
                                                 p.n, d->k_total, dense, st)
                         : launch_unpack_dense(SURGEON_BF16, vals, mask, word_rank, p.n, d->k_total, dense, st);
     if (rc == SURGEON_OK)
-      rc = launch_linear_bf16(p.l.g.M, p.l.g.K, p.l.g.N, dense, dY, out, p.l.splits, p.l.g.rows_per_split, st);
+      rc = launch_linear_bf16(p.l.g.M, p.l.g.K, p.l.g.N, dense, dY, out, p.l.splits, p.l.g.rows_per_split, p.l.bf16_wide, st);
   } else {
     rc = p.conv ? launch_conv<InT>(p.c, pk, dY, out, st) : launch_linear<InT>(p.l, pk, dY, out, st);
   }
