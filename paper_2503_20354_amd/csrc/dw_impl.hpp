@@ -402,7 +402,8 @@ struct RunStager {
       const bool has_run = q < gm.n_runs && cv < gm.Ci;
       e_const[r] = (uint32_t)((ci * gm.H + dih) * gm.W + iw0);
       ih_const[r] = has_run ? dih : -(1 << 30);
-      const int in_valid = min(kRunLen * fs, gm.W - iw0);  // input pixels of the run that exist in the row (1..32)
+      // input pixels of the run that exist in the row and whose LDS column exists in the patch row (1..32)
+      const int in_valid = min(min(kRunLen, gm.Wv - col0) * fs, gm.W - iw0);
       nv_mask[r] = (q < gm.n_runs) ? (0xffffffffu >> (32 - in_valid)) : 0u;
       lds_dst[r] = (int)(c * gm.PS + pr * gm.PW) + col0 + gm.pad;
     }

@@ -185,8 +185,8 @@ def test_dw_linear_ratio0_is_dense_gradient():
 
 
 def run_conv(shape, dtype, r, dist="relu", seed=0):
-    Nb, Ci, H, W, Co, k, st = shape
-    pad = k // 2
+    Nb, Ci, H, W, Co, k, st = shape[:7]
+    pad = shape[7] if len(shape) > 7 else k // 2
     print("dw conv", shape, dtype, "r=%g" % r, flush=True)
     OH, OW = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
     A = wl.draw((Nb, Ci, H, W), dist, dtype, seed + 1)
@@ -218,6 +218,23 @@ def test_dw_conv(dtype, shape):
         assert rel_l2(got, ref) <= TOL[dtype]
     got, _ = run_conv(shape, dtype, 1.0)
     assert not got.any()
+
+
+# unpadded and strided filters: the patch kept in LDS is narrower than the input row
+UNPADDED_SHAPES = [
+    # Nb, Ci, H, W, Co, k, stride, pad
+    (2, 5, 9, 14, 65, 7, 2, 0), (3, 1, 7, 8, 65, 3, 3, 0), (3, 1, 33, 32, 65, 3, 2, 0), (2, 16, 17, 17, 16, 3, 1, 0),
+    (2, 33, 16, 16, 64, 1, 2, 0), (2, 8, 20, 20, 24, 5, 2, 1), (1, 64, 14, 14, 65, 3, 3, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", UNPADDED_SHAPES)
+def test_dw_conv_unpadded_and_strided(dtype, shape):
+    for r in (0.0, 0.5):
+        got, ref = run_conv(shape, dtype, r, seed=sum(shape))
+        assert got.shape == ref.shape
+        assert rel_l2(got, ref) <= TOL[dtype]
 
 
 def test_dw_group_hint_changes_nothing():
