@@ -325,7 +325,7 @@ __device__ __forceinline__ void conv_stage_tile(const ConvGeom& gm, const Packed
 // selects: an offset at or beyond the buffer size returns 0.  The host enables the path only when every buffer is
 // smaller than 2 GiB, so kOutOfRange is out of range for all of them.
 constexpr int kRunLen = 16;
-constexpr int kRunsPerThread = 2;
+constexpr int kRunsPerThread = 4;
 constexpr uint32_t kOutOfRange = 0x80000000u;
 constexpr int kRawBufferWord3 = 0x00020000;  // raw buffer, 32-bit data format (gfx9 family)
 
@@ -361,11 +361,11 @@ struct DyVec<uint16_t> {
     return __builtin_bit_cast(floatx4, w);
   }
 };
-__device__ __forceinline__ uint32_t load_val_bits(__amdgpu_buffer_rsrc_t r, uint32_t voff, float) {
-  return __builtin_amdgcn_raw_buffer_load_b32(r, voff, 0, 0);
+__device__ __forceinline__ uint32_t load_val_bits(__amdgpu_buffer_rsrc_t r, uint32_t voff, float, uint32_t soff = 0) {
+  return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
 }
-__device__ __forceinline__ uint32_t load_val_bits(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint16_t) {
-  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, voff, 0, 0) << 16;  // bf16 -> the fp32 with the same value
+__device__ __forceinline__ uint32_t load_val_bits(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint16_t, uint32_t soff = 0) {
+  return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0) << 16;  // bf16 -> the fp32 with the same value
 }
 
 // Per-thread state of the run-based staging: everything that does not change from K-tile to K-tile is computed once.
@@ -380,6 +380,11 @@ struct RunStager {
   int lds_dst[kRunsPerThread];       // float offset of the run inside the patch area
   uint32_t y_voff[NY];               // byte offset of this thread's j-th dY vector inside the K-tile's dY block
   int y_lds;                         // float offset of the first of them in the dY area (the j-th is 16*SY*j... further)
+  // dY rows that are not vector-aligned (e.g. 7x7 maps) are staged element by element: a thread keeps its position
+  // k = ltid % P and walks over the output channels ltid / P + j * (256 / P)
+  static constexpr int NE = TCO * P / kConvLoaders;
+  uint32_t ys_voff;                  // byte offset of the first of them, or kOutOfRange past the valid positions
+  int ys_lds;
 
   __device__ __forceinline__ void init(const ConvGeom& gm, const Packed<InT>& pk, const InT* __restrict__ dY, int ltid,
                                        int co0, int ci0, int u0) {
@@ -416,6 +421,9 @@ struct RunStager {
       y_voff[j] = ok ? (uint32_t)(c * gm.OH * gm.OW + 4 * k4) * ES : kOutOfRange;
     }
     y_lds = (ltid / (P / 4)) * SY + 4 * (ltid % (P / 4));
+    const int ks = ltid % P, cs = ltid / P;
+    ys_voff = ks < valid_pos ? (uint32_t)(cs * gm.OH * gm.OW + ks) * ES : kOutOfRange;
+    ys_lds = cs * SY + ks;
   }
 
   // the metadata loads of K-tile `tile`
@@ -439,20 +447,27 @@ struct RunStager {
   }
 
   // Stages K-tile `tile` from the metadata in `cur`; replaces `cur` by the metadata of K-tile tile + 1 when
-  // prefetch_next is set.  NV = 16 / 8: every run of this geometry has exactly NV elements; 0: they vary.
-  // FS = fill_step (1 or 2): LDS column t of a run is input pixel t * FS of it.
-  template <int NV, int FS>
+  // prefetch_next is set.  LEN = 16 / 8: LDS columns a run can have in this geometry; FULL: every run has exactly
+  // LEN; FS = fill_step (1 or 2): LDS column t of a run is input pixel t * FS of it; DYV: dY rows are vector-aligned.
+  template <int LEN, bool FULL, int FS, bool DYV>
   __device__ __forceinline__ void stage(const ConvGeom& gm, float* __restrict__ buf, int tile, int co0,
                                         RunLoad (&cur)[kRunsPerThread], bool prefetch_next) const {
-    constexpr int LEN = NV ? NV : kRunLen;
     float* __restrict__ dYs = buf;
     float* __restrict__ As = buf + TCO * SY;
     const int b = tile / gm.tiles_per_img;
     const int oh0 = (tile - b * gm.tiles_per_img) * gm.R;
     const uint32_t y_soff = (uint32_t)(((b * gm.Co + co0) * gm.OH + oh0) * gm.OW) * ES;
-    typename DyVec<InT>::raw_t y[NY];
+    typename DyVec<InT>::raw_t y[DYV ? NY : 1];
+    uint32_t ys[DYV ? 1 : NE];
+    if constexpr (DYV) {
 #pragma unroll
-    for (int j = 0; j < NY; ++j) y[j] = DyVec<InT>::load(r_dy, y_voff[j], y_soff);
+      for (int j = 0; j < NY; ++j) y[j] = DyVec<InT>::load(r_dy, y_voff[j], y_soff);
+    } else {
+      // rows past Co read another channel or image (or 0 past the end): they only reach output rows that are never stored
+      const uint32_t step = (uint32_t)((kConvLoaders / P) * gm.OH * gm.OW) * ES;
+#pragma unroll
+      for (int j = 0; j < NE; ++j) ys[j] = load_val_bits(r_dy, ys_voff, InT(), y_soff + (uint32_t)j * step);
+    }
 
     uint32_t bits[kRunsPerThread], raw[kRunsPerThread][LEN];
 #pragma unroll
@@ -488,13 +503,18 @@ struct RunStager {
 #pragma unroll
         for (int t = 0; t < LEN; ++t) {
           const uint32_t keep = (uint32_t)(((int32_t)(bits[r] << (31 - t * FS))) >> 31);  // all ones if the pixel's bit is set
-          if (NV || ((nv_mask[r] >> (t * FS)) & 1u)) dst[t] = __uint_as_float(raw[r][t] & keep);
+          if (FULL || ((nv_mask[r] >> (t * FS)) & 1u)) dst[t] = __uint_as_float(raw[r][t] & keep);
         }
       }
     }
+    if constexpr (DYV) {
 #pragma unroll
-    for (int j = 0; j < NY; ++j)
-      *reinterpret_cast<floatx4*>(&dYs[y_lds + j * (kConvLoaders / (P / 4)) * SY]) = DyVec<InT>::widen4(y[j]);
+      for (int j = 0; j < NY; ++j)
+        *reinterpret_cast<floatx4*>(&dYs[y_lds + j * (kConvLoaders / (P / 4)) * SY]) = DyVec<InT>::widen4(y[j]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < NE; ++j) dYs[ys_lds + j * (kConvLoaders / P) * SY] = __uint_as_float(ys[j]);
+    }
   }
 };
 
@@ -554,21 +574,36 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
       RunLoad meta[kRunsPerThread];
       if (t_begin < t_end) rs.issue(gm, t_begin, meta);
       __syncthreads();  // the patches are cleared before the first run is written
-      // uniform choice of the run length handling: all runs full (W a multiple of 16), all of 8 elements, or mixed
-      const int nv = (gm.Wv % kRunLen == 0 && gm.W % (kRunLen * gm.fill_step) == 0) ? kRunLen
-                     : ((gm.Wv == 8 && gm.W == 8 * gm.fill_step) ? 8 : 0);
+      // uniform choice of the variant: runs of up to 16 or up to 8 columns, all runs full or not, every pixel or every
+      // second one, dY rows vector-aligned or not
+      const int fs = gm.fill_step;
+      const bool len8 = gm.Wv <= 8;
+      const bool full = len8 ? (gm.Wv == 8 && gm.W == 8 * fs) : (gm.Wv % kRunLen == 0 && gm.W % (kRunLen * fs) == 0);
       for (int tile = t_begin; tile < t_end; ++tile) {
         float* __restrict__ buf = smem + ((tile - t_begin) & 1) * buf_floats;
         const bool more = tile + 1 < t_end;
-        if (gm.fill_step == 1) {
-          if (nv == kRunLen) rs.template stage<kRunLen, 1>(gm, buf, tile, co0, meta, more);
-          else if (nv == 8) rs.template stage<8, 1>(gm, buf, tile, co0, meta, more);
-          else rs.template stage<0, 1>(gm, buf, tile, co0, meta, more);
-        } else {
-          if (nv == kRunLen) rs.template stage<kRunLen, 2>(gm, buf, tile, co0, meta, more);
-          else if (nv == 8) rs.template stage<8, 2>(gm, buf, tile, co0, meta, more);
-          else rs.template stage<0, 2>(gm, buf, tile, co0, meta, more);
+#define SURGEON_STAGE(LEN, FULL, FS) \
+  do { \
+    if (gm.dy_vec) rs.template stage<LEN, FULL, FS, true>(gm, buf, tile, co0, meta, more); \
+    else rs.template stage<LEN, FULL, FS, false>(gm, buf, tile, co0, meta, more); \
+  } while (0)
+        bool staged = false;
+        if constexpr (KHC == 1 && KW == 1) {  // only a strided 1x1 filter skips pixels inside a run
+          if (fs == 2) {
+            staged = true;
+            if (len8 && full) SURGEON_STAGE(8, true, 2);
+            else if (len8) SURGEON_STAGE(8, false, 2);
+            else if (full) SURGEON_STAGE(16, true, 2);
+            else SURGEON_STAGE(16, false, 2);
+          }
         }
+        if (!staged) {
+          if (len8 && full) SURGEON_STAGE(8, true, 1);
+          else if (len8) SURGEON_STAGE(8, false, 1);
+          else if (full) SURGEON_STAGE(16, true, 1);
+          else SURGEON_STAGE(16, false, 1);
+        }
+#undef SURGEON_STAGE
         __syncthreads();  // this buffer is complete; the other one is no longer being read
       }
       return;
@@ -927,7 +962,7 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
         // the run-based staging (far cheaper per element) needs at most kRunsPerThread runs per staging thread
         const int wv = g.fill_step == 1 ? std::min(g.W, pw - g.pad) : std::min(pw, (g.W + g.fill_step - 1) / g.fill_step);
         const bool runs_fit = (int64_t)tci * pr * ceil_div(std::max(wv, 1), kRunLen) <= kRunsPerThread * kConvLoaders &&
-                              n_buf == 2 && (r * g.OW) % 4 == 0;
+                              n_buf == 2;
         const double score = (double)(r * g.OW) / p - (p == 64 ? 0.0 : 0.05) + (runs_fit ? 0.5 : 0.0);
         if (score > best_score) {
           best_score = score;
@@ -961,7 +996,7 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
   // the run-based staging addresses vals and dY with 32-bit byte offsets whose top bit marks "no access"
   const int64_t es = d->dtype == SURGEON_F32 ? 4 : 2;
   const bool small_buffers = d->k_total * es < big && (int64_t)g.Nb * g.Co * g.OH * g.OW * es < big;
-  g.run_mode = ((g.fill_step == 1 || (g.fill_step == 2 && g.pad == 0)) && g.n_buf == 2 && g.dy_vec && g.Wv >= 1 && small_buffers &&
+  g.run_mode = ((g.fill_step == 1 || (g.fill_step == 2 && g.pad == 0)) && g.n_buf == 2 && g.Wv >= 1 && small_buffers &&
                 g.n_runs <= kRunsPerThread * kConvLoaders) ? 1 : 0;
   int64_t per;
   const double tile_us = 2.0 * tco * tci * cp->khc * cp->kw_t * cp->p / kFlopsPerCuPerUs;
