@@ -71,6 +71,8 @@ int launch_unpack_grouped(const void* vals, const uint64_t* mask, int64_t n_word
                           int64_t k_full, int64_t n, int64_t k_total, void* dense, hipStream_t st);
 int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,
                        int64_t rows_per_split, int wide, hipStream_t st);
+int launch_conv1x1_bf16(int Nb, int Ci, int Co, int HW, const void* A_dense, const void* dY, float* out, int splits,
+                        int64_t ktiles_per_split, hipStream_t st);
 constexpr int kBf16LinearTile = 128, kBf16LinearTokens = 64;          // 128 x 128 tile, 64 tokens per K-tile
 constexpr int kBf16LinearTileWide = 256, kBf16LinearTokensWide = 32;  // 128 (out) x 256 (in) tile, 32 tokens
 

@@ -76,6 +76,60 @@ __global__ __launch_bounds__(256) void unpack_grouped_kernel(const T* __restrict
   }
   const uint32_t rank = (uint32_t)grp * k_full + incl - c;
   const int n_here = (int)min((int64_t)words_per_group, n_words - w0);
+  // 8 words = 512 elements per step: lane l expands byte l % 8 of word l / 8 (8 consecutive elements, one 16-byte store)
+  for (int j0 = 0; j0 < n_here; j0 += 8) {
+    const int src = j0 + (lane >> 3);
+    const bool has = src < n_here;
+    const uint32_t w_lo = (uint32_t)__shfl((int)(uint32_t)word, src & 63, 64);
+    const uint32_t w_hi = (uint32_t)__shfl((int)(uint32_t)(word >> 32), src & 63, 64);
+    const uint32_t r0 = (uint32_t)__shfl((int)rank, src & 63, 64);
+    const uint64_t w = has ? (((uint64_t)w_hi << 32) | w_lo) : 0ull;
+    const int sh = 8 * (lane & 7);
+    const uint32_t bits = (uint32_t)(w >> sh) & 0xffu;
+    const int64_t first = (int64_t)r0 + __popcll(w & ((1ull << sh) - 1ull));
+    T v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      int64_t pos = first + __builtin_popcount(bits & ((1u << t) - 1u));
+      pos = pos > k_last ? k_last : pos;
+      v[t] = vals[pos];
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      if (!((bits >> t) & 1u)) v[t] = (T)0;
+    const int64_t e0 = (w0 + src) * 64 + sh;
+    if (has && e0 + 8 <= n) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) dense[e0 + t] = v[t];  // contiguous: merged into one 16-byte store by the compiler
+    } else if (has) {
+      for (int t = 0; t < 8 && e0 + t < n; ++t) dense[e0 + t] = v[t];
+    }
+  }
+}
+
+// Variant for short groups (a few mask words, e.g. token rows of 64-256 features): the wavefront expands one word per
+// step with all 64 lanes on its 64 elements, which keeps every lane busy where the 8-elements-per-lane form above
+// would use only 8 lanes per word.
+template <typename T>
+__global__ __launch_bounds__(256) void unpack_grouped_short_kernel(const T* __restrict__ vals,
+                                                                   const uint64_t* __restrict__ mask, int64_t n_words,
+                                                                   int words_per_group, int64_t n_groups, uint32_t k_full,
+                                                                   int64_t k_last, int64_t n, T* __restrict__ dense) {
+  const int lane = threadIdx.x & 63;
+  const int64_t grp = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (grp >= n_groups) return;
+  const int64_t w0 = grp * words_per_group;
+  const bool has_word = lane < words_per_group && w0 + lane < n_words;
+  const uint64_t word = has_word ? mask[w0 + lane] : 0ull;
+  const uint32_t c = (uint32_t)__popcll(word);
+  uint32_t incl = c;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t up = (uint32_t)__shfl_up((int)incl, off, 64);
+    if (lane >= off) incl += up;
+  }
+  const uint32_t rank = (uint32_t)grp * k_full + incl - c;
+  const int n_here = (int)min((int64_t)words_per_group, n_words - w0);
   for (int j = 0; j < n_here; ++j) {
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)word, j);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(word >> 32), j);
@@ -93,9 +147,14 @@ int launch_unpack_grouped(const void* vals, const uint64_t* mask, int64_t n_word
                           int64_t k_full, int64_t n, int64_t k_total, void* dense, hipStream_t st) {
   if (n == 0) return SURGEON_OK;
   ProfScope prof(SURGEON_PROF_DW_AUX, st);
-  SURGEON_LAUNCH(unpack_grouped_kernel<uint16_t>, dim3((unsigned)ceil_div(n_groups, 4)), dim3(256), 0, st,
-                 (const uint16_t*)vals, mask, n_words, words_per_group, n_groups, (uint32_t)k_full, k_total - 1, n,
-                 (uint16_t*)dense);
+  if (words_per_group <= 4)
+    SURGEON_LAUNCH(unpack_grouped_short_kernel<uint16_t>, dim3((unsigned)ceil_div(n_groups, 4)), dim3(256), 0, st,
+                   (const uint16_t*)vals, mask, n_words, words_per_group, n_groups, (uint32_t)k_full, k_total - 1, n,
+                   (uint16_t*)dense);
+  else
+    SURGEON_LAUNCH(unpack_grouped_kernel<uint16_t>, dim3((unsigned)ceil_div(n_groups, 4)), dim3(256), 0, st,
+                   (const uint16_t*)vals, mask, n_words, words_per_group, n_groups, (uint32_t)k_full, k_total - 1, n,
+                   (uint16_t*)dense);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }
@@ -243,6 +302,141 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
         if (o < N && i < K) dst[o * K + i] = acc[p][q][v];
       }
     }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// 1x1 stride-1 convolution in NCHW = per image a contraction over the pixels, which are the contiguous index of
+// both operands: dW[co][ci] = sum_b sum_p dY[b][co][p] * A[b][ci][p].  Tiles are staged [channel][pixel] and read
+// back with plain 16-byte LDS reads (8 consecutive pixels of one channel are exactly one MFMA operand register set).
+// Same shape as the linear kernel: 128 x 128 tile, 4 wavefronts, 64 pixels per K-tile; a K-tile never spans images.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kPxTile = 128, kPxTok = 64, kPxStride = kPxTok + 8;  // row stride 144 bytes: 8 rows cover all banks
+constexpr size_t kPxLdsBytes = (size_t)2 * 2 * kPxTile * kPxStride * sizeof(uint16_t);
+
+// CE = elements per staged chunk: 8 (16 bytes; HW a multiple of 8) or 4 (8 bytes; HW a multiple of 4, e.g. 14 x 14 maps)
+template <int CE>
+__global__ __launch_bounds__(256) void dw_conv1x1_bf16_kernel(int Nb, int Ci, int Co, int HW, int i_tiles, int tiles_per_img,
+                                                              int64_t ktiles_per_split, const uint16_t* __restrict__ A,
+                                                              const uint16_t* __restrict__ dY, float* __restrict__ out) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t px_lds[];
+  constexpr int TILE_ELEMS = kPxTile * kPxStride;
+  constexpr int CPR = kPxTok / CE;                // chunks per tile row
+  constexpr int CH = kPxTile * CPR / 256;         // chunks per thread, operand and K-tile
+  typedef uint32_t chunk_t __attribute__((ext_vector_type(CE / 2)));
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int o0 = (int)(blockIdx.x / i_tiles) * kPxTile, i0 = (int)(blockIdx.x % i_tiles) * kPxTile;
+  const int64_t n_ktiles = (int64_t)Nb * tiles_per_img;
+  const int64_t t_begin = (int64_t)blockIdx.y * ktiles_per_split;
+  const int64_t t_end = min(t_begin + ktiles_per_split, n_ktiles);
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.0f;
+
+  // one chunk = CE consecutive pixels of one channel; zero past the channel count or the image
+  auto chunk = [&](const uint16_t* __restrict__ src, int C, int c0, int64_t t, int c) {
+    const int b = (int)(t / tiles_per_img), p0 = (int)(t - (int64_t)b * tiles_per_img) * kPxTok;
+    const int row = c / CPR, px = p0 + (c % CPR) * CE;
+    const bool ok = c0 + row < C && px < HW;  // HW is a multiple of CE
+    const int64_t off = ok ? ((int64_t)b * C + c0 + row) * HW + px : 0;
+    chunk_t v = *reinterpret_cast<const chunk_t*>(src + off);
+    if (!ok) v = chunk_t(0);
+    return v;
+  };
+  chunk_t ry[CH], ra[CH];
+  auto load_tile = [&](int64_t t) {
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      ry[j] = chunk(dY, Co, o0, t, tid + 256 * j);
+      ra[j] = chunk(A, Ci, i0, t, tid + 256 * j);
+    }
+  };
+  auto store_tile = [&](int buf) {
+    uint16_t* ys = px_lds + (2 * buf) * TILE_ELEMS;
+    uint16_t* as = ys + TILE_ELEMS;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const int c = tid + 256 * j, row = c / CPR, col = (c % CPR) * CE;
+      *reinterpret_cast<chunk_t*>(&ys[row * kPxStride + col]) = ry[j];
+      *reinterpret_cast<chunk_t*>(&as[row * kPxStride + col]) = ra[j];
+    }
+  };
+
+  if (t_begin < t_end) {
+    load_tile(t_begin);
+    store_tile(0);
+  }
+  __syncthreads();
+  int buf = 0;
+  const int row32 = lane & 31, khalf = 8 * (lane >> 5);
+  for (int64_t t = t_begin; t < t_end; ++t) {
+    const bool more = t + 1 < t_end;
+    if (more) load_tile(t + 1);
+    const uint16_t* ys = px_lds + (2 * buf) * TILE_ELEMS;
+    const uint16_t* as = ys + TILE_ELEMS;
+#pragma unroll
+    for (int ks = 0; ks < kPxTok; ks += 16) {
+      bf16x8 a[2], b[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        a[q] = *reinterpret_cast<const bf16x8*>(&ys[(wm * 64 + q * 32 + row32) * kPxStride + ks + khalf]);
+        b[q] = *reinterpret_cast<const bf16x8*>(&as[(wn * 64 + q * 32 + row32) * kPxStride + ks + khalf]);
+      }
+#pragma unroll
+      for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) acc[p][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[p], b[q], acc[p][q], 0, 0, 0);
+    }
+    if (more) store_tile(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // 32x32 result tile: lane holds column lane%32 and rows 8*(v/4) + 4*(lane/32) + v%4, v = 0..15
+  float* __restrict__ dst = out + (int64_t)blockIdx.y * Co * Ci;
+  const int col = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int p = 0; p < 2; ++p)
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int i = i0 + wn * 64 + q * 32 + col;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int o = o0 + wm * 64 + p * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+        if (o < Co && i < Ci) dst[(int64_t)o * Ci + i] = acc[p][q][v];
+      }
+    }
+}
+
+template <int CE>
+static int launch_conv1x1_bf16_ce(int Nb, int Ci, int Co, int HW, const void* A_dense, const void* dY, float* out,
+                                  int splits, int64_t ktiles_per_split, hipStream_t st) {
+  const int i_tiles = (int)ceil_div(Ci, kPxTile), o_tiles = (int)ceil_div(Co, kPxTile);
+  const int tiles_per_img = (int)ceil_div(HW, kPxTok);
+  const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
+  static bool attr_set = false;
+  if (!attr_set) {
+    SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)dw_conv1x1_bf16_kernel<CE>,
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPxLdsBytes));
+    attr_set = true;
+  }
+  ProfScope prof(SURGEON_PROF_DW, st);
+  SURGEON_LAUNCH(dw_conv1x1_bf16_kernel<CE>, grid, dim3(256), kPxLdsBytes, st, Nb, Ci, Co, HW, i_tiles, tiles_per_img,
+                 ktiles_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+int launch_conv1x1_bf16(int Nb, int Ci, int Co, int HW, const void* A_dense, const void* dY, float* out, int splits,
+                        int64_t ktiles_per_split, hipStream_t st) {
+  if (HW % 8 == 0) return launch_conv1x1_bf16_ce<8>(Nb, Ci, Co, HW, A_dense, dY, out, splits, ktiles_per_split, st);
+  return launch_conv1x1_bf16_ce<4>(Nb, Ci, Co, HW, A_dense, dY, out, splits, ktiles_per_split, st);
 }
 
 int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,

@@ -835,6 +835,8 @@ constexpr size_t kMaxLds = 160 * 1024;
 
 struct ConvPlan {
   ConvGeom g;
+  int gemm1x1;               // 1: bf16 1x1 stride-1 layer handled as a dense contraction over the pixels
+  int64_t gemm_ktiles_per_split;
   int khc, kw_t, mt, nt, p;  // kernel variant
   int co_tiles, z, splits;
   size_t lds_bytes;
@@ -898,6 +900,22 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
   g.OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1;
   g.OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
   g.n_w = (int64_t)g.Co * g.Ci * g.KH * g.KW;
+  cp->gemm1x1 = 0;
+  if (d->dtype == SURGEON_BF16 && g.KH == 1 && g.KW == 1 && g.stride == 1 && g.pad == 0 && (g.H * g.W) % 4 == 0) {
+    // a 1x1 stride-1 convolution has no tap reuse to pay for un-packing inside the tile loads: un-pack once to a
+    // dense transient copy and contract over the pixels on the bf16 matrix cores (as the bf16 linear path does)
+    cp->gemm1x1 = 1;
+    cp->khc = 1; cp->kw_t = 1; cp->mt = cp->nt = 0; cp->p = 0; cp->z = 1; cp->lds_bytes = 0;
+    cp->co_tiles = (int)ceil_div(g.Co, kBf16LinearTile);
+    g.ci_tiles = (int)ceil_div(g.Ci, kBf16LinearTile);
+    g.Ci_in = g.Ci; g.fold = 0; g.magic_fold = 0;
+    const int64_t k_tiles = (int64_t)g.Nb * ceil_div((int64_t)g.H * g.W, kBf16LinearTokens);
+    const double tile_us = 2.0 * kBf16LinearTile * kBf16LinearTile * kBf16LinearTokens / (0.35 * kBf16FlopsPerCuPerUs);
+    int64_t per;
+    cp->splits = choose_splits(k_tiles, (int64_t)cp->co_tiles * g.ci_tiles, kLinSlots, tile_us, g.n_w, &per);
+    cp->gemm_ktiles_per_split = per;
+    return SURGEON_OK;
+  }
   if (g.KH == 3 && g.KW == 3) {
     cp->khc = 3; cp->kw_t = 3;
   } else if (g.KW == 1 || g.KW == 3 || g.KW == 5 || g.KW == 7) {
@@ -1087,7 +1105,7 @@ static int plan_dw(const surgeon_layer_desc* d, DwPlan* p) {
   p->off_part = off;
   if (p->splits > 1) off += align_up((size_t)p->splits * (size_t)p->n_w * 4, 256);
   p->off_dense = off;
-  if (!p->conv && p->l.bf16_mfma) off += align_up((size_t)p->n * 2, 256);  // transient dense activation
+  if ((!p->conv && p->l.bf16_mfma) || (p->conv && p->c.gemm1x1)) off += align_up((size_t)p->n * 2, 256);  // transient dense activation
   p->ws_bytes = off;
   return SURGEON_OK;
 }
@@ -1177,7 +1195,8 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
     return SURGEON_OK;
   }
   // the bf16 linear path un-packs whole groups when their positions are known in closed form: no rank table at all
-  const bool grouped_unpack = !p.conv && p.l.bf16_mfma && p.rank_words_per_group > 0;
+  const bool dense_path = (!p.conv && p.l.bf16_mfma) || (p.conv && p.c.gemm1x1);
+  const bool grouped_unpack = dense_path && p.rank_words_per_group > 0;
   // rank table
   if (!grouped_unpack) {
   ProfScope prof(SURGEON_PROF_DW_AUX, st);
@@ -1205,13 +1224,18 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   pk.n_words = p.n_words;
   float* out = p.splits > 1 ? part : dW;
   int rc;
-  if (!p.conv && p.l.bf16_mfma) {
+  if (dense_path) {
     void* dense = w + p.off_dense;
     rc = grouped_unpack ? launch_unpack_grouped(vals, mask, p.n_words, p.rank_words_per_group, p.rank_groups, p.rank_k_full,
                                                 p.n, d->k_total, dense, st)
                         : launch_unpack_dense(SURGEON_BF16, vals, mask, word_rank, p.n, d->k_total, dense, st);
-    if (rc == SURGEON_OK)
-      rc = launch_linear_bf16(p.l.g.M, p.l.g.K, p.l.g.N, dense, dY, out, p.l.splits, p.l.g.rows_per_split, p.l.bf16_wide, st);
+    if (rc == SURGEON_OK) {
+      if (p.conv)
+        rc = launch_conv1x1_bf16(p.c.g.Nb, p.c.g.Ci, p.c.g.Co, p.c.g.H * p.c.g.W, dense, dY, out, p.c.splits,
+                                 p.c.gemm_ktiles_per_split, st);
+      else
+        rc = launch_linear_bf16(p.l.g.M, p.l.g.K, p.l.g.N, dense, dY, out, p.l.splits, p.l.g.rows_per_split, p.l.bf16_wide, st);
+    }
   } else {
     rc = p.conv ? launch_conv<InT>(p.c, pk, dY, out, st) : launch_linear<InT>(p.l, pk, dY, out, st);
   }
