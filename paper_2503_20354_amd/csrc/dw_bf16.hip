@@ -1,4 +1,5 @@
-// bf16 weight gradient of linear layers (Eq. 2, Alg. 1 lines 11-12) on the bf16 matrix cores.
+// bf16 weight gradient of linear layers and of 1x1 stride-1 convolutions (Eq. 2, Alg. 1 lines 11-12) on the bf16
+// matrix cores.
 //
 // At bf16 MFMA rates (16x the fp32 rate) un-packing inside the GEMM's tile loads would cost more vector-ALU time
 // than the contraction itself, so this path does what Alg. 1 line 11 says literally: un-pack the cached activation
@@ -10,6 +11,7 @@
 // back with ds_read_b64_tr_b16, gfx950's transposing LDS read: within a block of 16 lanes, lane i receives in element
 // r the value source lane 4r + i/4 pointed at, element i%4.  Pointing source lane s at [token t0 + s/4][feature
 // f0 + 4*(s%4)] therefore gives lane i the 4 consecutive tokens t0..t0+3 of feature f0 + i.
+// (A 1x1 convolution in NCHW has the contraction index, the pixels, as the FAST index of both operands: no transpose.)
 #include "common.hpp"
 
 namespace surgeon {

@@ -14,7 +14,10 @@
 //   linear : dW[o][i] = sum_m dY[m][o] * A[m][i]; K-tiles of TM tokens.
 // Long contractions are split over workgroups; each split writes its partial tile to the workspace and a last
 // kernel adds the splits in index order (no floating-point atomics: results are reproducible bit for bit).
-// Inputs in bf16 are widened to fp32 while staging (exact), so all products and sums are fp32 MFMA.
+// bf16 inputs: convolutions with taps widen to fp32 while staging (exact) and feed either the fp32 MFMA or, where the
+// patch layout allows, the bf16 MFMA after re-narrowing (the original bits); linear layers and 1x1 stride-1
+// convolutions un-pack once to a dense transient copy and run a dense bf16 contraction (dw_bf16.hip).
+// Accumulation is always fp32.
 #include <algorithm>
 #include <type_traits>
 
