@@ -185,14 +185,32 @@ int launch_unpack_dense(int dtype, const void* vals, const uint64_t* mask, const
 // port is the limit of this kernel) and needs a quarter less L2 traffic per flop.
 constexpr int kBfPad = 16;  // LDS row padding in elements: 4 consecutive rows hit distinct banks
 
-// one 16-byte chunk (8 bf16) of row `row`, columns col0..col0+7, zero outside the matrix
+// one 16-byte chunk (8 bf16) of row `row`, columns col0..col0+7, zero outside the matrix.  ALIGNED: the row pitch is a
+// multiple of 8 elements, so a chunk is inside or outside as a whole and is one 16-byte load; otherwise the chunk is
+// gathered from eight 2-byte loads, each with its own column check.
+template <bool ALIGNED>
 __device__ __forceinline__ u32x4 load_chunk(const uint16_t* __restrict__ src, int64_t row, int64_t row_end, int64_t col0,
                                             int64_t n_cols, int64_t ld) {
-  const bool ok = row < row_end && col0 < n_cols;  // n_cols is a multiple of 8: a chunk is inside or outside as a whole
-  const int64_t off = ok ? row * ld + col0 : 0;
-  u32x4 v = *reinterpret_cast<const u32x4*>(src + off);
-  if (!ok) v = u32x4{0, 0, 0, 0};
-  return v;
+  if constexpr (ALIGNED) {
+    const bool ok = row < row_end && col0 < n_cols;
+    const int64_t off = ok ? row * ld + col0 : 0;
+    u32x4 v = *reinterpret_cast<const u32x4*>(src + off);
+    if (!ok) v = u32x4{0, 0, 0, 0};
+    return v;
+  } else {
+    u32x4 v = {0, 0, 0, 0};
+    if (row < row_end && col0 < n_cols) {
+      const uint16_t* __restrict__ p = src + row * ld + col0;
+      const int left = (int)min((int64_t)8, n_cols - col0);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t e0 = 2 * q < left ? (uint32_t)p[2 * q] : 0u;
+        const uint32_t e1 = 2 * q + 1 < left ? (uint32_t)p[2 * q + 1] : 0u;
+        v[q] = e0 | (e1 << 16);
+      }
+    }
+    return v;
+  }
 }
 
 // 8 consecutive tokens (t0..t0+7) of feature (f0 + lane%16) as one MFMA operand register set
@@ -209,7 +227,7 @@ __device__ __forceinline__ bf16x8 read_operand(const uint16_t* tile, int t0, int
 }
 
 // blockIdx.x = o_tile * i_tiles + i_tile, blockIdx.y = split along the tokens.
-template <int PO, int PI, int TOK>
+template <int PO, int PI, int TOK, bool YALIGNED>
 __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t K, int64_t N, int i_tiles,
                                                              int64_t rows_per_split, const uint16_t* __restrict__ A,
                                                              const uint16_t* __restrict__ dY, float* __restrict__ out) {
@@ -239,12 +257,12 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
 #pragma unroll
     for (int j = 0; j < CY; ++j) {
       const int c = tid + 256 * j, row = c / (TO / 8), col = (c % (TO / 8)) * 8;
-      ry[j] = load_chunk(dY, m0 + row, m_end, o0 + col, N, N);
+      ry[j] = load_chunk<YALIGNED>(dY, m0 + row, m_end, o0 + col, N, N);
     }
 #pragma unroll
     for (int j = 0; j < CA; ++j) {
       const int c = tid + 256 * j, row = c / (TI / 8), col = (c % (TI / 8)) * 8;
-      ra[j] = load_chunk(A, m0 + row, m_end, i0 + col, K, K);
+      ra[j] = load_chunk<true>(A, m0 + row, m_end, i0 + col, K, K);
     }
   };
   auto store_tile = [&](int buf) {
@@ -447,11 +465,14 @@ int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, con
   const int i_tiles = (int)ceil_div(K, tile_i), o_tiles = (int)ceil_div(N, kBf16LinearTile);
   const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
   ProfScope prof(SURGEON_PROF_DW, st);
-  if (wide)
-    SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 4, kBf16LinearTokensWide>), grid, dim3(256), 0, st, M, K, N, i_tiles,
+  if (N % 8 != 0)  // dY rows are not 16-byte aligned: element-wise dY loads (never chosen together with the wide tile)
+    SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 2, kBf16LinearTokens, false>), grid, dim3(256), 0, st, M, K, N, i_tiles,
+                   rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);
+  else if (wide)
+    SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 4, kBf16LinearTokensWide, true>), grid, dim3(256), 0, st, M, K, N, i_tiles,
                    rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);
   else
-    SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 2, kBf16LinearTokens>), grid, dim3(256), 0, st, M, K, N, i_tiles,
+    SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 2, kBf16LinearTokens, true>), grid, dim3(256), 0, st, M, K, N, i_tiles,
                    rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;

@@ -1034,12 +1034,12 @@ static int plan_linear(const surgeon_layer_desc* d, LinPlan* lp) {
   LinGeom& g = lp->g;
   g.M = d->M; g.K = d->K; g.N = d->N;
   g.n_w = d->N * d->K;
-  lp->bf16_mfma = d->dtype == SURGEON_BF16 && d->N % 8 == 0 && d->K % 8 == 0 && d->M > 0;
+  lp->bf16_mfma = d->dtype == SURGEON_BF16 && d->K % 8 == 0 && d->M > 0;
   lp->bf16_wide = 0;
   if (lp->bf16_mfma) {
     lp->mt = lp->nt = 0;
     // the wide tile when the in-feature dimension fills it and the layer is large enough to keep the chip busy with it
-    lp->bf16_wide = (d->K % kBf16LinearTileWide == 0 &&
+    lp->bf16_wide = (d->K % kBf16LinearTileWide == 0 && d->N % 8 == 0 &&
                      ceil_div(d->N, kBf16LinearTile) * (d->K / kBf16LinearTileWide) >= 36) ? 1 : 0;
     const int tile_i = lp->bf16_wide ? kBf16LinearTileWide : kBf16LinearTile;
     lp->tm = lp->bf16_wide ? kBf16LinearTokensWide : kBf16LinearTokens;

@@ -165,9 +165,11 @@ def test_dw_linear(dtype, M, K, N):
     assert not got.any()  # nothing cached: the gradient is exactly zero
 
 
-@pytest.mark.parametrize("M,K,N", [(130, 136, 264), (1000, 768, 384), (77, 8, 8), (4096, 320, 1280), (257, 1032, 72)])
+@pytest.mark.parametrize("M,K,N", [(130, 136, 264), (1000, 768, 384), (77, 8, 8), (4096, 320, 1280), (257, 1032, 72),
+                                   (2000, 768, 19), (333, 72, 1), (129, 264, 131)])
 def test_dw_linear_bf16_matrix_core_path(M, K, N):
-    """bf16 linears with in/out features that are multiples of 8 take the dense bf16-MFMA path."""
+    """bf16 linears whose in-feature count is a multiple of 8 take the dense bf16-MFMA path; an out-feature count
+    that is not (a 19-class head) reads dY element by element."""
     for r in (0.5, 0.93):
         got, ref = run_linear(M, K, N, "bf16", r, seed=3 * M + K)
         assert rel_l2(got, ref) <= TOL["bf16"]
