@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBPS = 8000.0       # MI355X HBM3E
 PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+PEAK_VALU_F32_TFLOPS = 78.6  # non-packed fp32 FMA on the vector ALU
 METRIC = "pruned-activation GB/s (select+pack) + packed-dW TFLOP/s, % of MI355X roofline"
 WORKLOAD_NAMES = {
     0: "cfg0 single linear 512->256, 64 tokens, fp32, r=0.5",
@@ -92,7 +93,8 @@ def main():
     G_dev = torch.zeros(len(layers), dtype=torch.float32, device=dev)
     G_host = torch.zeros(len(layers), dtype=torch.float32).pin_memory()
     m_bytes = [L.n * L.elem_bytes for L in layers]
-    acct = {"sp_bytes": 0.0, "dw_flops": 0.0, "imp_bytes": 0.0, "nnz_flops": 0.0}
+    acct = {"sp_bytes": 0.0, "dw_flops": 0.0, "imp_bytes": 0.0, "nnz_flops": 0.0,
+            "sparse_dense_flops": 0.0, "sparse_nnz_flops": 0.0}
 
     def forward_half(ratios, count):
         for e, r in zip(st, ratios):
@@ -103,7 +105,13 @@ def main():
             surgeon.surgeon_prune_pack(e["A"], L.group_len, r, e["vals"], e["mask"], None, ws)
             if count:
                 acct["sp_bytes"] += L.n * L.elem_bytes + k * L.elem_bytes + 8 * ((L.n + 63) // 64)
-                acct["nnz_flops"] += L.dense_flops * (k / L.n)
+                # flops go to the kernel class the library will use for this (shape, kept count)
+                if surgeon.surgeon_dw_kernel_class(e["desc"]) == "dw_sparse":
+                    acct["sparse_dense_flops"] += L.dense_flops
+                    acct["sparse_nnz_flops"] += L.dense_flops * (k / L.n)
+                else:
+                    acct["dw_flops"] += L.dense_flops
+                    acct["nnz_flops"] += L.dense_flops * (k / L.n)
 
     dW_list = [e["dW"] for e in st]
 
@@ -111,8 +119,6 @@ def main():
         for li in range(len(st) - 1, -1, -1):
             e = st[li]
             surgeon.surgeon_dw_from_packed(e["desc"], e["vals"], e["mask"], e["dY"], e["dW"], ws)
-            if count:
-                acct["dw_flops"] += e["L"].dense_flops
         if with_importance:  # Eq. 4 for every layer in one call, once all weight gradients of the pass exist
             surgeon.surgeon_grad_importance_batched(dW_list, G_dev, ws)
             if count:
@@ -158,6 +164,7 @@ def main():
     dw_ms, dw_n = prof["dw"]
     sp_ms, sp_n = prof["select_pack"]
     imp_ms, imp_n = prof["importance"]
+    dws_ms, dws_n = prof["dw_sparse"]
     dw_tflops = rate(acct["dw_flops"], dw_ms) / 1e12
     sp_gbps = rate(acct["sp_bytes"], sp_ms) / 1e9
     imp_gbps = rate(acct["imp_bytes"], imp_ms) / 1e9
@@ -188,6 +195,15 @@ def main():
                            "frac": round(imp_gbps / PEAK_HBM_GBPS, 4), "launches": int(imp_n),
                            "avg_launch_ms": round(imp_ms / max(imp_n, 1), 5), "ms_per_step": round(imp_ms / args.steps, 4)},
             "dw": {"ms_per_step": round(dw_ms / args.steps, 4), "tflops_dense_equiv": round(dw_tflops, 3)},
+            # layers with few kept elements (fp32 3x3 stride 1, <= 17 % kept): the sum of Eq. 2 over the kept elements
+            # only, on the vector ALU; achieved = multiply-adds actually done, peak = fp32 vector FMA rate (256 CUs x
+            # 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz; packed fp32 is disabled in this build)
+            "dw_sparse": {"bound": "alu", "achieved": round(rate(acct["sparse_nnz_flops"], dws_ms) / 1e12, 3),
+                          "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s",
+                          "frac": round(rate(acct["sparse_nnz_flops"], dws_ms) / 1e12 / PEAK_VALU_F32_TFLOPS, 4),
+                          "launches": int(dws_n), "avg_launch_ms": round(dws_ms / max(dws_n, 1), 5),
+                          "ms_per_step": round(dws_ms / args.steps, 4),
+                          "tflops_dense_equiv": round(rate(acct["sparse_dense_flops"], dws_ms) / 1e12, 3)},
             "dw_aux": {"ms_per_step": round(prof["dw_aux"][0] / args.steps, 4), "launches": int(prof["dw_aux"][1])},
             "select_other": {"ms_per_step": round(prof["select_other"][0] / args.steps, 4)},
         },

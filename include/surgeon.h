@@ -45,6 +45,10 @@ typedef enum {
 
 typedef enum { SURGEON_LINEAR = 0, SURGEON_CONV2D = 1 } surgeon_layer_kind;
 
+/* kernel classes of the timing aid at the end of this header */
+enum { SURGEON_PROF_SELECT_PACK = 0, SURGEON_PROF_DW = 1, SURGEON_PROF_IMPORTANCE = 2, SURGEON_PROF_DW_AUX = 3,
+       SURGEON_PROF_SELECT_OTHER = 4, SURGEON_PROF_DW_SPARSE = 5, SURGEON_PROF_CLASSES = 6 };
+
 /*
  * Shape of one adapted layer for surgeon_dw_from_packed (Eq. 2, second line).
  *   LINEAR : cached activation A is [M tokens x K in-features] row-major, dY is [M x N out-features]
@@ -120,8 +124,18 @@ int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, float r, int
                        void* vals, uint64_t* mask, uint32_t* idx,
                        void* ws, size_t ws_bytes, void* stream);
 
-/* Workspace surgeon_dw_from_packed needs for `desc`.  Host only. */
+/* Workspace surgeon_dw_from_packed needs for `desc`, whatever its k_total: one query serves every prune ratio the
+ * layer will be called with.  Host only. */
 int surgeon_dw_ws_bytes(const surgeon_layer_desc* desc, size_t* ws_bytes);
+
+/*
+ * Which kernel surgeon_dw_from_packed will use for `desc` (it depends on the shape and on k_total): writes
+ * SURGEON_PROF_DW (dense contraction on the matrix cores; Alg. 1 line 11 read literally) or SURGEON_PROF_DW_SPARSE
+ * (fp32 3x3 stride-1 pad-1 layers of width 8, 16 or 32 with at most 17 % of the elements kept: the sum of Eq. 2 taken
+ * over the kept elements only; same result up to fp32 summation order).  For benchmarks that account flops per
+ * kernel.  Host only.
+ */
+int surgeon_dw_kernel_class(const surgeon_layer_desc* desc, int* kernel_class);
 
 /*
  * Alg. 1 lines 11-12 / Eq. 2 (weight gradient): dW = dY^T . A_pruned, where A_pruned is rebuilt from
@@ -168,12 +182,11 @@ int surgeon_grad_importance_batched(const float* const* dW, const int64_t* n_w, 
  *   class 2 SURGEON_PROF_IMPORTANCE   sum-of-squares kernels of Eq. 4
  *   class 3 SURGEON_PROF_DW_AUX       rank-table pre-pass and split reduction around class 1
  *   class 4 SURGEON_PROF_SELECT_OTHER kernels of the other two selection paths, mask clearing
+ *   class 5 SURGEON_PROF_DW_SPARSE    the weight-gradient kernel that works from the kept elements alone
  * ms / launches are host arrays of n_classes entries (at most SURGEON_PROF_CLASSES are filled).
  * Not thread-safe; intended for one benchmarking thread.  Event objects are created by the HIP runtime, kept in a
  * pool and reused by later profiling sessions of the process.
  */
-enum { SURGEON_PROF_SELECT_PACK = 0, SURGEON_PROF_DW = 1, SURGEON_PROF_IMPORTANCE = 2, SURGEON_PROF_DW_AUX = 3,
-       SURGEON_PROF_SELECT_OTHER = 4, SURGEON_PROF_CLASSES = 5 };
 int surgeon_profile_begin(void);
 int surgeon_profile_end(int n_classes, double* ms, int64_t* launches);
 

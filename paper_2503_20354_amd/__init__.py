@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     load_library,
     prune_pack,
     surgeon_dw_from_packed,
+    surgeon_dw_kernel_class,
     surgeon_dw_ws_bytes,
     surgeon_grad_importance,
     surgeon_grad_importance_batched,

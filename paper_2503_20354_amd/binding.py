@@ -59,6 +59,8 @@ def load_library():
     L.surgeon_prune_pack.argtypes = [vp, i64, i64, f32, ci, vp, vp, vp, vp, sz, vp]
     L.surgeon_dw_ws_bytes.restype = ci
     L.surgeon_dw_ws_bytes.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(sz)]
+    L.surgeon_dw_kernel_class.restype = ci
+    L.surgeon_dw_kernel_class.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(ci)]
     L.surgeon_dw_from_packed.restype = ci
     L.surgeon_dw_from_packed.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, sz, vp]
     L.surgeon_grad_importance_ws_bytes.restype = sz
@@ -154,6 +156,13 @@ def surgeon_dw_ws_bytes(desc: LayerDesc) -> int:
     return wb.value
 
 
+def surgeon_dw_kernel_class(desc: LayerDesc) -> str:
+    """Name of the kernel class ("dw" or "dw_sparse") surgeon_dw_from_packed will use for this descriptor."""
+    c = ctypes.c_int()
+    _check(load_library().surgeon_dw_kernel_class(ctypes.byref(desc), ctypes.byref(c)))
+    return PROF_CLASSES[c.value]
+
+
 def surgeon_dw_from_packed(desc: LayerDesc, vals, mask, dY, dW, ws):
     _dev(dY, "dY")
     _dev(dW, "dW")
@@ -203,7 +212,7 @@ def surgeon_grad_importance_batched(dWs, G_out, ws):
                                                           _stream(G_out.device)))
 
 
-PROF_CLASSES = ("select_pack", "dw", "importance", "dw_aux", "select_other")
+PROF_CLASSES = ("select_pack", "dw", "importance", "dw_aux", "select_other", "dw_sparse")
 
 
 def surgeon_profile_begin():

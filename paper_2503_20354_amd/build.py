@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsurgeon.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["surgeon_host.cpp", "importance.hip", "prune_pack.hip", "dw.hip", "dw_f32.hip", "dw_bf16in.hip", "dw_bf16.hip"]
+SOURCES = ["surgeon_host.cpp", "importance.hip", "prune_pack.hip", "dw.hip", "dw_f32.hip", "dw_bf16in.hip", "dw_bf16.hip", "dw_sparse.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

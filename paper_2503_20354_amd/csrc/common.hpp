@@ -76,6 +76,15 @@ int launch_conv1x1_bf16(int Nb, int Ci, int Co, int HW, const void* A_dense, con
 constexpr int kBf16LinearTile = 128, kBf16LinearTokens = 64;          // 128 x 128 tile, 64 tokens per K-tile
 constexpr int kBf16LinearTileWide = 256, kBf16LinearTokensWide = 32;  // 128 (out) x 256 (in) tile, 32 tokens
 
+// 3x3 stride-1 pad-1 fp32 convolutions with few kept elements: weight gradient from the kept elements alone
+// (dw_sparse.hip).  One workgroup = 64 output channels x (kSparseWaves x kSparseCiPerWave) input channels.
+constexpr int kSparseCo = 64, kSparseWaves = 8, kSparseCiPerWave = 4, kSparseCi = kSparseWaves * kSparseCiPerWave;
+constexpr int kSparseSlots = 3 * 256;  // workgroups resident on the chip: three per compute unit (LDS, registers)
+int sparse_conv_band_rows(int W);  // input rows per staged band for a map of width W (8, 16 or 32)
+int launch_conv3x3_sparse_f32(int Nb, int Ci, int Co, int H, int W, int64_t k_total, int splits, int tiles_per_split,
+                              const void* vals, const uint64_t* mask, const uint32_t* word_rank, const void* dY, float* out,
+                              hipStream_t st);
+
 constexpr int kWaveRegMaxGroup = 4096;  // largest group one wavefront keeps in registers (64 lanes x 64)
 constexpr int kGlobalHistChunk = 16384;  // elements per block in the histogram passes of the global path
 constexpr int kGlobalWaveChunk = 4096;   // elements per wavefront in the count / pack passes of the global path

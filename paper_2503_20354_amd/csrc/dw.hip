@@ -14,10 +14,23 @@ using namespace surgeon;
 
 extern "C" int surgeon_dw_ws_bytes(const surgeon_layer_desc* desc, size_t* ws_bytes) {
   if (!ws_bytes) return fail(SURGEON_EINVAL, "dw_ws_bytes: null pointer");
+  // the kernel is chosen per call from k_total: size the workspace for either choice, so that one query covers
+  // every prune ratio the layer will see
+  DwPlan p, q;
+  int rc = plan_dw(desc, &p, SPARSE_NEVER);
+  if (rc != SURGEON_OK) return rc;
+  rc = plan_dw(desc, &q, SPARSE_IF_SHAPE_ALLOWS);
+  if (rc != SURGEON_OK) return rc;
+  *ws_bytes = std::max(p.ws_bytes, q.ws_bytes);
+  return SURGEON_OK;
+}
+
+extern "C" int surgeon_dw_kernel_class(const surgeon_layer_desc* desc, int* kernel_class) {
+  if (!kernel_class) return fail(SURGEON_EINVAL, "dw_kernel_class: null pointer");
   DwPlan p;
   const int rc = plan_dw(desc, &p);
   if (rc != SURGEON_OK) return rc;
-  *ws_bytes = p.ws_bytes;
+  *kernel_class = (p.conv && p.c.sparse) ? SURGEON_PROF_DW_SPARSE : SURGEON_PROF_DW;
   return SURGEON_OK;
 }
 

@@ -840,10 +840,18 @@ struct ConvPlan {
   ConvGeom g;
   int gemm1x1;               // 1: bf16 1x1 stride-1 layer handled as a dense contraction over the pixels
   int64_t gemm_ktiles_per_split;
+  int sparse;                // 1: fp32 3x3 stride-1 layer with few kept elements, gradient from the kept elements alone
+  int sparse_tiles_per_split;
   int khc, kw_t, mt, nt, p;  // kernel variant
   int co_tiles, z, splits;
   size_t lds_bytes;
 };
+
+// which weight-gradient kernel a convolution may use
+enum SparseChoice { SPARSE_BY_DENSITY = -1, SPARSE_NEVER = 0, SPARSE_IF_SHAPE_ALLOWS = 1 };
+// kept fraction up to which the kernel that skips the dropped elements beats the dense matrix-core kernel (its time
+// grows linearly with the kept count and crosses the dense kernel's at 17.5 - 23 % on the layers measured)
+constexpr int64_t kSparseMaxKeptNum = 17, kSparseMaxKeptDen = 100;
 
 struct LinPlan {
   LinGeom g;
@@ -888,7 +896,7 @@ static int choose_splits(int64_t k_tiles, int64_t out_tiles, int slots, double t
   return (int)ceil_div(k_tiles, per);
 }
 
-static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
+static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp, int sparse_choice) {
   if (d->Nb < 1 || d->Ci < 1 || d->H < 1 || d->W < 1 || d->Co < 1 || d->kh < 1 || d->kw < 1 || d->stride < 1 ||
       d->pad < 0)
     return fail(SURGEON_EINVAL, "dw_from_packed: bad conv shape");
@@ -904,6 +912,25 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp) {
   g.OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
   g.n_w = (int64_t)g.Co * g.Ci * g.KH * g.KW;
   cp->gemm1x1 = 0;
+  cp->sparse = 0;
+  if (sparse_choice != SPARSE_NEVER && d->dtype == SURGEON_F32 && g.KH == 3 && g.KW == 3 && g.stride == 1 && g.pad == 1 &&
+      (g.W == 8 || g.W == 16 || g.W == 32) && g.H % sparse_conv_band_rows(g.W) == 0 && g.Co >= kSparseCo / 2 &&
+      d->k_total < ((int64_t)1 << 32) && (int64_t)g.Nb * g.H < ((int64_t)1 << 30) &&
+      (sparse_choice == SPARSE_IF_SHAPE_ALLOWS ||
+       d->k_total * kSparseMaxKeptDen <= kSparseMaxKeptNum * (int64_t)g.Nb * g.Ci * g.H * g.W)) {
+    cp->sparse = 1;
+    cp->khc = 3; cp->kw_t = 3; cp->mt = cp->nt = 0; cp->p = 0; cp->z = 1; cp->lds_bytes = 0;
+    cp->co_tiles = (int)ceil_div(g.Co, kSparseCo);
+    g.ci_tiles = (int)ceil_div(g.Ci, kSparseCi);
+    g.Ci_in = g.Ci; g.fold = 0; g.magic_fold = 0;
+    // all workgroups resident at once and none left for a second round; every split walks whole (image, band) tiles
+    const int64_t n_tiles = (int64_t)g.Nb * (g.H / sparse_conv_band_rows(g.W));
+    const int64_t want = std::min<int64_t>(std::min<int64_t>(n_tiles, kMaxSplits),
+                                           std::max<int64_t>(1, kSparseSlots / ((int64_t)cp->co_tiles * g.ci_tiles)));
+    cp->sparse_tiles_per_split = (int)ceil_div(n_tiles, want);
+    cp->splits = (int)ceil_div(n_tiles, cp->sparse_tiles_per_split);
+    return SURGEON_OK;
+  }
   if (d->dtype == SURGEON_BF16 && g.KH == 1 && g.KW == 1 && g.stride == 1 && g.pad == 0 && (g.H * g.W) % 4 == 0) {
     // a 1x1 stride-1 convolution has no tap reuse to pay for un-packing inside the tile loads: un-pack once to a
     // dense transient copy and contract over the pixels on the bf16 matrix cores (as the bf16 linear path does)
@@ -1067,14 +1094,14 @@ static int plan_linear(const surgeon_layer_desc* d, LinPlan* lp) {
   return SURGEON_OK;
 }
 
-static int plan_dw(const surgeon_layer_desc* d, DwPlan* p) {
+static int plan_dw(const surgeon_layer_desc* d, DwPlan* p, int sparse_choice = SPARSE_BY_DENSITY) {
   if (!d) return fail(SURGEON_EINVAL, "dw_from_packed: null descriptor");
   if (d->dtype != SURGEON_F32 && d->dtype != SURGEON_BF16) return fail(SURGEON_EINVAL, "dw_from_packed: bad dtype");
   if (d->k_total < 0) return fail(SURGEON_EINVAL, "dw_from_packed: k_total < 0");
   int rc;
   if (d->kind == SURGEON_CONV2D) {
     p->conv = true;
-    if ((rc = plan_conv(d, &p->c)) != SURGEON_OK) return rc;
+    if ((rc = plan_conv(d, &p->c, sparse_choice)) != SURGEON_OK) return rc;
     p->n = d->Nb * d->Ci * d->H * d->W;
     p->n_w = p->c.g.n_w;
     p->splits = p->c.splits;
@@ -1239,6 +1266,9 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
       else
         rc = launch_linear_bf16(p.l.g.M, p.l.g.K, p.l.g.N, dense, dY, out, p.l.splits, p.l.g.rows_per_split, p.l.bf16_wide, st);
     }
+  } else if (p.conv && p.c.sparse) {
+    rc = launch_conv3x3_sparse_f32(p.c.g.Nb, p.c.g.Ci, p.c.g.Co, p.c.g.H, p.c.g.W, d->k_total, p.c.splits,
+                                   p.c.sparse_tiles_per_split, vals, mask, word_rank, dY, out, st);
   } else {
     rc = p.conv ? launch_conv<InT>(p.c, pk, dY, out, st) : launch_linear<InT>(p.l, pk, dY, out, st);
   }

@@ -239,6 +239,45 @@ def test_dw_conv_unpadded_and_strided(dtype, shape):
         assert rel_l2(got, ref) <= TOL[dtype]
 
 
+# fp32 3x3 stride-1 pad-1 layers of width 8 / 16 / 32 with few kept elements: gradient from the kept elements alone
+SPARSE_SHAPES = [
+    # Nb, Ci, H, W, Co, k, stride
+    (5, 160, 32, 32, 160, 3, 1), (3, 320, 16, 16, 320, 3, 1), (7, 640, 8, 8, 640, 3, 1), (2, 33, 12, 32, 70, 3, 1),
+    (3, 5, 24, 16, 32, 3, 1), (9, 40, 16, 8, 129, 3, 1), (1, 1, 8, 8, 64, 3, 1), (2, 96, 4, 32, 33, 3, 1),
+]
+
+
+@pytest.mark.parametrize("shape", SPARSE_SHAPES)
+def test_dw_conv_from_kept_elements_only(shape):
+    Nb, Ci, H, W, Co = shape[:5]
+    n = Nb * Ci * H * W
+    for r, dist in ((0.9, "relu"), (0.97, "normal"), (0.85, "normal")):
+        k = surgeon.surgeon_packed_sizes(n, 4096, r, surgeon.F32)[0]
+        desc = surgeon.conv2d_desc(Nb, Ci, H, W, Co, 3, 3, 1, 1, surgeon.F32, k)
+        assert surgeon.surgeon_dw_kernel_class(desc) == "dw_sparse"
+        got, ref = run_conv(shape, "f32", r, dist=dist, seed=sum(shape))
+        assert got.shape == ref.shape
+        assert rel_l2(got, ref) <= TOL["f32"]
+    # the same layer with more elements kept takes the dense kernel; both agree with the oracle, hence with each other
+    k = surgeon.surgeon_packed_sizes(n, 4096, 0.5, surgeon.F32)[0]
+    assert surgeon.surgeon_dw_kernel_class(surgeon.conv2d_desc(Nb, Ci, H, W, Co, 3, 3, 1, 1, surgeon.F32, k)) == "dw"
+
+
+def test_dw_conv_from_kept_elements_is_deterministic_and_profiled():
+    Nb, Ci, H, W, Co = 6, 64, 16, 16, 96
+    A = wl.draw((Nb, Ci, H, W), "relu", "f32", 71).to(DEV)
+    dY = wl.draw((Nb, Co, H, W), "normal", "f32", 72).to(DEV)
+    p = surgeon.prune_pack(A, 4096, 0.9)
+    desc = surgeon.conv2d_desc(Nb, Ci, H, W, Co, 3, 3, 1, 1, surgeon.F32, p.k_total)
+    surgeon.surgeon_profile_begin()
+    a = surgeon.dw_from_packed(desc, p, dY)
+    b = surgeon.dw_from_packed(desc, p, dY)
+    torch.cuda.synchronize()
+    prof = surgeon.surgeon_profile_end()
+    assert torch.equal(a, b)
+    assert prof["dw_sparse"][1] == 2 and prof["dw"][1] == 0
+
+
 def test_dw_group_hint_changes_nothing():
     """The optional (group_len, r) hint only selects a cheaper pre-pass: same bits with and without it."""
     Nb, Ci, H, W, Co = 4, 160, 32, 32, 160

@@ -78,6 +78,26 @@ def test_layer_ratios_errors():
         surgeon.surgeon_layer_ratios([1.0], [1], 0.9, 0.3)
 
 
+def test_dw_kernel_class_and_one_workspace_for_all_ratios():
+    """The weight-gradient kernel is chosen from the shape and the kept count; the workspace query covers both."""
+    n = 8 * 160 * 32 * 32
+
+    def conv(k_total, dt=surgeon.F32, W=32, stride=1, ksz=3, pad=1):
+        return surgeon.conv2d_desc(8, 160, 32, W, 160, ksz, ksz, stride, pad, dt, k_total)
+
+    assert surgeon.surgeon_dw_kernel_class(conv(n // 10)) == "dw_sparse"
+    assert surgeon.surgeon_dw_kernel_class(conv(n * 17 // 100)) == "dw_sparse"
+    assert surgeon.surgeon_dw_kernel_class(conv(n * 17 // 100 + 1)) == "dw"
+    assert surgeon.surgeon_dw_kernel_class(conv(n // 2)) == "dw"
+    assert surgeon.surgeon_dw_kernel_class(conv(n // 20, dt=surgeon.BF16)) == "dw"
+    assert surgeon.surgeon_dw_kernel_class(conv(n // 20, stride=2)) == "dw"
+    assert surgeon.surgeon_dw_kernel_class(conv(n // 20, ksz=1, pad=0)) == "dw"
+    assert surgeon.surgeon_dw_kernel_class(surgeon.conv2d_desc(8, 160, 32, 24, 160, 3, 3, 1, 1, surgeon.F32, 1000)) == "dw"
+    assert surgeon.surgeon_dw_kernel_class(surgeon.linear_desc(64, 512, 256, surgeon.F32, 100)) == "dw"
+    sizes = {surgeon.surgeon_dw_ws_bytes(conv(k)) for k in (0, n // 10, n // 2, n)}
+    assert len(sizes) == 1  # sized once, valid for every prune ratio
+
+
 def test_dw_workspace_and_shape_errors():
     d = surgeon.conv2d_desc(200, 160, 32, 32, 160, 3, 3, 1, 1, surgeon.F32, 1000)
     assert surgeon.surgeon_dw_ws_bytes(d) > 0
