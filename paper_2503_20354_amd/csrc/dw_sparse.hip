@@ -17,7 +17,10 @@ namespace surgeon {
 
 namespace {
 
-constexpr int kSpPix = kSparseCo + 1;  // floats per staged pixel: 64 channels + 1 so that pixels rotate over the banks
+// floats per staged pixel = the 64 channels of the tile, unpadded: any two taps of an element are then a multiple of
+// 64 floats apart, so one ds_read2st64_b32 fetches two of them (an LDS instruction occupies the LDS for four cycles
+// whether it moves 256 or 512 bytes)
+constexpr int kSpPix = kSparseCo;
 
 struct SparseGeom {
   int Nb, Ci, Co, H;
@@ -75,9 +78,11 @@ __global__ __launch_bounds__(64 * kSparseWaves) void dw_conv3x3_sparse_kernel(Sp
       }
     }
     __syncthreads();  // the previous tile's readers (first pass: the zero fill) are done
-    // ---- stage dY rows r0-1 .. r0+R of 64 output channels: consecutive lanes read consecutive 16-byte chunks of a row
+    // ---- stage dY rows r0-1 .. r0+R of 64 output channels.  Lanes run over the channels, so that the LDS writes of a
+    // wavefront fall on consecutive banks; a lane reads its channel's row 16 bytes at a time (the other seven chunks of
+    // the 128-byte line are read by the neighbouring chunk indices and hit in the vector cache).
     for (int c = tid; c < kChunks; c += kThreads) {
-      const int c4 = c % kChunksPerRow, co = (c / kChunksPerRow) % kSparseCo, rr = c / (kChunksPerRow * kSparseCo);
+      const int co = c % kSparseCo, c4 = (c / kSparseCo) % kChunksPerRow, rr = c / (kChunksPerRow * kSparseCo);
       const int oh = r0 - 1 + rr;
       float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
       if (oh >= 0 && oh < g.H && co0 + co < g.Co)
@@ -90,9 +95,6 @@ __global__ __launch_bounds__(64 * kSparseWaves) void dw_conv3x3_sparse_kernel(Sp
     }
     __syncthreads();
     // ---- the kept elements of this wavefront's channels inside the band
-    // WI (an integral_constant) = index of the mask word inside the band: its rows are a compile-time LDS offset.
-    // The six 8-byte reads are written in assembly: left to itself the compiler narrows them to the 4-byte reads of
-    // the floats that are used.
 #pragma unroll
     for (int c = 0; c < CPW; ++c) {
 #pragma unroll
