@@ -7,8 +7,10 @@ packed, Gradient Importance for every layer), the ratio rule of Eq. 5-7 on the h
 (select + pack at the per-layer ratios, dW from packed).  Inputs are resident in HBM before the timed region.
 
 Prints ONE JSON line.  `value` is dense activation bytes pushed through the whole step per second;
-`roofline` is for the dominant kernel (the MFMA weight-gradient kernel), timed with HIP events inside the
-library on the launching stream; `stages` gives the same figures for the two HBM-bound kernel classes;
+`roofline` is for the dominant kernel (the MFMA weight-gradient kernel, which serves every layer with more than
+17 % of its elements kept), timed with HIP events inside the library on the launching stream; `stages` gives the same
+figures for the two HBM-bound kernel classes and for the weight-gradient kernel that works from the kept elements alone
+(fp32 3x3 stride-1 layers with at most 17 % kept: the importance pass);
 `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
