@@ -81,6 +81,34 @@ def test_random_conv_shapes(seed):
         done += 1
 
 
+@pytest.mark.parametrize("seed", [151, 152, 153])
+def test_random_shapes_of_the_kept_elements_kernel(seed):
+    """fp32 3x3 stride-1 pad-1 layers of width 8 / 16 / 32 with few kept elements (the kernel that sums Eq. 2 over the
+    kept elements only): odd channel counts, partial channel tiles, one to many bands and images, every group scope."""
+    rng = random.Random(seed)
+    for case in range(12):
+        W = rng.choice([8, 16, 32])
+        H = rng.choice([1, 2, 3, 5]) * (4 if W == 32 else 8)
+        Nb = rng.randint(1, 7)
+        Ci = rng.choice([1, 3, 31, 32, 33, 64, 100, 160])
+        Co = rng.choice([32, 33, 63, 64, 65, 128, 200])
+        r = rng.choice([0.85, 0.9, 0.9, 0.95, 0.99, 1.0])
+        n = Nb * Ci * H * W
+        g = rng.choice([64, 4096, 4096, n, 1000, 128])
+        hint = rng.random() < 0.5
+        print("kept-elements conv Nb=%d Ci=%d H=%d W=%d Co=%d r=%g g=%d hint=%d" % (Nb, Ci, H, W, Co, r, g, hint), flush=True)
+        A = wl.draw((Nb, Ci, H, W), rng.choice(["relu", "normal"]), "f32", seed * 1000 + case * 3 + 1)
+        dY = wl.draw((Nb, Co, H, W), "normal", "f32", seed * 1000 + case * 3 + 2)
+        p, o_vals, o_mask = pack_and_check(A, g, r)
+        desc = surgeon.conv2d_desc(Nb, Ci, H, W, Co, 3, 3, 1, 1, surgeon.F32, p.k_total, group_len=g if hint else 0,
+                                   r=r if hint else 0.0)
+        if p.k_total * 100 <= 17 * n:
+            assert surgeon.surgeon_dw_kernel_class(desc) == "dw_sparse"
+        got = dw_on_gpu(desc, p, dY, (Co, Ci, 3, 3))
+        ref = oracle.dw_conv2d(o_vals, o_mask, wl.to_numpy_bits(dY), Nb, Ci, H, W, Co, 3, 3, 1, 1)
+        assert rel_l2(got, ref) <= TOL["f32"]
+
+
 @pytest.mark.parametrize("seed", [201, 202])
 def test_random_linear_shapes(seed):
     rng = random.Random(seed)
