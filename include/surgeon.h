@@ -131,7 +131,8 @@ int surgeon_dw_ws_bytes(const surgeon_layer_desc* desc, size_t* ws_bytes);
 /*
  * Which kernel surgeon_dw_from_packed will use for `desc` (it depends on the shape and on k_total): writes
  * SURGEON_PROF_DW (dense contraction on the matrix cores; Alg. 1 line 11 read literally) or SURGEON_PROF_DW_SPARSE
- * (fp32 3x3 stride-1 pad-1 layers of width 8, 16 or 32 with at most 17 % of the elements kept: the sum of Eq. 2 taken
+ * (fp32 3x3 stride-1 pad-1 layers of width 8, 16 or 32 with at most 17 % of the elements kept, 22 % when the input
+ * channels fill 64-channel tiles without padding: the sum of Eq. 2 taken
  * over the kept elements only; same result up to fp32 summation order).  For benchmarks that account flops per
  * kernel.  Host only.
  */

@@ -77,9 +77,13 @@ constexpr int kBf16LinearTile = 128, kBf16LinearTokens = 64;          // 128 x 1
 constexpr int kBf16LinearTileWide = 256, kBf16LinearTokensWide = 32;  // 128 (out) x 256 (in) tile, 32 tokens
 
 // 3x3 stride-1 pad-1 fp32 convolutions with few kept elements: weight gradient from the kept elements alone
-// (dw_sparse.hip).  One workgroup = 64 output channels x (kSparseWaves x kSparseCiPerWave) input channels.
-constexpr int kSparseCo = 64, kSparseWaves = 8, kSparseCiPerWave = 4, kSparseCi = kSparseWaves * kSparseCiPerWave;
-constexpr int kSparseSlots = 3 * 256;  // workgroups resident on the chip: three per compute unit (LDS, registers)
+// (dw_sparse.hip).  One workgroup = 64 output channels x (waves x kSparseCiPerWave) input channels, with 8 or 16
+// wavefronts (32 or 64 input channels) chosen per layer.
+constexpr int kSparseCo = 64, kSparseCiPerWave = 4;
+// wavefronts per workgroup for a layer with Ci input channels: the largest channel tile that pads Ci the least
+int sparse_conv_waves(int Ci);
+// workgroups of that size resident on the chip at once (LDS: 3 per compute unit; 32 wavefronts per compute unit)
+inline int sparse_conv_slots(int waves) { return (waves > 8 ? 2 : 3) * 256; }
 int sparse_conv_band_rows(int W);  // input rows per staged band for a map of width W (8, 16 or 32)
 int launch_conv3x3_sparse_f32(int Nb, int Ci, int Co, int H, int W, int64_t k_total, int splits, int tiles_per_split,
                               const void* vals, const uint64_t* mask, const uint32_t* word_rank, const void* dY, float* out,

@@ -849,9 +849,10 @@ struct ConvPlan {
 
 // which weight-gradient kernel a convolution may use
 enum SparseChoice { SPARSE_BY_DENSITY = -1, SPARSE_NEVER = 0, SPARSE_IF_SHAPE_ALLOWS = 1 };
-// kept fraction up to which the kernel that skips the dropped elements beats the dense matrix-core kernel (its time
-// grows linearly with the kept count and crosses the dense kernel's at 17.5 - 23 % on the layers measured)
-constexpr int64_t kSparseMaxKeptNum = 17, kSparseMaxKeptDen = 100;
+// kept percentage up to which the kernel that skips the dropped elements beats the dense matrix-core kernel: its time
+// grows linearly with the kept count and crosses the dense kernel's at 18.5 % with 32-channel workgroups and at 24 %
+// with 64-channel ones on the layers measured
+static inline int64_t sparse_max_kept_percent(int Ci) { return sparse_conv_waves(Ci) == 16 ? 22 : 17; }
 
 struct LinPlan {
   LinGeom g;
@@ -917,16 +918,17 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp, int sparse_choic
       (g.W == 8 || g.W == 16 || g.W == 32) && g.H % sparse_conv_band_rows(g.W) == 0 && g.Co >= kSparseCo / 2 &&
       d->k_total < ((int64_t)1 << 32) && (int64_t)g.Nb * g.H < ((int64_t)1 << 30) &&
       (sparse_choice == SPARSE_IF_SHAPE_ALLOWS ||
-       d->k_total * kSparseMaxKeptDen <= kSparseMaxKeptNum * (int64_t)g.Nb * g.Ci * g.H * g.W)) {
+       d->k_total * 100 <= sparse_max_kept_percent(g.Ci) * (int64_t)g.Nb * g.Ci * g.H * g.W)) {
     cp->sparse = 1;
     cp->khc = 3; cp->kw_t = 3; cp->mt = cp->nt = 0; cp->p = 0; cp->z = 1; cp->lds_bytes = 0;
     cp->co_tiles = (int)ceil_div(g.Co, kSparseCo);
-    g.ci_tiles = (int)ceil_div(g.Ci, kSparseCi);
+    const int sp_waves = sparse_conv_waves(g.Ci);
+    g.ci_tiles = (int)ceil_div(g.Ci, sp_waves * kSparseCiPerWave);
     g.Ci_in = g.Ci; g.fold = 0; g.magic_fold = 0;
     // all workgroups resident at once and none left for a second round; every split walks whole (image, band) tiles
     const int64_t n_tiles = (int64_t)g.Nb * (g.H / sparse_conv_band_rows(g.W));
     const int64_t want = std::min<int64_t>(std::min<int64_t>(n_tiles, kMaxSplits),
-                                           std::max<int64_t>(1, kSparseSlots / ((int64_t)cp->co_tiles * g.ci_tiles)));
+                                           std::max<int64_t>(1, sparse_conv_slots(sp_waves) / ((int64_t)cp->co_tiles * g.ci_tiles)));
     cp->sparse_tiles_per_split = (int)ceil_div(n_tiles, want);
     cp->splits = (int)ceil_div(n_tiles, cp->sparse_tiles_per_split);
     return SURGEON_OK;

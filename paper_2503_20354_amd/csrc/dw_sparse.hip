@@ -3,7 +3,7 @@
 // to dW[:, ci, u, v].  With few kept elements (prune ratio >= ~0.85) this is less work than the dense contraction
 // on the matrix cores, which spends most of its multiplications on zeros.
 //
-// One workgroup owns 64 output channels (one per lane) and kSpWaves * CPW input channels (CPW per wavefront, nine
+// One workgroup owns 64 output channels (one per lane) and WAVES * CPW input channels (CPW per wavefront, nine
 // accumulators each, in registers), and walks a range of (image, band of R input rows) tiles.  Per tile it stages the
 // R + 2 rows of dY that the band touches as [row][column + halo][channel] in LDS (the halo columns and out-of-range
 // rows are zero, so the taps need no bounds checks); then each wavefront walks the mask words of its channels: the
@@ -29,13 +29,15 @@ struct SparseGeom {
   uint32_t k_last;
 };
 
-template <int W, int R, int CPW>
-__global__ __launch_bounds__(64 * kSparseWaves) void dw_conv3x3_sparse_kernel(SparseGeom g, const float* __restrict__ vals,
+// 16 wavefronts: 64 registers per lane (8 wavefronts per SIMD), so that two such workgroups fit a compute unit;
+// 8 wavefronts: three workgroups per compute unit (LDS), 6 wavefronts per SIMD
+template <int W, int R, int CPW, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(WAVES == 16 ? 8 : 6))) void dw_conv3x3_sparse_kernel(SparseGeom g, const float* __restrict__ vals,
                                                                             const uint64_t* __restrict__ mask,
                                                                             const uint32_t* __restrict__ word_rank,
                                                                             const float* __restrict__ dY,
                                                                             float* __restrict__ out) {
-  constexpr int kThreads = 64 * kSparseWaves;
+  constexpr int kThreads = 64 * WAVES;
   constexpr int PW = W + 2, ROWS = R + 2;
   constexpr int kLdsFloats = ROWS * PW * kSpPix;
   constexpr int kWords = R * W / 64;            // mask words per (image, channel, band)
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(64 * kSparseWaves) void dw_conv3x3_sparse_kernel(Sp
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int co0 = (int)(blockIdx.x / (unsigned)g.ci_tiles) * kSparseCo;
-  const int ci0 = (int)(blockIdx.x % (unsigned)g.ci_tiles) * (kSparseWaves * CPW) + wave * CPW;
+  const int ci0 = (int)(blockIdx.x % (unsigned)g.ci_tiles) * (WAVES * CPW) + wave * CPW;
   const int t_begin = (int)blockIdx.y * g.tiles_per_split;
   const int t_end = min(t_begin + g.tiles_per_split, g.n_tiles);
 
@@ -135,16 +137,16 @@ __global__ __launch_bounds__(64 * kSparseWaves) void dw_conv3x3_sparse_kernel(Sp
   }
 }
 
-template <int W, int R, int CPW>
+template <int W, int R, int CPW, int WAVES>
 int launch_variant(const SparseGeom& g, int co_tiles, int splits, const float* vals, const uint64_t* mask,
                    const uint32_t* word_rank, const float* dY, float* out, hipStream_t st) {
-  auto kernel = dw_conv3x3_sparse_kernel<W, R, CPW>;
+  auto kernel = dw_conv3x3_sparse_kernel<W, R, CPW, WAVES>;
   const size_t lds = (size_t)(R + 2) * (W + 2) * kSpPix * sizeof(float);
   if (lds > 48 * 1024)
     SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const dim3 grid((unsigned)(co_tiles * g.ci_tiles), (unsigned)splits);
   ProfScope prof(SURGEON_PROF_DW_SPARSE, st);
-  SURGEON_LAUNCH(kernel, grid, dim3(64 * kSparseWaves), lds, st, g, vals, mask, word_rank, dY, out);
+  SURGEON_LAUNCH(kernel, grid, dim3(64 * WAVES), lds, st, g, vals, mask, word_rank, dY, out);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }
@@ -153,13 +155,29 @@ int launch_variant(const SparseGeom& g, int co_tiles, int splits, const float* v
 
 int sparse_conv_band_rows(int W) { return W == 32 ? 4 : 8; }
 
+int sparse_conv_waves(int Ci) {
+  int best = 8;
+  const int64_t best_padded = ceil_div(Ci, 8 * kSparseCiPerWave) * 8 * kSparseCiPerWave;
+  const int64_t padded16 = ceil_div(Ci, 16 * kSparseCiPerWave) * 16 * kSparseCiPerWave;
+  if (padded16 <= best_padded) best = 16;
+  return best;
+}
+
+template <int W, int R>
+static int launch_waves(int waves, const SparseGeom& g, int co_tiles, int splits, const float* v, const uint64_t* mask,
+                        const uint32_t* word_rank, const float* y, float* out, hipStream_t st) {
+  if (waves == 16) return launch_variant<W, R, kSparseCiPerWave, 16>(g, co_tiles, splits, v, mask, word_rank, y, out, st);
+  return launch_variant<W, R, kSparseCiPerWave, 8>(g, co_tiles, splits, v, mask, word_rank, y, out, st);
+}
+
 int launch_conv3x3_sparse_f32(int Nb, int Ci, int Co, int H, int W, int64_t k_total, int splits, int tiles_per_split,
                               const void* vals, const uint64_t* mask, const uint32_t* word_rank, const void* dY, float* out,
                               hipStream_t st) {
   const int R = sparse_conv_band_rows(W);
   SparseGeom g;
   g.Nb = Nb; g.Ci = Ci; g.Co = Co; g.H = H;
-  g.ci_tiles = (int)ceil_div(Ci, kSparseCi);
+  const int waves = sparse_conv_waves(Ci);
+  g.ci_tiles = (int)ceil_div(Ci, waves * kSparseCiPerWave);
   g.bands = H / R;
   g.n_tiles = Nb * g.bands;
   g.tiles_per_split = tiles_per_split;
@@ -168,9 +186,9 @@ int launch_conv3x3_sparse_f32(int Nb, int Ci, int Co, int H, int W, int64_t k_to
   const int co_tiles = (int)ceil_div(Co, kSparseCo);
   const float* v = (const float*)vals;
   const float* y = (const float*)dY;
-  if (W == 32) return launch_variant<32, 4, kSparseCiPerWave>(g, co_tiles, splits, v, mask, word_rank, y, out, st);
-  if (W == 16) return launch_variant<16, 8, kSparseCiPerWave>(g, co_tiles, splits, v, mask, word_rank, y, out, st);
-  if (W == 8) return launch_variant<8, 8, kSparseCiPerWave>(g, co_tiles, splits, v, mask, word_rank, y, out, st);
+  if (W == 32) return launch_waves<32, 4>(waves, g, co_tiles, splits, v, mask, word_rank, y, out, st);
+  if (W == 16) return launch_waves<16, 8>(waves, g, co_tiles, splits, v, mask, word_rank, y, out, st);
+  if (W == 8) return launch_waves<8, 8>(waves, g, co_tiles, splits, v, mask, word_rank, y, out, st);
   return fail(SURGEON_EUNSUPPORTED, "sparse conv: width %d", W);
 }
 

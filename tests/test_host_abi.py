@@ -94,6 +94,11 @@ def test_dw_kernel_class_and_one_workspace_for_all_ratios():
     assert surgeon.surgeon_dw_kernel_class(conv(n // 20, ksz=1, pad=0)) == "dw"
     assert surgeon.surgeon_dw_kernel_class(surgeon.conv2d_desc(8, 160, 32, 24, 160, 3, 3, 1, 1, surgeon.F32, 1000)) == "dw"
     assert surgeon.surgeon_dw_kernel_class(surgeon.linear_desc(64, 512, 256, surgeon.F32, 100)) == "dw"
+    # input channels that fill 64-channel workgroups: the kernel that skips dropped elements pays up to 22 % kept
+    n2 = 8 * 320 * 16 * 16
+    wide = lambda k: surgeon.conv2d_desc(8, 320, 16, 16, 320, 3, 3, 1, 1, surgeon.F32, k)
+    assert surgeon.surgeon_dw_kernel_class(wide(n2 * 22 // 100)) == "dw_sparse"
+    assert surgeon.surgeon_dw_kernel_class(wide(n2 * 22 // 100 + 1)) == "dw"
     sizes = {surgeon.surgeon_dw_ws_bytes(conv(k)) for k in (0, n // 10, n // 2, n)}
     assert len(sizes) == 1  # sized once, valid for every prune ratio
 
