@@ -8,9 +8,9 @@ packed, Gradient Importance for every layer), the ratio rule of Eq. 5-7 on the h
 
 Prints ONE JSON line.  `value` is dense activation bytes pushed through the whole step per second;
 `roofline` is for the dominant kernel (the MFMA weight-gradient kernel, which serves every layer with more than
-17 % of its elements kept), timed with HIP events inside the library on the launching stream; `stages` gives the same
+17 - 22 % of its elements kept), timed with HIP events inside the library on the launching stream; `stages` gives the same
 figures for the two HBM-bound kernel classes and for the weight-gradient kernel that works from the kept elements alone
-(fp32 3x3 stride-1 layers with at most 17 % kept: the importance pass);
+(fp32 3x3 stride-1 layers with at most 17 - 22 % kept: the importance pass and the last stage of the adaptation pass);
 `cpu_baseline` is the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
@@ -197,7 +197,7 @@ def main():
                            "frac": round(imp_gbps / PEAK_HBM_GBPS, 4), "launches": int(imp_n),
                            "avg_launch_ms": round(imp_ms / max(imp_n, 1), 5), "ms_per_step": round(imp_ms / args.steps, 4)},
             "dw": {"ms_per_step": round(dw_ms / args.steps, 4), "tflops_dense_equiv": round(dw_tflops, 3)},
-            # layers with few kept elements (fp32 3x3 stride 1, <= 17 % kept): the sum of Eq. 2 over the kept elements
+            # layers with few kept elements (fp32 3x3 stride 1, <= 17 - 22 % kept): the sum of Eq. 2 over the kept elements
             # only, on the vector ALU; achieved = multiply-adds actually done, peak = fp32 vector FMA rate (256 CUs x
             # 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz; packed fp32 is disabled in this build)
             "dw_sparse": {"bound": "alu", "achieved": round(rate(acct["sparse_nnz_flops"], dws_ms) / 1e12, 3),
