@@ -107,8 +107,11 @@ def main():
             surgeon.surgeon_prune_pack(e["A"], L.group_len, r, e["vals"], e["mask"], None, ws)
             if count:
                 acct["sp_bytes"] += L.n * L.elem_bytes + k * L.elem_bytes + 8 * ((L.n + 63) // 64)
-                # flops go to the kernel class the library will use for this (shape, kept count)
-                if surgeon.surgeon_dw_kernel_class(e["desc"]) == "dw_sparse":
+                # flops go to the kernel class the library will use for this (shape, kept count); asked once per pair
+                cls = e.setdefault("cls", {})
+                if k not in cls:
+                    cls[k] = surgeon.surgeon_dw_kernel_class(e["desc"])
+                if cls[k] == "dw_sparse":
                     acct["sparse_dense_flops"] += L.dense_flops
                     acct["sparse_nnz_flops"] += L.dense_flops * (k / L.n)
                 else:
