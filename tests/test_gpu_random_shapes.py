@@ -90,9 +90,9 @@ def test_random_shapes_of_the_kept_elements_kernel(seed):
         W = rng.choice([8, 16, 32])
         H = rng.choice([1, 2, 3, 5]) * (4 if W == 32 else 8)
         Nb = rng.randint(1, 7)
-        Ci = rng.choice([1, 3, 31, 32, 33, 64, 100, 160])
+        Ci = rng.choice([1, 3, 31, 32, 33, 64, 64, 100, 128, 160])
         Co = rng.choice([32, 33, 63, 64, 65, 128, 200])
-        r = rng.choice([0.85, 0.9, 0.9, 0.95, 0.99, 1.0])
+        r = rng.choice([0.8, 0.85, 0.9, 0.9, 0.95, 0.99, 1.0])
         n = Nb * Ci * H * W
         g = rng.choice([64, 4096, 4096, n, 1000, 128])
         hint = rng.random() < 0.5
