@@ -982,8 +982,8 @@ static int plan_conv(const surgeon_layer_desc* d, ConvPlan* cp, int sparse_choic
   }
   // tile shape
   if (cp->kw_t == 1 && cp->khc == 1) {
-    cp->mt = (g.Co > 64 || g.Ci > 64) ? 4 : 2;  // implemented pairs: (4,4) and (2,2)
-    cp->nt = cp->mt;
+    cp->mt = (g.Co > 64 || g.Ci > 64) ? 4 : 2;  // implemented pairs: (4,4), (2,2) and, for few input channels, (4,1), (2,1)
+    cp->nt = g.Ci <= 32 ? 1 : cp->mt;
   } else if (cp->khc == 3) {
     cp->nt = 1;
     cp->mt = (g.Co % 160 == 0) ? 5 : (g.Co > 64 ? 4 : 2);
@@ -1183,6 +1183,10 @@ static int launch_conv(const ConvPlan& cp, const Packed<InT>& pk, const void* dY
     return launch_conv_p<InT, 3, 3, 2, 1>(cp, pk, dY, out, st);
   }
   if (cp.kw_t == 1) {
+    if (cp.nt == 1) {
+      if (cp.mt == 4) return launch_conv_p<InT, 1, 1, 4, 1>(cp, pk, dY, out, st);
+      return launch_conv_p<InT, 1, 1, 2, 1>(cp, pk, dY, out, st);
+    }
     if (cp.mt == 4) return launch_conv_p<InT, 1, 1, 4, 4>(cp, pk, dY, out, st);
     return launch_conv_p<InT, 1, 1, 2, 2>(cp, pk, dY, out, st);
   }
