@@ -1,7 +1,7 @@
 // Weight gradient of a 3x3, stride-1, pad-1 convolution straight from the kept elements (Eq. 2; Alg. 1 lines 11-12
 // without building the dense activation): every kept element a at (b, ci, ih, iw) adds a * dY[b, :, ih+1-u, iw+1-v]
-// to dW[:, ci, u, v].  With few kept elements (prune ratio >= ~0.85) this is less work than the dense contraction
-// on the matrix cores, which spends most of its multiplications on zeros.
+// to dW[:, ci, u, v].  With few kept elements (at most 17 - 22 % of the layer) this takes less time than the dense
+// contraction on the matrix cores, which spends most of its multiplications on zeros.
 //
 // One workgroup owns 64 output channels (one per lane) and WAVES * CPW input channels (CPW per wavefront, nine
 // accumulators each, in registers), and walks a range of (image, band of R input rows) tiles.  Per tile it stages the
