@@ -440,12 +440,9 @@ static int launch_conv1x1_bf16_ce(int Nb, int Ci, int Co, int HW, const void* A_
   const int i_tiles = (int)ceil_div(Ci, kPxTile), o_tiles = (int)ceil_div(Co, kPxTile);
   const int tiles_per_img = (int)ceil_div(HW, kPxTok);
   const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
-  static bool attr_set = false;
-  if (!attr_set) {
-    SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)dw_conv1x1_bf16_kernel<CE>,
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPxLdsBytes));
-    attr_set = true;
-  }
+  // set on every call: the attribute belongs to the current device, and a cached flag would race between host threads
+  SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)dw_conv1x1_bf16_kernel<CE>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPxLdsBytes));
   ProfScope prof(SURGEON_PROF_DW, st);
   SURGEON_LAUNCH(dw_conv1x1_bf16_kernel<CE>, grid, dim3(256), kPxLdsBytes, st, Nb, Ci, Co, HW, i_tiles, tiles_per_img,
                  ktiles_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);

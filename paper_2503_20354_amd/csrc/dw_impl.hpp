@@ -388,6 +388,7 @@ struct RunStager {
   static constexpr int NE = TCO * P / kConvLoaders;
   uint32_t ys_voff;                  // byte offset of the first of them, or kOutOfRange past the valid positions
   int ys_lds;
+  const InT* dy_ptr;
 
   __device__ __forceinline__ void init(const ConvGeom& gm, const Packed<InT>& pk, const InT* __restrict__ dY, int ltid,
                                        int co0, int ci0, int u0) {
@@ -396,6 +397,7 @@ struct RunStager {
     r_vals = __builtin_amdgcn_make_buffer_rsrc((void*)pk.vals, 0, (int)((pk.k_last + 1) * (int64_t)ES), kRawBufferWord3);
     r_dy = __builtin_amdgcn_make_buffer_rsrc((void*)dY, 0, (int)((int64_t)gm.Nb * gm.Co * gm.OH * gm.OW * ES),
                                              kRawBufferWord3);
+    dy_ptr = dY;
 #pragma unroll
     for (int r = 0; r < kRunsPerThread; ++r) {
       const int q = ltid + kConvLoaders * r;
@@ -466,10 +468,18 @@ struct RunStager {
 #pragma unroll
       for (int j = 0; j < NY; ++j) y[j] = DyVec<InT>::load(r_dy, y_voff[j], y_soff);
     } else {
-      // rows past Co read another channel or image (or 0 past the end): they only reach output rows that are never stored
+      // The hardware range check covers the VGPR offset only (not the scalar offset), so the whole offset goes there,
+      // and the resource of this K-tile ends with the last channel of image b: output channels past Co (last co tile)
+      // are then out of range and read 0 instead of the next image or memory behind dY.
       const uint32_t step = (uint32_t)((kConvLoaders / P) * gm.OH * gm.OW) * ES;
+      const __amdgpu_buffer_rsrc_t r_img = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)dy_ptr, 0, (int)((uint32_t)((b + 1) * gm.Co * gm.OH * gm.OW) * ES), kRawBufferWord3);
+      uint32_t voff = ys_voff + y_soff;  // kOutOfRange + y_soff stays out of range: every buffer is below 2 GiB
 #pragma unroll
-      for (int j = 0; j < NE; ++j) ys[j] = load_val_bits(r_dy, ys_voff, InT(), y_soff + (uint32_t)j * step);
+      for (int j = 0; j < NE; ++j) {
+        ys[j] = load_val_bits(r_img, voff, InT());
+        voff += step;
+      }
     }
 
     uint32_t bits[kRunsPerThread], raw[kRunsPerThread][LEN];

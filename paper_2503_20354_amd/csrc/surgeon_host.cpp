@@ -68,7 +68,7 @@ struct ProfRecord {
   hipEvent_t start, stop;
 };
 static bool g_prof_on = false;
-static int g_prof_kind = -1;  // class of the innermost live ProfScope
+static thread_local int g_prof_kind = -1;  // class of the innermost live ProfScope on this thread
 static std::vector<ProfRecord> g_prof;
 
 ProfScope::ProfScope(int kind, hipStream_t) : prev_(g_prof_kind) { g_prof_kind = kind; }

@@ -10,18 +10,11 @@ import torch
 import oracle
 import paper_2503_20354_amd as surgeon
 import surgeon_workloads as wl
+from parity_bars import TOL, assert_dw_close, rel_l2
 
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
-TOL = {"f32": 1e-5, "bf16": 2e-2}
-
-
-def rel_l2(got, ref):
-    got, ref = np.asarray(got, np.float64).ravel(), np.asarray(ref, np.float64).ravel()
-    den = np.linalg.norm(ref)
-    return np.linalg.norm(got - ref) / den if den > 0 else np.linalg.norm(got)
-
 
 def host_bits(t):
     return wl.to_numpy_bits(t)
@@ -160,7 +153,7 @@ def test_dw_linear(dtype, M, K, N):
     for r in (0.0, 0.5, 0.9):
         got, ref = run_linear(M, K, N, dtype, r, seed=M + K + N)
         assert got.shape == ref.shape == (N, K)
-        assert rel_l2(got, ref) <= TOL[dtype]
+        assert_dw_close(got, ref, dtype)
     got, _ = run_linear(M, K, N, dtype, 1.0)
     assert not got.any()  # nothing cached: the gradient is exactly zero
 
@@ -172,8 +165,7 @@ def test_dw_linear_bf16_matrix_core_path(M, K, N):
     that is not (a 19-class head) reads dY element by element."""
     for r in (0.5, 0.93):
         got, ref = run_linear(M, K, N, "bf16", r, seed=3 * M + K)
-        assert rel_l2(got, ref) <= TOL["bf16"]
-        assert rel_l2(got, ref) <= 1e-5  # exact bf16 products, fp32 accumulation: far inside the bar
+        assert_dw_close(got, ref, "bf16")
 
 
 def test_dw_linear_ratio0_is_dense_gradient():
@@ -183,7 +175,7 @@ def test_dw_linear_ratio0_is_dense_gradient():
     p = surgeon.prune_pack(A.to(DEV), K, 0.0)
     dW = surgeon.dw_from_packed(surgeon.linear_desc(M, K, N, surgeon.F32, p.k_total), p, dY.to(DEV))
     dense = dY.double().T @ A.double()
-    assert rel_l2(dW.cpu().numpy(), dense.numpy()) <= 1e-5
+    assert_dw_close(dW.cpu().numpy(), dense.numpy(), "f32")
 
 
 def run_conv(shape, dtype, r, dist="relu", seed=0):
@@ -217,7 +209,7 @@ def test_dw_conv(dtype, shape):
     for r in (0.0, 0.7):
         got, ref = run_conv(shape, dtype, r, seed=sum(shape))
         assert got.shape == ref.shape
-        assert rel_l2(got, ref) <= TOL[dtype]
+        assert_dw_close(got, ref, dtype, shape)
     got, _ = run_conv(shape, dtype, 1.0)
     assert not got.any()
 
@@ -236,7 +228,7 @@ def test_dw_conv_unpadded_and_strided(dtype, shape):
     for r in (0.0, 0.5):
         got, ref = run_conv(shape, dtype, r, seed=sum(shape))
         assert got.shape == ref.shape
-        assert rel_l2(got, ref) <= TOL[dtype]
+        assert_dw_close(got, ref, dtype, shape)
 
 
 # fp32 3x3 stride-1 pad-1 layers of width 8 / 16 / 32 with few kept elements: gradient from the kept elements alone
@@ -259,7 +251,7 @@ def test_dw_conv_from_kept_elements_only(shape):
         assert surgeon.surgeon_dw_kernel_class(desc) == ("dw_sparse" if r >= 0.85 or wide else "dw")
         got, ref = run_conv(shape, "f32", r, dist=dist, seed=sum(shape))
         assert got.shape == ref.shape
-        assert rel_l2(got, ref) <= TOL["f32"]
+        assert_dw_close(got, ref, "f32", shape)
     # the same layer with more elements kept takes the dense kernel; both agree with the oracle, hence with each other
     k = surgeon.surgeon_packed_sizes(n, 4096, 0.5, surgeon.F32)[0]
     assert surgeon.surgeon_dw_kernel_class(surgeon.conv2d_desc(Nb, Ci, H, W, Co, 3, 3, 1, 1, surgeon.F32, k)) == "dw"
@@ -329,9 +321,9 @@ def whole_path_layer(cfg, li, layer, r):
     dW = surgeon.dw_from_packed(desc, p, dY.to(DEV))
     G = surgeon.grad_importance(dW)
     torch.cuda.synchronize()
-    assert rel_l2(dW.cpu().numpy(), ref) <= TOL[layer.dtype], layer.name
+    assert_dw_close(dW.cpu().numpy(), ref, layer.dtype, layer.name)
     o_G = oracle.grad_importance(ref)
-    assert abs(G.item() - o_G) <= TOL[layer.dtype] * max(o_G, 1e-30), layer.name
+    assert abs(G.item() - o_G) <= 1e-5 * max(o_G, 1e-30), layer.name
     return G.item(), o_G
 
 
@@ -356,26 +348,70 @@ def test_workload_shapes_reduced(cfg, batch_div):
 
 
 # ------------------------------------------------------------------------------------------------
-# the benchmark workload at full size (WideResNet-28-10, batch 200): complete select/pack parity,
-# dW on sampled entries evaluated one by one from the definition
+# all five workloads at FULL size, in the launch configuration the benchmark times: complete select/pack parity,
+# dW on sampled entries evaluated one by one from the definition (the oracle cannot finish a full-size dW)
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("name,r", [("s1b2.conv1", 0.9), ("s2b1.conv1", 0.45), ("s3b2.conv2", 0.3), ("s2b1.shortcut", 0.6),
-                                    ("stem", 0.5)])
-def test_benchmark_workload_full_size_sampled(name, r):
-    layers = wl.config_layers(1)
+def full_size_layer(cfg, name, r, n_samples=2048):
+    layers = wl.config_layers(cfg)
     li = [l.name for l in layers].index(name)
     layer = layers[li]
-    A, dY = wl.layer_tensors(1, li, layer)
-    p, (o_vals, o_mask) = check_pack(A, layer.group_len, r, want_idx=False, tag=name)
-    desc = surgeon.conv2d_desc(layer.Nb, layer.Ci, layer.H, layer.W, layer.Co, layer.kh, layer.kw, layer.stride,
-                               layer.pad, surgeon.F32, p.k_total)
-    dW = surgeon.dw_from_packed(desc, p, dY.to(DEV))
+    A, dY = wl.layer_tensors(cfg, li, layer)
+    p, (o_vals, o_mask) = check_pack(A, layer.group_len, r, want_idx=False, tag="cfg%d %s" % (cfg, name))
+    dt = surgeon.F32 if layer.dtype == "f32" else surgeon.BF16
+    where = np.random.default_rng(1000 * cfg + li).integers(0, layer.n_w, n_samples)
+    if layer.kind == "linear":
+        desc = surgeon.linear_desc(layer.M, layer.K, layer.N, dt, p.k_total)
+    else:
+        desc = surgeon.conv2d_desc(layer.Nb, layer.Ci, layer.H, layer.W, layer.Co, layer.kh, layer.kw, layer.stride,
+                                   layer.pad, dt, p.k_total)
+    kernel_class = surgeon.surgeon_dw_kernel_class(desc)
+    dW = surgeon.dw_from_packed(desc, p, dY.to(DEV))  # passes the packing's (group_len, r) on, as the benchmark does
     G = surgeon.grad_importance(dW)
     torch.cuda.synchronize()
-    where = np.random.default_rng(li).integers(0, layer.n_w, 2048)
-    ref = oracle.dw_conv2d_at(o_vals, o_mask, host_bits(dY), layer.Nb, layer.Ci, layer.H, layer.W, layer.Co, layer.kh,
-                              layer.kw, layer.stride, layer.pad, where)
+    if layer.kind == "linear":
+        ref = oracle.dw_linear_at(o_vals, o_mask, host_bits(dY), layer.M, layer.K, layer.N, where)
+    else:
+        ref = oracle.dw_conv2d_at(o_vals, o_mask, host_bits(dY), layer.Nb, layer.Ci, layer.H, layer.W, layer.Co,
+                                  layer.kh, layer.kw, layer.stride, layer.pad, where)
     got = dW.cpu().numpy().reshape(-1)
-    assert rel_l2(got[where], ref) <= 1e-5
+    assert np.isfinite(got).all()
+    assert_dw_close(got[where], ref, layer.dtype, (cfg, name, r))
     # Gradient Importance of the full gradient the GPU produced, against the oracle on the same values
     assert abs(G.item() - oracle.grad_importance(got)) <= 1e-5 * G.item()
+    return kernel_class
+
+
+# WideResNet-28-10, batch 200 (fp32).  0.9 is the importance pass; s3b2.conv2 at 0.79 is what the ratio rule gives
+# the last stage: the 16-wavefront kept-elements kernel with shared taps on 640 channels.
+@pytest.mark.parametrize("name,r", [("s1b2.conv1", 0.9), ("s2b1.conv1", 0.45), ("s3b2.conv2", 0.3), ("s2b1.shortcut", 0.6),
+                                    ("stem", 0.5), ("s3b2.conv2", 0.79), ("s3b3.conv1", 0.9), ("s2b3.conv2", 0.9),
+                                    ("s3b1.conv1", 0.9), ("s1b1.shortcut", 0.9)])
+def test_benchmark_workload_full_size_sampled(name, r):
+    cls = full_size_layer(1, name, r)
+    if name in ("s3b2.conv2", "s3b3.conv1", "s2b3.conv2", "s1b2.conv1") and r >= 0.79:
+        assert cls == "dw_sparse"
+
+
+# ResNet-50, batch 64 (bf16, post-ReLU): the stem, a 3x3 and a 1x1 of each stage, both kinds of downsample
+@pytest.mark.parametrize("name,r", [("stem", 0.5), ("s1b1.conv2", 0.9), ("s2b1.conv2", 0.7), ("s3b2.conv2", 0.9),
+                                    ("s4b2.conv2", 0.6), ("s1b1.conv1", 0.9), ("s1b1.conv3", 0.8), ("s2b2.conv1", 0.9),
+                                    ("s3b2.conv3", 0.55), ("s4b2.conv1", 0.9), ("s4b3.conv3", 0.95),
+                                    ("s1b1.downsample", 0.9), ("s2b1.downsample", 0.75), ("s4b1.downsample", 0.9)])
+def test_resnet50_workload_full_size_sampled(name, r):
+    full_size_layer(2, name, r)
+
+
+# ViT-B/16, 12 608 tokens (bf16): the wide tile and the long split contraction are only reached at this size
+@pytest.mark.parametrize("name,r", [("blk0.qkv", 0.9), ("blk0.qkv", 0.6), ("blk3.proj", 0.9), ("blk3.proj", 0.5),
+                                    ("blk5.fc1", 0.9), ("blk5.fc1", 0.7), ("blk11.fc2", 0.9), ("blk11.fc2", 0.55)])
+def test_vit_workload_full_size_sampled(name, r):
+    full_size_layer(3, name, r)
+
+
+# segmentation transformer, batch 2 (bf16): 65 536-token layers of 64 channels, the reduced-token kv layer, the
+# 3072 -> 768 fuse layer (201 M elements) and the 19-class head (dY rows not 16-byte aligned)
+@pytest.mark.parametrize("name,r", [("st1b1.fc1", 0.9), ("st1b1.q", 0.8), ("st1b2.fc2", 0.9), ("st2b1.proj", 0.7),
+                                    ("st3b1.kv", 0.9), ("st3b7.fc2", 0.75), ("st4b1.fc1", 0.9), ("dec.proj1", 0.9),
+                                    ("dec.fuse", 0.9), ("dec.fuse", 0.65), ("dec.cls", 0.9), ("dec.cls", 0.6)])
+def test_segmentation_workload_full_size_sampled(name, r):
+    full_size_layer(4, name, r)

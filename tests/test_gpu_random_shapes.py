@@ -13,16 +13,10 @@ import torch
 import oracle
 import paper_2503_20354_amd as surgeon
 import surgeon_workloads as wl
+from parity_bars import assert_dw_close
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-TOL = {"f32": 1e-5, "bf16": 2e-2}  # rel-L2 bounds of the benchmark spec for fp32 / bf16 inputs
-
-
-def rel_l2(got, ref):
-    got, ref = np.asarray(got, np.float64).ravel(), np.asarray(ref, np.float64).ravel()
-    den = np.linalg.norm(ref)
-    return np.linalg.norm(got - ref) / den if den > 0 else np.linalg.norm(got)
 
 
 def pack_and_check(A, g, r):
@@ -77,7 +71,7 @@ def test_random_conv_shapes(seed):
                                    r=r if hint else 0.0)
         got = dw_on_gpu(desc, p, dY, (Co, Ci, k, k))
         ref = oracle.dw_conv2d(o_vals, o_mask, wl.to_numpy_bits(dY), Nb, Ci, H, W, Co, k, k, st, pad)
-        assert rel_l2(got, ref) <= TOL[dtype]
+        assert_dw_close(got, ref, dtype)
         done += 1
 
 
@@ -106,7 +100,7 @@ def test_random_shapes_of_the_kept_elements_kernel(seed):
             assert surgeon.surgeon_dw_kernel_class(desc) == "dw_sparse"
         got = dw_on_gpu(desc, p, dY, (Co, Ci, 3, 3))
         ref = oracle.dw_conv2d(o_vals, o_mask, wl.to_numpy_bits(dY), Nb, Ci, H, W, Co, 3, 3, 1, 1)
-        assert rel_l2(got, ref) <= TOL["f32"]
+        assert_dw_close(got, ref, "f32")
 
 
 @pytest.mark.parametrize("seed", [201, 202])
@@ -128,7 +122,7 @@ def test_random_linear_shapes(seed):
         desc = surgeon.linear_desc(M, K, N, dt, p.k_total, group_len=g if hint else 0, r=r if hint else 0.0)
         got = dw_on_gpu(desc, p, dY, (N, K))
         ref = oracle.dw_linear(o_vals, o_mask, wl.to_numpy_bits(dY), M, K, N)
-        assert rel_l2(got, ref) <= TOL[dtype]
+        assert_dw_close(got, ref, dtype)
 
 
 @pytest.mark.parametrize("seed", [301])

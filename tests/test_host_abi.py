@@ -116,3 +116,31 @@ def test_dw_workspace_and_shape_errors():
     assert e.value.status == 1
     with pytest.raises(surgeon.SurgeonError):
         surgeon.surgeon_dw_ws_bytes(surgeon.linear_desc(4, 4, 4, surgeon.F32, 17))  # k_total > n
+
+
+def test_undersized_workspace_is_rejected_before_any_launch():
+    """SURGEON_ESIZE comes from the host checks: with a workspace one byte short nothing is launched, so made-up
+    (aligned, never dereferenced) pointers are enough and the test needs no GPU."""
+    lib = surgeon.load_library()
+    fake = lambda k: ctypes.c_void_p(0x10000 * k)
+    # weight gradient: conv layer with a split contraction
+    d = surgeon.conv2d_desc(200, 160, 32, 32, 160, 3, 3, 1, 1, surgeon.F32, 200 * 160 * 32 * 32 // 2)
+    need = surgeon.surgeon_dw_ws_bytes(d)
+    assert need > 16
+    rc = lib.surgeon_dw_from_packed(ctypes.byref(d), fake(1), fake(2), fake(3), fake(4), fake(5), need - 1, None)
+    assert rc == 2 and "workspace" in surgeon.surgeon_last_error()
+    rc = lib.surgeon_dw_from_packed(ctypes.byref(d), fake(1), fake(2), fake(3), fake(4), None, 0, None)
+    assert rc == 2
+    # selection over the whole tensor needs a workspace; groups of at most 4096 elements need none
+    n = 1 << 20
+    need = surgeon.surgeon_packed_sizes(n, n, 0.5, surgeon.F32)[3]
+    assert need > 0
+    rc = lib.surgeon_prune_pack(fake(1), n, n, 0.5, surgeon.F32, fake(2), fake(3), None, fake(4), need - 1, None)
+    assert rc == 2 and "workspace" in surgeon.surgeon_last_error()
+    rc = lib.surgeon_prune_pack(fake(1), n, n, 0.5, surgeon.F32, fake(2), fake(3), None, None, 0, None)
+    assert rc == 2
+    # Gradient Importance
+    need = surgeon.surgeon_grad_importance_ws_bytes(5_000_000)
+    if need > 0:
+        rc = lib.surgeon_grad_importance(fake(1), 5_000_000, fake(2), fake(3), need - 1, None)
+        assert rc == 2
