@@ -54,6 +54,22 @@ def lib():
         L.oracle_layer_scores.argtypes = [vp, vp, ci, vp, vp, vp]
         L.oracle_layer_ratios.restype = ci
         L.oracle_layer_ratios.argtypes = [vp, vp, ci, f32, f32, vp]
+        L.oracle_da_linear.restype = ci
+        L.oracle_da_linear.argtypes = [vp, vp, i64, i64, i64, ci, vp]
+        L.oracle_da_linear_at.restype = ci
+        L.oracle_da_linear_at.argtypes = [vp, vp, i64, i64, i64, ci, vp, i64, vp]
+        L.oracle_da_conv2d.restype = ci
+        L.oracle_da_conv2d.argtypes = [vp, vp] + [i64] * 9 + [ci, vp]
+        L.oracle_da_conv2d_at.restype = ci
+        L.oracle_da_conv2d_at.argtypes = [vp, vp] + [i64] * 9 + [ci, vp, i64, vp]
+        L.oracle_weight_update.restype = ci
+        L.oracle_weight_update.argtypes = [vp, vp, i64, f32, ci, vp]
+        L.oracle_affine_grad.restype = ci
+        L.oracle_affine_grad.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, vp]
+        L.oracle_dw_conv2d_grouped.restype = ci
+        L.oracle_dw_conv2d_grouped.argtypes = [vp, vp, vp] + [i64] * 10 + [ci, vp]
+        L.oracle_dw_conv2d_grouped_at.restype = ci
+        L.oracle_dw_conv2d_grouped_at.argtypes = [vp, vp, vp] + [i64] * 10 + [ci, vp, i64, vp]
         _lib = L
     return _lib
 
@@ -185,4 +201,75 @@ def layer_ratios(G, m, r_lo=0.0, r_hi=1.0):
     rc = lib().oracle_layer_ratios(_p(G), _p(m), G.size, float(r_lo), float(r_hi), _p(out))
     if rc != 0:
         raise ValueError("oracle_layer_ratios: bad input")
+    return out
+
+
+def da_linear(dY, W, M, K, N):
+    """Eq. 2, first line: dA [M, K] = dY [M, N] . W [N, K], in the dtype of the inputs."""
+    dY, W = _c(dY), _c(W)
+    assert _dt(dY) == _dt(W) and dY.size == M * N and W.size == N * K
+    dA = np.empty((M, K), dtype=dY.dtype)
+    assert lib().oracle_da_linear(_p(dY), _p(W), M, K, N, _dt(dY), _p(dA)) == 0
+    return dA
+
+
+def da_linear_at(dY, W, M, K, N, where):
+    dY, W, where = _c(dY), _c(W), _c(where, np.int64)
+    out = np.empty(where.size, dtype=dY.dtype)
+    assert lib().oracle_da_linear_at(_p(dY), _p(W), M, K, N, _dt(dY), _p(where), where.size, _p(out)) == 0
+    return out
+
+
+def da_conv2d(dY, W, Nb, Ci, H, Wd, Co, kh, kw, stride, pad):
+    """Activation gradient of a 2-D convolution: dA [Nb, Ci, H, Wd] in the dtype of the inputs."""
+    dY, W = _c(dY), _c(W)
+    OH, OW = (H + 2 * pad - kh) // stride + 1, (Wd + 2 * pad - kw) // stride + 1
+    assert _dt(dY) == _dt(W) and dY.size == Nb * Co * OH * OW and W.size == Co * Ci * kh * kw
+    dA = np.empty((Nb, Ci, H, Wd), dtype=dY.dtype)
+    assert lib().oracle_da_conv2d(_p(dY), _p(W), Nb, Ci, H, Wd, Co, kh, kw, stride, pad, _dt(dY), _p(dA)) == 0
+    return dA
+
+
+def da_conv2d_at(dY, W, Nb, Ci, H, Wd, Co, kh, kw, stride, pad, where):
+    dY, W, where = _c(dY), _c(W), _c(where, np.int64)
+    out = np.empty(where.size, dtype=dY.dtype)
+    assert lib().oracle_da_conv2d_at(_p(dY), _p(W), Nb, Ci, H, Wd, Co, kh, kw, stride, pad, _dt(dY), _p(where),
+                                     where.size, _p(out)) == 0
+    return out
+
+
+def weight_update(W, dW, lr):
+    """Alg. 1 line 14 as one plain gradient step: W - lr * dW in the dtype of W."""
+    W, dW = _c(W), _c(dW, np.float32)
+    assert W.size == dW.size
+    out = np.empty(W.shape, dtype=W.dtype)
+    assert lib().oracle_weight_update(_p(W), _p(dW), W.size, float(np.float32(lr)), _dt(W), _p(out)) == 0
+    return out
+
+
+def affine_grad(vals, mask, dY, outer, C, inner):
+    """Scale / shift gradients of a normalisation layer from the pruned normalised activation: (dgamma, dbeta)."""
+    vals, mask, dY = _c(vals), _c(mask, np.uint64), _c(dY)
+    assert _dt(vals) == _dt(dY) and dY.size == outer * C * inner
+    dgamma, dbeta = np.empty(C, dtype=np.float32), np.empty(C, dtype=np.float32)
+    assert lib().oracle_affine_grad(_p(vals), _p(mask), _p(dY), outer, C, inner, _dt(vals), _p(dgamma), _p(dbeta)) == 0
+    return dgamma, dbeta
+
+
+def dw_conv2d_grouped(vals, mask, dY, Nb, Ci, H, W, Co, kh, kw, stride, pad, groups):
+    """Weight gradient of a convolution with channel groups as [Co, Ci/groups, kh, kw] float32."""
+    vals, mask, dY = _c(vals), _c(mask, np.uint64), _c(dY)
+    dW = np.empty((Co, Ci // groups, kh, kw), dtype=np.float32)
+    rc = lib().oracle_dw_conv2d_grouped(_p(vals), _p(mask), _p(dY), Nb, Ci, H, W, Co, kh, kw, stride, pad, groups,
+                                        _dt(vals), _p(dW))
+    assert rc == 0
+    return dW
+
+
+def dw_conv2d_grouped_at(vals, mask, dY, Nb, Ci, H, W, Co, kh, kw, stride, pad, groups, where):
+    vals, mask, dY, where = _c(vals), _c(mask, np.uint64), _c(dY), _c(where, np.int64)
+    out = np.empty(where.size, dtype=np.float32)
+    rc = lib().oracle_dw_conv2d_grouped_at(_p(vals), _p(mask), _p(dY), Nb, Ci, H, W, Co, kh, kw, stride, pad, groups,
+                                           _dt(vals), _p(where), where.size, _p(out))
+    assert rc == 0
     return out

@@ -15,10 +15,20 @@
  *   oracle_dw_*_at         the same definitions evaluated at caller-chosen output entries only
  *   oracle_grad_importance Eq. 4
  *   oracle_layer_scores / oracle_layer_ratios   Eq. 5, 6, 7
+ *   oracle_da_linear / oracle_da_conv2d (+ _at)  Eq. 2, first line: the activation gradient dA = dY . W
+ *   oracle_weight_update   Alg. 1 line 14 read as one plain gradient step W <- W - lr * dW (the paper defers its
+ *                          optimiser settings to an appendix that is not available)
+ *   oracle_affine_grad     gradients of a normalisation layer's scale and shift from the pruned normalised
+ *                          activation (the variant of Section 5 that updates BN layers only): the same sum as
+ *                          Eq. 2's second line for an element-wise layer y = gamma * x_hat + beta
+ *   oracle_dw_conv2d_grouped (+ _at)  the convolution weight gradient with channel groups (grouped and depthwise
+ *                          convolutions of the ResNeXt / Segformer networks of Section 5.1)
  *
- * Floating point: every accumulation is in double; results are rounded once to float.
+ * Floating point: every accumulation is in double; results are rounded once to float (or once, to nearest even,
+ * to bfloat16 where an output is stored in the layer's own dtype).
  * Pins: tests/test_oracle_*.py check each function against brute-force rank counting, numpy float64
- * matmul, torch.nn.grad.conv2d_weight in float64, closed forms and hand-derived examples of Eq. 5-7.
+ * matmul, torch.nn.grad.conv2d_weight / conv2d_input in float64 (also with groups), the adjoint identity
+ * <dY, conv(A, W)> = <dA, A> = <dW, W>, closed forms and hand-derived examples of Eq. 5-7.
  * The paper prints no numeric example for any quantity on this path, so there is no pin against a value
  * printed in the paper ("parity unpinned" with respect to the paper's own tables).
  *
@@ -312,4 +322,214 @@ int oracle_layer_ratios(const float* G, const uint64_t* m, int l, float r_lo, fl
     for (int i = 0; i < l; ++i) r_out[i] = (float)((double)r_lo + ((double)r_hi - (double)r_lo) * p[i]);
   free(p);
   return rc;
+}
+
+
+/* ---------------------------------------------------------------------------------------------------------
+ * The rest of Alg. 1's backward step and the other layer types
+ * --------------------------------------------------------------------------------------------------------- */
+
+/* double -> bfloat16 bit pattern, round to nearest, ties to even, decided on the double itself (going through
+ * float first would round twice) */
+static uint16_t double_to_bf16(double x) {
+  if (isnan(x)) return 0x7fc0u;
+  float f = (float)x;
+  uint32_t fb;
+  memcpy(&fb, &f, 4);
+  if (isinf(f)) return (uint16_t)(fb >> 16);
+  /* candidates: the bfloat16 at or next to the truncated float pattern; pick the nearest to x, ties to even */
+  uint32_t base = fb & 0xffff0000u;
+  uint32_t best_bits = base;
+  double best_err = -1.0;
+  for (int d = -1; d <= 1; ++d) {
+    uint32_t cb = base + (uint32_t)(d * 0x10000);
+    if ((cb & 0x7f800000u) == 0x7f800000u && d != 0) {
+      /* stepping into the infinity pattern is a legal rounding result only for values beyond the largest finite */
+      if ((cb & 0x007f0000u) != 0) continue;
+    }
+    float cf;
+    memcpy(&cf, &cb, 4);
+    if ((cb ^ fb) & 0x80000000u) continue; /* crossed zero */
+    double err = fabs(x - (double)cf);
+    if (isinf(cf)) err = fabs(x) - 3.3961775292304601e38 >= 0 ? 0.0 : INFINITY; /* halfway point to infinity */
+    if (best_err < 0.0 || err < best_err || (err == best_err && ((cb >> 16) & 1u) == 0u)) {
+      best_err = err;
+      best_bits = cb;
+    }
+  }
+  return (uint16_t)(best_bits >> 16);
+}
+
+static void store_rounded(void* out, int dt, int64_t i, double x) {
+  if (dt == ORACLE_F32) ((float*)out)[i] = (float)x;
+  else ((uint16_t*)out)[i] = double_to_bf16(x);
+}
+
+/* Eq. 2, first line, linear layer: dA[m][k] = sum_n dY[m][n] * W[n][k]; dY is [M x N], W is [N x K] (the layout
+ * of a framework's weight), dA is [M x K] in the dtype of dY and W */
+int oracle_da_linear(const void* dY, const void* Wt, int64_t M, int64_t K, int64_t N, int dt, void* dA) {
+#pragma omp parallel for schedule(static)
+  for (int64_t m = 0; m < M; ++m) {
+    for (int64_t k = 0; k < K; ++k) {
+      double acc = 0.0;
+      for (int64_t n = 0; n < N; ++n) acc += elem_as_double(dY, dt, m * N + n) * elem_as_double(Wt, dt, n * K + k);
+      store_rounded(dA, dt, m * K + k, acc);
+    }
+  }
+  return 0;
+}
+
+int oracle_da_linear_at(const void* dY, const void* Wt, int64_t M, int64_t K, int64_t N, int dt,
+                        const int64_t* where, int64_t n_where, void* out) {
+  (void)M;
+#pragma omp parallel for schedule(static)
+  for (int64_t s = 0; s < n_where; ++s) {
+    const int64_t m = where[s] / K, k = where[s] % K;
+    double acc = 0.0;
+    for (int64_t n = 0; n < N; ++n) acc += elem_as_double(dY, dt, m * N + n) * elem_as_double(Wt, dt, n * K + k);
+    store_rounded(out, dt, s, acc);
+  }
+  return 0;
+}
+
+/* one entry of the activation gradient of y = conv2d(A, W): every output position (oh, ow) and tap (u, v) with
+ * oh*stride + u - pad == ih and ow*stride + v - pad == iw contributes dY[b][co][oh][ow] * W[co][ci][u][v] */
+static double conv_da_entry(const void* dY, const void* Wt, int dt, int64_t Ci, int64_t Co, int64_t OH, int64_t OW,
+                            int64_t kh, int64_t kw, int64_t stride, int64_t pad, int64_t b, int64_t ci, int64_t ih,
+                            int64_t iw) {
+  double acc = 0.0;
+  for (int64_t co = 0; co < Co; ++co) {
+    for (int64_t u = 0; u < kh; ++u) {
+      const int64_t top = ih + pad - u;
+      if (top < 0 || top % stride != 0 || top / stride >= OH) continue;
+      for (int64_t v = 0; v < kw; ++v) {
+        const int64_t left = iw + pad - v;
+        if (left < 0 || left % stride != 0 || left / stride >= OW) continue;
+        acc += elem_as_double(dY, dt, ((b * Co + co) * OH + top / stride) * OW + left / stride) *
+               elem_as_double(Wt, dt, ((co * Ci + ci) * kh + u) * kw + v);
+      }
+    }
+  }
+  return acc;
+}
+
+/* Activation gradient of a 2-D convolution (cross-correlation, zero padding, no dilation, groups = 1):
+ * dY [Nb, Co, OH, OW], W [Co, Ci, kh, kw]  ->  dA [Nb, Ci, H, W] in the dtype of the inputs */
+int oracle_da_conv2d(const void* dY, const void* Wt, int64_t Nb, int64_t Ci, int64_t H, int64_t W, int64_t Co,
+                     int64_t kh, int64_t kw, int64_t stride, int64_t pad, int dt, void* dA) {
+  const int64_t OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1;
+#pragma omp parallel for schedule(static) collapse(2)
+  for (int64_t b = 0; b < Nb; ++b) {
+    for (int64_t ci = 0; ci < Ci; ++ci) {
+      for (int64_t ih = 0; ih < H; ++ih)
+        for (int64_t iw = 0; iw < W; ++iw)
+          store_rounded(dA, dt, ((b * Ci + ci) * H + ih) * W + iw,
+                        conv_da_entry(dY, Wt, dt, Ci, Co, OH, OW, kh, kw, stride, pad, b, ci, ih, iw));
+    }
+  }
+  return 0;
+}
+
+int oracle_da_conv2d_at(const void* dY, const void* Wt, int64_t Nb, int64_t Ci, int64_t H, int64_t W, int64_t Co,
+                        int64_t kh, int64_t kw, int64_t stride, int64_t pad, int dt, const int64_t* where,
+                        int64_t n_where, void* out) {
+  const int64_t OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1;
+  (void)Nb;
+#pragma omp parallel for schedule(static)
+  for (int64_t s = 0; s < n_where; ++s) {
+    int64_t f = where[s];
+    const int64_t iw = f % W;
+    f /= W;
+    const int64_t ih = f % H;
+    f /= H;
+    const int64_t ci = f % Ci, b = f / Ci;
+    store_rounded(out, dt, s, conv_da_entry(dY, Wt, dt, Ci, Co, OH, OW, kh, kw, stride, pad, b, ci, ih, iw));
+  }
+  return 0;
+}
+
+/* Alg. 1 line 14 as one plain gradient step: W_new[j] = W[j] - lr * dW[j]; W in the layer's dtype, dW float */
+int oracle_weight_update(const void* Wt, const float* dW, int64_t n, float lr, int dt, void* W_new) {
+  for (int64_t j = 0; j < n; ++j) store_rounded(W_new, dt, j, elem_as_double(Wt, dt, j) - (double)lr * (double)dW[j]);
+  return 0;
+}
+
+/*
+ * Scale and shift gradients of a normalisation layer y = gamma[c] * x_hat + beta[c] from the pruned normalised
+ * activation: dgamma[c] = sum dY * x_hat_pruned, dbeta[c] = sum dY, both over every element of channel c.
+ * Element (o, c, i) of the [outer, C, inner] tensor sits at (o*C + c)*inner + i: batch norm over NCHW is
+ * (Nb, C, H*W), layer norm over [tokens, features] is (tokens, features, 1).
+ */
+int oracle_affine_grad(const void* vals, const uint64_t* mask, const void* dY, int64_t outer, int64_t C,
+                       int64_t inner, int dt, float* dgamma, float* dbeta) {
+  double* Xd = unpack_to_double(vals, mask, outer * C * inner, dt);
+  if (!Xd) return -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t c = 0; c < C; ++c) {
+    double g = 0.0, b = 0.0;
+    for (int64_t o = 0; o < outer; ++o) {
+      for (int64_t i = 0; i < inner; ++i) {
+        const int64_t e = (o * C + c) * inner + i;
+        const double dy = elem_as_double(dY, dt, e);
+        g += dy * Xd[e];
+        b += dy;
+      }
+    }
+    dgamma[c] = (float)g;
+    dbeta[c] = (float)b;
+  }
+  free(Xd);
+  return 0;
+}
+
+/* one entry of the weight gradient of a convolution with channel groups: output channel co belongs to group
+ * co / (Co/groups) and sees the input channels of that group only; cig indexes them inside the group */
+static double conv_dw_grouped_entry(const double* Ad, const void* dY, int dt, int64_t Nb, int64_t Ci, int64_t H,
+                                    int64_t W, int64_t Co, int64_t OH, int64_t OW, int64_t stride, int64_t pad,
+                                    int64_t groups, int64_t co, int64_t cig, int64_t u, int64_t v) {
+  const int64_t ci = (co / (Co / groups)) * (Ci / groups) + cig;
+  return conv_dw_entry(Ad, dY, dt, Nb, Ci, H, W, Co, OH, OW, stride, pad, co, ci, u, v);
+}
+
+/* dW [Co, Ci/groups, kh, kw]; groups == Ci == Co is a depthwise convolution */
+int oracle_dw_conv2d_grouped(const void* vals, const uint64_t* mask, const void* dY, int64_t Nb, int64_t Ci,
+                             int64_t H, int64_t W, int64_t Co, int64_t kh, int64_t kw, int64_t stride, int64_t pad,
+                             int64_t groups, int dt, float* dW) {
+  if (groups < 1 || Ci % groups || Co % groups) return -2;
+  const int64_t OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1, Cig = Ci / groups;
+  double* Ad = unpack_to_double(vals, mask, Nb * Ci * H * W, dt);
+  if (!Ad) return -1;
+#pragma omp parallel for schedule(static) collapse(2)
+  for (int64_t co = 0; co < Co; ++co) {
+    for (int64_t cig = 0; cig < Cig; ++cig) {
+      for (int64_t u = 0; u < kh; ++u)
+        for (int64_t v = 0; v < kw; ++v)
+          dW[((co * Cig + cig) * kh + u) * kw + v] = (float)conv_dw_grouped_entry(
+              Ad, dY, dt, Nb, Ci, H, W, Co, OH, OW, stride, pad, groups, co, cig, u, v);
+    }
+  }
+  free(Ad);
+  return 0;
+}
+
+int oracle_dw_conv2d_grouped_at(const void* vals, const uint64_t* mask, const void* dY, int64_t Nb, int64_t Ci,
+                                int64_t H, int64_t W, int64_t Co, int64_t kh, int64_t kw, int64_t stride,
+                                int64_t pad, int64_t groups, int dt, const int64_t* where, int64_t n_where,
+                                float* out) {
+  if (groups < 1 || Ci % groups || Co % groups) return -2;
+  const int64_t OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1, Cig = Ci / groups;
+  double* Ad = unpack_to_double(vals, mask, Nb * Ci * H * W, dt);
+  if (!Ad) return -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t s = 0; s < n_where; ++s) {
+    int64_t f = where[s];
+    const int64_t v = f % kw;
+    f /= kw;
+    const int64_t u = f % kh;
+    f /= kh;
+    const int64_t cig = f % Cig, co = f / Cig;
+    out[s] = (float)conv_dw_grouped_entry(Ad, dY, dt, Nb, Ci, H, W, Co, OH, OW, stride, pad, groups, co, cig, u, v);
+  }
+  free(Ad);
+  return 0;
 }
