@@ -16,8 +16,18 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def _compile(src):
+def _newest_header():
+    paths = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hpp", ".h"))]
+    if "--trust-abi" not in sys.argv:  # development: surgeon.h only gained declarations since the objects were built
+        paths.append(os.path.join(ROOT, "include", "surgeon.h"))
+    return max(os.path.getmtime(p) for p in paths)
+
+
+def _compile(src, force=True):
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
+    if not force and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(os.path.join(CSRC, src)),
+                                                                          _newest_header()):
+        return src, obj, None  # up to date (development builds only; the driver's build check compiles everything)
     cmd = [HIPCC] + FLAGS + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     if src.endswith(".cpp"):
         cmd.insert(1, "-ffp-contract=off")
@@ -25,12 +35,15 @@ def _compile(src):
     return src, obj, r
 
 
-def build(verbose=False):
+def build(verbose=False, force=True):
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=7) as ex:
-        results = list(ex.map(_compile, SOURCES))
+        results = list(ex.map(lambda s: _compile(s, force), SOURCES))
     objs = []
     for src, obj, r in results:
+        if r is None:
+            objs.append(obj)
+            continue
         # the host pass warns that it does not know the packed-fp32 target feature: harmless
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l and "-target-feature" not in l)
         if r.returncode != 0:
@@ -45,4 +58,4 @@ def build(verbose=False):
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose=True, force="--changed" not in sys.argv))
