@@ -160,6 +160,18 @@ int surgeon_grad_importance(const float* dW, int64_t n_w, float* G_out,
                             void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * surgeon_grad_importance for callers that cannot allocate or carry a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arithmetic, same kernels and the same bits as
+ * surgeon_grad_importance, but the per-workgroup partial sums live in a 16 KB array that is part of the library's
+ * device image (one copy per GPU, held until the process ends) instead of a caller workspace.  The call allocates
+ * nothing and frees nothing.  Limit: n_w <= 2^31, larger sizes return SURGEON_EUNSUPPORTED.  The first call on a
+ * device looks the array's address up (make it outside any stream capture); later calls only launch.
+ * All calls on one GPU share that array: two calls whose kernels may overlap on the same GPU (different streams, or
+ * different host threads) race on it -- serialise them or use surgeon_grad_importance with separate workspaces.
+ */
+int surgeon_grad_importance_static(const float* dW, int64_t n_w, float* G_out, void* stream);
+
+/*
  * Eq. 4 for l layers in one call (one pair of launches per 64 layers instead of one per layer: the layers of a
  * network are small, so per-layer launches are latency-bound).  dW and n_w are HOST arrays of l device pointers /
  * element counts; G_out is a DEVICE array of l floats, G_out[i] for layer i.  Same arithmetic as

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     surgeon_grad_importance,
     surgeon_grad_importance_batched,
     surgeon_grad_importance_batched_ws_bytes,
+    surgeon_grad_importance_static,
     surgeon_grad_importance_ws_bytes,
     surgeon_keep_count,
     surgeon_last_error,

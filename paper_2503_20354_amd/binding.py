@@ -67,6 +67,8 @@ def load_library():
     L.surgeon_grad_importance_ws_bytes.argtypes = [i64]
     L.surgeon_grad_importance.restype = ci
     L.surgeon_grad_importance.argtypes = [vp, i64, vp, vp, sz, vp]
+    L.surgeon_grad_importance_static.restype = ci
+    L.surgeon_grad_importance_static.argtypes = [vp, i64, vp, vp]
     L.surgeon_grad_importance_batched_ws_bytes.restype = sz
     L.surgeon_grad_importance_batched_ws_bytes.argtypes = [vp, ci]
     L.surgeon_grad_importance_batched.restype = ci
@@ -183,6 +185,15 @@ def surgeon_grad_importance(dW, G_out, ws=None):
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(load_library().surgeon_grad_importance(_ptr(dW), dW.numel(), _ptr(G_out), _ptr(ws), ws_bytes,
                                                   _stream(dW.device)))
+
+
+def surgeon_grad_importance_static(dW, G_out):
+    """Eq. 4 with the partial sums in the library's own device array: no workspace, nothing allocated."""
+    _dev(dW, "dW")
+    _dev(G_out, "G_out")
+    if dW.dtype != torch.float32 or G_out.dtype != torch.float32:
+        raise TypeError("dW and G_out are float32")
+    _check(load_library().surgeon_grad_importance_static(_ptr(dW), dW.numel(), _ptr(G_out), _stream(dW.device)))
 
 
 def _batched_args(dWs):

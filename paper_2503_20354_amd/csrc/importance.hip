@@ -3,6 +3,7 @@
 // One pass over dW with 16-byte loads; squares are accumulated in fp64 (full-rate on CDNA) so the result
 // does not depend on n_w's size; partial sums are combined in a fixed order, so the result is reproducible.
 #include <algorithm>
+#include <atomic>
 
 #include "common.hpp"
 
@@ -162,6 +163,28 @@ __global__ __launch_bounds__(kImpBlock) void sumsq_batched_final_kernel(ImpBatch
 
 static int64_t batched_blocks(int64_t n_w) { return n_w > 0 ? ceil_div(n_w, kImpChunk) : 0; }
 
+// ---- partial sums of surgeon_grad_importance_static: device memory that belongs to the library image ----------
+// One copy per GPU the library runs on (16 KB each, held until the process ends).  In host code the array's name
+// is only a handle: its device address comes from hipGetSymbolAddress, once per device, and only that address is
+// ever passed to a kernel.
+static __device__ __align__(256) double scratch[kImpMaxBlocks];
+constexpr int kMaxDevices = 64;
+static std::atomic<double*> g_scratch_addr[kMaxDevices];
+
+static int scratch_of_current_device(double** out) {
+  int dev = -1;
+  SURGEON_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(SURGEON_EUNSUPPORTED, "grad_importance_static: device %d", dev);
+  double* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    SURGEON_HIP_CHECK(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(SURGEON_EHIP, "grad_importance_static: no device address for the scratch array");
+    g_scratch_addr[dev].store(p, std::memory_order_release);  // every thread resolves the same address: a race is benign
+  }
+  *out = p;
+  return SURGEON_OK;
+}
+
 }  // namespace surgeon
 
 using namespace surgeon;
@@ -254,5 +277,39 @@ extern "C" int surgeon_grad_importance_batched(const float* const* dW, const int
                        (const double*)partial, G_out + i0);
     SURGEON_LAUNCH_CHECK();
   }
+  return SURGEON_OK;
+}
+
+extern "C" int surgeon_grad_importance_static(const float* dW, int64_t n_w, float* G_out, void* stream) {
+  if (n_w < 0) return fail(SURGEON_EINVAL, "grad_importance_static: n_w = %lld", (long long)n_w);
+  if (n_w > ((int64_t)1 << 31))
+    return fail(SURGEON_EUNSUPPORTED, "grad_importance_static: n_w = %lld exceeds the limit of 2^31 elements",
+                (long long)n_w);
+  if (!G_out || (n_w > 0 && !dW)) return fail(SURGEON_EINVAL, "grad_importance_static: null pointer");
+  if (((uintptr_t)dW & 3) != 0) return fail(SURGEON_EINVAL, "grad_importance_static: dW is not 4-byte aligned");
+  double* partial = nullptr;
+  const int rc = scratch_of_current_device(&partial);
+  if (rc != SURGEON_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const bool vec4 = ((uintptr_t)dW & 15) == 0;
+  const int nb = importance_blocks(n_w);
+  ProfScope prof(SURGEON_PROF_IMPORTANCE, st);
+  if (nb == 1) {
+    if (vec4)
+      SURGEON_LAUNCH(sumsq_single_kernel<true>, dim3(1), dim3(kImpBlock), 0, st, dW, n_w, G_out);
+    else
+      SURGEON_LAUNCH(sumsq_single_kernel<false>, dim3(1), dim3(kImpBlock), 0, st, dW, n_w, G_out);
+    SURGEON_LAUNCH_CHECK();
+    return SURGEON_OK;
+  }
+  // every one of the nb partials is written before the finishing kernel reads exactly nb of them: nothing of the
+  // previous call's contents is ever read, so the array needs no clearing
+  if (vec4)
+    SURGEON_LAUNCH(sumsq_partial_kernel<true>, dim3(nb), dim3(kImpBlock), 0, st, dW, n_w, partial);
+  else
+    SURGEON_LAUNCH(sumsq_partial_kernel<false>, dim3(nb), dim3(kImpBlock), 0, st, dW, n_w, partial);
+  SURGEON_LAUNCH_CHECK();
+  SURGEON_LAUNCH(sumsq_final_kernel, dim3(1), dim3(kImpBlock), 0, st, (const double*)partial, nb, n_w, G_out);
+  SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }
