@@ -10,7 +10,10 @@
  *
  * Conventions shared by every entry point
  *   - "device" pointers are HIP device memory the CALLER owns; the library never allocates, frees or
- *     retains device memory and keeps no state between calls.  "host" pointers are ordinary memory.
+ *     retains device memory.  It keeps no state between calls except: the thread-local text behind
+ *     surgeon_last_error(), the event pool and records of the timing aid at the end of this header (process-wide,
+ *     touched only between surgeon_profile_begin/end), and the per-device address of the static array that
+ *     surgeon_grad_importance_static uses.  "host" pointers are ordinary memory.
  *   - All device work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream)
  *     and the call returns without synchronising.
  *   - The return value is a surgeon_status.  Argument errors are found on the host before any launch and
@@ -47,16 +50,19 @@ typedef enum { SURGEON_LINEAR = 0, SURGEON_CONV2D = 1 } surgeon_layer_kind;
 
 /* kernel classes of the timing aid at the end of this header */
 enum { SURGEON_PROF_SELECT_PACK = 0, SURGEON_PROF_DW = 1, SURGEON_PROF_IMPORTANCE = 2, SURGEON_PROF_DW_AUX = 3,
-       SURGEON_PROF_SELECT_OTHER = 4, SURGEON_PROF_DW_SPARSE = 5, SURGEON_PROF_CLASSES = 6 };
+       SURGEON_PROF_SELECT_OTHER = 4, SURGEON_PROF_DW_SPARSE = 5, SURGEON_PROF_DA = 6, SURGEON_PROF_UPDATE = 7,
+       SURGEON_PROF_AFFINE = 8, SURGEON_PROF_DW_GROUPED = 9, SURGEON_PROF_CLASSES = 10 };
 
 /*
  * Shape of one adapted layer for surgeon_dw_from_packed (Eq. 2, second line).
  *   LINEAR : cached activation A is [M tokens x K in-features] row-major, dY is [M x N out-features]
  *            row-major, dW is [N x K] row-major (the layout of a framework's `weight`; it is the
  *            transpose of Eq. 2's A^T dY).
- *   CONV2D : A is [Nb, Ci, H, W], dY is [Nb, Co, OH, OW], dW is [Co, Ci, kh, kw], all contiguous NCHW,
- *            OH = (H + 2*pad - kh)/stride + 1 (same for OW); cross-correlation, zero padding,
- *            no dilation, groups = 1, no bias.
+ *   CONV2D : A is [Nb, Ci, H, W], dY is [Nb, Co, OH, OW], dW is [Co, Ci/groups, kh, kw], all contiguous NCHW
+ *            (channels-last layouts are not expressible: there is no layout field),
+ *            OH = (H + 2*pad - kh)/stride + 1 (same for OW); cross-correlation, zero padding, no dilation, no bias.
+ *            groups (0 and 1 both mean an ordinary convolution) must divide Ci and Co; output channel co then sees
+ *            input channels (co / (Co/groups)) * (Ci/groups) + [0, Ci/groups) only; groups == Ci == Co is depthwise.
  * dtype is the element type of vals and dY; dW is always fp32.
  * k_total is the number of values in the packed stream (as returned by surgeon_packed_sizes);
  * it bounds every read of `vals`.
@@ -74,6 +80,7 @@ typedef struct {
   int64_t k_total;
   int64_t group_len; /* 0 = unknown */
   float r;
+  int64_t groups;    /* CONV2D: channel groups; 0 or 1 = ordinary convolution */
 } surgeon_layer_desc;
 
 /*
@@ -118,7 +125,7 @@ int surgeon_layer_ratios(const float* G, const uint64_t* m, int l, float r_lo, f
  *   mask : ceil(n/64) uint64 words; element e <-> bit (e % 64) of word e / 64; padding bits are 0.
  *   idx  : NULL, or k_total uint32 = offset of each kept element inside its group, same order as vals.
  * n == 0 or k_total == 0 is legal.  ws/ws_bytes as reported by surgeon_packed_sizes (ws may be NULL when
- * that size is 0).  Requires n < 2^31 * 64 and group_len <= n rounded up (group_len > n is treated as n).
+ * that size is 0).  Requires n <= 2^31 (larger: SURGEON_EUNSUPPORTED); group_len > n is treated as n.
  */
 int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, float r, int dt,
                        void* vals, uint64_t* mask, uint32_t* idx,
@@ -147,6 +154,49 @@ int surgeon_dw_kernel_class(const surgeon_layer_desc* desc, int* kernel_class);
  */
 int surgeon_dw_from_packed(const surgeon_layer_desc* desc, const void* vals, const uint64_t* mask,
                            const void* dY, float* dW, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * surgeon_dw_from_packed that also returns the layer's Gradient Importance (Eq. 4) of the gradient it has just
+ * computed: the sum of squares is taken inside the pass that produces dW (the reduction over the contraction's
+ * splits) instead of reading dW again in a separate stage.  G_out: one fp32 on the device.  Same dW bits as
+ * surgeon_dw_from_packed; G agrees with surgeon_grad_importance(dW) to fp32 rounding (fp64 accumulation in a fixed
+ * order, deterministic).  Workspace from surgeon_dw_gi_ws_bytes (host only; 64 KB more than surgeon_dw_ws_bytes).
+ */
+int surgeon_dw_gi_ws_bytes(const surgeon_layer_desc* desc, size_t* ws_bytes);
+int surgeon_dw_from_packed_gi(const surgeon_layer_desc* desc, const void* vals, const uint64_t* mask, const void* dY,
+                              float* dW, float* G_out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Eq. 2, first line: the activation gradient dA = dY . W of the layer `desc` describes (k_total, group_len, r and the
+ * packed activation play no part: dA does not depend on A).
+ *   LINEAR : dY [M x N], W [N x K] (a framework's weight), dA [M x K]:  dA[m][k] = sum_n dY[m][n] * W[n][k]
+ *   CONV2D : dY [Nb, Co, OH, OW], W [Co, Ci, kh, kw], dA [Nb, Ci, H, W] (groups <= 1 only):
+ *            dA[b][ci][ih][iw] = sum over (co, u, v) with oh*stride + u - pad == ih, ow*stride + v - pad == iw
+ * dY, W and dA are device pointers of desc->dtype; accumulation is fp32 on the matrix cores, bf16 results are rounded
+ * once to nearest even.  dA is overwritten.  No workspace.  Deterministic.
+ */
+int surgeon_da(const surgeon_layer_desc* desc, const void* dY, const void* W, void* dA, void* stream);
+
+/*
+ * Alg. 1 line 14 as one plain gradient step, in place: W[j] <- W[j] - lr * dW[j] (the paper leaves its optimiser to an
+ * appendix; anything more elaborate is the caller's).  W: n elements of dtype dt on the device; dW: n fp32 on the
+ * device.  Computed as one fused multiply-add in fp32, bf16 weights rounded once to nearest even.
+ */
+int surgeon_weight_update(void* W, const float* dW, int64_t n, float lr, int dt, void* stream);
+
+/*
+ * Normalisation layers (the variant of Section 5 that adapts BN layers only): gradients of the scale and the shift
+ * of y = gamma[c] * x_hat + beta[c] from the pruned, packed normalised activation x_hat and dY,
+ *     dgamma[c] = sum dY * x_hat_pruned,   dbeta[c] = sum dY        over every element of channel c.
+ * The tensor is [outer, C, inner] with element (o, c, i) at (o*C + c)*inner + i: batch norm over NCHW is
+ * (Nb, C, H*W), layer norm over [tokens, features] is (tokens, features, 1).  vals / mask as written by
+ * surgeon_prune_pack for that tensor (any group_len), k_total its value count; dY has the dtype dt of vals.
+ * dgamma, dbeta: C fp32 each on the device, overwritten.  fp32 partial sums per slice, added per channel in fp64 in
+ * index order (deterministic).  Workspace from surgeon_affine_grad_ws_bytes (host only).
+ */
+int surgeon_affine_grad_ws_bytes(int64_t outer, int64_t C, int64_t inner, size_t* ws_bytes);
+int surgeon_affine_grad(const void* vals, const uint64_t* mask, const void* dY, int64_t outer, int64_t C, int64_t inner,
+                        int dt, int64_t k_total, float* dgamma, float* dbeta, void* ws, size_t ws_bytes, void* stream);
 
 /* Workspace surgeon_grad_importance needs for n_w elements.  Host only. */
 size_t surgeon_grad_importance_ws_bytes(int64_t n_w);
@@ -196,6 +246,10 @@ int surgeon_grad_importance_batched(const float* const* dW, const int64_t* n_w, 
  *   class 3 SURGEON_PROF_DW_AUX       rank-table pre-pass and split reduction around class 1
  *   class 4 SURGEON_PROF_SELECT_OTHER kernels of the other two selection paths, mask clearing
  *   class 5 SURGEON_PROF_DW_SPARSE    the weight-gradient kernel that works from the kept elements alone
+ *   class 6 SURGEON_PROF_DA           activation-gradient kernel (surgeon_da)
+ *   class 7 SURGEON_PROF_UPDATE       gradient step (surgeon_weight_update)
+ *   class 8 SURGEON_PROF_AFFINE       scale / shift gradients of normalisation layers, with their rank pre-pass
+ *   class 9 SURGEON_PROF_DW_GROUPED   weight-gradient kernel of grouped / depthwise convolutions
  * ms / launches are host arrays of n_classes entries (at most SURGEON_PROF_CLASSES are filled).
  * Not thread-safe; intended for one benchmarking thread.  Event objects are created by the HIP runtime, kept in a
  * pool and reused by later profiling sessions of the process.

@@ -32,7 +32,7 @@ class LayerDesc(ctypes.Structure):
                 ("Nb", ctypes.c_int64), ("Ci", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64),
                 ("Co", ctypes.c_int64), ("kh", ctypes.c_int64), ("kw", ctypes.c_int64),
                 ("stride", ctypes.c_int64), ("pad", ctypes.c_int64), ("k_total", ctypes.c_int64),
-                ("group_len", ctypes.c_int64), ("r", ctypes.c_float)]
+                ("group_len", ctypes.c_int64), ("r", ctypes.c_float), ("groups", ctypes.c_int64)]
 
 
 def library_path():
@@ -63,6 +63,18 @@ def load_library():
     L.surgeon_dw_kernel_class.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(ci)]
     L.surgeon_dw_from_packed.restype = ci
     L.surgeon_dw_from_packed.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, sz, vp]
+    L.surgeon_dw_gi_ws_bytes.restype = ci
+    L.surgeon_dw_gi_ws_bytes.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(sz)]
+    L.surgeon_dw_from_packed_gi.restype = ci
+    L.surgeon_dw_from_packed_gi.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, sz, vp]
+    L.surgeon_da.restype = ci
+    L.surgeon_da.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp]
+    L.surgeon_weight_update.restype = ci
+    L.surgeon_weight_update.argtypes = [vp, vp, i64, f32, ci, vp]
+    L.surgeon_affine_grad_ws_bytes.restype = ci
+    L.surgeon_affine_grad_ws_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
+    L.surgeon_affine_grad.restype = ci
+    L.surgeon_affine_grad.argtypes = [vp, vp, vp, i64, i64, i64, ci, i64, vp, vp, vp, sz, vp]
     L.surgeon_grad_importance_ws_bytes.restype = sz
     L.surgeon_grad_importance_ws_bytes.argtypes = [i64]
     L.surgeon_grad_importance.restype = ci
@@ -173,6 +185,59 @@ def surgeon_dw_from_packed(desc: LayerDesc, vals, mask, dY, dW, ws):
                                                  _ptr(ws), ws_bytes, _stream(dY.device)))
 
 
+def surgeon_dw_gi_ws_bytes(desc: LayerDesc) -> int:
+    wb = ctypes.c_size_t()
+    _check(load_library().surgeon_dw_gi_ws_bytes(ctypes.byref(desc), ctypes.byref(wb)))
+    return wb.value
+
+
+def surgeon_dw_from_packed_gi(desc: LayerDesc, vals, mask, dY, dW, G_out, ws):
+    """dW from the packed activation plus Eq. 4 of that gradient into G_out[0], in one call."""
+    _dev(dY, "dY")
+    _dev(dW, "dW")
+    _dev(G_out, "G_out")
+    if G_out.dtype != torch.float32:
+        raise TypeError("G_out is float32")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(load_library().surgeon_dw_from_packed_gi(ctypes.byref(desc), _ptr(vals), _ptr(mask), _ptr(dY), _ptr(dW),
+                                                    _ptr(G_out), _ptr(ws), ws_bytes, _stream(dY.device)))
+
+
+def surgeon_da(desc: LayerDesc, dY, W, dA):
+    """Eq. 2, first line: dA = dY . W (all three tensors of the layer's dtype, on the device)."""
+    for t, name in ((dY, "dY"), (W, "W"), (dA, "dA")):
+        _dev(t, name)
+        if _dt(t) != desc.dtype:
+            raise TypeError("%s does not have the layer's dtype" % name)
+    _check(load_library().surgeon_da(ctypes.byref(desc), _ptr(dY), _ptr(W), _ptr(dA), _stream(dY.device)))
+
+
+def surgeon_weight_update(W, dW, lr: float):
+    """Alg. 1 line 14 as one plain gradient step, in place: W <- W - lr * dW."""
+    _dev(W, "W")
+    _dev(dW, "dW")
+    if dW.dtype != torch.float32 or dW.numel() != W.numel():
+        raise TypeError("dW is float32 with as many elements as W")
+    _check(load_library().surgeon_weight_update(_ptr(W), _ptr(dW), W.numel(), float(lr), _dt(W), _stream(W.device)))
+
+
+def surgeon_affine_grad_ws_bytes(outer: int, C: int, inner: int) -> int:
+    wb = ctypes.c_size_t()
+    _check(load_library().surgeon_affine_grad_ws_bytes(int(outer), int(C), int(inner), ctypes.byref(wb)))
+    return wb.value
+
+
+def surgeon_affine_grad(vals, mask, dY, outer, C, inner, k_total, dgamma, dbeta, ws):
+    """Scale / shift gradients of a normalisation layer from the packed normalised activation."""
+    _dev(dY, "dY")
+    _dev(dgamma, "dgamma")
+    _dev(dbeta, "dbeta")
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(load_library().surgeon_affine_grad(_ptr(vals), _ptr(mask), _ptr(dY), int(outer), int(C), int(inner), _dt(dY),
+                                              int(k_total), _ptr(dgamma), _ptr(dbeta), _ptr(ws), ws_bytes,
+                                              _stream(dY.device)))
+
+
 def surgeon_grad_importance_ws_bytes(n_w: int) -> int:
     return int(load_library().surgeon_grad_importance_ws_bytes(int(n_w)))
 
@@ -223,7 +288,8 @@ def surgeon_grad_importance_batched(dWs, G_out, ws):
                                                           _stream(G_out.device)))
 
 
-PROF_CLASSES = ("select_pack", "dw", "importance", "dw_aux", "select_other", "dw_sparse")
+PROF_CLASSES = ("select_pack", "dw", "importance", "dw_aux", "select_other", "dw_sparse", "da", "update", "affine",
+                "dw_grouped")
 
 
 def surgeon_profile_begin():
@@ -275,9 +341,9 @@ def linear_desc(M, K, N, dtype, k_total, group_len=0, r=0.0) -> LayerDesc:
     return d
 
 
-def conv2d_desc(Nb, Ci, H, W, Co, kh, kw, stride, pad, dtype, k_total, group_len=0, r=0.0) -> LayerDesc:
+def conv2d_desc(Nb, Ci, H, W, Co, kh, kw, stride, pad, dtype, k_total, group_len=0, r=0.0, groups=1) -> LayerDesc:
     d = LayerDesc()
-    d.kind, d.dtype, d.k_total = 1, dtype, k_total
+    d.kind, d.dtype, d.k_total, d.groups = 1, dtype, k_total, groups
     d.group_len, d.r = group_len, r
     d.Nb, d.Ci, d.H, d.W, d.Co, d.kh, d.kw, d.stride, d.pad = Nb, Ci, H, W, Co, kh, kw, stride, pad
     return d
@@ -288,7 +354,7 @@ def dw_from_packed(desc: LayerDesc, packed: PackedActivation, dY: torch.Tensor, 
     if desc.kind == 0:
         shape = (desc.N, desc.K)
     else:
-        shape = (desc.Co, desc.Ci, desc.kh, desc.kw)
+        shape = (desc.Co, desc.Ci // max(desc.groups, 1), desc.kh, desc.kw)
     if dW is None:
         dW = torch.empty(shape, dtype=torch.float32, device=dY.device)
     if ws is None:
@@ -297,6 +363,15 @@ def dw_from_packed(desc: LayerDesc, packed: PackedActivation, dY: torch.Tensor, 
         desc.group_len, desc.r = packed.group_len, packed.r
     surgeon_dw_from_packed(desc, packed.vals, packed.mask, dY, dW, ws)
     return dW
+
+
+def affine_grad(packed: PackedActivation, dY: torch.Tensor, outer: int, C: int, inner: int):
+    """(dgamma, dbeta) of a normalisation layer from its packed normalised activation."""
+    dgamma = torch.empty(C, dtype=torch.float32, device=dY.device)
+    dbeta = torch.empty(C, dtype=torch.float32, device=dY.device)
+    ws = _workspace(surgeon_affine_grad_ws_bytes(outer, C, inner), dY.device)
+    surgeon_affine_grad(packed.vals, packed.mask, dY, outer, C, inner, packed.k_total, dgamma, dbeta, ws)
+    return dgamma, dbeta
 
 
 def grad_importance(dW: torch.Tensor, G_out: Optional[torch.Tensor] = None) -> torch.Tensor:

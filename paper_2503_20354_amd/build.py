@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsurgeon.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["surgeon_host.cpp", "importance.hip", "prune_pack.hip", "dw.hip", "dw_f32.hip", "dw_bf16in.hip", "dw_bf16.hip", "dw_sparse.hip"]
+SOURCES = ["surgeon_host.cpp", "importance.hip", "prune_pack.hip", "dw.hip", "dw_f32.hip", "dw_bf16in.hip", "dw_bf16.hip", "dw_sparse.hip", "da.hip", "layers.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -37,7 +37,7 @@ def _compile(src, force=True):
 
 def build(verbose=False, force=True):
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         results = list(ex.map(lambda s: _compile(s, force), SOURCES))
     objs = []
     for src, obj, r in results:

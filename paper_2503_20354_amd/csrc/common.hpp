@@ -89,6 +89,19 @@ int launch_conv3x3_sparse_f32(int Nb, int Ci, int Co, int H, int W, int64_t k_to
                               const void* vals, const uint64_t* mask, const uint32_t* word_rank, const void* dY, float* out,
                               hipStream_t st);
 
+// Eq. 4 folded into the weight-gradient call: fp64 partial sums of squares, at most kGiPartials of them (importance.hip)
+constexpr int kGiPartials = 8192;
+// sqrt(sum of the n_partial partials / n) -> G_out[0]
+int launch_sumsq_final(const double* partial, int n_partial, int64_t n, float* G_out, hipStream_t st);
+// Eq. 4 of x[0..n): partial sums into `partial` (kGiPartials doubles of scratch), then the finishing kernel
+int launch_sumsq(const float* x, int64_t n, double* partial, float* G_out, hipStream_t st);
+
+// weight gradient of convolutions with channel groups (layers.hip).  run_grouped validates, sizes and launches;
+// plan_only: validation and *off_gi (offset of the Gradient Importance partials behind its workspace) only.
+int grouped_ws_bytes(const surgeon_layer_desc* d, size_t* bytes);
+int run_grouped(const surgeon_layer_desc* d, const void* vals, const uint64_t* mask, const void* dY, float* dW, void* ws,
+                size_t ws_bytes, hipStream_t st, float* G_out, size_t* off_gi, bool plan_only);
+
 constexpr int kWaveRegMaxGroup = 4096;  // largest group one wavefront keeps in registers (64 lanes x 64)
 constexpr int kGlobalHistChunk = 16384;  // elements per block in the histogram passes of the global path
 constexpr int kGlobalWaveChunk = 4096;   // elements per wavefront in the count / pack passes of the global path

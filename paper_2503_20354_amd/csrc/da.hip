@@ -1,0 +1,294 @@
+// Activation gradient dA = dY . W (Eq. 2, first line) and the gradient step of Alg. 1 line 14.
+//
+// Together with surgeon_dw_from_packed this completes one layer's backward step of Alg. 1 (line 12 computes both
+// gradients); dA does not involve the pruned activation at all, so it is an ordinary dense contraction:
+//   linear : dA[m][k]         = sum_n        dY[m][n]        * W[n][k]
+//   conv2d : dA[b][ci][ih][iw] = sum_{co,u,v} dY[b][co][oh][ow] * W[co][ci][u][v]   with oh*stride + u - pad == ih (same for w)
+// Implicit GEMM on the fp32 matrix cores (v_mfma_f32_16x16x4_f32): one operand is gathered from dY (rows = the
+// positions of dA, i.e. tokens or pixels), the other from W (rows = the channels of dA), the contraction runs over
+// q = (co, u, v).  bf16 inputs are widened exactly while staging; accumulation is fp32; the result is rounded once
+// (to nearest even) when dA is stored as bf16.
+#include "common.hpp"
+
+namespace surgeon {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+struct DaGeom {
+  int Nb, Ci, H, W, Co, OH, OW, KH, KW, stride, pad;  // linear: Nb = M, Ci = K, Co = N, every spatial size 1
+  int64_t P;  // positions of dA: Nb * H * W
+  int Q;      // contraction length: Co * KH * KW
+  int HW;
+};
+
+template <typename T>
+__device__ __forceinline__ float da_widen(T v);
+template <>
+__device__ __forceinline__ float da_widen<float>(float v) {
+  return v;
+}
+template <>
+__device__ __forceinline__ float da_widen<uint16_t>(uint16_t v) {
+  return __uint_as_float((uint32_t)v << 16);
+}
+
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T>
+__device__ __forceinline__ void da_store(T* p, float v);
+template <>
+__device__ __forceinline__ void da_store<float>(float* p, float v) {
+  *p = v;
+}
+template <>
+__device__ __forceinline__ void da_store<uint16_t>(uint16_t* p, float v) {
+  *p = f32_to_bf16_rne(v);
+}
+
+constexpr int kDaTP = 128;  // positions per workgroup tile
+constexpr int kDaTC = 128;  // channels of dA per workgroup tile
+constexpr int kDaTQ = 32;   // contraction elements per K-tile
+constexpr int kDaSX = kDaTP + 1, kDaSY = kDaTC + 1;  // LDS row strides: odd, so that column-wise staging writes spread over the banks
+
+// blockIdx.x = position tile, blockIdx.y = channel tile.  4 wavefronts as 2 (positions) x 2 (channels), each 64 x 64.
+// LINEAR: positions are the rows of the 16x16 result tiles and channels the columns (dA is [m][k], k contiguous);
+// otherwise channels are the rows and positions the columns (dA is NCHW, pixels contiguous): either way a wavefront
+// stores runs of 16 consecutive elements.
+template <typename T, bool LINEAR>
+__global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__ dY, const T* __restrict__ Wt,
+                                                 T* __restrict__ dA) {
+  __shared__ float Xs[kDaTQ * kDaSX];  // [q][position]: gathered dY
+  __shared__ float Ys[kDaTQ * kDaSY];  // [q][channel]:  W
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wp = wave >> 1, wc = wave & 1;
+  const int i16 = lane & 15, kk = lane >> 4;
+  const int64_t p0 = (int64_t)blockIdx.x * kDaTP;
+  const int c0 = blockIdx.y * kDaTC;
+
+  floatx4 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // staging roles.  LINEAR: both operands are contiguous along their fast index in memory (dY along n = q, W along k = c).
+  // conv: dY is contiguous along the pixels (p), W is small and cached.
+  // X: LINEAR thread -> (q = tid % 32, p = tid / 32 + 8 j); conv thread -> (p = tid % 128, q = tid / 128 + 2 j)
+  int my_b = 0, my_ih = 0, my_iw = 0;
+  bool my_ok = false;
+  if (!LINEAR) {
+    const int64_t p = p0 + (tid & (kDaTP - 1));
+    my_ok = p < g.P;
+    if (my_ok) {
+      my_b = (int)(p / g.HW);
+      const int rem = (int)(p - (int64_t)my_b * g.HW);
+      my_ih = rem / g.W;
+      my_iw = rem - my_ih * g.W;
+    }
+  }
+
+  for (int q0 = 0; q0 < g.Q; q0 += kDaTQ) {
+    __syncthreads();
+    if (LINEAR) {
+      const int q = q0 + (tid & 31);
+#pragma unroll
+      for (int j = 0; j < kDaTP / 8; ++j) {
+        const int pl = (tid >> 5) + 8 * j;
+        const int64_t m = p0 + pl;
+        float v = 0.0f;
+        if (m < g.P && q < g.Q) v = da_widen<T>(dY[m * g.Co + q]);
+        Xs[(tid & 31) * kDaSX + pl] = v;
+      }
+    } else {
+      // q = (co, u, v) advanced incrementally: this thread walks q0 + (tid / 128) + 2 j
+      int q = q0 + (tid >> 7);
+      const int taps = g.KH * g.KW;
+      int co = q / taps;
+      int t = q - co * taps;
+      int u = t / g.KW, v = t - u * g.KW;
+#pragma unroll 4
+      for (int j = 0; j < kDaTQ / 2; ++j) {
+        float val = 0.0f;
+        if (my_ok && q < g.Q) {
+          const int top = my_ih + g.pad - u, left = my_iw + g.pad - v;
+          if (top >= 0 && left >= 0) {
+            int oh = top, ow = left;
+            bool hit = true;
+            if (g.stride > 1) {
+              oh = top / g.stride;
+              ow = left / g.stride;
+              hit = (oh * g.stride == top) && (ow * g.stride == left);
+            }
+            if (hit && oh < g.OH && ow < g.OW)
+              val = da_widen<T>(dY[(((int64_t)my_b * g.Co + co) * g.OH + oh) * g.OW + ow]);
+          }
+        }
+        Xs[((tid >> 7) + 2 * j) * kDaSX + (tid & (kDaTP - 1))] = val;
+        q += 2;
+        v += 2;
+        while (v >= g.KW) {
+          v -= g.KW;
+          ++u;
+        }
+        while (u >= g.KH) {
+          u -= g.KH;
+          ++co;
+        }
+      }
+    }
+    // Y: thread -> (c = tid % 128, q = tid / 128 + 2 j)
+    {
+      const int c = c0 + (tid & (kDaTC - 1));
+#pragma unroll 4
+      for (int j = 0; j < kDaTQ / 2; ++j) {
+        const int ql = (tid >> 7) + 2 * j, q = q0 + ql;
+        float val = 0.0f;
+        if (c < g.Ci && q < g.Q) {
+          if (LINEAR) {
+            val = da_widen<T>(Wt[(int64_t)q * g.Ci + c]);
+          } else {
+            const int taps = g.KH * g.KW;
+            const int co = q / taps, t = q - co * taps;
+            val = da_widen<T>(Wt[((int64_t)co * g.Ci + c) * taps + t]);
+          }
+        }
+        Ys[ql * kDaSY + (tid & (kDaTC - 1))] = val;
+      }
+    }
+    __syncthreads();
+    const float* rows = LINEAR ? Xs : Ys;  // operand whose index becomes the rows of the result tiles
+    const float* cols = LINEAR ? Ys : Xs;
+    const int srow = LINEAR ? kDaSX : kDaSY, scol = LINEAR ? kDaSY : kDaSX;
+    const int wr = LINEAR ? wp : wc, wcl = LINEAR ? wc : wp;
+#pragma unroll
+    for (int s = 0; s < kDaTQ / 4; ++s) {
+      float av[4], bv[4];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) av[a] = rows[(4 * s + kk) * srow + wr * 64 + a * 16 + i16];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) bv[b] = cols[(4 * s + kk) * scol + wcl * 64 + b * 16 + i16];
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+    }
+  }
+
+  // result tile: the lane holds rows 4*kk .. 4*kk+3 and column i16
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (LINEAR) {
+          const int64_t m = p0 + wp * 64 + a * 16 + 4 * kk + r;
+          const int c = c0 + wc * 64 + b * 16 + i16;
+          if (m < g.P && c < g.Ci) da_store<T>(&dA[m * g.Ci + c], acc[a][b][r]);
+        } else {
+          const int c = c0 + wc * 64 + a * 16 + 4 * kk + r;
+          const int64_t p = p0 + wp * 64 + b * 16 + i16;
+          if (p < g.P && c < g.Ci) {
+            const int64_t bimg = p / g.HW;
+            da_store<T>(&dA[(bimg * g.Ci + c) * g.HW + (p - bimg * g.HW)], acc[a][b][r]);
+          }
+        }
+      }
+}
+
+// Alg. 1 line 14 as one plain gradient step, in place: W <- W - lr * dW
+template <typename T>
+__global__ __launch_bounds__(256) void weight_update_kernel(T* __restrict__ Wt, const float* __restrict__ dW, int64_t n,
+                                                            float lr) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+    da_store<T>(&Wt[i], __builtin_fmaf(-lr, dW[i], da_widen<T>(Wt[i])));
+}
+
+}  // namespace surgeon
+
+using namespace surgeon;
+
+extern "C" int surgeon_da(const surgeon_layer_desc* d, const void* dY, const void* Wt, void* dA, void* stream) {
+  if (!d) return fail(SURGEON_EINVAL, "da: null descriptor");
+  if (d->dtype != SURGEON_F32 && d->dtype != SURGEON_BF16) return fail(SURGEON_EINVAL, "da: bad dtype");
+  DaGeom g;
+  bool linear;
+  if (d->kind == SURGEON_LINEAR) {
+    if (d->M < 0 || d->K < 1 || d->N < 1) return fail(SURGEON_EINVAL, "da: bad linear shape");
+    if (d->K > (1 << 30) || d->N > (1 << 30)) return fail(SURGEON_EUNSUPPORTED, "da: linear layer too wide");
+    linear = true;
+    g.Nb = 1; g.Ci = (int)d->K; g.Co = (int)d->N;
+    g.H = g.W = g.OH = g.OW = g.KH = g.KW = g.stride = 1;
+    g.pad = 0;
+    g.P = d->M;
+    g.Q = (int)d->N;
+    g.HW = 1;
+  } else if (d->kind == SURGEON_CONV2D) {
+    if (d->Nb < 1 || d->Ci < 1 || d->H < 1 || d->W < 1 || d->Co < 1 || d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0)
+      return fail(SURGEON_EINVAL, "da: bad conv shape");
+    if (d->H + 2 * d->pad < d->kh || d->W + 2 * d->pad < d->kw)
+      return fail(SURGEON_EINVAL, "da: filter larger than the padded input");
+    if (d->groups > 1) return fail(SURGEON_EUNSUPPORTED, "da: grouped convolutions are not implemented");
+    const int64_t big = (int64_t)1 << 31;
+    if (d->Co * d->kh * d->kw >= big || d->H * d->W >= big || d->Ci >= big || d->Nb >= big)
+      return fail(SURGEON_EUNSUPPORTED, "da: conv tensor too large");
+    linear = false;
+    g.Nb = (int)d->Nb; g.Ci = (int)d->Ci; g.H = (int)d->H; g.W = (int)d->W; g.Co = (int)d->Co;
+    g.KH = (int)d->kh; g.KW = (int)d->kw; g.stride = (int)d->stride; g.pad = (int)d->pad;
+    g.OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1;
+    g.OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
+    g.HW = g.H * g.W;
+    g.P = (int64_t)g.Nb * g.HW;
+    g.Q = g.Co * g.KH * g.KW;
+  } else {
+    return fail(SURGEON_EINVAL, "da: bad layer kind %d", d->kind);
+  }
+  if (g.P == 0) return SURGEON_OK;
+  if (!dY || !Wt || !dA) return fail(SURGEON_EINVAL, "da: null pointer");
+  const size_t es = d->dtype == SURGEON_F32 ? 4 : 2;
+  if (((uintptr_t)dY % es) || ((uintptr_t)Wt % es) || ((uintptr_t)dA % es)) return fail(SURGEON_EINVAL, "da: misaligned pointer");
+  const int64_t p_tiles = ceil_div(g.P, kDaTP), c_tiles = ceil_div(g.Ci, kDaTC);
+  if (p_tiles > 0x7fffffff || c_tiles > 65535) return fail(SURGEON_EUNSUPPORTED, "da: too many tiles");
+  const dim3 grid((unsigned)p_tiles, (unsigned)c_tiles);
+  hipStream_t st = (hipStream_t)stream;
+  ProfScope prof(SURGEON_PROF_DA, st);
+  if (d->dtype == SURGEON_F32) {
+    if (linear)
+      SURGEON_LAUNCH((da_kernel<float, true>), grid, dim3(256), 0, st, g, (const float*)dY, (const float*)Wt, (float*)dA);
+    else
+      SURGEON_LAUNCH((da_kernel<float, false>), grid, dim3(256), 0, st, g, (const float*)dY, (const float*)Wt, (float*)dA);
+  } else {
+    if (linear)
+      SURGEON_LAUNCH((da_kernel<uint16_t, true>), grid, dim3(256), 0, st, g, (const uint16_t*)dY, (const uint16_t*)Wt,
+                     (uint16_t*)dA);
+    else
+      SURGEON_LAUNCH((da_kernel<uint16_t, false>), grid, dim3(256), 0, st, g, (const uint16_t*)dY, (const uint16_t*)Wt,
+                     (uint16_t*)dA);
+  }
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+extern "C" int surgeon_weight_update(void* Wt, const float* dW, int64_t n, float lr, int dt, void* stream) {
+  if (dt != SURGEON_F32 && dt != SURGEON_BF16) return fail(SURGEON_EINVAL, "weight_update: bad dtype %d", dt);
+  if (n < 0 || !(lr == lr)) return fail(SURGEON_EINVAL, "weight_update: bad arguments");
+  if (n == 0) return SURGEON_OK;
+  if (!Wt || !dW) return fail(SURGEON_EINVAL, "weight_update: null pointer");
+  if (((uintptr_t)Wt % (dt == SURGEON_F32 ? 4 : 2)) || ((uintptr_t)dW % 4)) return fail(SURGEON_EINVAL, "weight_update: misaligned pointer");
+  const int blocks = (int)std::min<int64_t>(ceil_div(n, 256), 8192);
+  hipStream_t st = (hipStream_t)stream;
+  ProfScope prof(SURGEON_PROF_UPDATE, st);
+  if (dt == SURGEON_F32)
+    SURGEON_LAUNCH(weight_update_kernel<float>, dim3(blocks), dim3(256), 0, st, (float*)Wt, dW, n, lr);
+  else
+    SURGEON_LAUNCH(weight_update_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, (uint16_t*)Wt, dW, n, lr);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}

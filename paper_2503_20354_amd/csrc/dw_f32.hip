@@ -3,5 +3,5 @@
 
 namespace surgeon {
 template int run_dw<float>(const DwPlan&, const surgeon_layer_desc*, const void*, const uint64_t*, const void*, float*, void*,
-                           hipStream_t);
+                        hipStream_t, float*, double*);
 }  // namespace surgeon

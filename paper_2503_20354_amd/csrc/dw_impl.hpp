@@ -813,9 +813,12 @@ __global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) void dw_linear
     }
 }
 
-// adds the split partials in index order
+// adds the split partials in index order.  GI: also the sum of squares of what this workgroup wrote (Eq. 4's sum folded
+// into the pass that produces dW, so that the gradient is not read again): fp64, fixed order, one partial per workgroup.
+template <bool GI>
 static __global__ __launch_bounds__(256) void dw_reduce_splits_kernel(const float* __restrict__ part, int n_splits, int64_t n_w,
-                                                               float* __restrict__ dW) {
+                                                               float* __restrict__ dW, double* __restrict__ sq_partial) {
+  double sq = 0.0;
   for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n_w; x += (int64_t)gridDim.x * 256) {
     // eight loads in flight at a time; the additions stay in split order, so the result does not depend on the batching
     float s = 0.0f;
@@ -829,11 +832,21 @@ static __global__ __launch_bounds__(256) void dw_reduce_splits_kernel(const floa
     }
     for (; k < n_splits; ++k) s += part[(int64_t)k * n_w + x];
     dW[x] = s;
+    if (GI) sq += (double)s * (double)s;
+  }
+  if (GI) {
+    __shared__ double wave_sq[4];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sq += __shfl_down(sq, off, 64);
+    if ((threadIdx.x & 63) == 0) wave_sq[threadIdx.x >> 6] = sq;
+    __syncthreads();
+    if (threadIdx.x == 0) sq_partial[blockIdx.x] = (wave_sq[0] + wave_sq[1]) + (wave_sq[2] + wave_sq[3]);
   }
 }
 
-static __global__ void fill_zero_f32_kernel(float* __restrict__ p, int64_t n) {
+static __global__ void fill_zero_f32_kernel(float* __restrict__ p, int64_t n, float* __restrict__ also_zero) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0.0f;
+  if (also_zero && blockIdx.x == 0 && threadIdx.x == 0) also_zero[0] = 0.0f;  // Gradient Importance of a zero gradient
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -1224,9 +1237,10 @@ static int launch_linear(const LinPlan& lp, const Packed<InT>& pk, const void* d
   return SURGEON_OK;
 }
 
+// G_out != nullptr: also Eq. 4 of the gradient just computed; sq_partial then holds kGiPartials doubles of scratch
 template <typename InT>
 int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const uint64_t* mask, const void* dY,
-                  float* dW, void* ws, hipStream_t st) {
+                  float* dW, void* ws, hipStream_t st, float* G_out, double* sq_partial) {
   char* w = (char*)ws;
   uint32_t* word_rank = (uint32_t*)(w + p.off_rank);
   uint32_t* block_sum = (uint32_t*)(w + p.off_blocks);
@@ -1236,7 +1250,7 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   if (d->k_total == 0 || p.n == 0) {
     ProfScope prof(SURGEON_PROF_DW_AUX, st);
     const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 4096);
-    SURGEON_LAUNCH(fill_zero_f32_kernel, dim3(blocks), dim3(256), 0, st, dW, p.n_w);
+    SURGEON_LAUNCH(fill_zero_f32_kernel, dim3(blocks), dim3(256), 0, st, dW, p.n_w, G_out);
     SURGEON_LAUNCH_CHECK();
     return SURGEON_OK;
   }
@@ -1290,10 +1304,20 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   }
   if (rc != SURGEON_OK) return rc;
   if (p.splits > 1) {
-    const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), 8192);
+    const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), kGiPartials);
     ProfScope prof(SURGEON_PROF_DW_AUX, st);
-    SURGEON_LAUNCH(dw_reduce_splits_kernel, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w, dW);
+    if (G_out) {
+      SURGEON_LAUNCH(dw_reduce_splits_kernel<true>, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w,
+                     dW, sq_partial);
+      SURGEON_LAUNCH_CHECK();
+      return launch_sumsq_final(sq_partial, blocks, p.n_w, G_out, st);
+    }
+    SURGEON_LAUNCH(dw_reduce_splits_kernel<false>, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w, dW,
+                   (double*)nullptr);
     SURGEON_LAUNCH_CHECK();
+  } else if (G_out) {
+    // the matrix-core kernel wrote dW itself: one read of it (small, mostly still in cache) for the sum of squares
+    return launch_sumsq(dW, p.n_w, sq_partial, G_out, st);
   }
   return SURGEON_OK;
 }

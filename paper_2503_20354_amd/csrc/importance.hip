@@ -185,6 +185,35 @@ static int scratch_of_current_device(double** out) {
   return SURGEON_OK;
 }
 
+int launch_sumsq_final(const double* partial, int n_partial, int64_t n, float* G_out, hipStream_t st) {
+  ProfScope prof(SURGEON_PROF_IMPORTANCE, st);
+  SURGEON_LAUNCH(sumsq_final_kernel, dim3(1), dim3(kImpBlock), 0, st, partial, n_partial, n, G_out);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+int launch_sumsq(const float* x, int64_t n, double* partial, float* G_out, hipStream_t st) {
+  const bool vec4 = ((uintptr_t)x & 15) == 0;
+  const int nb = importance_blocks(n);
+  ProfScope prof(SURGEON_PROF_IMPORTANCE, st);
+  if (nb == 1) {
+    if (vec4)
+      SURGEON_LAUNCH(sumsq_single_kernel<true>, dim3(1), dim3(kImpBlock), 0, st, x, n, G_out);
+    else
+      SURGEON_LAUNCH(sumsq_single_kernel<false>, dim3(1), dim3(kImpBlock), 0, st, x, n, G_out);
+    SURGEON_LAUNCH_CHECK();
+    return SURGEON_OK;
+  }
+  if (vec4)
+    SURGEON_LAUNCH(sumsq_partial_kernel<true>, dim3(nb), dim3(kImpBlock), 0, st, x, n, partial);
+  else
+    SURGEON_LAUNCH(sumsq_partial_kernel<false>, dim3(nb), dim3(kImpBlock), 0, st, x, n, partial);
+  SURGEON_LAUNCH_CHECK();
+  SURGEON_LAUNCH(sumsq_final_kernel, dim3(1), dim3(kImpBlock), 0, st, (const double*)partial, nb, n, G_out);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
 }  // namespace surgeon
 
 using namespace surgeon;

@@ -1,0 +1,415 @@
+// Other layer types whose weight gradients come from the packed activation:
+//   * normalisation layers (batch norm over NCHW, layer norm over [tokens, features]): gradients of the scale and the
+//     shift from the pruned normalised activation -- the variant of Section 5 that adapts BN layers only.  With
+//     y = gamma[c] * x_hat + beta[c] this is Eq. 2's second line for an element-wise layer:
+//     dgamma[c] = sum dY * x_hat_pruned, dbeta[c] = sum dY over the elements of channel c.  HBM-bound.
+//   * convolutions with channel groups (grouped and depthwise convolutions of the ResNeXt / Segformer networks of
+//     Section 5.1): dW[co][cig][u][v] = sum_{b,oh,ow} dY[b][co][oh][ow] * A_pruned[b][g(co)*Cig + cig][ih][iw].
+//     Per output channel only Ci/groups (1 - 16) input channels contribute, far too few rows for a matrix-core
+//     tile, so the sum runs on the vector ALU.
+#include "dw_impl.hpp"
+
+namespace surgeon {
+
+// ---------------------------------------------------------------------------------------------------------
+// scale / shift gradients
+// ---------------------------------------------------------------------------------------------------------
+// Element (o, c, i) of the [outer, C, inner] tensor is at (o*C + c)*inner + i.  Three partial kernels write
+// (dgamma, dbeta) partial sums as float2 part[slice][c]; the finishing kernel adds the slices per channel in index
+// order in fp64 (deterministic).
+
+// inner % 64 == 0 (batch norm on maps of 8x8 and larger): one wavefront per (o, c) row, lane = element of a mask word
+template <typename T>
+__global__ __launch_bounds__(256) void affine_rows_kernel(Packed<T> pk, const T* __restrict__ dY, int64_t outer, int C,
+                                                          int inner, float2* __restrict__ part) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // = o*C + c
+  if (row >= outer * C) return;
+  const int64_t e0 = row * inner;
+  float g = 0.0f, b = 0.0f;
+  for (int j = 0; j < inner; j += 64) {
+    const int64_t w = (e0 + j) >> 6;
+    const uint64_t word = pk.mask[w];
+    const uint32_t lo = (uint32_t)word, hi = (uint32_t)(word >> 32);
+    const bool kept = (word >> lane) & 1ull;
+    int64_t pos = (int64_t)pk.word_rank[w] + __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
+    pos = pos > pk.k_last ? pk.k_last : pos;
+    const float x = kept ? widen<T>(pk.vals[pos]) : 0.0f;
+    const float dy = widen<T>(dY[e0 + j + lane]);
+    g = __builtin_fmaf(dy, x, g);
+    b += dy;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    g += __shfl_down(g, off, 64);
+    b += __shfl_down(b, off, 64);
+  }
+  const int64_t o = row / C;
+  const int c = (int)(row - o * C);
+  if (lane == 0) part[o * C + c] = make_float2(g, b);
+}
+
+// inner == 1 and C % 64 == 0 (layer norm): a wavefront owns one 64-feature mask word of kLnRows consecutive tokens
+constexpr int kLnRows = 32;
+template <typename T>
+__global__ __launch_bounds__(256) void affine_cols_kernel(Packed<T> pk, const T* __restrict__ dY, int64_t outer, int C,
+                                                          float2* __restrict__ part) {
+  const int lane = threadIdx.x & 63;
+  const int words = C >> 6;
+  const int wq = blockIdx.x * 4 + (threadIdx.x >> 6);  // word inside the token row
+  if (wq >= words) return;
+  const int64_t m0 = (int64_t)blockIdx.y * kLnRows, m1 = min(m0 + kLnRows, outer);
+  float g = 0.0f, b = 0.0f;
+  for (int64_t m = m0; m < m1; ++m) {
+    const int64_t w = m * words + wq;
+    const uint64_t word = pk.mask[w];
+    const uint32_t lo = (uint32_t)word, hi = (uint32_t)(word >> 32);
+    const bool kept = (word >> lane) & 1ull;
+    int64_t pos = (int64_t)pk.word_rank[w] + __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
+    pos = pos > pk.k_last ? pk.k_last : pos;
+    const float x = kept ? widen<T>(pk.vals[pos]) : 0.0f;
+    const float dy = widen<T>(dY[m * C + wq * 64 + lane]);
+    g = __builtin_fmaf(dy, x, g);
+    b += dy;
+  }
+  part[(int64_t)blockIdx.y * C + wq * 64 + lane] = make_float2(g, b);
+}
+
+// any shape: one thread per channel and slice of `outer`
+template <typename T>
+__global__ __launch_bounds__(256) void affine_generic_kernel(Packed<T> pk, const T* __restrict__ dY, int64_t outer, int C,
+                                                             int inner, int64_t o_per_slice, float2* __restrict__ part) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  const int64_t o0 = (int64_t)blockIdx.y * o_per_slice, o1 = min(o0 + o_per_slice, outer);
+  float g = 0.0f, b = 0.0f;
+  for (int64_t o = o0; o < o1; ++o)
+    for (int i = 0; i < inner; ++i) {
+      const int64_t e = (o * C + c) * inner + i;
+      const float dy = widen<T>(dY[e]);
+      g = __builtin_fmaf(dy, unpack_at<T>(pk, e), g);
+      b += dy;
+    }
+  part[(int64_t)blockIdx.y * C + c] = make_float2(g, b);
+}
+
+static __global__ __launch_bounds__(256) void affine_final_kernel(const float2* __restrict__ part, int64_t n_slices, int C,
+                                                                  float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  double g = 0.0, b = 0.0;
+  for (int64_t s = 0; s < n_slices; ++s) {
+    const float2 v = part[s * C + c];
+    g += (double)v.x;
+    b += (double)v.y;
+  }
+  dgamma[c] = (float)g;
+  dbeta[c] = (float)b;
+}
+
+struct AffinePlan {
+  int mode;  // 0 rows (inner % 64 == 0), 1 columns (inner == 1, C % 64 == 0), 2 generic
+  int64_t n, n_words, n_rank_blocks, n_slices, o_per_slice;
+  size_t off_rank, off_blocks, off_part, ws_bytes;
+};
+
+static int plan_affine(int64_t outer, int64_t C, int64_t inner, AffinePlan* p) {
+  if (outer < 0 || C < 1 || inner < 1) return fail(SURGEON_EINVAL, "affine_grad: bad shape");
+  if (C > (1 << 24) || inner > (1 << 24) || outer * C * inner > ((int64_t)1 << 31))
+    return fail(SURGEON_EUNSUPPORTED, "affine_grad: tensor too large");
+  p->n = outer * C * inner;
+  p->n_words = ceil_div(p->n, 64);
+  p->n_rank_blocks = ceil_div(p->n_words, kRankWordsPerBlock);
+  if (inner % 64 == 0) {
+    p->mode = 0;
+    p->n_slices = outer;
+    p->o_per_slice = 1;
+  } else if (inner == 1 && C % 64 == 0) {
+    p->mode = 1;
+    p->n_slices = ceil_div(outer, kLnRows);
+    p->o_per_slice = kLnRows;
+    if (p->n_slices > 65535) return fail(SURGEON_EUNSUPPORTED, "affine_grad: more than %d rows", 65535 * kLnRows);
+  } else {
+    p->mode = 2;
+    p->n_slices = std::max<int64_t>(1, std::min<int64_t>(outer, 4096 / ceil_div(C, 256)));
+    p->o_per_slice = ceil_div(std::max<int64_t>(outer, 1), p->n_slices);
+    p->n_slices = ceil_div(std::max<int64_t>(outer, 1), p->o_per_slice);
+  }
+  size_t off = 0;
+  p->off_rank = off;
+  off += align_up((size_t)std::max<int64_t>(p->n_words, 1) * 4, 256);
+  p->off_blocks = off;
+  off += align_up((size_t)std::max<int64_t>(p->n_rank_blocks, 1) * 4, 256);
+  p->off_part = off;
+  off += align_up((size_t)std::max<int64_t>(p->n_slices, 1) * (size_t)C * sizeof(float2), 256);
+  p->ws_bytes = off;
+  return SURGEON_OK;
+}
+
+template <typename T>
+static int run_affine(const AffinePlan& p, const void* vals, const uint64_t* mask, const void* dY, int64_t outer, int C,
+                      int inner, int64_t k_total, float* dgamma, float* dbeta, void* ws, hipStream_t st) {
+  char* w = (char*)ws;
+  uint32_t* word_rank = (uint32_t*)(w + p.off_rank);
+  uint32_t* block_sum = (uint32_t*)(w + p.off_blocks);
+  float2* part = (float2*)(w + p.off_part);
+  ProfScope prof(SURGEON_PROF_AFFINE, st);
+  if (p.n > 0) {
+    SURGEON_LAUNCH(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words, block_sum);
+    SURGEON_LAUNCH_CHECK();
+    SURGEON_LAUNCH(rank_scan_kernel, dim3(1), dim3(1024), 0, st, block_sum, (int)p.n_rank_blocks);
+    SURGEON_LAUNCH_CHECK();
+    SURGEON_LAUNCH(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
+                   (const uint32_t*)block_sum, word_rank);
+    SURGEON_LAUNCH_CHECK();
+  }
+  Packed<T> pk;
+  pk.vals = (const T*)vals;
+  pk.mask = mask;
+  pk.word_rank = word_rank;
+  pk.k_last = std::max<int64_t>(k_total - 1, 0);  // vals is only read where a mask bit is set: never when nothing is kept
+  pk.n_words = p.n_words;
+  int64_t n_slices = p.n_slices;
+  if (p.n == 0) {
+    n_slices = 0;
+  } else if (p.mode == 0) {
+    SURGEON_LAUNCH(affine_rows_kernel<T>, dim3((unsigned)ceil_div(outer * C, 4)), dim3(256), 0, st, pk, (const T*)dY, outer,
+                   C, inner, part);
+    SURGEON_LAUNCH_CHECK();
+  } else if (p.mode == 1) {
+    SURGEON_LAUNCH(affine_cols_kernel<T>, dim3((unsigned)ceil_div(C / 64, 4), (unsigned)p.n_slices), dim3(256), 0, st, pk,
+                   (const T*)dY, outer, C, part);
+    SURGEON_LAUNCH_CHECK();
+  } else {
+    SURGEON_LAUNCH(affine_generic_kernel<T>, dim3((unsigned)ceil_div(C, 256), (unsigned)p.n_slices), dim3(256), 0, st, pk,
+                   (const T*)dY, outer, C, inner, p.o_per_slice, part);
+    SURGEON_LAUNCH_CHECK();
+  }
+  SURGEON_LAUNCH(affine_final_kernel, dim3((unsigned)ceil_div(C, 256)), dim3(256), 0, st, (const float2*)part, n_slices, C,
+                 dgamma, dbeta);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// convolutions with channel groups
+// ---------------------------------------------------------------------------------------------------------
+struct GroupedGeom {
+  int Nb, Ci, H, W, Co, OH, OW, KH, KW, stride, pad, groups, Cig, Cog;
+  int64_t pos_per_split;  // (b, oh, ow) positions per workgroup along the contraction
+  int64_t n_pos, n_w;
+};
+
+constexpr int kGroupedMaxTaps = 49;
+
+// One workgroup per (co, cig, split): its threads walk the split's output positions, each keeping the kh*kw taps of
+// its positions in registers; a workgroup-wide sum in a fixed order writes the split's partial filter.
+template <typename T, int TAPS_MAX>
+__global__ __launch_bounds__(256) void dw_grouped_kernel(GroupedGeom g, Packed<T> pk, const T* __restrict__ dY,
+                                                         float* __restrict__ out) {
+  __shared__ float red[4][TAPS_MAX];
+  const int pair = blockIdx.x;  // co * Cig + cig
+  const int co = pair / g.Cig, cig = pair - co * g.Cig;
+  const int ci = (co / g.Cog) * g.Cig + cig;
+  const int taps = g.KH * g.KW;
+  const int64_t p_begin = (int64_t)blockIdx.y * g.pos_per_split, p_end = min(p_begin + g.pos_per_split, g.n_pos);
+  float acc[TAPS_MAX];
+#pragma unroll
+  for (int t = 0; t < TAPS_MAX; ++t) acc[t] = 0.0f;
+  const int ohw = g.OH * g.OW;
+  for (int64_t p = p_begin + threadIdx.x; p < p_end; p += 256) {
+    const int b = (int)(p / ohw);
+    const int rem = (int)(p - (int64_t)b * ohw);
+    const int oh = rem / g.OW, ow = rem - oh * g.OW;
+    const float dy = widen<T>(dY[((int64_t)b * g.Co + co) * ohw + rem]);
+    const int64_t a_base = ((int64_t)b * g.Ci + ci) * g.H;
+#pragma unroll
+    for (int t = 0; t < TAPS_MAX; ++t) {
+      if (t < taps) {
+        const int u = t / g.KW, v = t - u * g.KW;
+        const int ih = oh * g.stride + u - g.pad, iw = ow * g.stride + v - g.pad;
+        if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
+          acc[t] = __builtin_fmaf(dy, unpack_at<T>(pk, (a_base + ih) * g.W + iw), acc[t]);
+      }
+    }
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int t = 0; t < TAPS_MAX; ++t) {
+    float v = acc[t];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    if (lane == 0) red[wave][t] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < taps)
+    out[(int64_t)blockIdx.y * g.n_w + (int64_t)pair * taps + threadIdx.x] =
+        (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+struct GroupedPlan {
+  GroupedGeom g;
+  int splits;
+  int64_t n, n_words, n_rank_blocks;
+  size_t off_rank, off_blocks, off_part, ws_bytes;
+};
+
+int plan_grouped(const surgeon_layer_desc* d, GroupedPlan* p) {
+  if (d->Nb < 1 || d->Ci < 1 || d->H < 1 || d->W < 1 || d->Co < 1 || d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0)
+    return fail(SURGEON_EINVAL, "dw_from_packed: bad conv shape");
+  if (d->groups < 1 || d->Ci % d->groups || d->Co % d->groups)
+    return fail(SURGEON_EINVAL, "dw_from_packed: groups = %lld does not divide the channel counts", (long long)d->groups);
+  if (d->H + 2 * d->pad < d->kh || d->W + 2 * d->pad < d->kw)
+    return fail(SURGEON_EINVAL, "dw_from_packed: filter larger than the padded input");
+  if (d->kh * d->kw > kGroupedMaxTaps)
+    return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: grouped filters larger than %d taps are not implemented", kGroupedMaxTaps);
+  const int64_t big = (int64_t)1 << 31;
+  if (d->Nb * d->Ci * d->H * d->W > big || d->Nb * d->Co * d->H * d->W > big)
+    return fail(SURGEON_EUNSUPPORTED, "dw_from_packed: conv tensor too large");
+  GroupedGeom& g = p->g;
+  g.Nb = (int)d->Nb; g.Ci = (int)d->Ci; g.H = (int)d->H; g.W = (int)d->W; g.Co = (int)d->Co;
+  g.KH = (int)d->kh; g.KW = (int)d->kw; g.stride = (int)d->stride; g.pad = (int)d->pad;
+  g.groups = (int)d->groups;
+  g.Cig = g.Ci / g.groups;
+  g.Cog = g.Co / g.groups;
+  g.OH = (g.H + 2 * g.pad - g.KH) / g.stride + 1;
+  g.OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
+  g.n_pos = (int64_t)g.Nb * g.OH * g.OW;
+  g.n_w = (int64_t)g.Co * g.Cig * g.KH * g.KW;
+  // enough workgroups to fill the chip, at least 2048 positions each
+  const int64_t pairs = (int64_t)g.Co * g.Cig;
+  int64_t splits = std::max<int64_t>(1, std::min<int64_t>(ceil_div(g.n_pos, 2048), ceil_div(4096, pairs)));
+  splits = std::min<int64_t>(splits, 256);
+  g.pos_per_split = ceil_div(g.n_pos, splits);
+  p->splits = (int)ceil_div(g.n_pos, g.pos_per_split);
+  p->n = (int64_t)g.Nb * g.Ci * g.H * g.W;
+  p->n_words = ceil_div(p->n, 64);
+  p->n_rank_blocks = ceil_div(p->n_words, kRankWordsPerBlock);
+  size_t off = 0;
+  p->off_rank = off;
+  off += align_up((size_t)p->n_words * 4, 256);
+  p->off_blocks = off;
+  off += align_up((size_t)p->n_rank_blocks * 4, 256);
+  p->off_part = off;
+  if (p->splits > 1) off += align_up((size_t)p->splits * (size_t)g.n_w * 4, 256);
+  p->ws_bytes = off;
+  return SURGEON_OK;
+}
+
+template <typename T>
+static int run_grouped_t(const GroupedPlan& p, const surgeon_layer_desc* d, const void* vals, const uint64_t* mask,
+                         const void* dY, float* dW, void* ws, hipStream_t st, float* G_out, double* sq_partial) {
+  char* w = (char*)ws;
+  uint32_t* word_rank = (uint32_t*)(w + p.off_rank);
+  uint32_t* block_sum = (uint32_t*)(w + p.off_blocks);
+  float* part = (float*)(w + p.off_part);
+  const GroupedGeom& g = p.g;
+  if (d->k_total == 0) {
+    ProfScope prof(SURGEON_PROF_DW_AUX, st);
+    SURGEON_LAUNCH(fill_zero_f32_kernel, dim3((unsigned)std::min<int64_t>(ceil_div(g.n_w, 256), 4096)), dim3(256), 0, st, dW,
+                   g.n_w, G_out);
+    SURGEON_LAUNCH_CHECK();
+    return SURGEON_OK;
+  }
+  {
+    ProfScope prof(SURGEON_PROF_DW_AUX, st);
+    SURGEON_LAUNCH(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words, block_sum);
+    SURGEON_LAUNCH_CHECK();
+    SURGEON_LAUNCH(rank_scan_kernel, dim3(1), dim3(1024), 0, st, block_sum, (int)p.n_rank_blocks);
+    SURGEON_LAUNCH_CHECK();
+    SURGEON_LAUNCH(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
+                   (const uint32_t*)block_sum, word_rank);
+    SURGEON_LAUNCH_CHECK();
+  }
+  Packed<T> pk;
+  pk.vals = (const T*)vals;
+  pk.mask = mask;
+  pk.word_rank = word_rank;
+  pk.k_last = d->k_total - 1;
+  pk.n_words = p.n_words;
+  float* out = p.splits > 1 ? part : dW;
+  const dim3 grid((unsigned)(g.Co * g.Cig), (unsigned)p.splits);
+  {
+    ProfScope prof(SURGEON_PROF_DW_GROUPED, st);
+    if (g.KH * g.KW <= 9)
+      SURGEON_LAUNCH((dw_grouped_kernel<T, 9>), grid, dim3(256), 0, st, g, pk, (const T*)dY, out);
+    else if (g.KH * g.KW <= 25)
+      SURGEON_LAUNCH((dw_grouped_kernel<T, 25>), grid, dim3(256), 0, st, g, pk, (const T*)dY, out);
+    else
+      SURGEON_LAUNCH((dw_grouped_kernel<T, kGroupedMaxTaps>), grid, dim3(256), 0, st, g, pk, (const T*)dY, out);
+    SURGEON_LAUNCH_CHECK();
+  }
+  if (p.splits > 1) {
+    const int blocks = (int)std::min<int64_t>(ceil_div(g.n_w, 256), kGiPartials);
+    ProfScope prof(SURGEON_PROF_DW_AUX, st);
+    if (G_out) {
+      SURGEON_LAUNCH(dw_reduce_splits_kernel<true>, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, g.n_w, dW,
+                     sq_partial);
+      SURGEON_LAUNCH_CHECK();
+      return launch_sumsq_final(sq_partial, blocks, g.n_w, G_out, st);
+    }
+    SURGEON_LAUNCH(dw_reduce_splits_kernel<false>, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, g.n_w, dW,
+                   (double*)nullptr);
+    SURGEON_LAUNCH_CHECK();
+  } else if (G_out) {
+    return launch_sumsq(dW, g.n_w, sq_partial, G_out, st);
+  }
+  return SURGEON_OK;
+}
+
+int grouped_ws_bytes(const surgeon_layer_desc* d, size_t* bytes) {
+  GroupedPlan p;
+  const int rc = plan_grouped(d, &p);
+  if (rc == SURGEON_OK) *bytes = p.ws_bytes;
+  return rc;
+}
+
+int run_grouped(const surgeon_layer_desc* d, const void* vals, const uint64_t* mask, const void* dY, float* dW, void* ws,
+                size_t ws_bytes, hipStream_t st, float* G_out, size_t* off_gi_out, bool plan_only) {
+  GroupedPlan p;
+  const int rc = plan_grouped(d, &p);
+  if (rc != SURGEON_OK) return rc;
+  if (d->k_total < 0 || d->k_total > p.n) return fail(SURGEON_EINVAL, "dw_from_packed: bad k_total");
+  const size_t off_gi = align_up(p.ws_bytes, 256);
+  if (off_gi_out) *off_gi_out = off_gi;
+  if (plan_only) return SURGEON_OK;
+  const size_t need = G_out ? off_gi + (size_t)kGiPartials * sizeof(double) : p.ws_bytes;
+  if (!ws || ws_bytes < need)
+    return fail(SURGEON_ESIZE, "dw_from_packed: workspace of %zu bytes needed, %zu given", need, ws_bytes);
+  double* sq_partial = G_out ? (double*)((char*)ws + off_gi) : nullptr;
+  if (d->dtype == SURGEON_F32) return run_grouped_t<float>(p, d, vals, mask, dY, dW, ws, st, G_out, sq_partial);
+  return run_grouped_t<uint16_t>(p, d, vals, mask, dY, dW, ws, st, G_out, sq_partial);
+}
+
+}  // namespace surgeon
+
+using namespace surgeon;
+
+extern "C" int surgeon_affine_grad_ws_bytes(int64_t outer, int64_t C, int64_t inner, size_t* ws_bytes) {
+  if (!ws_bytes) return fail(SURGEON_EINVAL, "affine_grad_ws_bytes: null pointer");
+  AffinePlan p;
+  const int rc = plan_affine(outer, C, inner, &p);
+  if (rc == SURGEON_OK) *ws_bytes = p.ws_bytes;
+  return rc;
+}
+
+extern "C" int surgeon_affine_grad(const void* vals, const uint64_t* mask, const void* dY, int64_t outer, int64_t C,
+                                   int64_t inner, int dt, int64_t k_total, float* dgamma, float* dbeta, void* ws,
+                                   size_t ws_bytes, void* stream) {
+  if (dt != SURGEON_F32 && dt != SURGEON_BF16) return fail(SURGEON_EINVAL, "affine_grad: bad dtype %d", dt);
+  AffinePlan p;
+  const int rc = plan_affine(outer, C, inner, &p);
+  if (rc != SURGEON_OK) return rc;
+  if (k_total < 0 || k_total > p.n) return fail(SURGEON_EINVAL, "affine_grad: bad k_total");
+  if (!dgamma || !dbeta) return fail(SURGEON_EINVAL, "affine_grad: null output");
+  if (p.n > 0 && (!mask || !dY || (k_total > 0 && !vals))) return fail(SURGEON_EINVAL, "affine_grad: null pointer");
+  if (!ws || ws_bytes < p.ws_bytes)
+    return fail(SURGEON_ESIZE, "affine_grad: workspace of %zu bytes needed, %zu given", p.ws_bytes, ws_bytes);
+  if (((uintptr_t)ws % 16) || ((uintptr_t)mask % 8) || ((uintptr_t)dY % (dt == SURGEON_F32 ? 4 : 2)) ||
+      ((uintptr_t)vals % (dt == SURGEON_F32 ? 4 : 2)) || ((uintptr_t)dgamma % 4) || ((uintptr_t)dbeta % 4))
+    return fail(SURGEON_EINVAL, "affine_grad: misaligned pointer");
+  hipStream_t st = (hipStream_t)stream;
+  if (dt == SURGEON_F32)
+    return run_affine<float>(p, vals, mask, dY, outer, (int)C, (int)inner, k_total, dgamma, dbeta, ws, st);
+  return run_affine<uint16_t>(p, vals, mask, dY, outer, (int)C, (int)inner, k_total, dgamma, dbeta, ws, st);
+}

@@ -1,0 +1,267 @@
+"""GPU parity of the rest of Alg. 1's backward step and of the other layer types, against the CPU oracle:
+Gradient Importance folded into the weight-gradient call (Eq. 4 inside Alg. 1 line 12), the activation gradient
+dA = dY . W (Eq. 2, first line), the gradient step (Alg. 1 line 14), scale / shift gradients of normalisation layers
+(Section 5, the variant that adapts BN layers only) and grouped / depthwise convolution weight gradients.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_20354_amd as surgeon
+import surgeon_workloads as wl
+from parity_bars import TOL, assert_dw_close, rel_l2
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def bits(t):
+    return wl.to_numpy_bits(t)
+
+
+def f64(a):
+    a = np.asarray(a)
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return a.astype(np.float64)
+
+
+def sdt(dtype):
+    return surgeon.F32 if dtype == "f32" else surgeon.BF16
+
+
+def assert_out_close(got_bits, ref_bits, dtype, what=""):
+    """Outputs stored in the layer's dtype.  fp32: the dW bars.  bf16: the stated 2e-2 norm bar, a tight one, and per
+    entry at most one bf16 step (the oracle rounds the exact sum, the kernel rounds an fp32 sum: they can land on
+    neighbouring values, never further apart)."""
+    got, ref = f64(got_bits).ravel(), f64(ref_bits).ravel()
+    if dtype == "f32":
+        assert_dw_close(got, ref, "f32", what)
+        return
+    e = rel_l2(got, ref)
+    assert e <= TOL["bf16"], (what, e)
+    assert e <= 2e-3, (what, e)
+    step = np.maximum(np.abs(ref), 1e-30) * 2.0 ** -7  # one bf16 step is at most 2^-7 of the value
+    worst = np.abs(got - ref) - step
+    floor = 1e-5 * float(np.abs(ref).max())            # sums that cancel to ~0: an absolute floor from the fp32 accumulation
+    assert (worst <= floor).all(), (what, float(worst.max()), floor)
+
+
+# ------------------------------------------------------------------------------------------------
+# Eq. 4 inside the weight-gradient call
+# ------------------------------------------------------------------------------------------------
+def _dw_gi(desc, p, dY):
+    shape = (desc.N, desc.K) if desc.kind == 0 else (desc.Co, desc.Ci // max(desc.groups, 1), desc.kh, desc.kw)
+    desc.group_len, desc.r = p.group_len, p.r
+    plain = torch.empty(shape, device=DEV)
+    fused = torch.empty(shape, device=DEV)
+    G = torch.full((1,), -1.0, device=DEV)
+    ws = torch.empty(surgeon.surgeon_dw_gi_ws_bytes(desc), dtype=torch.uint8, device=DEV)
+    surgeon.surgeon_dw_from_packed(desc, p.vals, p.mask, dY, plain, ws)
+    surgeon.surgeon_dw_from_packed_gi(desc, p.vals, p.mask, dY, fused, G, ws)
+    G2 = torch.full((1,), -2.0, device=DEV)
+    again = torch.empty(shape, device=DEV)
+    surgeon.surgeon_dw_from_packed_gi(desc, p.vals, p.mask, dY, again, G2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(plain, fused) and torch.equal(fused, again)  # same bits with and without, and call after call
+    assert G.item() == G2.item()
+    return fused.cpu().numpy(), G.item()
+
+
+GI_CONVS = [
+    # Nb, Ci, H, W, Co, k, stride, dtype, r   (the first ones split the contraction, the small ones do not)
+    (16, 160, 32, 32, 160, 3, 1, "f32", 0.5), (16, 160, 32, 32, 160, 3, 1, "f32", 0.9), (8, 64, 56, 56, 256, 1, 1, "bf16", 0.8),
+    (2, 3, 32, 32, 16, 3, 1, "f32", 0.3), (4, 128, 28, 28, 128, 3, 2, "bf16", 0.7), (1, 8, 8, 8, 8, 3, 1, "f32", 0.5),
+    (3, 40, 16, 16, 64, 3, 1, "f32", 1.0),
+]
+
+
+@pytest.mark.parametrize("case", GI_CONVS)
+def test_gradient_importance_inside_the_conv_weight_gradient(case):
+    Nb, Ci, H, W, Co, k, st, dtype, r = case
+    print("dw_gi conv", case, flush=True)
+    pad = k // 2
+    OH, OW = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+    A = wl.draw((Nb, Ci, H, W), "relu", dtype, sum(case[:7]) + 1)
+    dY = wl.draw((Nb, Co, OH, OW), "normal", dtype, sum(case[:7]) + 2)
+    p = surgeon.prune_pack(A.to(DEV), 4096, r)
+    desc = surgeon.conv2d_desc(Nb, Ci, H, W, Co, k, k, st, pad, sdt(dtype), p.k_total)
+    dW, G = _dw_gi(desc, p, dY.to(DEV))
+    o_vals, o_mask, _, _ = oracle.prune_pack(bits(A).reshape(-1), 4096, r)
+    ref = oracle.dw_conv2d(o_vals, o_mask, bits(dY), Nb, Ci, H, W, Co, k, k, st, pad)
+    assert_dw_close(dW, ref, dtype, case)
+    o_G = oracle.grad_importance(ref)
+    assert abs(G - o_G) <= 1e-5 * max(o_G, 1e-30)
+    if r == 1.0:
+        assert G == 0.0 and not dW.any()
+
+
+@pytest.mark.parametrize("M,K,N,dtype,r", [(4096, 768, 2304, "bf16", 0.9), (2000, 320, 1280, "bf16", 0.6),
+                                            (64, 512, 256, "f32", 0.5), (3000, 64, 64, "bf16", 0.7), (500, 96, 40, "f32", 0.0)])
+def test_gradient_importance_inside_the_linear_weight_gradient(M, K, N, dtype, r):
+    print("dw_gi linear", (M, K, N, dtype, r), flush=True)
+    A = wl.draw((M, K), "normal", dtype, M + K + 1)
+    dY = wl.draw((M, N), "normal", dtype, M + K + 2)
+    p = surgeon.prune_pack(A.to(DEV), K, r)
+    dW, G = _dw_gi(surgeon.linear_desc(M, K, N, sdt(dtype), p.k_total), p, dY.to(DEV))
+    o_vals, o_mask, _, _ = oracle.prune_pack(bits(A).reshape(-1), K, r)
+    ref = oracle.dw_linear(o_vals, o_mask, bits(dY), M, K, N)
+    assert_dw_close(dW, ref, dtype, (M, K, N))
+    o_G = oracle.grad_importance(ref)
+    assert abs(G - o_G) <= 1e-5 * o_G
+
+
+# ------------------------------------------------------------------------------------------------
+# activation gradient (Eq. 2, first line)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,K,N", [(64, 512, 256), (100, 70, 50), (300, 129, 257), (1, 64, 64), (517, 320, 1280),
+                                   (1000, 768, 19), (129, 8, 8)])
+def test_da_linear(dtype, M, K, N):
+    print("da linear", (M, K, N), dtype, flush=True)
+    dY = wl.draw((M, N), "normal", dtype, M + N + 5)
+    W = wl.draw((N, K), "normal", dtype, N + K + 6) * 0.1
+    W = W.to(dY.dtype)
+    dA = torch.empty((M, K), dtype=dY.dtype, device=DEV)
+    surgeon.surgeon_da(surgeon.linear_desc(M, K, N, sdt(dtype), 0), dY.to(DEV), W.to(DEV), dA)
+    torch.cuda.synchronize()
+    ref = oracle.da_linear(bits(dY), bits(W), M, K, N)
+    assert_out_close(bits(dA), ref, dtype, (M, K, N))
+
+
+DA_CONVS = [
+    # Nb, Ci, H, W, Co, k, stride, pad
+    (2, 16, 32, 32, 160, 3, 1, 1), (2, 160, 16, 16, 160, 3, 1, 1), (2, 160, 32, 32, 320, 3, 2, 1), (2, 16, 32, 32, 160, 1, 1, 0),
+    (2, 160, 32, 32, 320, 1, 2, 0), (2, 3, 32, 32, 16, 3, 1, 1), (1, 3, 64, 64, 64, 7, 2, 3), (2, 64, 14, 14, 256, 1, 1, 0),
+    (2, 5, 9, 9, 7, 5, 1, 2), (3, 6, 12, 12, 20, 3, 1, 0), (2, 40, 13, 13, 24, 3, 1, 1), (2, 8, 20, 20, 24, 5, 2, 1),
+    (1, 64, 14, 14, 65, 3, 3, 1), (2, 130, 7, 7, 512, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", DA_CONVS)
+def test_da_conv(dtype, case):
+    Nb, Ci, H, W, Co, k, st, pad = case
+    print("da conv", case, dtype, flush=True)
+    OH, OW = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+    dY = wl.draw((Nb, Co, OH, OW), "normal", dtype, sum(case) + 5)
+    Wt = (wl.draw((Co, Ci, k, k), "normal", dtype, sum(case) + 6) * 0.1).to(dY.dtype)
+    dA = torch.empty((Nb, Ci, H, W), dtype=dY.dtype, device=DEV)
+    surgeon.surgeon_da(surgeon.conv2d_desc(Nb, Ci, H, W, Co, k, k, st, pad, sdt(dtype), 0), dY.to(DEV), Wt.to(DEV), dA)
+    torch.cuda.synchronize()
+    ref = oracle.da_conv2d(bits(dY), bits(Wt), Nb, Ci, H, W, Co, k, k, st, pad)
+    assert_out_close(bits(dA), ref, dtype, case)
+
+
+@pytest.mark.parametrize("cfg,name", [(1, "s2b1.conv1"), (1, "s3b2.conv2"), (2, "s2b1.conv2"), (2, "s3b2.conv3"),
+                                      (3, "blk0.qkv"), (3, "blk11.fc2"), (4, "st1b1.fc1"), (4, "dec.cls")])
+def test_da_full_size_sampled(cfg, name):
+    """One layer of each kind at the benchmark's full size: sampled entries from the definition."""
+    layers = wl.config_layers(cfg)
+    li = [l.name for l in layers].index(name)
+    L = layers[li]
+    print("da full size", cfg, name, flush=True)
+    _, dY = wl.layer_tensors(cfg, li, L)
+    Wt = (wl.draw(L.dw_shape, "normal", L.dtype, 777 + li) * 0.05).to(dY.dtype)
+    dA = torch.empty(L.a_shape, dtype=dY.dtype, device=DEV)
+    where = np.random.default_rng(li).integers(0, L.n, 2048)
+    if L.kind == "linear":
+        surgeon.surgeon_da(surgeon.linear_desc(L.M, L.K, L.N, sdt(L.dtype), 0), dY.to(DEV), Wt.to(DEV), dA)
+        ref = oracle.da_linear_at(bits(dY), bits(Wt), L.M, L.K, L.N, where)
+    else:
+        surgeon.surgeon_da(surgeon.conv2d_desc(L.Nb, L.Ci, L.H, L.W, L.Co, L.kh, L.kw, L.stride, L.pad, sdt(L.dtype), 0),
+                           dY.to(DEV), Wt.to(DEV), dA)
+        ref = oracle.da_conv2d_at(bits(dY), bits(Wt), L.Nb, L.Ci, L.H, L.W, L.Co, L.kh, L.kw, L.stride, L.pad, where)
+    torch.cuda.synchronize()
+    assert_out_close(bits(dA).reshape(-1)[where], ref, L.dtype, (cfg, name))
+
+
+# ------------------------------------------------------------------------------------------------
+# gradient step (Alg. 1 line 14)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n", [1, 255, 4097, 1_000_003])
+def test_weight_update(dtype, n):
+    W = wl.draw((n,), "normal", dtype, n + 1)
+    dW = wl.draw((n,), "normal", "f32", n + 2)
+    lr = 0.0123
+    Wd = W.to(DEV).clone()
+    surgeon.surgeon_weight_update(Wd, dW.to(DEV), lr)
+    torch.cuda.synchronize()
+    ref = oracle.weight_update(bits(W), dW.numpy(), lr)
+    got, ref = f64(bits(Wd)), f64(ref)
+    # one fused multiply-add in fp32 against the oracle's double arithmetic: at most one unit in the last place apart
+    ulp = np.abs(ref) * (2.0 ** -23 if dtype == "f32" else 2.0 ** -7) + 1e-30
+    assert (np.abs(got - ref) <= ulp).all()
+    assert rel_l2(got, ref) <= (1e-5 if dtype == "f32" else 2e-3)
+    same = W.to(DEV).clone()
+    surgeon.surgeon_weight_update(same, torch.zeros(n, device=DEV), lr)  # a zero gradient changes nothing
+    assert torch.equal(same.cpu(), W)
+
+
+# ------------------------------------------------------------------------------------------------
+# scale / shift gradients of normalisation layers
+# ------------------------------------------------------------------------------------------------
+AFFINE_CASES = [
+    # outer, C, inner, group_len        batch norm: (Nb, C, H*W); layer norm: (tokens, C, 1)
+    (8, 160, 1024, 4096), (5, 64, 64, 4096), (200, 16, 1024, 4096), (3, 7, 49, 1000), (2, 33, 196, 4096),
+    (1000, 768, 1, 768), (333, 64, 1, 64), (77, 320, 1, 320), (50, 19, 1, 19), (64, 100, 1, 4096), (1, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", AFFINE_CASES)
+def test_affine_grad(dtype, case):
+    outer, C, inner, g = case
+    for r in (0.0, 0.7, 1.0):
+        print("affine_grad", case, dtype, "r=%g" % r, flush=True)
+        x = wl.draw((outer, C, inner), "normal", dtype, sum(case) + 1)
+        dY = wl.draw((outer, C, inner), "normal", dtype, sum(case) + 2)
+        p = surgeon.prune_pack(x.to(DEV), g, r)
+        dgamma, dbeta = surgeon.affine_grad(p, dY.to(DEV), outer, C, inner)
+        torch.cuda.synchronize()
+        o_vals, o_mask, _, o_k = oracle.prune_pack(bits(x).reshape(-1), g, r)
+        assert o_k == p.k_total
+        rg, rb = oracle.affine_grad(o_vals, o_mask, bits(dY), outer, C, inner)
+        # fp32 sums over up to 2e5 terms per channel: compared with the size of what is summed
+        scale = max(float(np.sqrt(outer * inner)), 1.0)
+        assert np.abs(dgamma.cpu().numpy() - rg).max() <= 1e-5 * scale * max(1.0, float(np.abs(rg).max()) / scale), case
+        assert np.abs(dbeta.cpu().numpy() - rb).max() <= 1e-5 * scale * max(1.0, float(np.abs(rb).max()) / scale), case
+        if outer * inner >= 64:
+            assert rel_l2(dgamma.cpu().numpy(), rg) <= 1e-5 or r == 1.0
+            assert rel_l2(dbeta.cpu().numpy(), rb) <= 1e-5
+        if r == 1.0:
+            assert not dgamma.any().item()
+
+
+# ------------------------------------------------------------------------------------------------
+# grouped and depthwise convolutions
+# ------------------------------------------------------------------------------------------------
+GROUPED = [
+    # Nb, Ci, H, W, Co, k, stride, pad, groups
+    (8, 128, 16, 16, 128, 3, 1, 1, 32), (4, 256, 8, 8, 512, 3, 2, 1, 32), (2, 64, 32, 32, 64, 3, 1, 1, 64),
+    (2, 320, 16, 32, 320, 3, 1, 1, 320), (3, 12, 9, 9, 24, 5, 2, 2, 4), (2, 6, 11, 11, 6, 7, 1, 3, 6),
+    (2, 8, 8, 8, 8, 1, 1, 0, 2), (1, 4, 5, 5, 4, 3, 1, 0, 4),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", GROUPED)
+def test_dw_grouped_conv(dtype, case):
+    Nb, Ci, H, W, Co, k, st, pad, groups = case
+    OH, OW = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+    for r in (0.0, 0.8, 1.0):
+        print("dw grouped", case, dtype, "r=%g" % r, flush=True)
+        A = wl.draw((Nb, Ci, H, W), "relu", dtype, sum(case) + 1)
+        dY = wl.draw((Nb, Co, OH, OW), "normal", dtype, sum(case) + 2)
+        p = surgeon.prune_pack(A.to(DEV), 4096, r)
+        desc = surgeon.conv2d_desc(Nb, Ci, H, W, Co, k, k, st, pad, sdt(dtype), p.k_total, groups=groups)
+        assert surgeon.surgeon_dw_kernel_class(desc) == "dw_grouped"
+        dW, G = _dw_gi(desc, p, dY.to(DEV))
+        o_vals, o_mask, _, _ = oracle.prune_pack(bits(A).reshape(-1), 4096, r)
+        ref = oracle.dw_conv2d_grouped(o_vals, o_mask, bits(dY), Nb, Ci, H, W, Co, k, k, st, pad, groups)
+        assert dW.shape == ref.shape
+        assert_dw_close(dW, ref, dtype, case)
+        o_G = oracle.grad_importance(ref)
+        assert abs(G - o_G) <= 1e-5 * max(o_G, 1e-30)
