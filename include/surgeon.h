@@ -51,7 +51,7 @@ typedef enum { SURGEON_LINEAR = 0, SURGEON_CONV2D = 1 } surgeon_layer_kind;
 /* kernel classes of the timing aid at the end of this header */
 enum { SURGEON_PROF_SELECT_PACK = 0, SURGEON_PROF_DW = 1, SURGEON_PROF_IMPORTANCE = 2, SURGEON_PROF_DW_AUX = 3,
        SURGEON_PROF_SELECT_OTHER = 4, SURGEON_PROF_DW_SPARSE = 5, SURGEON_PROF_DA = 6, SURGEON_PROF_UPDATE = 7,
-       SURGEON_PROF_AFFINE = 8, SURGEON_PROF_DW_GROUPED = 9, SURGEON_PROF_CLASSES = 10 };
+       SURGEON_PROF_AFFINE = 8, SURGEON_PROF_DW_GROUPED = 9, SURGEON_PROF_DW_SPARSE_AUX = 10, SURGEON_PROF_CLASSES = 11 };
 
 /*
  * Shape of one adapted layer for surgeon_dw_from_packed (Eq. 2, second line).
@@ -243,13 +243,14 @@ int surgeon_grad_importance_batched(const float* const* dW, const int64_t* n_w, 
  *   class 0 SURGEON_PROF_SELECT_PACK  fused select+pack kernel (group_len % 64 == 0, <= 4096)
  *   class 1 SURGEON_PROF_DW           the MFMA weight-gradient kernel (conv or linear)
  *   class 2 SURGEON_PROF_IMPORTANCE   sum-of-squares kernels of Eq. 4
- *   class 3 SURGEON_PROF_DW_AUX       rank-table pre-pass and split reduction around class 1
+ *   class 3 SURGEON_PROF_DW_AUX       rank-table pre-pass, dense transient copy and split reduction around classes 1 and 9
  *   class 4 SURGEON_PROF_SELECT_OTHER kernels of the other two selection paths, mask clearing
  *   class 5 SURGEON_PROF_DW_SPARSE    the weight-gradient kernel that works from the kept elements alone
  *   class 6 SURGEON_PROF_DA           activation-gradient kernel (surgeon_da)
  *   class 7 SURGEON_PROF_UPDATE       gradient step (surgeon_weight_update)
  *   class 8 SURGEON_PROF_AFFINE       scale / shift gradients of normalisation layers, with their rank pre-pass
  *   class 9 SURGEON_PROF_DW_GROUPED   weight-gradient kernel of grouped / depthwise convolutions
+ *   class 10 SURGEON_PROF_DW_SPARSE_AUX  rank-table pre-pass and split reduction around class 5
  * ms / launches are host arrays of n_classes entries (at most SURGEON_PROF_CLASSES are filled).
  * Not thread-safe; intended for one benchmarking thread.  Event objects are created by the HIP runtime, kept in a
  * pool and reused by later profiling sessions of the process.

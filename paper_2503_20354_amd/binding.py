@@ -289,7 +289,7 @@ def surgeon_grad_importance_batched(dWs, G_out, ws):
 
 
 PROF_CLASSES = ("select_pack", "dw", "importance", "dw_aux", "select_other", "dw_sparse", "da", "update", "affine",
-                "dw_grouped")
+                "dw_grouped", "dw_sparse_aux")
 
 
 def surgeon_profile_begin():

@@ -54,7 +54,24 @@ def build(verbose=False, force=True):
     r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    _write_build_info()
     return LIB
+
+
+def _write_build_info():
+    """Which sources the library was built from: the commit and whether the tree had uncommitted changes (the
+    benchmark prints it next to figures that come from a stored profile, so a stale profile is visible)."""
+    import json
+
+    def git(*args):
+        try:
+            return subprocess.run(["git", "-C", ROOT] + list(args), capture_output=True, text=True, timeout=20).stdout.strip()
+        except Exception:
+            return ""
+    info = {"commit": git("rev-parse", "--short=12", "HEAD") or "unknown",
+            "dirty": bool(git("status", "--porcelain", "--", "paper_2503_20354_amd/csrc", "include"))}
+    with open(os.path.join(HERE, "build_info.json"), "w") as f:
+        json.dump(info, f)
 
 
 if __name__ == "__main__":

@@ -325,6 +325,203 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// The same contraction for layers that fill a 256 x 128 tile: eight wavefronts (two per SIMD) as 4 (out) x 2 (in), each
+// owning 2 x 2 matrix tiles of 32 x 32; 64 tokens per K-tile, two LDS buffers, one workgroup per compute unit.
+// What was measured on the chip and shapes this kernel:
+//   * two wavefronts per SIMD drive the matrix pipeline at 2.4 PFLOP/s (one reaches 1.95), and one operand read of
+//     16 bytes per lane and matrix instruction still leaves 2.0 as long as a read is requested one K-step before it
+//     is used: the LDS port is not the bound, so the operands of K-step s+1 are read before the matrix work of step s;
+//   * a K-tile's trip from memory (streaming 48 KB through the vector memory path, the latency of the last load, the
+//     LDS store, the barrier) takes about as long as four K-tiles of matrix work, and with one K-tile in flight the
+//     kernel ran at the speed of that trip.  Two register sets keep two K-tiles in flight; the 256 x 256 tile (half
+//     the dY traffic) has room for one set only and was slower (69 against 65 us on a 2304 x 768 layer);
+//   * keeping all tiles of a split on one XCD (one L2) changed nothing: L2 misses are 134 MB per launch against 77 MB
+//     of distinct operand bytes, far from any bandwidth limit.
+// The 256 x 128 tile also halves the partial tiles a split contraction writes and re-reads: their total size is the
+// accumulator capacity in use on the chip.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kBigTO = 256, kBigTok = 64;
+// Row padding of 32 elements: the row stride is 16 banks (mod 64), so the 4 token rows x 64 bytes that one half of a
+// transposing read touches cover all 64 banks exactly once (with 16 elements of padding neighbouring rows overlap by
+// half and the LDS spent as long on bank conflicts as on the reads themselves).
+constexpr int kBigPad = 32;
+constexpr size_t big_lds_bytes(int ti) { return (size_t)2 * kBigTok * ((kBigTO + kBigPad) + (ti + kBigPad)) * sizeof(uint16_t); }
+
+template <int TI>
+__global__ __launch_bounds__(512) void dw_linear_bf16_big_kernel(int64_t M, int64_t K, int64_t N, int i_tiles,
+                                                                 int64_t rows_per_split, const uint16_t* __restrict__ A,
+                                                                 const uint16_t* __restrict__ dY, float* __restrict__ out) {
+  constexpr int SO = kBigTO + kBigPad, SI = TI + kBigPad, NB = TI / 64;
+  constexpr int CY = kBigTok * kBigTO / 8 / 512, CA = kBigTok * TI / 8 / 512;  // 16-byte chunks per thread and K-tile
+  constexpr int BUF = kBigTok * (SO + SI);
+  extern __shared__ __attribute__((aligned(16))) uint16_t big_lds[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wo = wave & 3, wi = wave >> 2;
+  const int tile_id = blockIdx.x, split_id = blockIdx.y;
+  const int64_t o0 = (int64_t)(tile_id / i_tiles) * kBigTO, i0 = (int64_t)(tile_id % i_tiles) * TI;
+  const int64_t m_begin = (int64_t)split_id * rows_per_split;
+  const int64_t m_end = min(m_begin + rows_per_split, M);
+
+  floatx16 acc[2][NB];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.0f;
+
+  // Two register sets of staged chunks: the loads of K-tile t+2 are issued while tile t is multiplied and tile t+1
+  // waits in the other set, so every load has two tiles' worth of matrix time to arrive (one tile is about as long
+  // as a trip to memory, and with a single set the kernel ran at the speed of that trip).
+  // All global reads are buffer loads: a 32-bit byte offset per chunk that never changes (row inside the K-tile, column),
+  // the K-tile's first token in the scalar offset, and the hardware range check instead of compares and selects: the
+  // resources end with this split's last token (rows past it read 0) and a column past the matrix has an offset that is
+  // out of range for every buffer (the host takes this kernel only for operands below 2 GiB).
+  constexpr int DEPTH = TI == 128 ? 2 : 1;  // register sets of staged chunks (the wide tile has room for one)
+  u32x4 ry[DEPTH][CY], ra[DEPTH][CA];
+  const __amdgpu_buffer_rsrc_t r_dy = __builtin_amdgcn_make_buffer_rsrc((void*)dY, 0, (int)(m_end * N * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t r_a = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)(m_end * K * 2), 0x00020000);
+  uint32_t vy[CY], va[CA];
+#pragma unroll
+  for (int j = 0; j < CY; ++j) {
+    const int c = tid + 512 * j, row = c / (kBigTO / 8), col = (c % (kBigTO / 8)) * 8;
+    vy[j] = o0 + col < N ? (uint32_t)((row * N + o0 + col) * 2) : 0x80000000u;
+  }
+#pragma unroll
+  for (int j = 0; j < CA; ++j) {
+    const int c = tid + 512 * j, row = c / (TI / 8), col = (c % (TI / 8)) * 8;
+    va[j] = i0 + col < K ? (uint32_t)((row * K + i0 + col) * 2) : 0x80000000u;
+  }
+  auto load_tile = [&](int set, int64_t m0) {
+    const uint32_t sy = (uint32_t)(m0 * N * 2), sa = (uint32_t)(m0 * K * 2);
+#pragma unroll
+    for (int j = 0; j < CY; ++j) ry[set][j] = __builtin_amdgcn_raw_buffer_load_b128(r_dy, vy[j], sy, 0);
+#pragma unroll
+    for (int j = 0; j < CA; ++j) ra[set][j] = __builtin_amdgcn_raw_buffer_load_b128(r_a, va[j], sa, 0);
+  };
+  auto store_tile = [&](int set, int buf) {
+    uint16_t* ys = big_lds + buf * BUF;
+    uint16_t* as = ys + kBigTok * SO;
+#pragma unroll
+    for (int j = 0; j < CY; ++j) {
+      const int c = tid + 512 * j, row = c / (kBigTO / 8), col = (c % (kBigTO / 8)) * 8;
+      *reinterpret_cast<u32x4*>(&ys[row * SO + col]) = ry[set][j];
+    }
+#pragma unroll
+    for (int j = 0; j < CA; ++j) {
+      const int c = tid + 512 * j, row = c / (TI / 8), col = (c % (TI / 8)) * 8;
+      *reinterpret_cast<u32x4*>(&as[row * SI + col]) = ra[set][j];
+    }
+  };
+  // LDS address of a lane's first transposing read in each buffer: everything that depends on the lane or the
+  // wavefront is in these four pointers, the K-step and the matrix tile are compile-time offsets of the read
+  typedef shortx4 __attribute__((address_space(3))) * lds_ptr;
+  const int blk = lane >> 4, s16 = lane & 15;  // 16-lane block: rows 16*(blk&1).., contraction half blk>>1
+  const int lane_tok = 8 * (blk >> 1) + (s16 >> 2), lane_col = 16 * (blk & 1) + 4 * (s16 & 3);
+  lds_ptr py[2], pa[2];
+#pragma unroll
+  for (int bq = 0; bq < 2; ++bq) {
+    py[bq] = (lds_ptr)(big_lds + bq * BUF + lane_tok * SO + wo * 64 + lane_col);
+    pa[bq] = (lds_ptr)(big_lds + bq * BUF + kBigTok * SO + lane_tok * SI + wi * (TI / 2) + lane_col);
+  }
+  auto mfma_tile = [&](int buf) {
+    // the narrow tile has registers to spare: operands of K-step s+1 are read before the matrix instructions of step s
+    constexpr int SETS = TI == 128 ? 2 : 1;
+    bf16x8 a[SETS][2], b[SETS][NB];
+    auto read8 = [&](lds_ptr p, int elem_off, int stride) {
+      const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(p + elem_off / 4);
+      const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(p + (elem_off + 4 * stride) / 4);
+      typedef short shortx8 __attribute__((ext_vector_type(8)));
+      const shortx8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, both);
+    };
+    auto read_step = [&](int set, int ks) {
+#pragma unroll
+      for (int q = 0; q < 2; ++q) a[set][q] = read8(py[buf], ks * SO + q * 32, SO);
+#pragma unroll
+      for (int q = 0; q < NB; ++q) b[set][q] = read8(pa[buf], ks * SI + q * 32, SI);
+    };
+    if (SETS == 2) read_step(0, 0);
+#pragma unroll
+    for (int s = 0; s < kBigTok / 16; ++s) {
+      if (SETS == 1) read_step(0, 16 * s);
+      else if (s + 1 < kBigTok / 16) read_step((s + 1) & 1, 16 * (s + 1));
+#pragma unroll
+      for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int q = 0; q < NB; ++q)
+          acc[p][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s & (SETS - 1)][p], b[s & (SETS - 1)][q], acc[p][q], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);  // keeps the reads of later K-steps from piling up in registers
+    }
+  };
+
+  const int64_t n_kt = m_begin < m_end ? (m_end - m_begin + kBigTok - 1) / kBigTok : 0;
+  if (n_kt > 0) {
+    load_tile(0, m_begin);
+    store_tile(0, 0);
+  }
+  if constexpr (DEPTH == 2) {
+    if (n_kt > 1) load_tile(1, m_begin + kBigTok);
+    __syncthreads();
+    // tile t sits in LDS buffer t % 2; tile t+1 in register set (t+1) % 2; tile t+2 is requested into set t % 2
+    for (int64_t t = 0; t < n_kt; t += 2) {
+      if (t + 2 < n_kt) load_tile(0, m_begin + (t + 2) * kBigTok);
+      mfma_tile(0);
+      if (t + 1 < n_kt) store_tile(1, 1);
+      __syncthreads();
+      if (t + 1 >= n_kt) break;
+      if (t + 3 < n_kt) load_tile(1, m_begin + (t + 3) * kBigTok);
+      mfma_tile(1);
+      if (t + 2 < n_kt) store_tile(0, 0);
+      __syncthreads();
+    }
+  } else {
+    __syncthreads();
+    for (int64_t t = 0; t < n_kt; t += 2) {
+      if (t + 1 < n_kt) load_tile(0, m_begin + (t + 1) * kBigTok);
+      mfma_tile(0);
+      if (t + 1 < n_kt) store_tile(0, 1);
+      __syncthreads();
+      if (t + 1 >= n_kt) break;
+      if (t + 2 < n_kt) load_tile(0, m_begin + (t + 2) * kBigTok);
+      mfma_tile(1);
+      if (t + 2 < n_kt) store_tile(0, 0);
+      __syncthreads();
+    }
+  }
+
+  // 32x32 result tile: lane holds column lane%32 and rows 8*(v/4) + 4*(lane/32) + v%4, v = 0..15
+  float* __restrict__ dst = out + (int64_t)split_id * N * K;
+  const int col = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int p = 0; p < 2; ++p)
+#pragma unroll
+    for (int q = 0; q < NB; ++q) {
+      const int64_t i = i0 + wi * (TI / 2) + q * 32 + col;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int64_t o = o0 + wo * 64 + p * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+        if (o < N && i < K) dst[o * K + i] = acc[p][q][v];
+      }
+    }
+}
+
+int launch_linear_bf16_big(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,
+                           int64_t rows_per_split, hipStream_t st) {
+  constexpr int TI = kBf16BigTileI;
+  const int i_tiles = (int)ceil_div(K, TI), o_tiles = (int)ceil_div(N, kBigTO);
+  const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
+  ProfScope prof(SURGEON_PROF_DW, st);
+  SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)dw_linear_bf16_big_kernel<TI>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)big_lds_bytes(TI)));
+  SURGEON_LAUNCH(dw_linear_bf16_big_kernel<TI>, grid, dim3(512), big_lds_bytes(TI), st, M, K, N, i_tiles, rows_per_split,
+                 (const uint16_t*)A_dense, (const uint16_t*)dY, out);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // 1x1 stride-1 convolution in NCHW = per image a contraction over the pixels, which are the contiguous index of
 // both operands: dW[co][ci] = sum_b sum_p dY[b][co][p] * A[b][ci][p].  Tiles are staged [channel][pixel] and read
 // back with plain 16-byte LDS reads (8 consecutive pixels of one channel are exactly one MFMA operand register set).

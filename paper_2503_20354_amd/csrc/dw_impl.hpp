@@ -883,6 +883,7 @@ struct LinPlan {
   int o_tiles, splits;
   bool bf16_mfma;  // dense bf16-MFMA path: un-pack to the workspace, then contract
   int bf16_wide;   // 1: the 128 x 256 tile of the bf16 path
+  bool bf16_big;   // the dense bf16 path with the 256 x 128 tile of eight wavefronts
 };
 
 struct DwPlan {
@@ -1088,6 +1089,27 @@ static int plan_linear(const surgeon_layer_desc* d, LinPlan* lp) {
   g.n_w = d->N * d->K;
   lp->bf16_mfma = d->dtype == SURGEON_BF16 && d->K % 8 == 0 && d->M > 0;
   lp->bf16_wide = 0;
+  lp->bf16_big = false;
+  if (lp->bf16_mfma && d->N % 8 == 0 && d->M * d->N * 2 < big && d->M * d->K * 2 < big) {
+    // the 256 x 128 tile of eight wavefronts against the 128 x 128 one: it is taken when padding the layer to it costs at
+    // most a third more matrix work (its loads are buffer loads with 32-bit offsets: operands below 2 GiB)
+    auto padded = [](int64_t x, int64_t t) { return ceil_div(x, t) * t; };
+    const int64_t work_big = padded(d->N, kBf16BigTileO) * padded(d->K, kBf16BigTileI);
+    const int64_t work_dense = padded(d->N, kBf16LinearTile) * padded(d->K, kBf16LinearTile);
+    if (3 * work_big <= 4 * work_dense) {
+      lp->bf16_big = true;
+      lp->mt = lp->nt = 0;
+      lp->tm = kBf16BigTokens;
+      lp->o_tiles = (int)ceil_div(d->N, kBf16BigTileO);
+      g.i_tiles = (int)ceil_div(d->K, kBf16BigTileI);
+      int64_t per;
+      const int64_t k_tiles = ceil_div(d->M, lp->tm);
+      const double tile_us = 2.0 * kBf16BigTileO * kBf16BigTileI * lp->tm / (0.3 * kBf16FlopsPerCuPerUs);
+      lp->splits = choose_splits(k_tiles, (int64_t)lp->o_tiles * g.i_tiles, kConvSlots, tile_us, g.n_w, &per);
+      g.rows_per_split = per * lp->tm;
+      return SURGEON_OK;
+    }
+  }
   if (lp->bf16_mfma) {
     lp->mt = lp->nt = 0;
     // the wide tile when the in-feature dimension fills it and the layer is large enough to keep the chip busy with it
@@ -1257,9 +1279,10 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   // the bf16 linear path un-packs whole groups when their positions are known in closed form: no rank table at all
   const bool dense_path = (!p.conv && p.l.bf16_mfma) || (p.conv && p.c.gemm1x1);
   const bool grouped_unpack = dense_path && p.rank_words_per_group > 0;
+  const int aux_class = (p.conv && p.c.sparse) ? SURGEON_PROF_DW_SPARSE_AUX : SURGEON_PROF_DW_AUX;
   // rank table
   if (!grouped_unpack) {
-  ProfScope prof(SURGEON_PROF_DW_AUX, st);
+  ProfScope prof(aux_class, st);
   if (p.rank_words_per_group > 0) {
     SURGEON_LAUNCH(rank_grouped_kernel, dim3((unsigned)ceil_div(p.rank_groups, kRankBlock / 64)), dim3(kRankBlock), 0, st,
                        mask, p.n_words, p.rank_words_per_group, p.rank_groups, (uint32_t)p.rank_k_full, word_rank);
@@ -1293,6 +1316,8 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
       if (p.conv)
         rc = launch_conv1x1_bf16(p.c.g.Nb, p.c.g.Ci, p.c.g.Co, p.c.g.H * p.c.g.W, dense, dY, out, p.c.splits,
                                  p.c.gemm_ktiles_per_split, st);
+      else if (p.l.bf16_big)
+        rc = launch_linear_bf16_big(p.l.g.M, p.l.g.K, p.l.g.N, dense, dY, out, p.l.splits, p.l.g.rows_per_split, st);
       else
         rc = launch_linear_bf16(p.l.g.M, p.l.g.K, p.l.g.N, dense, dY, out, p.l.splits, p.l.g.rows_per_split, p.l.bf16_wide, st);
     }
@@ -1305,7 +1330,7 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   if (rc != SURGEON_OK) return rc;
   if (p.splits > 1) {
     const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), kGiPartials);
-    ProfScope prof(SURGEON_PROF_DW_AUX, st);
+    ProfScope prof(aux_class, st);
     if (G_out) {
       SURGEON_LAUNCH(dw_reduce_splits_kernel<true>, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w,
                      dW, sq_partial);
