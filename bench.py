@@ -78,13 +78,17 @@ def run_config(cfg, steps, warmup, torch, surgeon, wl, dev):
     m_bytes = [L.n * L.elem_bytes for L in layers]
     acct = {"sp_bytes": 0.0, "imp_bytes": 0.0, "dw": 0.0, "dw_nnz": 0.0, "dw_sparse": 0.0, "dw_sparse_nnz": 0.0}
 
+    all_A, all_vals, all_mask = [e["A"] for e in st], [e["vals"] for e in st], [e["mask"] for e in st]
+    all_g = [e["L"].group_len for e in st]
+
     def forward_half(ratios, count):
+        # Alg. 1 lines 6-7 for every layer of the pass in one call (all layers select in groups of at most 4096)
+        surgeon.surgeon_prune_pack_batched(all_A, all_g, ratios, all_vals, all_mask)
         for e, r in zip(st, ratios):
             L = e["L"]
             k = surgeon.surgeon_packed_sizes(L.n, L.group_len, r, dt)[0]
             e["desc"].k_total = k
             e["desc"].group_len, e["desc"].r = L.group_len, r
-            surgeon.surgeon_prune_pack(e["A"], L.group_len, r, e["vals"], e["mask"], None, ws)
             if count:
                 acct["sp_bytes"] += L.n * L.elem_bytes + k * L.elem_bytes + 8 * ((L.n + 63) // 64)
                 # flops go to the kernel class the library will use for this (shape, kept count); asked once per pair

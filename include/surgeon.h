@@ -131,6 +131,17 @@ int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, float r, int
                        void* vals, uint64_t* mask, uint32_t* idx,
                        void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Alg. 1 lines 6-7 for l tensors in one call: the same results, bit for bit, as l calls of surgeon_prune_pack without
+ * idx.  The layers of a network are small next to the chip, so per-tensor launches each pay a launch gap and a ragged
+ * tail; here tensors whose group lengths share a kernel variant go out in one launch (at most ten launches per 48
+ * tensors).  A, n, group_len, r, vals, mask are HOST arrays of l entries (device pointers / sizes / ratios per
+ * tensor); all tensors have dtype dt.  Every tensor must take the in-register selection path: group_len (after
+ * clamping to n) a multiple of 64 and at most 4096, else SURGEON_EUNSUPPORTED and nothing is launched.  No workspace.
+ */
+int surgeon_prune_pack_batched(int l, const void* const* A, const int64_t* n, const int64_t* group_len, const float* r,
+                               int dt, void* const* vals, uint64_t* const* mask, void* stream);
+
 /* Workspace surgeon_dw_from_packed needs for `desc`, whatever its k_total: one query serves every prune ratio the
  * layer will be called with.  Host only. */
 int surgeon_dw_ws_bytes(const surgeon_layer_desc* desc, size_t* ws_bytes);

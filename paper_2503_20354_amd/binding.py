@@ -57,6 +57,8 @@ def load_library():
     L.surgeon_layer_ratios.argtypes = [vp, vp, ci, f32, f32, vp]
     L.surgeon_prune_pack.restype = ci
     L.surgeon_prune_pack.argtypes = [vp, i64, i64, f32, ci, vp, vp, vp, vp, sz, vp]
+    L.surgeon_prune_pack_batched.restype = ci
+    L.surgeon_prune_pack_batched.argtypes = [ci, vp, vp, vp, vp, ci, vp, vp, vp]
     L.surgeon_dw_ws_bytes.restype = ci
     L.surgeon_dw_ws_bytes.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(sz)]
     L.surgeon_dw_kernel_class.restype = ci
@@ -162,6 +164,21 @@ def surgeon_prune_pack(A, group_len, r, vals, mask, idx=None, ws=None):
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(load_library().surgeon_prune_pack(_ptr(A), A.numel(), int(group_len), float(r), _dt(A), _ptr(vals),
                                              _ptr(mask), _ptr(idx), _ptr(ws), ws_bytes, _stream(A.device)))
+
+
+def surgeon_prune_pack_batched(As, group_lens, ratios, vals, masks):
+    """Alg. 1 lines 6-7 for a list of tensors (one dtype) in one call; vals / masks: pre-sized tensors per layer."""
+    l = len(As)
+    for t in list(As) + list(masks):
+        _dev(t, "tensor")
+    dt = _dt(As[0])
+    a_p = (ctypes.c_void_p * l)(*[t.data_ptr() for t in As])
+    v_p = (ctypes.c_void_p * l)(*[t.data_ptr() for t in vals])
+    m_p = (ctypes.c_void_p * l)(*[t.data_ptr() for t in masks])
+    n_a = (ctypes.c_int64 * l)(*[t.numel() for t in As])
+    g_a = (ctypes.c_int64 * l)(*[int(g) for g in group_lens])
+    r_a = (ctypes.c_float * l)(*[float(r) for r in ratios])
+    _check(load_library().surgeon_prune_pack_batched(l, a_p, n_a, g_a, r_a, dt, v_p, m_p, _stream(As[0].device)))
 
 
 def surgeon_dw_ws_bytes(desc: LayerDesc) -> int:

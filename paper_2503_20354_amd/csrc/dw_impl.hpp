@@ -1329,7 +1329,8 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   }
   if (rc != SURGEON_OK) return rc;
   if (p.splits > 1) {
-    const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), kGiPartials);
+    // with Gradient Importance: at most 1024 workgroups, so that the finishing launch adds 4 partials per thread
+    const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), G_out ? 1024 : kGiPartials);
     ProfScope prof(aux_class, st);
     if (G_out) {
       SURGEON_LAUNCH(dw_reduce_splits_kernel<true>, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w,

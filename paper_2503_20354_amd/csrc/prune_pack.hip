@@ -11,6 +11,8 @@
 //      histograms in the workspace, then count / scan / pack kernels over 1024-element wave chunks.
 // Paths 2 and 3 set mask bits with atomicOr on a zeroed mask because groups need not start on a word boundary.
 // No floating-point arithmetic decides anything: keys are integer bit patterns, so results are bit-exact.
+#include <vector>
+
 #include "common.hpp"
 
 namespace surgeon {
@@ -167,16 +169,12 @@ struct EmitSlots {
 // ---------------------------------------------------------------------------------------------------------
 // path 1: one wavefront per group, group in registers
 // ---------------------------------------------------------------------------------------------------------
+// group `grp` of one tensor, by the calling wavefront
 template <int E, typename BitsT, bool WITH_IDX>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void select_pack_wave_reg_kernel(const BitsT* __restrict__ A,
-                                                                   BitsT* __restrict__ vals,
-                                                                   uint64_t* __restrict__ mask,
-                                                                   uint32_t* __restrict__ idx, int64_t n_groups,
-                                                                   int g, int len_last, int k_full, int k_last) {
+__device__ __forceinline__ void select_pack_group(const BitsT* __restrict__ A, BitsT* __restrict__ vals,
+                                                  uint64_t* __restrict__ mask, uint32_t* __restrict__ idx, int64_t grp,
+                                                  int64_t n_groups, int g, int len_last, int k_full, int k_last) {
   const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t grp = (int64_t)blockIdx.x * 4 + wave;
-  if (grp >= n_groups) return;
   const bool is_last = grp == n_groups - 1;
   const int len = is_last ? len_last : g;
   const int k = is_last ? k_last : k_full;
@@ -314,6 +312,45 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void s
   EmitSlots<0, E, BitsT, WITH_IDX>::run(kr, lane, w_lo, w_hi, base, r_vals, r_idx);
   const int n_words = (len + 63) >> 6;
   if (lane < n_words) mask[(gstart >> 6) + lane] = ((uint64_t)w_hi << 32) | w_lo;
+}
+
+template <int E, typename BitsT, bool WITH_IDX>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void select_pack_wave_reg_kernel(const BitsT* __restrict__ A,
+                                                                   BitsT* __restrict__ vals,
+                                                                   uint64_t* __restrict__ mask,
+                                                                   uint32_t* __restrict__ idx, int64_t n_groups,
+                                                                   int g, int len_last, int k_full, int k_last) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t grp = (int64_t)blockIdx.x * 4 + wave;
+  if (grp >= n_groups) return;
+  select_pack_group<E, BitsT, WITH_IDX>(A, vals, mask, idx, grp, n_groups, g, len_last, k_full, k_last);
+}
+
+// ---- many tensors in one launch (surgeon_prune_pack_batched): the tensors of a network are small next to the chip
+// (a layer of 8 M elements is two rounds of wavefronts), so per-tensor launches pay a launch gap and a ragged tail each.
+// The descriptors of up to kPackBatch tensors travel as kernel arguments; workgroup -> tensor by its first workgroup.
+constexpr int kPackBatch = 48;
+struct PackBatch {
+  const void* A[kPackBatch];
+  void* vals[kPackBatch];
+  uint64_t* mask[kPackBatch];
+  int64_t n_groups[kPackBatch];
+  int first_block[kPackBatch + 1];  // workgroups [first_block[i], first_block[i+1]) belong to tensor i
+  int g[kPackBatch], len_last[kPackBatch], k_full[kPackBatch], k_last[kPackBatch];
+};
+
+template <int E, typename BitsT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void select_pack_wave_reg_batched_kernel(PackBatch bt) {
+  // the tensor of this workgroup = number of boundaries at or below its index (independent compares: the table comes in
+  // with a few wide scalar loads); entries past the last tensor hold the total, which no index reaches
+  int t = 0;
+#pragma unroll
+  for (int i = 1; i < kPackBatch; ++i) t += ((int)blockIdx.x >= bt.first_block[i]) ? 1 : 0;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t grp = (int64_t)((int)blockIdx.x - bt.first_block[t]) * 4 + wave;
+  if (grp >= bt.n_groups[t]) return;
+  select_pack_group<E, BitsT, false>((const BitsT*)bt.A[t], (BitsT*)bt.vals[t], bt.mask[t], (uint32_t*)nullptr, grp,
+                                     bt.n_groups[t], bt.g[t], bt.len_last[t], bt.k_full[t], bt.k_last[t]);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -712,6 +749,39 @@ static int run_wave_reg(const GroupPlan& p, const void* A, void* vals, uint64_t*
   return launch_wave_reg<64, BitsT>(p, A, vals, mask, idx, st);
 }
 
+// register slots per lane the in-register kernel is built with for a group length
+static int wave_reg_slots(int64_t g) {
+  const int slots = (int)(g / 64);
+  const int built[10] = {1, 2, 4, 8, 12, 16, 24, 32, 48, 64};
+  for (int i = 0; i < 10; ++i)
+    if (slots <= built[i]) return built[i];
+  return 64;
+}
+
+template <int E, typename BitsT>
+static int launch_wave_reg_batched(const PackBatch& bt, int blocks, hipStream_t st) {
+  ProfScope prof(SURGEON_PROF_SELECT_PACK, st);
+  SURGEON_LAUNCH((select_pack_wave_reg_batched_kernel<E, BitsT>), dim3((unsigned)blocks), dim3(256), 0, st, bt);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+template <typename BitsT>
+static int run_wave_reg_batched(int slots, const PackBatch& bt, int blocks, hipStream_t st) {
+  switch (slots) {
+    case 1: return launch_wave_reg_batched<1, BitsT>(bt, blocks, st);
+    case 2: return launch_wave_reg_batched<2, BitsT>(bt, blocks, st);
+    case 4: return launch_wave_reg_batched<4, BitsT>(bt, blocks, st);
+    case 8: return launch_wave_reg_batched<8, BitsT>(bt, blocks, st);
+    case 12: return launch_wave_reg_batched<12, BitsT>(bt, blocks, st);
+    case 16: return launch_wave_reg_batched<16, BitsT>(bt, blocks, st);
+    case 24: return launch_wave_reg_batched<24, BitsT>(bt, blocks, st);
+    case 32: return launch_wave_reg_batched<32, BitsT>(bt, blocks, st);
+    case 48: return launch_wave_reg_batched<48, BitsT>(bt, blocks, st);
+    default: return launch_wave_reg_batched<64, BitsT>(bt, blocks, st);
+  }
+}
+
 template <typename BitsT>
 static int run_wave_mem(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx, hipStream_t st) {
   const dim3 grid((unsigned)ceil_div(p.n_groups, 4)), block(256);
@@ -824,4 +894,72 @@ extern "C" int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, f
   hipStream_t st = (hipStream_t)stream;
   if (dt == SURGEON_F32) return run_prune_pack<uint32_t>(p, A, vals, mask, idx, ws, st);
   return run_prune_pack<uint16_t>(p, A, vals, mask, idx, ws, st);
+}
+
+extern "C" int surgeon_prune_pack_batched(int l, const void* const* A, const int64_t* n, const int64_t* group_len,
+                                          const float* r, int dt, void* const* vals, uint64_t* const* mask, void* stream) {
+  if (dt != SURGEON_F32 && dt != SURGEON_BF16) return fail(SURGEON_EINVAL, "prune_pack_batched: bad dtype %d", dt);
+  if (l < 0 || (l > 0 && (!A || !n || !group_len || !r || !vals || !mask)))
+    return fail(SURGEON_EINVAL, "prune_pack_batched: bad arguments");
+  const size_t es = dt == SURGEON_F32 ? 4 : 2;
+  // validate everything before the first launch
+  std::vector<GroupPlan> plans((size_t)l);
+  for (int i = 0; i < l; ++i) {
+    GroupPlan& p = plans[(size_t)i];
+    if (!make_group_plan(n[i], group_len[i], r[i], &p))
+      return fail(SURGEON_EINVAL, "prune_pack_batched: tensor %d: need n >= 0, group_len >= 1, 0 <= r <= 1", i);
+    if (n[i] > ((int64_t)1 << 31)) return fail(SURGEON_EUNSUPPORTED, "prune_pack_batched: tensor %d exceeds 2^31 elements", i);
+    if (n[i] == 0) continue;
+    if (choose_prune_path(p) != PATH_WAVE_REG)
+      return fail(SURGEON_EUNSUPPORTED,
+                  "prune_pack_batched: tensor %d: group_len %lld is not a multiple of 64 up to 4096 (use surgeon_prune_pack)", i,
+                  (long long)p.g);
+    if (!A[i] || !mask[i] || (p.k_total > 0 && !vals[i])) return fail(SURGEON_EINVAL, "prune_pack_batched: tensor %d: null pointer", i);
+    if (((uintptr_t)A[i] % es) || ((uintptr_t)vals[i] % es) || ((uintptr_t)mask[i] % 8))
+      return fail(SURGEON_EINVAL, "prune_pack_batched: tensor %d: misaligned pointer", i);
+    if (ceil_div(p.n_groups, 4) > 0x3fffffff) return fail(SURGEON_EUNSUPPORTED, "prune_pack_batched: tensor %d too large", i);
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const int built[10] = {1, 2, 4, 8, 12, 16, 24, 32, 48, 64};
+  for (int bi = 0; bi < 10; ++bi) {
+    PackBatch bt;
+    int count = 0;
+    int64_t blocks = 0;
+    auto flush = [&]() -> int {
+      if (count == 0) return SURGEON_OK;
+      for (int j = count; j <= kPackBatch; ++j) bt.first_block[j] = (int)blocks;
+      for (int j = count; j < kPackBatch; ++j) {
+        bt.A[j] = nullptr; bt.vals[j] = nullptr; bt.mask[j] = nullptr; bt.n_groups[j] = 0;
+        bt.g[j] = 64; bt.len_last[j] = 0; bt.k_full[j] = 0; bt.k_last[j] = 0;
+      }
+      const int rc = dt == SURGEON_F32 ? run_wave_reg_batched<uint32_t>(built[bi], bt, (int)blocks, st)
+                                       : run_wave_reg_batched<uint16_t>(built[bi], bt, (int)blocks, st);
+      count = 0;
+      blocks = 0;
+      return rc;
+    };
+    for (int i = 0; i < l; ++i) {
+      const GroupPlan& p = plans[(size_t)i];
+      if (p.n == 0 || wave_reg_slots(p.g) != built[bi]) continue;
+      if (p.k_total == 0) {  // nothing kept: an all-zero mask, as the single-tensor call writes
+        ProfScope prof(SURGEON_PROF_SELECT_OTHER, st);
+        const int rc = zero_mask(mask[i], ceil_div(p.n, 64), st);
+        if (rc != SURGEON_OK) return rc;
+        continue;
+      }
+      const int64_t b = ceil_div(p.n_groups, 4);
+      if (count == kPackBatch || blocks + b > 0x7fffffff) {
+        const int rc = flush();
+        if (rc != SURGEON_OK) return rc;
+      }
+      bt.A[count] = A[i]; bt.vals[count] = vals[i]; bt.mask[count] = mask[i]; bt.n_groups[count] = p.n_groups;
+      bt.first_block[count] = (int)blocks;
+      bt.g[count] = (int)p.g; bt.len_last[count] = (int)p.len_last; bt.k_full[count] = (int)p.k_full; bt.k_last[count] = (int)p.k_last;
+      blocks += b;
+      ++count;
+    }
+    const int rc = flush();
+    if (rc != SURGEON_OK) return rc;
+  }
+  return SURGEON_OK;
 }

@@ -415,3 +415,39 @@ def test_vit_workload_full_size_sampled(name, r):
                                     ("dec.fuse", 0.9), ("dec.fuse", 0.65), ("dec.cls", 0.9), ("dec.cls", 0.6)])
 def test_segmentation_workload_full_size_sampled(name, r):
     full_size_layer(4, name, r)
+
+
+# ------------------------------------------------------------------------------------------------
+# many tensors in one call
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prune_pack_batched_matches_single_calls_and_oracle(dtype):
+    """70 tensors of mixed group lengths, sizes and ratios (more than one batch of 48, every kernel variant, ragged last
+    groups, a ratio of 1): the batched call writes the same bits as one call per tensor, which match the oracle."""
+    rng = np.random.default_rng(5)
+    g_choices = [64, 128, 256, 320, 512, 768, 1280, 2048, 3072, 4096, 4096, 4096]
+    As, gs, rs = [], [], []
+    for i in range(70):
+        g = int(rng.choice(g_choices))
+        n = g * int(rng.integers(1, 40)) + (int(rng.integers(0, g // 64)) * 64 if i % 3 == 0 else 0)
+        As.append(wl.draw((n,), "relu" if i % 2 else "normal", dtype, 9000 + i))
+        gs.append(g)
+        rs.append(1.0 if i == 7 else float(rng.choice([0.0, 0.3, 0.5, 0.9, 0.95])))
+    dev_A = [a.to(DEV) for a in As]
+    vals, masks = [], []
+    for a, g, r in zip(dev_A, gs, rs):
+        k = surgeon.surgeon_packed_sizes(a.numel(), g, r, surgeon.F32 if dtype == "f32" else surgeon.BF16)[0]
+        vals.append(torch.full((max(k, 1),), 7.0, dtype=a.dtype, device=DEV))
+        masks.append(torch.full(((a.numel() + 63) // 64,), -1, dtype=torch.int64, device=DEV))
+    surgeon.surgeon_prune_pack_batched(dev_A, gs, rs, vals, masks)
+    torch.cuda.synchronize()
+    for i, (a, g, r) in enumerate(zip(As, gs, rs)):
+        o_vals, o_mask, _, o_k = oracle.prune_pack(host_bits(a), g, r)
+        assert np.array_equal(masks[i].cpu().numpy().view(np.uint64), o_mask), (i, g, r)
+        assert np.array_equal(host_bits(vals[i])[:o_k].view(np.uint8), o_vals.view(np.uint8)), (i, g, r)
+        single = surgeon.prune_pack(dev_A[i], g, r)
+        assert torch.equal(single.mask, masks[i]) and torch.equal(single.vals, vals[i][:o_k])
+    # a tensor that does not take the in-register path is refused before anything is launched
+    with pytest.raises(surgeon.SurgeonError) as e:
+        surgeon.surgeon_prune_pack_batched([dev_A[0], dev_A[1]], [gs[0], 100], [0.5, 0.5], vals[:2], masks[:2])
+    assert e.value.status == 3
