@@ -75,9 +75,11 @@ __device__ __forceinline__ uint64_t low_bits64(int q) { return q >= 64 ? ~0ull :
 // compare -> add-with-carry chains per block so that no instruction waits for its predecessor; each compare
 // result sits in its own SGPR pair and is consumed three instructions later (gfx940+ needs two wait states
 // between a vector write of an SGPR and a vector read of it, which the compiler cannot add inside inline asm).
+// Short groups (at most 16 slots) count with one ballot and a scalar popcount per slot instead: the per-lane counters
+// end in a wave-wide sum (a DPP scan and four readlanes) whose cost no longer disappears behind a few slots.
 template <int E>
 __device__ __forceinline__ int count_ge(const uint32_t (&kr)[E], uint32_t thr2) {
-  if constexpr (E % 4 == 0) {
+  if constexpr (E % 4 == 0 && E > 16) {
     uint32_t c0 = 0, c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
     for (int j = 0; j < E; j += 4) {
