@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 #include <algorithm>
+#include <atomic>
 #include <stdint.h>
 #include <stdio.h>
 
@@ -44,6 +45,19 @@ bool prof_next_events(hipEvent_t* start, hipEvent_t* stop);
     else                                                                                                  \
       hipLaunchKernelGGL(kernel, grid, block, shmem, st, __VA_ARGS__);                                    \
   } while (0)
+
+// Raises a kernel's dynamic-LDS limit once per (kernel, device): the attribute belongs to the device, the flag word is
+// one bit per device and is only ever OR-ed into, so host threads that race here at worst set the attribute twice.
+// `done` is a static of the calling launch function (one per kernel).
+inline int ensure_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  SURGEON_HIP_CHECK(hipGetDevice(&dev));
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return SURGEON_OK;
+  SURGEON_HIP_CHECK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  done.fetch_or(bit, std::memory_order_release);
+  return SURGEON_OK;
+}
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

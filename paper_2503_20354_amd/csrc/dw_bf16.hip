@@ -513,8 +513,9 @@ int launch_linear_bf16_big(int64_t M, int64_t K, int64_t N, const void* A_dense,
   const int i_tiles = (int)ceil_div(K, TI), o_tiles = (int)ceil_div(N, kBigTO);
   const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
   ProfScope prof(SURGEON_PROF_DW, st);
-  SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)dw_linear_bf16_big_kernel<TI>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)big_lds_bytes(TI)));
+  static std::atomic<uint64_t> lds_set{0};
+  const int rc_lds = ensure_dynamic_lds((const void*)dw_linear_bf16_big_kernel<TI>, big_lds_bytes(TI), lds_set);
+  if (rc_lds != SURGEON_OK) return rc_lds;
   SURGEON_LAUNCH(dw_linear_bf16_big_kernel<TI>, grid, dim3(512), big_lds_bytes(TI), st, M, K, N, i_tiles, rows_per_split,
                  (const uint16_t*)A_dense, (const uint16_t*)dY, out);
   SURGEON_LAUNCH_CHECK();
@@ -637,9 +638,9 @@ static int launch_conv1x1_bf16_ce(int Nb, int Ci, int Co, int HW, const void* A_
   const int i_tiles = (int)ceil_div(Ci, kPxTile), o_tiles = (int)ceil_div(Co, kPxTile);
   const int tiles_per_img = (int)ceil_div(HW, kPxTok);
   const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
-  // set on every call: the attribute belongs to the current device, and a cached flag would race between host threads
-  SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)dw_conv1x1_bf16_kernel<CE>,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPxLdsBytes));
+  static std::atomic<uint64_t> lds_set{0};
+  const int rc_lds = ensure_dynamic_lds((const void*)dw_conv1x1_bf16_kernel<CE>, kPxLdsBytes, lds_set);
+  if (rc_lds != SURGEON_OK) return rc_lds;
   ProfScope prof(SURGEON_PROF_DW, st);
   SURGEON_LAUNCH(dw_conv1x1_bf16_kernel<CE>, grid, dim3(256), kPxLdsBytes, st, Nb, Ci, Co, HW, i_tiles, tiles_per_img,
                  ktiles_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);

@@ -1187,18 +1187,18 @@ static int plan_dw(const surgeon_layer_desc* d, DwPlan* p, int sparse_choice = S
   return SURGEON_OK;
 }
 
-template <typename K>
-static int allow_lds(K kernel, size_t bytes) {
-  if (bytes > 48 * 1024)
-    SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-  return SURGEON_OK;
-}
+
 
 template <typename InT, bool BF, int KHC, int KW, int MT, int NT, int P>
 static int launch_conv_variant(const ConvPlan& cp, const Packed<InT>& pk, const void* dY, float* out, hipStream_t st) {
   auto kernel = dw_conv_kernel<InT, BF, KHC, KW, MT, NT, P>;
-  const int rc = allow_lds(kernel, cp.lds_bytes);
-  if (rc != SURGEON_OK) return rc;
+  // the dynamic-LDS limit is raised to the whole LDS once per kernel (this function is instantiated per kernel) and
+  // device; what a launch occupies is its own lds_bytes
+  static std::atomic<uint64_t> lds_set{0};
+  if (cp.lds_bytes > 48 * 1024) {
+    const int rc = ensure_dynamic_lds((const void*)kernel, kMaxLds, lds_set);
+    if (rc != SURGEON_OK) return rc;
+  }
   const dim3 grid((unsigned)(cp.co_tiles * cp.g.ci_tiles), (unsigned)cp.splits, (unsigned)cp.z);
   ProfScope prof(SURGEON_PROF_DW, st);
   SURGEON_LAUNCH(kernel, grid, dim3(512), cp.lds_bytes, st, cp.g, pk, (const InT*)dY, out);

@@ -179,8 +179,11 @@ int launch_variant(const SparseGeom& g, int co_tiles, int splits, const float* v
                    const uint32_t* word_rank, const float* dY, float* out, hipStream_t st) {
   auto kernel = dw_conv3x3_sparse_kernel<W, R, CPW, WAVES, SHARE>;
   const size_t lds = (size_t)(R + 2) * (W + 2) * kSpPix * sizeof(float);
-  if (lds > 48 * 1024)
-    SURGEON_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  if (lds > 48 * 1024) {
+    static std::atomic<uint64_t> lds_set{0};  // one per instantiation = per kernel; lds is a constant of the instantiation
+    const int rc_lds = ensure_dynamic_lds((const void*)kernel, lds, lds_set);
+    if (rc_lds != SURGEON_OK) return rc_lds;
+  }
   const dim3 grid((unsigned)(co_tiles * g.ci_tiles), (unsigned)splits);
   ProfScope prof(SURGEON_PROF_DW_SPARSE, st);
   SURGEON_LAUNCH(kernel, grid, dim3(64 * WAVES), lds, st, g, vals, mask, word_rank, dY, out);
