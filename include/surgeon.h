@@ -12,8 +12,8 @@
  *   - "device" pointers are HIP device memory the CALLER owns; the library never allocates, frees or
  *     retains device memory.  It keeps no state between calls except: the thread-local text behind
  *     surgeon_last_error(), the event pool and records of the timing aid at the end of this header (process-wide,
- *     touched only between surgeon_profile_begin/end), and the per-device address of the static array that
- *     surgeon_grad_importance_static uses.  "host" pointers are ordinary memory.
+ *     touched only between surgeon_profile_begin/end), the per-device address of the static array that
+ *     surgeon_grad_importance_static uses, and the value of surgeon_set_select_margin.  "host" pointers are ordinary memory.
  *   - All device work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream)
  *     and the call returns without synchronising.
  *   - The return value is a surgeon_status.  Argument errors are found on the host before any launch and
@@ -130,6 +130,18 @@ int surgeon_layer_ratios(const float* G, const uint64_t* m, int l, float r_lo, f
 int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, float r, int dt,
                        void* vals, uint64_t* mask, uint32_t* idx,
                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Tuning knob of surgeon_prune_pack for groups of 32768 elements or more (the whole-tensor scope among them).  There
+ * the threshold is first bracketed from a 4096-element sample, `deviations` standard deviations of the sample rank to
+ * either side, so that the activation is read twice (once to count and to copy the few per cent of elements inside the
+ * bracket, once to pack) instead of five times.  A bracket that misses the threshold is detected on the device and
+ * the call then selects over the whole group: the result is bit-identical for every value of the knob, only the time
+ * differs.  Default 5 (a miss about once in a million groups); smaller values copy fewer elements and miss more often;
+ * negative values make every bracket miss (a test hook for the full-width route).  Process-wide, not synchronised
+ * with calls in flight on other threads.  Host only.  Outside [-100, 100]: SURGEON_EINVAL.
+ */
+int surgeon_set_select_margin(float deviations);
 
 /*
  * Alg. 1 lines 6-7 for l tensors in one call: the same results, bit for bit, as l calls of surgeon_prune_pack without

@@ -57,6 +57,8 @@ def load_library():
     L.surgeon_layer_ratios.argtypes = [vp, vp, ci, f32, f32, vp]
     L.surgeon_prune_pack.restype = ci
     L.surgeon_prune_pack.argtypes = [vp, i64, i64, f32, ci, vp, vp, vp, vp, sz, vp]
+    L.surgeon_set_select_margin.restype = ci
+    L.surgeon_set_select_margin.argtypes = [f32]
     L.surgeon_prune_pack_batched.restype = ci
     L.surgeon_prune_pack_batched.argtypes = [ci, vp, vp, vp, vp, ci, vp, vp, vp]
     L.surgeon_dw_ws_bytes.restype = ci
@@ -164,6 +166,11 @@ def surgeon_prune_pack(A, group_len, r, vals, mask, idx=None, ws=None):
     ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
     _check(load_library().surgeon_prune_pack(_ptr(A), A.numel(), int(group_len), float(r), _dt(A), _ptr(vals),
                                              _ptr(mask), _ptr(idx), _ptr(ws), ws_bytes, _stream(A.device)))
+
+
+def surgeon_set_select_margin(deviations: float):
+    """Bracket width (standard deviations of the sample rank) of the two-read selection of long groups."""
+    _check(load_library().surgeon_set_select_margin(float(deviations)))
 
 
 def surgeon_prune_pack_batched(As, group_lens, ratios, vals, masks):

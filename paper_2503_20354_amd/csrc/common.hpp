@@ -75,7 +75,7 @@ size_t prune_pack_ws_bytes(const GroupPlan& p);
 int global_hist_replicas(const GroupPlan& p);
 
 // selection paths of prune_pack
-enum PrunePath { PATH_WAVE_REG = 0, PATH_WAVE_MEM = 1, PATH_GLOBAL = 2 };
+enum PrunePath { PATH_WAVE_REG = 0, PATH_WAVE_MEM = 1, PATH_GLOBAL = 2, PATH_TWO_READ = 3 };
 PrunePath choose_prune_path(const GroupPlan& p);
 
 // bf16 linear weight gradient: un-pack to a dense transient copy, then a dense bf16-MFMA contraction (dw_bf16.hip)
@@ -125,5 +125,7 @@ constexpr int kGlobalHistChunk = 16384;  // elements per block in the histogram 
 constexpr int kGlobalWaveChunk = 4096;   // elements per wavefront in the count / pack passes of the global path
 constexpr int kGlobalDigitBits = 11;     // key bits resolved per histogram pass
 constexpr int kGlobalHistBins = 1 << kGlobalDigitBits;
+constexpr int kTwoReadMinGroup = 32768;   // shortest group that takes the sampled two-read selection
+constexpr int kTwoReadSlotKeys = 1024;    // candidate keys kept per 4096-element chunk on that path
 
 }  // namespace surgeon

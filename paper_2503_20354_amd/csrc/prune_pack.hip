@@ -76,7 +76,9 @@ __device__ __forceinline__ uint64_t low_bits64(int q) { return q >= 64 ? ~0ull :
 // result sits in its own SGPR pair and is consumed three instructions later (gfx940+ needs two wait states
 // between a vector write of an SGPR and a vector read of it, which the compiler cannot add inside inline asm).
 // Short groups (at most 16 slots) count with one ballot and a scalar popcount per slot instead: the per-lane counters
-// end in a wave-wide sum (a DPP scan and four readlanes) whose cost no longer disappears behind a few slots.
+// end in a wave-wide sum (a DPP scan and four readlanes) whose cost no longer disappears behind a few slots.  For long
+// groups the scalar route is no faster (measured: 4.5 against 5.0 TB/s on 4096-element groups): the scalar unit is
+// shared by the four SIMDs of a compute unit and each pop-count waits for its compare.
 template <int E>
 __device__ __forceinline__ int count_ge(const uint32_t (&kr)[E], uint32_t thr2) {
   if constexpr (E % 4 == 0 && E > 16) {
@@ -164,6 +166,27 @@ struct EmitSlots {
       store_or_drop(r_vals, Key<BitsT>::unrot(kr[J]), keep ? pos * (uint32_t)sizeof(BitsT) : 0xffffffffu);
       if constexpr (WITH_IDX) store_or_drop(r_idx, (uint32_t)(J * 64 + lane), keep ? pos * 4u : 0xffffffffu);
       EmitSlots<J + 1, E, BitsT, WITH_IDX>::run(kr, lane, w_lo, w_hi, base, r_vals, r_idx);
+    }
+  }
+};
+
+// Select and emit in one walk, for a threshold with exactly k keys at or above it: slot J's keep word comes from one
+// compare, feeds the prefix ranks and the store directly, and lands in lane J of (w_lo, w_hi); `base` (kept elements of
+// the earlier slots) is a scalar running count.  The two wait states that a vector read of a vector-written SGPR needs
+// are spent inside the asm statement, wherever the compiler schedules it.
+template <int J, int E, typename BitsT, bool WITH_IDX>
+struct SelectEmitSlots {
+  __device__ static __forceinline__ void run(const uint32_t (&kr)[E], int lane, uint32_t thr2, uint32_t base, uint32_t& w_lo,
+                                             uint32_t& w_hi, __amdgpu_buffer_rsrc_t r_vals, __amdgpu_buffer_rsrc_t r_idx) {
+    if constexpr (J < E) {
+      const bool keep = kr[J] >= thr2;
+      const uint64_t b = ballot64(keep);
+      const uint32_t pos = lane_rank(b, base);
+      store_or_drop(r_vals, Key<BitsT>::unrot(kr[J]), keep ? pos * (uint32_t)sizeof(BitsT) : 0xffffffffu);
+      if constexpr (WITH_IDX) store_or_drop(r_idx, (uint32_t)(J * 64 + lane), keep ? pos * 4u : 0xffffffffu);
+      asm volatile("s_nop 1\n\tv_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+                   : "+v"(w_lo), "+v"(w_hi) : "s"((uint32_t)b), "s"((uint32_t)(b >> 32)), "n"(J));
+      SelectEmitSlots<J + 1, E, BitsT, WITH_IDX>::run(kr, lane, thr2, base + (uint32_t)__popcll(b), w_lo, w_hi, r_vals, r_idx);
     }
   }
 };
@@ -276,7 +299,16 @@ __device__ __forceinline__ void select_pack_group(const BitsT* __restrict__ A, B
       }
     }
     if (found) {
-      CollectWords<0, E, false>::run(kr, thr2, w_lo, w_hi);
+      // exactly k keys are >= thr2: no tie to resolve, so each slot's keep word goes from its compare straight into the
+      // pack (prefix ranks inside the slot, a scalar running count for the slot's base) and into lane j of the mask words
+      const __amdgpu_buffer_rsrc_t r_vals = __builtin_amdgcn_make_buffer_rsrc(
+          vals + grp * (int64_t)k_full, 0, k * (int)sizeof(BitsT), kBufferRsrcWord3);
+      const __amdgpu_buffer_rsrc_t r_idx = __builtin_amdgcn_make_buffer_rsrc(
+          WITH_IDX ? idx + grp * (int64_t)k_full : (uint32_t*)nullptr, 0, WITH_IDX ? k * 4 : 0, kBufferRsrcWord3);
+      SelectEmitSlots<0, E, BitsT, WITH_IDX>::run(kr, lane, thr2, 0u, w_lo, w_hi, r_vals, r_idx);
+      const int n_words = (len + 63) >> 6;
+      if (lane < n_words) mask[(gstart >> 6) + lane] = ((uint64_t)w_hi << 32) | w_lo;
+      return;
     } else {
       // hi == lo + 1: more than k keys are >= lo, fewer than k are > lo.  Keep everything above the threshold key
       // and the first `need` elements equal to it in index order.
@@ -611,6 +643,383 @@ __global__ __launch_bounds__(256) void gsel_count_kernel(const BitsT* __restrict
   if (lane == 0) ccount[id] = make_uint2(gt, eq);
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// path 4: long groups in two reads of the activation (groups of at least kTwoReadMinGroup elements)
+// ---------------------------------------------------------------------------------------------------------
+// The radix select of path 3 reads the activation once per digit pass, then once to count and once to pack.  Here a
+// sample brackets the threshold first: one wavefront per group draws 4096 elements at hashed positions and takes two
+// of the sample's order statistics, `margin` standard deviations of the sample rank to either side of rank k * 4096 /
+// len, as the bracket lo_key <= threshold <= hi_key.  One pass over the activation then counts, per 4096-element chunk,
+// the elements above the bracket, at its two ends, and strictly inside it, and copies the keys strictly inside (the
+// candidates, a few per cent of the group) to the chunk's slot of a side buffer.  The exact threshold is then selected
+// among the candidates alone (the digit passes of path 3 over the side buffer, on key - lo_key - 1, whose range the
+// bracket makes narrow), the per-chunk counts follow from the chunk's record and slot, and the pack pass of path 3 is
+// the second read.  The bracket's ends are counted, not copied: a plateau of equal keys (the zeros behind a ReLU, a
+// clipped maximum) sits at an end, where it costs nothing, because both order statistics of the sample fall on it.
+// Whether the bracket holds the threshold is known only on the device, after the first pass.  If it does not (a
+// sample that far off is a once-in-millions event at the default margin of five deviations), or a chunk has more
+// candidates than its slot, the same kernels select over the activation itself: the result is the same, three more
+// reads are spent.  Nothing is decided by floating point except which keys are copied.
+constexpr int kTwoReadSample = 64;       // sample slots per lane of the bracketing wavefront (4096 elements)
+constexpr int kTwoReadSlot = kTwoReadSlotKeys;  // candidate keys a chunk's slot holds
+
+
+struct Sel2 {  // per group
+  uint32_t lo_key, hi_key;  // bracket on the magnitude key; candidates are lo_key < key < hi_key
+  uint32_t mode;            // after the decision: 0 = threshold known, 1 = select among the candidates, 2 = over A
+  uint32_t base;            // digits are taken from key - base
+  uint32_t bits;            // significant bits of the largest key - base
+  uint32_t pad[3];
+};
+struct ChunkRec {
+  uint32_t above, top, bottom, cand;  // keys > hi_key, == hi_key, == lo_key (when lo_key != hi_key), strictly inside
+};
+static_assert(sizeof(Sel2) == 32 && sizeof(ChunkRec) == 16, "the workspace query sizes these");
+
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+  x ^= x >> 16; x *= 0x85ebca6bu; x ^= x >> 13; x *= 0xc2b2ae35u; x ^= x >> 16;
+  return x;
+}
+
+// The rank-th largest magnitude key of the E * 64 rot keys a wavefront holds (1 <= rank <= E * 64): the largest t with
+// count(key >= t) >= rank, or any t with count(key >= t) == rank.  Same bracketing search on counts as the in-register selection.
+template <int E>
+__device__ uint32_t kth_largest_key(const uint32_t (&kr)[E], int rank) {
+  uint32_t m = 0;
+#pragma unroll
+  for (int j = 0; j < E; ++j) m = max(m, kr[j]);
+  m = wave_max_u32(m);
+  uint32_t lo = 0, hi = (m >> 1) + 1;  // count(key >= lo) >= rank > count(key >= hi)
+  float f_lo = (float)(E * 64 - rank), f_hi = (float)(-rank);
+  int last_side = 0;
+  while (hi - lo > 1) {
+    const uint32_t span = hi - lo;
+    uint32_t d = (uint32_t)(f_lo * __builtin_amdgcn_rcpf(f_lo - f_hi) * (float)span);
+    d = min(max(d, 1u), span - 1u);
+    const uint32_t mid = lo + d;
+    const int c = count_ge<E>(kr, mid << 1);
+    if (c == rank) return mid;  // not a key of the sample, but as good a bracket end as one
+    if (c > rank) {
+      lo = mid;
+      f_lo = (float)(c - rank);
+      if (last_side > 0) f_hi *= 0.5f;
+      last_side = 1;
+    } else {
+      hi = mid;
+      f_hi = (float)(c - rank);
+      if (last_side < 0) f_lo *= 0.5f;
+      last_side = -1;
+    }
+  }
+  return lo;
+}
+
+template <typename BitsT>
+__global__ __launch_bounds__(64) void sel2_bracket_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g, int64_t n_groups,
+                                                          uint32_t k_full, uint32_t k_last, float margin,
+                                                          Sel2* __restrict__ sel) {
+  constexpr int S = kTwoReadSample * 64;
+  const int lane = threadIdx.x;
+  const int64_t grp = blockIdx.x;
+  const int64_t gstart = grp * g;
+  const uint32_t len = (uint32_t)(min(gstart + g, n) - gstart);
+  const uint32_t k = grp == n_groups - 1 ? k_last : k_full;
+  uint32_t kr[kTwoReadSample];
+#pragma unroll
+  for (int j = 0; j < kTwoReadSample; ++j) {
+    const uint32_t h = mix32((uint32_t)(j * 64 + lane) * 0x9e3779b9u + 0x7f4a7c15u);
+    const uint32_t pos = (uint32_t)(((uint64_t)h * (uint64_t)len) >> 32);
+    kr[j] = Key<BitsT>::rot(A[gstart + pos]);
+  }
+  const float f = (float)k / (float)len;
+  const float ks = f * (float)S;
+  const float m = margin * sqrtf((float)S * f * (1.0f - f)) + 2.0f;
+  const int r_hi = (int)floorf(ks - m), r_lo = (int)ceilf(ks + m);
+  // a rank outside the sample: that end of the bracket is open (0x80000000 is above every key; below, key 0 is the end)
+  uint32_t hi_key = r_hi < 1 ? 0x80000000u : kth_largest_key<kTwoReadSample>(kr, min(r_hi, S));
+  const uint32_t lo_key = r_lo > S ? 0u : kth_largest_key<kTwoReadSample>(kr, max(r_lo, 1));
+  hi_key = max(hi_key, lo_key);  // a negative margin crosses the ranks: a one-key bracket, decided like any other
+  if (lane == 0) {
+    Sel2 o;
+    o.lo_key = lo_key; o.hi_key = hi_key; o.mode = 0; o.base = 0; o.bits = 0; o.pad[0] = o.pad[1] = o.pad[2] = 0;
+    sel[grp] = o;
+  }
+}
+
+// first read: per wave chunk the record of counts and the candidate keys
+template <typename BitsT>
+__global__ __launch_bounds__(256) void sel2_collect_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
+                                                           int64_t chunks_per_group, int64_t n_chunks,
+                                                           const Sel2* __restrict__ sel, ChunkRec* __restrict__ rec,
+                                                           uint32_t* __restrict__ cand) {
+  const int lane = threadIdx.x & 63;
+  const int64_t id = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (id >= n_chunks) return;
+  const int64_t grp = id / chunks_per_group, chunk = id % chunks_per_group;
+  const int64_t gstart = grp * g;
+  const int64_t gend = min(gstart + g, n);
+  const int64_t e0 = gstart + chunk * kGlobalWaveChunk;
+  const uint32_t lo = sel[grp].lo_key, hi = sel[grp].hi_key;
+  const uint32_t width = hi - lo;  // candidates: 0 < key - lo < width
+  constexpr int kRows = kGlobalWaveChunk / 64;
+  uint32_t key[kRows];
+  // rows past the end of the group read its last element and are masked out of every count below
+#pragma unroll
+  for (int q = 0; q < kRows; ++q) {
+    const int64_t e = e0 + q * 64 + lane;
+    key[q] = (uint32_t)A[e < gend ? e : gend - 1] & Key<BitsT>::kMask;
+  }
+  const int64_t left = gend - e0;  // > 0
+  uint32_t above = 0, top = 0, bottom = 0, n_cand = 0;
+#pragma unroll
+  for (int q = 0; q < kRows; ++q) {
+    const bool valid = (int64_t)(q * 64 + lane) < left;
+    above += (valid && key[q] > hi) ? 1u : 0u;
+    top += (valid && key[q] == hi) ? 1u : 0u;
+    bottom += (valid && key[q] == lo && width != 0u) ? 1u : 0u;
+    n_cand += (valid && key[q] - lo - 1u < width - 1u && width != 0u) ? 1u : 0u;
+  }
+  above = wave_sum_u32(above);
+  top = wave_sum_u32(top);
+  bottom = wave_sum_u32(bottom);
+  n_cand = wave_sum_u32(n_cand);
+  if (lane == 0) {
+    ChunkRec o;
+    o.above = above; o.top = top; o.bottom = bottom; o.cand = n_cand;  // cand > kTwoReadSlot: the slot was not written
+    rec[id] = o;
+  }
+  if (n_cand == 0 || n_cand > (uint32_t)kTwoReadSlot) return;
+  uint32_t* __restrict__ dst = cand + id * kTwoReadSlot;
+  uint32_t run = 0;
+#pragma unroll
+  for (int q = 0; q < kRows; ++q) {
+    const bool valid = (int64_t)(q * 64 + lane) < left;
+    const bool c = valid && key[q] - lo - 1u < width - 1u && width != 0u;
+    const uint64_t b = ballot64(c);
+    if (c) dst[lane_rank(b, run)] = key[q];
+    run += (uint32_t)__popcll(b);
+  }
+}
+
+// Per group: where the threshold lies relative to the bracket, from the sums of the chunk records.
+__global__ __launch_bounds__(256) void sel2_decide_kernel(Sel2* __restrict__ sel, GroupState* __restrict__ st,
+                                                          const ChunkRec* __restrict__ rec, int64_t chunks_per_group,
+                                                          int64_t n_groups, uint32_t k_full, uint32_t k_last) {
+  __shared__ uint32_t lds17[17];
+  const int64_t grp = blockIdx.x;
+  const ChunkRec* __restrict__ r = rec + grp * chunks_per_group;
+  uint32_t above = 0, top = 0, bottom = 0, cnd = 0, over = 0;
+  for (int64_t c = threadIdx.x; c < chunks_per_group; c += 256) {
+    const ChunkRec x = r[c];
+    above += x.above; top += x.top; bottom += x.bottom; cnd += x.cand;
+    over += x.cand > (uint32_t)kTwoReadSlot ? 1u : 0u;
+  }
+  uint32_t t_above, t_top, t_bottom, t_cand, t_over;
+  block_excl_scan(above, lds17, &t_above);
+  block_excl_scan(top, lds17, &t_top);
+  block_excl_scan(bottom, lds17, &t_bottom);
+  block_excl_scan(cnd, lds17, &t_cand);
+  block_excl_scan(over, lds17, &t_over);
+  if (threadIdx.x != 0) return;
+  const uint32_t k = grp == n_groups - 1 ? k_last : k_full;
+  Sel2 s = sel[grp];
+  GroupState o;
+  o.prefix = 0; o.k_rem = k; o.t_key = 0; o.need = 0;
+  s.mode = 2; s.base = 0; s.bits = Key<uint32_t>::kBits;  // unless the bracket holds the threshold: select over A
+  if (t_over == 0 && k > t_above) {
+    uint32_t kk = k - t_above;
+    if (kk <= t_top) {
+      s.mode = 0; o.t_key = s.hi_key; o.need = kk;
+    } else if (kk - t_top <= t_cand) {
+      kk -= t_top;
+      const uint32_t vmax = s.hi_key - s.lo_key - 2u;  // candidates exist, so hi_key - lo_key >= 2
+      s.base = s.lo_key + 1u;
+      s.bits = vmax == 0u ? 0u : 32u - (uint32_t)__clz((int)vmax);
+      o.k_rem = kk;
+      if (s.bits == 0u) {  // one candidate key
+        s.mode = 0; o.t_key = s.base; o.need = kk;
+      } else {
+        s.mode = 1;
+      }
+    } else if (kk - t_top - t_cand <= t_bottom) {
+      s.mode = 0; o.t_key = s.lo_key; o.need = kk - t_top - t_cand;
+    }
+  }
+  sel[grp] = s;
+  st[grp] = o;
+}
+
+// digit pass `pass` of a group with `bits` significant bits: the bits [shift, shift + nbits) of key - base
+__device__ __forceinline__ bool sel2_pass_geometry(uint32_t bits, int pass, int* shift, int* nbits) {
+  const int done = kGlobalDigitBits * pass;
+  if ((int)bits <= done) return false;
+  *shift = max((int)bits - done - kGlobalDigitBits, 0);
+  *nbits = (int)bits - done - *shift;
+  return true;
+}
+
+template <typename BitsT>
+__global__ __launch_bounds__(256) void sel2_hist_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
+                                                        int64_t blocks_per_group, int64_t chunks_per_group, int pass,
+                                                        const Sel2* __restrict__ sel, const GroupState* __restrict__ st,
+                                                        const ChunkRec* __restrict__ rec, const uint32_t* __restrict__ cand,
+                                                        uint32_t* __restrict__ hist, int replicas) {
+  __shared__ uint32_t lh[kGlobalHistBins];
+  const int64_t grp = blockIdx.x / blocks_per_group;
+  const int64_t blk = blockIdx.x % blocks_per_group;
+  const Sel2 s = sel[grp];
+  int shift, nbits;
+  if (s.mode == 0 || !sel2_pass_geometry(s.bits, pass, &shift, &nbits)) return;
+  for (int b = threadIdx.x; b < kGlobalHistBins; b += 256) lh[b] = 0;
+  __syncthreads();
+  const int hshift = shift + nbits;  // <= 31
+  const uint32_t want = st[grp].prefix >> hshift;
+  const uint32_t dmask = (1u << nbits) - 1u;
+  const int lane = threadIdx.x & 63;
+  uint32_t zeros = 0;  // elements of this wavefront with digit 0 (wave-uniform): one ballot instead of same-address atomics
+  if (s.mode == 2) {
+    const int64_t gstart = grp * g;
+    const int64_t gend = min(gstart + g, n);
+    const int64_t e0 = gstart + blk * kGlobalHistChunk;
+    constexpr int kBatch = 8;
+    for (int t0 = 0; t0 < kGlobalHistChunk; t0 += 256 * kBatch) {
+      uint32_t key[kBatch];
+      bool ok[kBatch];
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        const int64_t e = e0 + t0 + q * 256 + threadIdx.x;
+        ok[q] = e < gend;
+        key[q] = (uint32_t)A[ok[q] ? e : gend - 1] & Key<BitsT>::kMask;
+      }
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        const bool match = ok[q] && (key[q] >> hshift) == want;
+        const uint32_t digit = (key[q] >> shift) & dmask;
+        zeros += (uint32_t)__popcll(ballot64(match && digit == 0u));
+        if (match && digit != 0u) atomicAdd(&lh[digit], 1u);
+      }
+    }
+  } else {
+    constexpr int kChunksPerBlock = kGlobalHistChunk / kGlobalWaveChunk;
+    for (int cc = 0; cc < kChunksPerBlock; ++cc) {
+      const int64_t chunk = blk * kChunksPerBlock + cc;
+      if (chunk >= chunks_per_group) break;
+      const int64_t id = grp * chunks_per_group + chunk;
+      const uint32_t cnt = rec[id].cand;  // <= kTwoReadSlot in this mode
+      const uint32_t* __restrict__ src = cand + id * kTwoReadSlot;
+      for (uint32_t i0 = 0; i0 < cnt; i0 += 256) {  // uniform trip count: the ballot below needs whole wavefronts
+        const uint32_t i = i0 + threadIdx.x;
+        const bool ok = i < cnt;
+        const uint32_t v = (ok ? src[i] : s.base) - s.base;
+        const bool match = ok && (v >> hshift) == want;
+        const uint32_t digit = (v >> shift) & dmask;
+        zeros += (uint32_t)__popcll(ballot64(match && digit == 0u));
+        if (match && digit != 0u) atomicAdd(&lh[digit], 1u);
+      }
+    }
+  }
+  if (lane == 0 && zeros) atomicAdd(&lh[0], zeros);
+  __syncthreads();
+  uint32_t* __restrict__ h = hist + (grp * replicas + blk % replicas) * (int64_t)kGlobalHistBins;
+  for (int b = threadIdx.x; b < kGlobalHistBins; b += 256) {
+    const uint32_t c = lh[b];
+    if (c) atomicAdd(&h[b], c);
+  }
+}
+
+__global__ __launch_bounds__(256) void sel2_resolve_kernel(const Sel2* __restrict__ sel, GroupState* __restrict__ st,
+                                                           uint32_t* __restrict__ hist, int replicas, int pass) {
+  constexpr int kPer = kGlobalHistBins / 256;
+  __shared__ uint32_t lds17[17];
+  const int64_t grp = blockIdx.x;
+  const Sel2 sl = sel[grp];
+  int shift, nbits;
+  if (sl.mode == 0 || !sel2_pass_geometry(sl.bits, pass, &shift, &nbits)) return;  // its histogram was not touched
+  const int tid = threadIdx.x;
+  uint32_t* __restrict__ h = hist + grp * replicas * (int64_t)kGlobalHistBins;
+  uint32_t c[kPer];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) c[q] = 0;
+  for (int rep = 0; rep < replicas; ++rep) {
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+      c[q] += h[rep * kGlobalHistBins + tid * kPer + q];
+      h[rep * kGlobalHistBins + tid * kPer + q] = 0;
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) sum += c[q];
+  const GroupState s = st[grp];
+  uint32_t total;
+  const uint32_t below = block_excl_scan(sum, lds17, &total);
+  uint32_t above = total - below - sum;
+#pragma unroll
+  for (int q = kPer - 1; q >= 0; --q) {
+    if (above < s.k_rem && s.k_rem <= above + c[q]) {  // exactly one bin of one thread satisfies this
+      GroupState o = s;
+      o.prefix = s.prefix | ((uint32_t)(tid * kPer + q) << shift);
+      o.k_rem = s.k_rem - above;
+      if (shift == 0) {
+        o.t_key = sl.base + o.prefix;
+        o.need = o.k_rem;
+      }
+      st[grp] = o;
+    }
+    above += c[q];
+  }
+}
+
+// per wave chunk: elements above the threshold key and elements equal to it, from the chunk's record and slot
+template <typename BitsT>
+__global__ __launch_bounds__(256) void sel2_count_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
+                                                         int64_t chunks_per_group, int64_t n_chunks,
+                                                         const Sel2* __restrict__ sel, const GroupState* __restrict__ st,
+                                                         const ChunkRec* __restrict__ rec, const uint32_t* __restrict__ cand,
+                                                         uint2* __restrict__ ccount) {
+  const int lane = threadIdx.x & 63;
+  const int64_t id = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (id >= n_chunks) return;
+  const int64_t grp = id / chunks_per_group, chunk = id % chunks_per_group;
+  const Sel2 s = sel[grp];
+  const uint32_t t_key = st[grp].t_key;
+  uint32_t gt = 0, eq = 0;  // per-lane counts
+  if (s.mode == 2) {
+    const int64_t gstart = grp * g;
+    const int64_t gend = min(gstart + g, n);
+    const int64_t e0 = gstart + chunk * kGlobalWaveChunk;
+    constexpr int kBatch = 8;
+    for (int r0 = 0; r0 < kGlobalWaveChunk / 64; r0 += kBatch) {
+      uint32_t key[kBatch];
+      bool valid[kBatch];
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        const int64_t e = e0 + (r0 + q) * 64 + lane;
+        valid[q] = e < gend;
+        key[q] = (uint32_t)A[valid[q] ? e : gend - 1] & Key<BitsT>::kMask;
+      }
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        gt += (valid[q] && key[q] > t_key) ? 1u : 0u;
+        eq += (valid[q] && key[q] == t_key) ? 1u : 0u;
+      }
+    }
+    gt = wave_sum_u32(gt);
+    eq = wave_sum_u32(eq);
+  } else {
+    const ChunkRec x = rec[id];
+    const uint32_t* __restrict__ src = cand + id * kTwoReadSlot;
+    for (uint32_t i = lane; i < x.cand; i += 64) {
+      const uint32_t key = src[i];
+      gt += key > t_key ? 1u : 0u;
+      eq += key == t_key ? 1u : 0u;
+    }
+    gt = wave_sum_u32(gt) + x.above + (s.hi_key > t_key ? x.top : 0u);
+    eq = wave_sum_u32(eq) + (s.hi_key == t_key ? x.top : 0u) + (s.lo_key == t_key ? x.bottom : 0u);
+  }
+  if (lane == 0) ccount[id] = make_uint2(gt, eq);
+}
+
 // Per group: exclusive prefix over its chunks of (equal elements seen, values written).  One workgroup of 1024
 // threads; a thread holds kScanPer consecutive chunks in registers, so a tile of 1024 * kScanPer chunks costs one
 // round of loads, two block-wide scans (ties first: how many tied elements a chunk may keep depends on the ties
@@ -848,6 +1257,73 @@ static int run_global(const GroupPlan& p, const void* A, void* vals, uint64_t* m
   return SURGEON_OK;
 }
 
+static float g_two_read_margin = 5.0f;
+
+template <typename BitsT>
+static int run_two_read(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx, void* ws,
+                        hipStream_t st) {
+  const int64_t cpg = ceil_div(p.g, kGlobalWaveChunk);
+  const int64_t n_chunks = p.n_groups * cpg;
+  const int64_t bpg = ceil_div(p.g, kGlobalHistChunk);
+  if (p.n_groups * bpg > 0x7fffffffLL || n_chunks > 0x7fffffffLL)
+    return fail(SURGEON_EUNSUPPORTED, "prune_pack: too many chunks");
+  // the workspace of path 3 first, in its order, then this path's own
+  char* w = (char*)ws;
+  GroupState* state = (GroupState*)w;
+  w += align_up((size_t)p.n_groups * 16, 256);
+  uint32_t* hist = (uint32_t*)w;
+  const int replicas = global_hist_replicas(p);
+  w += align_up((size_t)p.n_groups * replicas * kGlobalHistBins * 4, 256);
+  uint2* ccount = (uint2*)w;
+  w += align_up((size_t)n_chunks * 8, 256);
+  uint2* cbase = (uint2*)w;
+  w += align_up((size_t)n_chunks * 8, 256);
+  Sel2* sel = (Sel2*)w;
+  w += align_up((size_t)p.n_groups * sizeof(Sel2), 256);
+  ChunkRec* rec = (ChunkRec*)w;
+  w += align_up((size_t)n_chunks * sizeof(ChunkRec), 256);
+  uint32_t* cand = (uint32_t*)w;
+
+  const int init_blocks = (int)std::min<int64_t>(ceil_div(p.n_groups * replicas * kGlobalHistBins, 256), 4096);
+  SURGEON_LAUNCH(gsel_init_kernel, dim3(init_blocks), dim3(256), 0, st, state, hist, p.n_groups,
+                     (uint32_t)p.k_full, (uint32_t)p.k_last, replicas);
+  SURGEON_LAUNCH_CHECK();
+  SURGEON_LAUNCH((sel2_bracket_kernel<BitsT>), dim3((unsigned)p.n_groups), dim3(64), 0, st, (const BitsT*)A, p.n, p.g,
+                     p.n_groups, (uint32_t)p.k_full, (uint32_t)p.k_last, g_two_read_margin, sel);
+  SURGEON_LAUNCH_CHECK();
+  const dim3 wgrid((unsigned)ceil_div(n_chunks, 4)), block(256);
+  SURGEON_LAUNCH((sel2_collect_kernel<BitsT>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
+                     (const Sel2*)sel, rec, cand);
+  SURGEON_LAUNCH_CHECK();
+  SURGEON_LAUNCH(sel2_decide_kernel, dim3((unsigned)p.n_groups), dim3(256), 0, st, sel, state, (const ChunkRec*)rec, cpg,
+                     p.n_groups, (uint32_t)p.k_full, (uint32_t)p.k_last);
+  SURGEON_LAUNCH_CHECK();
+  const int passes = (Key<uint32_t>::kBits + kGlobalDigitBits - 1) / kGlobalDigitBits;  // a group that needs fewer skips the rest
+  for (int pass = 0; pass < passes; ++pass) {
+    SURGEON_LAUNCH((sel2_hist_kernel<BitsT>), dim3((unsigned)(p.n_groups * bpg)), dim3(256), 0, st, (const BitsT*)A, p.n,
+                       p.g, bpg, cpg, pass, (const Sel2*)sel, (const GroupState*)state, (const ChunkRec*)rec,
+                       (const uint32_t*)cand, hist, replicas);
+    SURGEON_LAUNCH_CHECK();
+    SURGEON_LAUNCH(sel2_resolve_kernel, dim3((unsigned)p.n_groups), dim3(256), 0, st, (const Sel2*)sel, state, hist,
+                       replicas, pass);
+    SURGEON_LAUNCH_CHECK();
+  }
+  SURGEON_LAUNCH((sel2_count_kernel<BitsT>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
+                     (const Sel2*)sel, (const GroupState*)state, (const ChunkRec*)rec, (const uint32_t*)cand, ccount);
+  SURGEON_LAUNCH_CHECK();
+  SURGEON_LAUNCH(gsel_scan_kernel, dim3((unsigned)p.n_groups), dim3(1024), 0, st, (const GroupState*)state,
+                     (const uint2*)ccount, cbase, cpg);
+  SURGEON_LAUNCH_CHECK();
+  if (idx)
+    SURGEON_LAUNCH((gsel_pack_kernel<BitsT, true>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
+                       (const GroupState*)state, (const uint2*)cbase, p.k_full, (BitsT*)vals, mask, idx);
+  else
+    SURGEON_LAUNCH((gsel_pack_kernel<BitsT, false>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
+                       (const GroupState*)state, (const uint2*)cbase, p.k_full, (BitsT*)vals, mask, idx);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
 template <typename BitsT>
 static int run_prune_pack(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx, void* ws,
                           hipStream_t st) {
@@ -867,6 +1343,7 @@ static int run_prune_pack(const GroupPlan& p, const void* A, void* vals, uint64_
     default: {
       const int rc = zero_mask(mask, n_words, st);
       if (rc != SURGEON_OK) return rc;
+      if (path == PATH_TWO_READ) return run_two_read<BitsT>(p, A, vals, mask, idx, ws, st);
       return run_global<BitsT>(p, A, vals, mask, idx, ws, st);
     }
   }
@@ -896,6 +1373,12 @@ extern "C" int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, f
   hipStream_t st = (hipStream_t)stream;
   if (dt == SURGEON_F32) return run_prune_pack<uint32_t>(p, A, vals, mask, idx, ws, st);
   return run_prune_pack<uint16_t>(p, A, vals, mask, idx, ws, st);
+}
+
+extern "C" int surgeon_set_select_margin(float deviations) {
+  if (!(deviations >= -100.0f && deviations <= 100.0f)) return fail(SURGEON_EINVAL, "select margin %g outside [-100, 100]", (double)deviations);
+  g_two_read_margin = deviations;
+  return SURGEON_OK;
 }
 
 extern "C" int surgeon_prune_pack_batched(int l, const void* const* A, const int64_t* n, const int64_t* group_len,

@@ -40,6 +40,7 @@ bool make_group_plan(int64_t n, int64_t group_len, float r, GroupPlan* p) {
 }
 
 PrunePath choose_prune_path(const GroupPlan& p) {
+  if (p.g >= kTwoReadMinGroup) return PATH_TWO_READ;
   if (p.g > kWaveRegMaxGroup) return PATH_GLOBAL;
   if (p.g % 64 == 0) return PATH_WAVE_REG;
   return PATH_WAVE_MEM;
@@ -51,7 +52,8 @@ int global_hist_replicas(const GroupPlan& p) {
 }
 
 size_t prune_pack_ws_bytes(const GroupPlan& p) {
-  if (p.n == 0 || choose_prune_path(p) != PATH_GLOBAL) return 0;
+  const PrunePath path = choose_prune_path(p);
+  if (p.n == 0 || (path != PATH_GLOBAL && path != PATH_TWO_READ)) return 0;
   const int64_t chunks_per_group = ceil_div(p.g, kGlobalWaveChunk);
   const int64_t n_chunks = p.n_groups * chunks_per_group;
   size_t bytes = 0;
@@ -59,6 +61,11 @@ size_t prune_pack_ws_bytes(const GroupPlan& p) {
   bytes += align_up((size_t)p.n_groups * global_hist_replicas(p) * kGlobalHistBins * 4, 256);  // per-group digit histograms
   bytes += align_up((size_t)n_chunks * 8, 256);          // per-chunk (greater, equal) counts
   bytes += align_up((size_t)n_chunks * 8, 256);          // per-chunk (equal-before, out-before) bases
+  if (path == PATH_TWO_READ) {
+    bytes += align_up((size_t)p.n_groups * 32, 256);     // per-group bracket and decision
+    bytes += align_up((size_t)n_chunks * 16, 256);       // per-chunk counts relative to the bracket
+    bytes += (size_t)n_chunks * kTwoReadSlotKeys * 4;    // per-chunk candidate keys
+  }
   return bytes;
 }
 

@@ -107,6 +107,34 @@ def test_prune_pack_matches_oracle(dtype, n, g):
     check_pack(draw((n,), "const", dtype, seed), g, 0.7, tag="const")
 
 
+TWO_READ_CASES = [(100000, 100000), (300000, 50000), (1 << 20, 1 << 20), (70001, 70001), (32768 * 3 + 10, 32768),
+                  (40000 * 7 + 33000, 40000)]
+
+
+@pytest.mark.parametrize("margin", [5.0, 0.3, -1.0])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prune_pack_long_groups_two_reads(dtype, margin):
+    """Groups of 32768 elements or more: the sampled bracket (default margin), a narrow bracket that often misses the
+    threshold, and a negative margin under which every group takes the full-width route; all three bit-exact."""
+    surgeon.surgeon_set_select_margin(margin)
+    try:
+        for n, g in TWO_READ_CASES:
+            seed = n * 3 + g
+            for dist in ("normal", "relu", "few", "image01"):
+                for r in (0.0, 0.3, 0.5, 0.9, 0.999, 1.0):
+                    check_pack(draw((n,), dist, dtype, seed), g, r, want_idx=(r == 0.5), tag="%s m=%g" % (dist, margin))
+            check_pack(draw((n,), "const", dtype, seed), g, 0.7, tag="const")
+        # plateaus at the top and inside the populated range (a clipped activation), negative zeros, non-finite values
+        a = torch.randn(200000).clamp_(-1.0, 1.0)
+        a[::7] = -0.0
+        a[5], a[70000], a[150001] = float("inf"), float("nan"), float("-inf")
+        for r in (0.2, 0.5, 0.7, 0.9):
+            check_pack(a, 200000, r)
+            check_pack(a.to(torch.bfloat16), 100000, r)
+    finally:
+        surgeon.surgeon_set_select_margin(5.0)
+
+
 def test_prune_pack_signed_zero_and_non_finite():
     a = torch.zeros(4096)
     a[::3] = -0.0
