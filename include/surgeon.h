@@ -133,7 +133,7 @@ int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, float r, int
 
 /*
  * Tuning knob of surgeon_prune_pack for groups of 32768 elements or more (the whole-tensor scope among them).  There
- * the threshold is first bracketed from a 4096-element sample, `deviations` standard deviations of the sample rank to
+ * the threshold is first bracketed from a 2048-element sample, `deviations` standard deviations of the sample rank to
  * either side, so that the activation is read twice (once to count and to copy the few per cent of elements inside the
  * bracket, once to pack) instead of five times.  A bracket that misses the threshold is detected on the device and
  * the call then selects over the whole group: the result is bit-identical for every value of the knob, only the time
@@ -170,7 +170,11 @@ int surgeon_dw_kernel_class(const surgeon_layer_desc* desc, int* kernel_class);
 
 /*
  * Alg. 1 lines 11-12 / Eq. 2 (weight gradient): dW = dY^T . A_pruned, where A_pruned is rebuilt from
- * (vals, mask) inside the kernels (dropped positions are +0) and never written to memory.
+ * (vals, mask) with dropped positions +0.  For fp32 layers and for bf16 convolutions with filters larger than 1x1
+ * the rebuilding happens while a tile is staged into LDS and A_pruned never exists in memory.  For bf16 linear layers
+ * and bf16 1x1 stride-1 convolutions it is first written once, dense and in bf16, into `ws` (n elements; part of the
+ * size surgeon_dw_ws_bytes reports) and a dense contraction reads it from there: on these layers un-packing inside the
+ * tile load was measured slower than the extra 2 bytes per element written and read.
  * vals, mask, dY, dW, ws are device pointers; desc is a host pointer.  dW (fp32) is overwritten.
  * The result does not depend on the group_len / r the packing used.  Deterministic: the same inputs give
  * the same bits on every call.

@@ -18,6 +18,8 @@ namespace surgeon {
 // (dgamma, dbeta) partial sums as float2 part[slice][c]; the finishing kernel adds the slices per channel in index
 // order in fp64 (deterministic).
 
+constexpr int kAffineBatch = 8;
+
 // inner % 64 == 0 (batch norm on maps of 8x8 and larger): one wavefront per (o, c) row, lane = element of a mask word
 template <typename T>
 __global__ __launch_bounds__(256) void affine_rows_kernel(Packed<T> pk, const T* __restrict__ dY, int64_t outer, int C,
@@ -27,17 +29,34 @@ __global__ __launch_bounds__(256) void affine_rows_kernel(Packed<T> pk, const T*
   if (row >= outer * C) return;
   const int64_t e0 = row * inner;
   float g = 0.0f, b = 0.0f;
-  for (int j = 0; j < inner; j += 64) {
-    const int64_t w = (e0 + j) >> 6;
-    const uint64_t word = pk.mask[w];
-    const uint32_t lo = (uint32_t)word, hi = (uint32_t)(word >> 32);
-    const bool kept = (word >> lane) & 1ull;
-    int64_t pos = (int64_t)pk.word_rank[w] + __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
-    pos = pos > pk.k_last ? pk.k_last : pos;
-    const float x = kept ? widen<T>(pk.vals[pos]) : 0.0f;
-    const float dy = widen<T>(dY[e0 + j + lane]);
-    g = __builtin_fmaf(dy, x, g);
-    b += dy;
+  // kAffineBatch words at a time, level by level (mask words and ranks, then positions, then values), so that a
+  // wavefront keeps kAffineBatch independent chains of dependent loads in flight instead of one
+  for (int j0 = 0; j0 < inner; j0 += 64 * kAffineBatch) {
+    uint64_t word[kAffineBatch];
+    uint32_t rank[kAffineBatch];
+    float dy[kAffineBatch];
+#pragma unroll
+    for (int q = 0; q < kAffineBatch; ++q) {
+      const int j = min(j0 + 64 * q, inner - 64);  // past the row's end: its last word again, weighted 0 below
+      const int64_t w = (e0 + j) >> 6;
+      word[q] = pk.mask[w];
+      rank[q] = pk.word_rank[w];
+      dy[q] = j0 + 64 * q < inner ? widen<T>(dY[e0 + j + lane]) : 0.0f;
+    }
+    float x[kAffineBatch];
+#pragma unroll
+    for (int q = 0; q < kAffineBatch; ++q) {
+      const uint32_t lo = (uint32_t)word[q], hi = (uint32_t)(word[q] >> 32);
+      int64_t pos = (int64_t)rank[q] + __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
+      pos = pos > pk.k_last ? pk.k_last : pos;
+      const bool kept = (word[q] >> lane) & 1ull;
+      x[q] = kept ? widen<T>(pk.vals[pos]) : 0.0f;  // vals is read only where a bit is set (it may be empty otherwise)
+    }
+#pragma unroll
+    for (int q = 0; q < kAffineBatch; ++q) {
+      g = __builtin_fmaf(dy[q], x[q], g);
+      b += dy[q];
+    }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) {
@@ -60,17 +79,32 @@ __global__ __launch_bounds__(256) void affine_cols_kernel(Packed<T> pk, const T*
   if (wq >= words) return;
   const int64_t m0 = (int64_t)blockIdx.y * kLnRows, m1 = min(m0 + kLnRows, outer);
   float g = 0.0f, b = 0.0f;
-  for (int64_t m = m0; m < m1; ++m) {
-    const int64_t w = m * words + wq;
-    const uint64_t word = pk.mask[w];
-    const uint32_t lo = (uint32_t)word, hi = (uint32_t)(word >> 32);
-    const bool kept = (word >> lane) & 1ull;
-    int64_t pos = (int64_t)pk.word_rank[w] + __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
-    pos = pos > pk.k_last ? pk.k_last : pos;
-    const float x = kept ? widen<T>(pk.vals[pos]) : 0.0f;
-    const float dy = widen<T>(dY[m * C + wq * 64 + lane]);
-    g = __builtin_fmaf(dy, x, g);
-    b += dy;
+  for (int64_t mb = m0; mb < m1; mb += kAffineBatch) {  // levels of dependent loads batched as in the row kernel
+    uint64_t word[kAffineBatch];
+    uint32_t rank[kAffineBatch];
+    float dy[kAffineBatch];
+#pragma unroll
+    for (int q = 0; q < kAffineBatch; ++q) {
+      const int64_t m = min(mb + q, m1 - 1);
+      const int64_t w = m * words + wq;
+      word[q] = pk.mask[w];
+      rank[q] = pk.word_rank[w];
+      dy[q] = mb + q < m1 ? widen<T>(dY[m * C + wq * 64 + lane]) : 0.0f;
+    }
+    float x[kAffineBatch];
+#pragma unroll
+    for (int q = 0; q < kAffineBatch; ++q) {
+      const uint32_t lo = (uint32_t)word[q], hi = (uint32_t)(word[q] >> 32);
+      int64_t pos = (int64_t)rank[q] + __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u));
+      pos = pos > pk.k_last ? pk.k_last : pos;
+      const bool kept = (word[q] >> lane) & 1ull;
+      x[q] = kept ? widen<T>(pk.vals[pos]) : 0.0f;  // vals is read only where a bit is set (it may be empty otherwise)
+    }
+#pragma unroll
+    for (int q = 0; q < kAffineBatch; ++q) {
+      g = __builtin_fmaf(dy[q], x[q], g);
+      b += dy[q];
+    }
   }
   part[(int64_t)blockIdx.y * C + wq * 64 + lane] = make_float2(g, b);
 }

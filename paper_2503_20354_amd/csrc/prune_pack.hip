@@ -647,8 +647,8 @@ __global__ __launch_bounds__(256) void gsel_count_kernel(const BitsT* __restrict
 // path 4: long groups in two reads of the activation (groups of at least kTwoReadMinGroup elements)
 // ---------------------------------------------------------------------------------------------------------
 // The radix select of path 3 reads the activation once per digit pass, then once to count and once to pack.  Here a
-// sample brackets the threshold first: one wavefront per group draws 4096 elements at hashed positions and takes two
-// of the sample's order statistics, `margin` standard deviations of the sample rank to either side of rank k * 4096 /
+// sample brackets the threshold first: one workgroup per group draws 2048 elements at hashed positions and takes two
+// of the sample's order statistics, `margin` standard deviations of the sample rank to either side of rank k * 2048 /
 // len, as the bracket lo_key <= threshold <= hi_key.  One pass over the activation then counts, per 4096-element chunk,
 // the elements above the bracket, at its two ends, and strictly inside it, and copies the keys strictly inside (the
 // candidates, a few per cent of the group) to the chunk's slot of a side buffer.  The exact threshold is then selected
@@ -660,7 +660,8 @@ __global__ __launch_bounds__(256) void gsel_count_kernel(const BitsT* __restrict
 // sample that far off is a once-in-millions event at the default margin of five deviations), or a chunk has more
 // candidates than its slot, the same kernels select over the activation itself: the result is the same, three more
 // reads are spent.  Nothing is decided by floating point except which keys are copied.
-constexpr int kTwoReadSample = 64;       // sample slots per lane of the bracketing wavefront (4096 elements)
+constexpr int kTwoReadSample = 32;       // sample size / 64: 2048 elements (a larger sample narrows the bracket, but its
+                                         // scattered loads, issued by one compute unit, are what the bracketing kernel waits for)
 constexpr int kTwoReadSlot = kTwoReadSlotKeys;  // candidate keys a chunk's slot holds
 
 
@@ -681,78 +682,167 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
   return x;
 }
 
-// The rank-th largest magnitude key of the E * 64 rot keys a wavefront holds (1 <= rank <= E * 64): the largest t with
-// count(key >= t) >= rank, or any t with count(key >= t) == rank.  Same bracketing search on counts as the in-register selection.
-template <int E>
-__device__ uint32_t kth_largest_key(const uint32_t (&kr)[E], int rank) {
-  uint32_t m = 0;
-#pragma unroll
-  for (int j = 0; j < E; ++j) m = max(m, kr[j]);
-  m = wave_max_u32(m);
-  uint32_t lo = 0, hi = (m >> 1) + 1;  // count(key >= lo) >= rank > count(key >= hi)
-  float f_lo = (float)(E * 64 - rank), f_hi = (float)(-rank);
-  int last_side = 0;
-  while (hi - lo > 1) {
-    const uint32_t span = hi - lo;
-    uint32_t d = (uint32_t)(f_lo * __builtin_amdgcn_rcpf(f_lo - f_hi) * (float)span);
-    d = min(max(d, 1u), span - 1u);
-    const uint32_t mid = lo + d;
-    const int c = count_ge<E>(kr, mid << 1);
-    if (c == rank) return mid;  // not a key of the sample, but as good a bracket end as one
-    if (c > rank) {
-      lo = mid;
-      f_lo = (float)(c - rank);
-      if (last_side > 0) f_hi *= 0.5f;
-      last_side = 1;
-    } else {
-      hi = mid;
-      f_hi = (float)(c - rank);
-      if (last_side < 0) f_lo *= 0.5f;
-      last_side = -1;
-    }
-  }
-  return lo;
-}
-
+// One workgroup of eight wavefronts per group brackets the threshold: wavefronts 0-3 search the upper end, 4-7 the lower
+// end, each holding a quarter of the sample (both halves draw the same sample).  A search keeps
+// count(key >= lo) >= rank > count(key >= hi) over the sample and probes between them (the in-register selection's
+// search: first 16 octaves below the largest key, then key 1, then regula falsi with the Illinois rule); the four
+// wavefronts of a search hold identical copies of its state and exchange their part counts through LDS, one barrier
+// per probe.  After at most kBracketProbes probes the upper end takes hi - 1 and the lower end lo: both err outwards,
+// so a search that has not converged widens the bracket, never invalidates it.  Meanwhile the workgroup clears the
+// group's digit histograms (the workspace comes with arbitrary contents).
+constexpr int kBracketProbes = 48;
 template <typename BitsT>
-__global__ __launch_bounds__(64) void sel2_bracket_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g, int64_t n_groups,
-                                                          uint32_t k_full, uint32_t k_last, float margin,
-                                                          Sel2* __restrict__ sel) {
+__global__ __launch_bounds__(512) void sel2_bracket_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g, int64_t n_groups,
+                                                           uint32_t k_full, uint32_t k_last, float margin,
+                                                           Sel2* __restrict__ sel, uint32_t* __restrict__ hist, int replicas) {
   constexpr int S = kTwoReadSample * 64;
-  const int lane = threadIdx.x;
+  constexpr int E = kTwoReadSample / 4;  // slots per wavefront
+  __shared__ uint32_t part[2][2][4];     // [probe parity][search][wavefront of the search]: part counts
+  __shared__ uint32_t live[2][2];        // [probe parity][search]: the search still probes
+  __shared__ uint32_t wmax[4];
+  __shared__ uint32_t ends[2];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int search = wave >> 2, quarter = wave & 3;
   const int64_t grp = blockIdx.x;
   const int64_t gstart = grp * g;
   const uint32_t len = (uint32_t)(min(gstart + g, n) - gstart);
   const uint32_t k = grp == n_groups - 1 ? k_last : k_full;
-  uint32_t kr[kTwoReadSample];
+  uint32_t kr[E];
 #pragma unroll
-  for (int j = 0; j < kTwoReadSample; ++j) {
-    const uint32_t h = mix32((uint32_t)(j * 64 + lane) * 0x9e3779b9u + 0x7f4a7c15u);
+  for (int j = 0; j < E; ++j) {
+    const uint32_t h = mix32((uint32_t)((quarter * E + j) * 64 + lane) * 0x9e3779b9u + 0x7f4a7c15u);
     const uint32_t pos = (uint32_t)(((uint64_t)h * (uint64_t)len) >> 32);
     kr[j] = Key<BitsT>::rot(A[gstart + pos]);
   }
+  uint4* __restrict__ hz = reinterpret_cast<uint4*>(hist + grp * replicas * (int64_t)kGlobalHistBins);
+  for (int i = threadIdx.x; i < replicas * kGlobalHistBins / 4; i += 512) hz[i] = make_uint4(0u, 0u, 0u, 0u);
+  uint32_t m = 0;
+#pragma unroll
+  for (int j = 0; j < E; ++j) m = max(m, kr[j]);
+  m = wave_max_u32(m);
+  if (search == 0 && lane == 0) wmax[quarter] = m;
+  __syncthreads();
+  m = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+
   const float f = (float)k / (float)len;
   const float ks = f * (float)S;
-  const float m = margin * sqrtf((float)S * f * (1.0f - f)) + 2.0f;
-  const int r_hi = (int)floorf(ks - m), r_lo = (int)ceilf(ks + m);
+  const float dev = margin * sqrtf((float)S * f * (1.0f - f)) + 2.0f;
   // a rank outside the sample: that end of the bracket is open (0x80000000 is above every key; below, key 0 is the end)
-  uint32_t hi_key = r_hi < 1 ? 0x80000000u : kth_largest_key<kTwoReadSample>(kr, min(r_hi, S));
-  const uint32_t lo_key = r_lo > S ? 0u : kth_largest_key<kTwoReadSample>(kr, max(r_lo, 1));
-  hi_key = max(hi_key, lo_key);  // a negative margin crosses the ranks: a one-key bracket, decided like any other
-  if (lane == 0) {
+  const int want = search == 0 ? (int)floorf(ks - dev) : (int)ceilf(ks + dev);
+  const bool open_end = search == 0 ? want < 1 : want > S;
+  const int rank = min(max(want, 1), S);
+  uint32_t lo = 0, hi = (m >> 1) + 1;
+  float f_lo = (float)(S - rank), f_hi = (float)(-rank);
+  int last_side = 0;
+  bool tried_one = false, found = false;
+  constexpr uint32_t kSixteenOctaves = 16u << (Key<BitsT>::kBits - 8);
+  for (int probe = 0; probe < kBracketProbes; ++probe) {
+    const int par = probe & 1;
+    const bool active = !open_end && !found && hi - lo > 1;
+    uint32_t mid = lo;
+    if (active) {
+      const uint32_t span = hi - lo;
+      if (probe == 0 && hi > kSixteenOctaves + 1u) {
+        mid = hi - 1u - kSixteenOctaves;
+      } else if (lo == 0 && !tried_one) {
+        mid = 1;
+        tried_one = true;
+      } else {
+        uint32_t d = (uint32_t)(f_lo * __builtin_amdgcn_rcpf(f_lo - f_hi) * (float)span);
+        d = min(max(d, 1u), span - 1u);
+        mid = lo + d;
+      }
+      const int c_part = count_ge<E>(kr, mid << 1);
+      if (lane == 0) part[par][search][quarter] = (uint32_t)c_part;
+    }
+    if (lane == 0 && quarter == 0) live[par][search] = active ? 1u : 0u;
+    __syncthreads();
+    if (!live[par][0] && !live[par][1]) break;  // the same two words for every wavefront
+    if (active) {
+      const int c = (int)(part[par][search][0] + part[par][search][1] + part[par][search][2] + part[par][search][3]);
+      if (c == rank) {  // not a key of the sample, but as good a bracket end as one
+        found = true;
+        lo = mid;
+        hi = mid + 1;
+      } else if (c > rank) {
+        lo = mid;
+        f_lo = (float)(c - rank);
+        if (last_side > 0) f_hi *= 0.5f;
+        last_side = 1;
+      } else {
+        hi = mid;
+        f_hi = (float)(c - rank);
+        if (last_side < 0) f_lo *= 0.5f;
+        last_side = -1;
+      }
+    }
+  }
+  if (lane == 0 && quarter == 0) ends[search] = open_end ? (search == 0 ? 0x80000000u : 0u) : (search == 0 ? hi - 1u : lo);
+  __syncthreads();
+  if (threadIdx.x == 0) {
     Sel2 o;
-    o.lo_key = lo_key; o.hi_key = hi_key; o.mode = 0; o.base = 0; o.bits = 0; o.pad[0] = o.pad[1] = o.pad[2] = 0;
+    o.lo_key = ends[1];
+    o.hi_key = max(ends[0], ends[1]);  // a negative margin crosses the ranks: a one-key bracket, decided like any other
+    o.mode = 0; o.base = 0; o.bits = 0; o.pad[0] = o.pad[1] = o.pad[2] = 0;
     sel[grp] = o;
   }
 }
 
-// first read: per wave chunk the record of counts and the candidate keys
+// first read: per wave chunk the record of counts and the candidate keys.  The four counts come from four nested
+// "greater" predicates (their differences), each one compare and one add-with-carry per element.
+template <typename BitsT, bool FULL>
+__device__ __forceinline__ void sel2_collect_chunk(const BitsT* __restrict__ src, int left, uint32_t lo, uint32_t hi,
+                                                   ChunkRec* __restrict__ rec_out, uint32_t* __restrict__ dst) {
+  const int lane = threadIdx.x & 63;
+  constexpr int kRows = kGlobalWaveChunk / 64;
+  uint32_t key[kRows];
+  // rows past the end of the group read its last element and are turned into key 0xffffffff, which no count sees
+#pragma unroll
+  for (int q = 0; q < kRows; ++q) key[q] = (uint32_t)src[FULL ? q * 64 + lane : min(q * 64 + lane, left - 1)];
+#pragma unroll
+  for (int q = 0; q < kRows; ++q) {
+    key[q] &= Key<BitsT>::kMask;
+    if (!FULL) key[q] = q * 64 + lane < left ? key[q] : 0xffffffffu;
+  }
+  // c_gt_hi <= c_ge_hi <= c_gt_lo <= c_ge_lo over the valid keys; an invalid key counts in all four and is taken out below
+  uint32_t c_gt_hi = 0, c_ge_hi = 0, c_gt_lo = 0, c_ge_lo = 0;
+#pragma unroll
+  for (int q = 0; q < kRows; ++q) {
+    c_gt_hi += key[q] > hi ? 1u : 0u;
+    c_ge_hi += key[q] >= hi ? 1u : 0u;
+    c_gt_lo += key[q] > lo ? 1u : 0u;
+    c_ge_lo += key[q] >= lo ? 1u : 0u;
+  }
+  const uint32_t invalid = FULL ? 0u : (uint32_t)(kGlobalWaveChunk - left);
+  c_gt_hi = wave_sum_u32(c_gt_hi) - invalid;
+  c_ge_hi = wave_sum_u32(c_ge_hi) - invalid;
+  c_gt_lo = wave_sum_u32(c_gt_lo) - invalid;
+  c_ge_lo = wave_sum_u32(c_ge_lo) - invalid;
+  const bool one_key = lo == hi;  // then everything equal to it is `top`, and nothing is inside
+  const uint32_t n_cand = one_key ? 0u : c_gt_lo - c_ge_hi;
+  if (lane == 0) {
+    ChunkRec o;
+    o.above = c_gt_hi; o.top = c_ge_hi - c_gt_hi; o.bottom = one_key ? 0u : c_ge_lo - c_gt_lo;
+    o.cand = n_cand;  // more than kTwoReadSlot: the slot is not written
+    *rec_out = o;
+  }
+  if (n_cand == 0 || n_cand > (uint32_t)kTwoReadSlot) return;
+  uint32_t run = 0;
+#pragma unroll
+  for (int q = 0; q < kRows; ++q) {
+    const bool c = key[q] > lo && key[q] < hi;
+    const uint64_t b = ballot64(c);
+    if (c) dst[lane_rank(b, run)] = key[q];
+    run += (uint32_t)__popcll(b);
+  }
+}
+
 template <typename BitsT>
 __global__ __launch_bounds__(256) void sel2_collect_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
                                                            int64_t chunks_per_group, int64_t n_chunks,
                                                            const Sel2* __restrict__ sel, ChunkRec* __restrict__ rec,
                                                            uint32_t* __restrict__ cand) {
-  const int lane = threadIdx.x & 63;
   const int64_t id = (int64_t)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   if (id >= n_chunks) return;
   const int64_t grp = id / chunks_per_group, chunk = id % chunks_per_group;
@@ -760,79 +850,59 @@ __global__ __launch_bounds__(256) void sel2_collect_kernel(const BitsT* __restri
   const int64_t gend = min(gstart + g, n);
   const int64_t e0 = gstart + chunk * kGlobalWaveChunk;
   const uint32_t lo = sel[grp].lo_key, hi = sel[grp].hi_key;
-  const uint32_t width = hi - lo;  // candidates: 0 < key - lo < width
-  constexpr int kRows = kGlobalWaveChunk / 64;
-  uint32_t key[kRows];
-  // rows past the end of the group read its last element and are masked out of every count below
-#pragma unroll
-  for (int q = 0; q < kRows; ++q) {
-    const int64_t e = e0 + q * 64 + lane;
-    key[q] = (uint32_t)A[e < gend ? e : gend - 1] & Key<BitsT>::kMask;
+  const int64_t left = gend - e0;
+  if (left <= 0) {  // the last group is shorter than the others and does not reach this chunk
+    if ((threadIdx.x & 63) == 0) {
+      ChunkRec o;
+      o.above = o.top = o.bottom = o.cand = 0;
+      rec[id] = o;
+    }
+    return;
   }
-  const int64_t left = gend - e0;  // > 0
-  uint32_t above = 0, top = 0, bottom = 0, n_cand = 0;
-#pragma unroll
-  for (int q = 0; q < kRows; ++q) {
-    const bool valid = (int64_t)(q * 64 + lane) < left;
-    above += (valid && key[q] > hi) ? 1u : 0u;
-    top += (valid && key[q] == hi) ? 1u : 0u;
-    bottom += (valid && key[q] == lo && width != 0u) ? 1u : 0u;
-    n_cand += (valid && key[q] - lo - 1u < width - 1u && width != 0u) ? 1u : 0u;
-  }
-  above = wave_sum_u32(above);
-  top = wave_sum_u32(top);
-  bottom = wave_sum_u32(bottom);
-  n_cand = wave_sum_u32(n_cand);
-  if (lane == 0) {
-    ChunkRec o;
-    o.above = above; o.top = top; o.bottom = bottom; o.cand = n_cand;  // cand > kTwoReadSlot: the slot was not written
-    rec[id] = o;
-  }
-  if (n_cand == 0 || n_cand > (uint32_t)kTwoReadSlot) return;
-  uint32_t* __restrict__ dst = cand + id * kTwoReadSlot;
-  uint32_t run = 0;
-#pragma unroll
-  for (int q = 0; q < kRows; ++q) {
-    const bool valid = (int64_t)(q * 64 + lane) < left;
-    const bool c = valid && key[q] - lo - 1u < width - 1u && width != 0u;
-    const uint64_t b = ballot64(c);
-    if (c) dst[lane_rank(b, run)] = key[q];
-    run += (uint32_t)__popcll(b);
-  }
+  if (left >= kGlobalWaveChunk)
+    sel2_collect_chunk<BitsT, true>(A + e0, kGlobalWaveChunk, lo, hi, rec + id, cand + id * kTwoReadSlot);
+  else
+    sel2_collect_chunk<BitsT, false>(A + e0, (int)left, lo, hi, rec + id, cand + id * kTwoReadSlot);
 }
 
 // Per group: where the threshold lies relative to the bracket, from the sums of the chunk records.
-__global__ __launch_bounds__(256) void sel2_decide_kernel(Sel2* __restrict__ sel, GroupState* __restrict__ st,
-                                                          const ChunkRec* __restrict__ rec, int64_t chunks_per_group,
-                                                          int64_t n_groups, uint32_t k_full, uint32_t k_last) {
-  __shared__ uint32_t lds17[17];
+__global__ __launch_bounds__(1024) void sel2_decide_kernel(Sel2* __restrict__ sel, GroupState* __restrict__ st,
+                                                           const ChunkRec* __restrict__ rec, int64_t chunks_per_group,
+                                                           int64_t n_groups, uint32_t k_full, uint32_t k_last,
+                                                           uint32_t key_bits) {
+  __shared__ uint32_t tot[5];
   const int64_t grp = blockIdx.x;
-  const ChunkRec* __restrict__ r = rec + grp * chunks_per_group;
+  const uint4* __restrict__ r = reinterpret_cast<const uint4*>(rec + grp * chunks_per_group);
+  if (threadIdx.x < 5) tot[threadIdx.x] = 0;
+  __syncthreads();
   uint32_t above = 0, top = 0, bottom = 0, cnd = 0, over = 0;
-  for (int64_t c = threadIdx.x; c < chunks_per_group; c += 256) {
-    const ChunkRec x = r[c];
-    above += x.above; top += x.top; bottom += x.bottom; cnd += x.cand;
-    over += x.cand > (uint32_t)kTwoReadSlot ? 1u : 0u;
+  for (int64_t c = threadIdx.x; c < chunks_per_group; c += 1024) {
+    const uint4 x = r[c];  // (above, top, bottom, cand)
+    above += x.x; top += x.y; bottom += x.z; cnd += x.w;
+    over += x.w > (uint32_t)kTwoReadSlot ? 1u : 0u;
   }
-  uint32_t t_above, t_top, t_bottom, t_cand, t_over;
-  block_excl_scan(above, lds17, &t_above);
-  block_excl_scan(top, lds17, &t_top);
-  block_excl_scan(bottom, lds17, &t_bottom);
-  block_excl_scan(cnd, lds17, &t_cand);
-  block_excl_scan(over, lds17, &t_over);
+  above = wave_sum_u32(above); top = wave_sum_u32(top); bottom = wave_sum_u32(bottom); cnd = wave_sum_u32(cnd);
+  over = wave_sum_u32(over);
+  if ((threadIdx.x & 63) == 0) {  // integer sums: the order of the atomics does not matter
+    atomicAdd(&tot[0], above); atomicAdd(&tot[1], top); atomicAdd(&tot[2], bottom); atomicAdd(&tot[3], cnd);
+    atomicAdd(&tot[4], over);
+  }
+  __syncthreads();
+  const uint32_t t_above = tot[0], t_top = tot[1], t_bottom = tot[2], t_cand = tot[3], t_over = tot[4];
   if (threadIdx.x != 0) return;
   const uint32_t k = grp == n_groups - 1 ? k_last : k_full;
   Sel2 s = sel[grp];
   GroupState o;
   o.prefix = 0; o.k_rem = k; o.t_key = 0; o.need = 0;
-  s.mode = 2; s.base = 0; s.bits = Key<uint32_t>::kBits;  // unless the bracket holds the threshold: select over A
+  s.mode = 2; s.base = 0; s.bits = key_bits;  // unless the bracket holds the threshold: select over A, all key bits
   if (t_over == 0 && k > t_above) {
     uint32_t kk = k - t_above;
     if (kk <= t_top) {
       s.mode = 0; o.t_key = s.hi_key; o.need = kk;
     } else if (kk - t_top <= t_cand) {
       kk -= t_top;
-      const uint32_t vmax = s.hi_key - s.lo_key - 2u;  // candidates exist, so hi_key - lo_key >= 2
+      // largest candidate key - base; an open upper end stands above every key of this dtype (candidates exist, so >= 0)
+      const uint32_t vmax = min(s.hi_key, 1u << key_bits) - s.lo_key - 2u;
       s.base = s.lo_key + 1u;
       s.bits = vmax == 0u ? 0u : 32u - (uint32_t)__clz((int)vmax);
       o.k_rem = kk;
@@ -900,15 +970,15 @@ __global__ __launch_bounds__(256) void sel2_hist_kernel(const BitsT* __restrict_
       }
     }
   } else {
-    constexpr int kChunksPerBlock = kGlobalHistChunk / kGlobalWaveChunk;
-    for (int cc = 0; cc < kChunksPerBlock; ++cc) {
-      const int64_t chunk = blk * kChunksPerBlock + cc;
-      if (chunk >= chunks_per_group) break;
+    // one chunk's slot per wavefront (kGlobalHistChunk / kGlobalWaveChunk = 4 = the wavefronts of the workgroup)
+    static_assert(kGlobalHistChunk / kGlobalWaveChunk == 4, "one slot per wavefront");
+    const int64_t chunk = blk * 4 + (threadIdx.x >> 6);
+    if (chunk < chunks_per_group) {
       const int64_t id = grp * chunks_per_group + chunk;
       const uint32_t cnt = rec[id].cand;  // <= kTwoReadSlot in this mode
       const uint32_t* __restrict__ src = cand + id * kTwoReadSlot;
-      for (uint32_t i0 = 0; i0 < cnt; i0 += 256) {  // uniform trip count: the ballot below needs whole wavefronts
-        const uint32_t i = i0 + threadIdx.x;
+      for (uint32_t i0 = 0; i0 < cnt; i0 += 64) {  // wave-uniform trip count: the ballot below needs the whole wavefront
+        const uint32_t i = i0 + lane;
         const bool ok = i < cnt;
         const uint32_t v = (ok ? src[i] : s.base) - s.base;
         const bool match = ok && (v >> hshift) == want;
@@ -927,9 +997,13 @@ __global__ __launch_bounds__(256) void sel2_hist_kernel(const BitsT* __restrict_
   }
 }
 
+// Picks the digit that holds the k_rem-th largest matching element of each group and clears its histograms for the next
+// pass.  (A separate launch on purpose: letting the group's last histogram workgroup do this needs a device-scope
+// fence in every workgroup, which on this chip costs far more than the launch: 59 against 6 + 5 microseconds.)
 __global__ __launch_bounds__(256) void sel2_resolve_kernel(const Sel2* __restrict__ sel, GroupState* __restrict__ st,
                                                            uint32_t* __restrict__ hist, int replicas, int pass) {
   constexpr int kPer = kGlobalHistBins / 256;
+  static_assert(kPer % 4 == 0, "16-byte loads");
   __shared__ uint32_t lds17[17];
   const int64_t grp = blockIdx.x;
   const Sel2 sl = sel[grp];
@@ -941,12 +1015,18 @@ __global__ __launch_bounds__(256) void sel2_resolve_kernel(const Sel2* __restric
   uint32_t sum = 0;
 #pragma unroll
   for (int q = 0; q < kPer; ++q) c[q] = 0;
-  for (int rep = 0; rep < replicas; ++rep) {
+  for (int rep = 0; rep < replicas; ++rep) {  // all loads before the first store: they do not wait for each other
+    const uint4* __restrict__ src = reinterpret_cast<const uint4*>(h + rep * kGlobalHistBins + tid * kPer);
 #pragma unroll
-    for (int q = 0; q < kPer; ++q) {
-      c[q] += h[rep * kGlobalHistBins + tid * kPer + q];
-      h[rep * kGlobalHistBins + tid * kPer + q] = 0;
+    for (int q = 0; q < kPer; q += 4) {
+      const uint4 x = src[q / 4];
+      c[q] += x.x; c[q + 1] += x.y; c[q + 2] += x.z; c[q + 3] += x.w;
     }
+  }
+  for (int rep = 0; rep < replicas; ++rep) {
+    uint4* __restrict__ dst = reinterpret_cast<uint4*>(h + rep * kGlobalHistBins + tid * kPer);
+#pragma unroll
+    for (int q = 0; q < kPer; q += 4) dst[q / 4] = make_uint4(0u, 0u, 0u, 0u);
   }
 #pragma unroll
   for (int q = 0; q < kPer; ++q) sum += c[q];
@@ -1065,7 +1145,9 @@ __global__ __launch_bounds__(1024) void gsel_scan_kernel(const GroupState* __res
   }
 }
 
-template <typename BitsT, bool WITH_IDX>
+// DIRECT: every group starts on a mask word, so a row of 64 elements is one whole word, stored as such; otherwise the
+// rows are OR-ed into a zeroed mask.
+template <typename BitsT, bool WITH_IDX, bool DIRECT>
 __global__ __launch_bounds__(256) void gsel_pack_kernel(const BitsT* __restrict__ A, int64_t n, int64_t g,
                                                         int64_t chunks_per_group, int64_t n_chunks,
                                                         const GroupState* __restrict__ st,
@@ -1111,13 +1193,36 @@ __global__ __launch_bounds__(256) void gsel_pack_kernel(const BitsT* __restrict_
           out_vals[o] = bits;
           if (WITH_IDX) out_idx[o] = (uint32_t)(e - gstart);
         }
-        or_into_mask(mask, e_first, b, lane);
+        if constexpr (DIRECT) {
+          if (lane == 0) mask[e_first >> 6] = b;
+        } else {
+          or_into_mask(mask, e_first, b, lane);
+        }
         run += (uint32_t)__popcll(b);
         eq_run += (uint32_t)__popcll(beq);
       }
     }
   }
 }
+
+template <typename BitsT>
+static int launch_gsel_pack(const GroupPlan& p, int64_t cpg, int64_t n_chunks, const void* A, const GroupState* state,
+                            const uint2* cbase, void* vals, uint64_t* mask, uint32_t* idx, bool direct, hipStream_t st) {
+  const dim3 wgrid((unsigned)ceil_div(n_chunks, 4)), block(256);
+#define SURGEON_PACK(IDX, DIR)                                                                                        \
+  SURGEON_LAUNCH((gsel_pack_kernel<BitsT, IDX, DIR>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks, \
+                     state, cbase, p.k_full, (BitsT*)vals, mask, idx)
+  if (idx && direct) SURGEON_PACK(true, true);
+  else if (idx) SURGEON_PACK(true, false);
+  else if (direct) SURGEON_PACK(false, true);
+  else SURGEON_PACK(false, false);
+#undef SURGEON_PACK
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+// groups that start on mask words: the pack pass of the long-group paths then stores whole words and needs no zeroed mask
+static bool groups_word_aligned(const GroupPlan& p) { return p.n_groups == 1 || p.g % 64 == 0; }
 
 // ---------------------------------------------------------------------------------------------------------
 // host dispatch
@@ -1247,14 +1352,8 @@ static int run_global(const GroupPlan& p, const void* A, void* vals, uint64_t* m
   SURGEON_LAUNCH(gsel_scan_kernel, dim3((unsigned)p.n_groups), dim3(1024), 0, st, (const GroupState*)state,
                      (const uint2*)ccount, cbase, cpg);
   SURGEON_LAUNCH_CHECK();
-  if (idx)
-    SURGEON_LAUNCH((gsel_pack_kernel<BitsT, true>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
-                       (const GroupState*)state, (const uint2*)cbase, p.k_full, (BitsT*)vals, mask, idx);
-  else
-    SURGEON_LAUNCH((gsel_pack_kernel<BitsT, false>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
-                       (const GroupState*)state, (const uint2*)cbase, p.k_full, (BitsT*)vals, mask, idx);
-  SURGEON_LAUNCH_CHECK();
-  return SURGEON_OK;
+  return launch_gsel_pack<BitsT>(p, cpg, n_chunks, A, (const GroupState*)state, (const uint2*)cbase, vals, mask, idx,
+                                 groups_word_aligned(p), st);
 }
 
 static float g_two_read_margin = 5.0f;
@@ -1284,21 +1383,19 @@ static int run_two_read(const GroupPlan& p, const void* A, void* vals, uint64_t*
   w += align_up((size_t)n_chunks * sizeof(ChunkRec), 256);
   uint32_t* cand = (uint32_t*)w;
 
-  const int init_blocks = (int)std::min<int64_t>(ceil_div(p.n_groups * replicas * kGlobalHistBins, 256), 4096);
-  SURGEON_LAUNCH(gsel_init_kernel, dim3(init_blocks), dim3(256), 0, st, state, hist, p.n_groups,
-                     (uint32_t)p.k_full, (uint32_t)p.k_last, replicas);
-  SURGEON_LAUNCH_CHECK();
-  SURGEON_LAUNCH((sel2_bracket_kernel<BitsT>), dim3((unsigned)p.n_groups), dim3(64), 0, st, (const BitsT*)A, p.n, p.g,
-                     p.n_groups, (uint32_t)p.k_full, (uint32_t)p.k_last, g_two_read_margin, sel);
+  SURGEON_LAUNCH((sel2_bracket_kernel<BitsT>), dim3((unsigned)p.n_groups), dim3(512), 0, st, (const BitsT*)A, p.n, p.g,
+                     p.n_groups, (uint32_t)p.k_full, (uint32_t)p.k_last, g_two_read_margin, sel, hist, replicas);
   SURGEON_LAUNCH_CHECK();
   const dim3 wgrid((unsigned)ceil_div(n_chunks, 4)), block(256);
   SURGEON_LAUNCH((sel2_collect_kernel<BitsT>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
                      (const Sel2*)sel, rec, cand);
   SURGEON_LAUNCH_CHECK();
-  SURGEON_LAUNCH(sel2_decide_kernel, dim3((unsigned)p.n_groups), dim3(256), 0, st, sel, state, (const ChunkRec*)rec, cpg,
-                     p.n_groups, (uint32_t)p.k_full, (uint32_t)p.k_last);
+  SURGEON_LAUNCH(sel2_decide_kernel, dim3((unsigned)p.n_groups), dim3(1024), 0, st, sel, state, (const ChunkRec*)rec, cpg,
+                     p.n_groups, (uint32_t)p.k_full, (uint32_t)p.k_last, (uint32_t)Key<BitsT>::kBits);
   SURGEON_LAUNCH_CHECK();
-  const int passes = (Key<uint32_t>::kBits + kGlobalDigitBits - 1) / kGlobalDigitBits;  // a group that needs fewer skips the rest
+  // digit passes for all bits of the key (3 for fp32, 2 for bf16): how many a group needs is known only on the
+  // device, and a group that needs fewer skips the rest
+  const int passes = (Key<BitsT>::kBits + kGlobalDigitBits - 1) / kGlobalDigitBits;
   for (int pass = 0; pass < passes; ++pass) {
     SURGEON_LAUNCH((sel2_hist_kernel<BitsT>), dim3((unsigned)(p.n_groups * bpg)), dim3(256), 0, st, (const BitsT*)A, p.n,
                        p.g, bpg, cpg, pass, (const Sel2*)sel, (const GroupState*)state, (const ChunkRec*)rec,
@@ -1314,14 +1411,8 @@ static int run_two_read(const GroupPlan& p, const void* A, void* vals, uint64_t*
   SURGEON_LAUNCH(gsel_scan_kernel, dim3((unsigned)p.n_groups), dim3(1024), 0, st, (const GroupState*)state,
                      (const uint2*)ccount, cbase, cpg);
   SURGEON_LAUNCH_CHECK();
-  if (idx)
-    SURGEON_LAUNCH((gsel_pack_kernel<BitsT, true>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
-                       (const GroupState*)state, (const uint2*)cbase, p.k_full, (BitsT*)vals, mask, idx);
-  else
-    SURGEON_LAUNCH((gsel_pack_kernel<BitsT, false>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
-                       (const GroupState*)state, (const uint2*)cbase, p.k_full, (BitsT*)vals, mask, idx);
-  SURGEON_LAUNCH_CHECK();
-  return SURGEON_OK;
+  return launch_gsel_pack<BitsT>(p, cpg, n_chunks, A, (const GroupState*)state, (const uint2*)cbase, vals, mask, idx,
+                                 groups_word_aligned(p), st);
 }
 
 template <typename BitsT>
@@ -1341,7 +1432,7 @@ static int run_prune_pack(const GroupPlan& p, const void* A, void* vals, uint64_
       return run_wave_mem<BitsT>(p, A, vals, mask, idx, st);
     }
     default: {
-      const int rc = zero_mask(mask, n_words, st);
+      const int rc = groups_word_aligned(p) ? SURGEON_OK : zero_mask(mask, n_words, st);
       if (rc != SURGEON_OK) return rc;
       if (path == PATH_TWO_READ) return run_two_read<BitsT>(p, A, vals, mask, idx, ws, st);
       return run_global<BitsT>(p, A, vals, mask, idx, ws, st);
