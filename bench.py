@@ -217,9 +217,8 @@ def next_rows(extras, torch, surgeon, wl, dev, cfg):
                  "note": "fp32 matrix cores for both dtypes (bf16 widened while staging)"}
 
     # gradient step W <- W - lr dW (Alg. 1 line 14)
-    def run_update():
-        for e, W in zip(st, Ws):
-            surgeon.surgeon_weight_update(W, e["dW"], 1e-4)
+    def run_update():  # all layers in one call (at most 64 tensors per launch)
+        surgeon.surgeon_weight_update_batched(Ws, [e["dW"].reshape(-1) for e in st], 1e-4)
     p = timed(run_update)
     nbytes = float(sum(e["L"].n_w * (2 * es + 4) for e in st))
     gb = _rate(nbytes, p["update"][0]) / 1e9

@@ -212,6 +212,15 @@ int surgeon_da(const surgeon_layer_desc* desc, const void* dY, const void* W, vo
 int surgeon_weight_update(void* W, const float* dW, int64_t n, float lr, int dt, void* stream);
 
 /*
+ * Alg. 1 line 14 for l tensors in one call: the same results, bit for bit, as l calls of surgeon_weight_update.  The
+ * weights of a layer are small next to the chip, so per-layer launches are mostly launch gap; here up to 64 tensors go
+ * out in one launch.  W, dW, n are HOST arrays of l entries (device pointers / element counts per tensor); all W have
+ * dtype dt, all dW are fp32.  Everything is validated before the first launch.
+ */
+int surgeon_weight_update_batched(int l, void* const* W, const float* const* dW, const int64_t* n, float lr, int dt,
+                                  void* stream);
+
+/*
  * Normalisation layers (the variant of Section 5 that adapts BN layers only): gradients of the scale and the shift
  * of y = gamma[c] * x_hat + beta[c] from the pruned, packed normalised activation x_hat and dY,
  *     dgamma[c] = sum dY * x_hat_pruned,   dbeta[c] = sum dY        over every element of channel c.

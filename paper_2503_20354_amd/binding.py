@@ -75,6 +75,8 @@ def load_library():
     L.surgeon_da.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp]
     L.surgeon_weight_update.restype = ci
     L.surgeon_weight_update.argtypes = [vp, vp, i64, f32, ci, vp]
+    L.surgeon_weight_update_batched.restype = ci
+    L.surgeon_weight_update_batched.argtypes = [ci, vp, vp, vp, f32, ci, vp]
     L.surgeon_affine_grad_ws_bytes.restype = ci
     L.surgeon_affine_grad_ws_bytes.argtypes = [i64, i64, i64, ctypes.POINTER(sz)]
     L.surgeon_affine_grad.restype = ci
@@ -243,6 +245,20 @@ def surgeon_weight_update(W, dW, lr: float):
     if dW.dtype != torch.float32 or dW.numel() != W.numel():
         raise TypeError("dW is float32 with as many elements as W")
     _check(load_library().surgeon_weight_update(_ptr(W), _ptr(dW), W.numel(), float(lr), _dt(W), _stream(W.device)))
+
+
+def surgeon_weight_update_batched(Ws, dWs, lr: float):
+    """Alg. 1 line 14 for a list of weight tensors (one dtype) in one call."""
+    l = len(Ws)
+    for t in list(Ws) + list(dWs):
+        _dev(t, "tensor")
+    w_p = (ctypes.c_void_p * l)(*[t.data_ptr() for t in Ws])
+    g_p = (ctypes.c_void_p * l)(*[t.data_ptr() for t in dWs])
+    n_a = (ctypes.c_int64 * l)(*[t.numel() for t in Ws])
+    for w, g in zip(Ws, dWs):
+        if g.numel() != w.numel() or g.dtype != torch.float32:
+            raise SurgeonError(1, "weight_update_batched: dW must be fp32 with W's element count")
+    _check(load_library().surgeon_weight_update_batched(l, w_p, g_p, n_a, float(lr), _dt(Ws[0]), _stream(Ws[0].device)))
 
 
 def surgeon_affine_grad_ws_bytes(outer: int, C: int, inner: int) -> int:

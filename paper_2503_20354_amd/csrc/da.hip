@@ -211,9 +211,102 @@ __global__ __launch_bounds__(256) void weight_update_kernel(T* __restrict__ Wt, 
     da_store<T>(&Wt[i], __builtin_fmaf(-lr, dW[i], da_widen<T>(Wt[i])));
 }
 
+// ---- the gradient step for many tensors in one launch: the weights of a layer are small next to the chip (at most a
+// few MB), so one launch per layer is mostly launch gap.  Up to kUpdateBatch tensors travel as kernel arguments; a
+// workgroup owns one 4096-element chunk of one tensor (workgroup -> tensor by the tensors' first workgroups).
+constexpr int kUpdateBatch = 64;
+constexpr int kUpdateChunk = 4096;
+struct UpdateBatch {
+  void* Wt[kUpdateBatch];
+  const float* dW[kUpdateBatch];
+  int64_t n[kUpdateBatch];
+  int first_block[kUpdateBatch + 1];  // entries past the last tensor hold the total
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void weight_update_batched_kernel(UpdateBatch bt, float lr) {
+  int t = 0;
+#pragma unroll
+  for (int i = 1; i < kUpdateBatch; ++i) t += ((int)blockIdx.x >= bt.first_block[i]) ? 1 : 0;
+  T* __restrict__ Wt = (T*)bt.Wt[t];
+  const float* __restrict__ dW = bt.dW[t];
+  const int64_t n = bt.n[t];
+  const int64_t c0 = (int64_t)((int)blockIdx.x - bt.first_block[t]) * kUpdateChunk;
+  // four consecutive elements per thread and round: 16-byte accesses when both pointers allow them
+  const bool wide = (((uintptr_t)Wt % (4 * sizeof(T))) | ((uintptr_t)dW % 16)) == 0;
+#pragma unroll
+  for (int q = 0; q < kUpdateChunk / 1024; ++q) {
+    const int64_t i = c0 + q * 1024 + threadIdx.x * 4;
+    if (wide && i + 4 <= n) {
+      const float4 g = *reinterpret_cast<const float4*>(dW + i);
+      if constexpr (sizeof(T) == 4) {
+        float4 w = *reinterpret_cast<const float4*>(Wt + i);
+        w.x = __builtin_fmaf(-lr, g.x, w.x); w.y = __builtin_fmaf(-lr, g.y, w.y);
+        w.z = __builtin_fmaf(-lr, g.z, w.z); w.w = __builtin_fmaf(-lr, g.w, w.w);
+        *reinterpret_cast<float4*>(Wt + i) = w;
+      } else {
+        ushort4 w = *reinterpret_cast<const ushort4*>(Wt + i);
+        da_store<T>(&w.x, __builtin_fmaf(-lr, g.x, da_widen<T>(w.x)));
+        da_store<T>(&w.y, __builtin_fmaf(-lr, g.y, da_widen<T>(w.y)));
+        da_store<T>(&w.z, __builtin_fmaf(-lr, g.z, da_widen<T>(w.z)));
+        da_store<T>(&w.w, __builtin_fmaf(-lr, g.w, da_widen<T>(w.w)));
+        *reinterpret_cast<ushort4*>(Wt + i) = w;
+      }
+    } else {
+      for (int64_t j = i; j < min(i + 4, n); ++j) da_store<T>(&Wt[j], __builtin_fmaf(-lr, dW[j], da_widen<T>(Wt[j])));
+    }
+  }
+}
+
 }  // namespace surgeon
 
 using namespace surgeon;
+
+extern "C" int surgeon_weight_update_batched(int l, void* const* Wt, const float* const* dW, const int64_t* n, float lr, int dt,
+                                             void* stream) {
+  if (dt != SURGEON_F32 && dt != SURGEON_BF16) return fail(SURGEON_EINVAL, "weight_update_batched: bad dtype %d", dt);
+  if (l < 0 || !(lr == lr)) return fail(SURGEON_EINVAL, "weight_update_batched: bad arguments");
+  if (l == 0) return SURGEON_OK;
+  if (!Wt || !dW || !n) return fail(SURGEON_EINVAL, "weight_update_batched: null array");
+  for (int i = 0; i < l; ++i) {  // everything is checked before the first launch
+    if (n[i] < 0) return fail(SURGEON_EINVAL, "weight_update_batched: tensor %d has n < 0", i);
+    if (n[i] > 0 && (!Wt[i] || !dW[i])) return fail(SURGEON_EINVAL, "weight_update_batched: tensor %d: null pointer", i);
+    if (((uintptr_t)Wt[i] % (dt == SURGEON_F32 ? 4 : 2)) || ((uintptr_t)dW[i] % 4))
+      return fail(SURGEON_EINVAL, "weight_update_batched: tensor %d: misaligned pointer", i);
+    if (ceil_div(n[i], kUpdateChunk) > 0x3fffffff) return fail(SURGEON_EUNSUPPORTED, "weight_update_batched: tensor %d too large", i);
+  }
+  hipStream_t st = (hipStream_t)stream;
+  ProfScope prof(SURGEON_PROF_UPDATE, st);
+  UpdateBatch bt;
+  int count = 0;
+  int64_t blocks = 0;
+  auto flush = [&]() -> int {
+    if (count == 0) return SURGEON_OK;
+    for (int i = count; i <= kUpdateBatch; ++i) bt.first_block[i] = (int)blocks;
+    for (int i = count; i < kUpdateBatch; ++i) { bt.Wt[i] = nullptr; bt.dW[i] = nullptr; bt.n[i] = 0; }
+    if (dt == SURGEON_F32)
+      SURGEON_LAUNCH(weight_update_batched_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, st, bt, lr);
+    else
+      SURGEON_LAUNCH(weight_update_batched_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, st, bt, lr);
+    SURGEON_LAUNCH_CHECK();
+    count = 0;
+    blocks = 0;
+    return SURGEON_OK;
+  };
+  for (int i = 0; i < l; ++i) {
+    if (n[i] == 0) continue;
+    const int64_t b = ceil_div(n[i], kUpdateChunk);
+    if (count == kUpdateBatch || blocks + b > 0x7fffffff) {
+      const int rc = flush();
+      if (rc != SURGEON_OK) return rc;
+    }
+    bt.Wt[count] = Wt[i]; bt.dW[count] = dW[i]; bt.n[count] = n[i];
+    bt.first_block[count] = (int)blocks;
+    blocks += b;
+    ++count;
+  }
+  return flush();
+}
 
 extern "C" int surgeon_da(const surgeon_layer_desc* d, const void* dY, const void* Wt, void* dA, void* stream) {
   if (!d) return fail(SURGEON_EINVAL, "da: null descriptor");

@@ -15,13 +15,11 @@ namespace surgeon {
 // scale / shift gradients
 // ---------------------------------------------------------------------------------------------------------
 // Element (o, c, i) of the [outer, C, inner] tensor is at (o*C + c)*inner + i.  Three partial kernels write
-// (dgamma, dbeta) partial sums as float2 part[slice][c]; the finishing kernel adds the slices per channel in index
-// order in fp64 (deterministic).
-
-constexpr int kAffineBatch = 8;
+// (dgamma, dbeta) partial sums as float2 part[slice][c]; the finishing kernel adds the slices per channel in fp64 in
+// a fixed order (deterministic).
 
 // inner % 64 == 0 (batch norm on maps of 8x8 and larger): one wavefront per (o, c) row, lane = element of a mask word
-template <typename T>
+template <typename T, int kAffineBatch>
 __global__ __launch_bounds__(256) void affine_rows_kernel(Packed<T> pk, const T* __restrict__ dY, int64_t outer, int C,
                                                           int inner, float2* __restrict__ part) {
   const int lane = threadIdx.x & 63;
@@ -69,7 +67,8 @@ __global__ __launch_bounds__(256) void affine_rows_kernel(Packed<T> pk, const T*
 }
 
 // inner == 1 and C % 64 == 0 (layer norm): a wavefront owns one 64-feature mask word of kLnRows consecutive tokens
-constexpr int kLnRows = 32;
+constexpr int kLnRows = 16;
+constexpr int kAffineBatch = 16;  // = kLnRows: a slice is one batch
 template <typename T>
 __global__ __launch_bounds__(256) void affine_cols_kernel(Packed<T> pk, const T* __restrict__ dY, int64_t outer, int C,
                                                           float2* __restrict__ part) {
@@ -85,7 +84,7 @@ __global__ __launch_bounds__(256) void affine_cols_kernel(Packed<T> pk, const T*
     float dy[kAffineBatch];
 #pragma unroll
     for (int q = 0; q < kAffineBatch; ++q) {
-      const int64_t m = min(mb + q, m1 - 1);
+      const int64_t m = min(mb + q, m1 - 1);  // past the slice's end: its last token again, weighted 0 below
       const int64_t w = m * words + wq;
       word[q] = pk.mask[w];
       rank[q] = pk.word_rank[w];
@@ -127,18 +126,42 @@ __global__ __launch_bounds__(256) void affine_generic_kernel(Packed<T> pk, const
   part[(int64_t)blockIdx.y * C + c] = make_float2(g, b);
 }
 
-static __global__ __launch_bounds__(256) void affine_final_kernel(const float2* __restrict__ part, int64_t n_slices, int C,
-                                                                  float* __restrict__ dgamma, float* __restrict__ dbeta) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= C) return;
+// Adds the slices per channel in fp64, in a fixed order: a workgroup owns 64 channels, its 16 wavefronts take the
+// slices s = w, w + 16, ... (eight loads in flight each), and the 16 partial sums are added in wavefront order.
+static __global__ __launch_bounds__(1024) void affine_final_kernel(const float2* __restrict__ part, int64_t n_slices, int C,
+                                                                   float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  __shared__ double sg[16][64], sb[16][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
   double g = 0.0, b = 0.0;
-  for (int64_t s = 0; s < n_slices; ++s) {
-    const float2 v = part[s * C + c];
-    g += (double)v.x;
-    b += (double)v.y;
+  if (c < C) {
+    for (int64_t s0 = w; s0 < n_slices; s0 += 16 * 8) {
+      float2 v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int64_t s = s0 + 16 * q;
+        v[q] = s < n_slices ? part[s * C + c] : make_float2(0.0f, 0.0f);
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        g += (double)v[q].x;
+        b += (double)v[q].y;
+      }
+    }
   }
-  dgamma[c] = (float)g;
-  dbeta[c] = (float)b;
+  sg[w][lane] = g;
+  sb[w][lane] = b;
+  __syncthreads();
+  if (w == 0 && c < C) {
+    double tg = 0.0, tb = 0.0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      tg += sg[q][lane];
+      tb += sb[q][lane];
+    }
+    dgamma[c] = (float)tg;
+    dbeta[c] = (float)tb;
+  }
 }
 
 struct AffinePlan {
@@ -207,8 +230,14 @@ static int run_affine(const AffinePlan& p, const void* vals, const uint64_t* mas
   if (p.n == 0) {
     n_slices = 0;
   } else if (p.mode == 0) {
-    SURGEON_LAUNCH(affine_rows_kernel<T>, dim3((unsigned)ceil_div(outer * C, 4)), dim3(256), 0, st, pk, (const T*)dY, outer,
-                   C, inner, part);
+    // words of a row requested together: as many as the row has, up to 16 (a shorter batch re-reads nothing)
+    const dim3 grid((unsigned)ceil_div(outer * C, 4));
+    const int words = inner / 64;
+    if (words >= 16) SURGEON_LAUNCH((affine_rows_kernel<T, 16>), grid, dim3(256), 0, st, pk, (const T*)dY, outer, C, inner, part);
+    else if (words >= 8) SURGEON_LAUNCH((affine_rows_kernel<T, 8>), grid, dim3(256), 0, st, pk, (const T*)dY, outer, C, inner, part);
+    else if (words >= 4) SURGEON_LAUNCH((affine_rows_kernel<T, 4>), grid, dim3(256), 0, st, pk, (const T*)dY, outer, C, inner, part);
+    else if (words >= 2) SURGEON_LAUNCH((affine_rows_kernel<T, 2>), grid, dim3(256), 0, st, pk, (const T*)dY, outer, C, inner, part);
+    else SURGEON_LAUNCH((affine_rows_kernel<T, 1>), grid, dim3(256), 0, st, pk, (const T*)dY, outer, C, inner, part);
     SURGEON_LAUNCH_CHECK();
   } else if (p.mode == 1) {
     SURGEON_LAUNCH(affine_cols_kernel<T>, dim3((unsigned)ceil_div(C / 64, 4), (unsigned)p.n_slices), dim3(256), 0, st, pk,
@@ -219,7 +248,7 @@ static int run_affine(const AffinePlan& p, const void* vals, const uint64_t* mas
                    (const T*)dY, outer, C, inner, p.o_per_slice, part);
     SURGEON_LAUNCH_CHECK();
   }
-  SURGEON_LAUNCH(affine_final_kernel, dim3((unsigned)ceil_div(C, 256)), dim3(256), 0, st, (const float2*)part, n_slices, C,
+  SURGEON_LAUNCH(affine_final_kernel, dim3((unsigned)ceil_div(C, 64)), dim3(1024), 0, st, (const float2*)part, n_slices, C,
                  dgamma, dbeta);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;

@@ -200,6 +200,42 @@ def test_weight_update(dtype, n):
     assert torch.equal(same.cpu(), W)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_layers", [1, 5, 70, 150])
+def test_weight_update_batched(dtype, n_layers):
+    """Many tensors per launch (more than 64 take several): the oracle's step per tensor, and the same bits as one call
+    per tensor; sizes around the 4096-element chunk, empty tensors, and pointers that rule out 16-byte accesses."""
+    rng = np.random.default_rng(n_layers)
+    sizes = [int(x) for x in rng.choice([0, 1, 3, 4095, 4096, 4097, 8192, 12289, 36864, 100003], n_layers)]
+    sizes[0] = 100003
+    lr = 0.0371
+    Ws = [wl.draw((n + 1,), "normal", dtype, 500 + i) for i, n in enumerate(sizes)]
+    dWs = [wl.draw((n + 1,), "normal", "f32", 900 + i) for i, n in enumerate(sizes)]
+    # every third tensor starts one element into its allocation
+    off = [1 if i % 3 == 1 else 0 for i in range(n_layers)]
+    W_dev = [w.to(DEV).clone() for w in Ws]
+    dW_dev = [g.to(DEV) for g in dWs]
+    W_view = [w[o:o + n] for w, o, n in zip(W_dev, off, sizes)]
+    dW_view = [g[o:o + n] for g, o, n in zip(dW_dev, off, sizes)]
+    single = [w.clone() for w in W_dev]
+    surgeon.surgeon_weight_update_batched(W_view, dW_view, lr)
+    for w, o, n, g in zip(single, off, sizes, dW_view):
+        surgeon.surgeon_weight_update(w[o:o + n], g, lr)
+    torch.cuda.synchronize()
+    for i, n in enumerate(sizes):
+        assert torch.equal(W_dev[i].cpu().view(torch.uint8), single[i].cpu().view(torch.uint8)), i
+        o = off[i]
+        got_all = W_dev[i].cpu()
+        # elements outside the view are untouched
+        assert torch.equal(got_all[:o], Ws[i][:o]) and torch.equal(got_all[o + n:], Ws[i][o + n:])
+        if n == 0:
+            continue
+        ref = f64(oracle.weight_update(bits(Ws[i][o:o + n]), dWs[i][o:o + n].numpy(), lr))
+        got = f64(bits(got_all[o:o + n]))
+        ulp = np.abs(ref) * (2.0 ** -23 if dtype == "f32" else 2.0 ** -7) + 1e-30
+        assert (np.abs(got - ref) <= ulp).all(), i
+
+
 # ------------------------------------------------------------------------------------------------
 # scale / shift gradients of normalisation layers
 # ------------------------------------------------------------------------------------------------
