@@ -31,6 +31,7 @@ if ROOT not in sys.path:
 PEAK_HBM_GBPS = 8000.0       # MI355X HBM3E
 PEAK_MFMA_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 PEAK_VALU_F32_TFLOPS = 78.6  # non-packed fp32 FMA on the vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2 flops x 2.4 GHz
+PEAK_LDS_TBPS = 78.6         # LDS data path: 256 compute units x 128 bytes per clock x 2.4 GHz
 METRIC = "pruned-activation GB/s (select+pack) + packed-dW TFLOP/s, % of MI355X roofline"
 WORKLOAD_NAMES = {
     0: "cfg0 single linear 512->256, 64 tokens, fp32, r=0.5",
@@ -179,7 +180,12 @@ def run_config(cfg, steps, warmup, torch, surgeon, wl, dev):
                           "frac": round(_rate(acct["dw_sparse_nnz"], sparse_ms) / 1e12 / PEAK_VALU_F32_TFLOPS, 4),
                           "launches": n_launch["dw_sparse"], "ms_per_step": round(sparse_ms / steps, 4),
                           "kernel_only_ms_per_step": round(ms["dw_sparse"] / steps, 4),
-                          "tflops_dense_equiv": round(_rate(acct["dw_sparse"], sparse_ms) / 1e12, 3)},
+                          "tflops_dense_equiv": round(_rate(acct["dw_sparse"], sparse_ms) / 1e12, 3),
+                          # every multiply-add of this kernel takes its dY operand from LDS (4 bytes per lane): the LDS
+                          # data path (128 bytes per clock and compute unit) is the unit it fills first
+                          "lds": {"achieved": round(_rate(acct["dw_sparse_nnz"] / 2 * 4, ms["dw_sparse"]) / 1e12, 2),
+                                  "peak": PEAK_LDS_TBPS, "unit": "TB/s",
+                                  "frac": round(_rate(acct["dw_sparse_nnz"] / 2 * 4, ms["dw_sparse"]) / 1e12 / PEAK_LDS_TBPS, 4)}},
         },
     }
     extras = {"st": st, "ws": ws, "layers": layers, "dt": dt, "tdt": tdt}
@@ -304,6 +310,7 @@ def main():
     ap.add_argument("--cfg", type=int, default=1, help="headline workload (default 1 = the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (used under rocprofv3)")
     ap.add_argument("--only-headline", action="store_true", help="skip the other workloads and the extra rows")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the other workloads, keep the extra rows")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain elementwise kernel reading and writing 1 GiB, as the known-size reference "
                     "for scaling FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc")
@@ -352,7 +359,7 @@ def main():
         out["next"] = next_rows(extras, torch, surgeon, wl, dev, args.cfg)
     del extras
     torch.cuda.empty_cache()
-    if not args.only_headline:
+    if not args.only_headline and not args.no_other_configs:
         out["configs"] = {}
         for cfg in (0, 2, 3, 4):
             if cfg == args.cfg:

@@ -90,6 +90,16 @@ def cmd_counters(args):
             cycles = c["SQ_BUSY_CYCLES"] / 32.0
             print("    -> matrix pipeline busy %.1f %% of SIMD cycles (cycles per dispatch %.0f)" %
                   (100.0 * c["SQ_VALU_MFMA_BUSY_CYCLES"] / (cycles * 1024.0), cycles))
+        if "SQ_INSTS_VALU" in c and "SQ_WAVES" in c and c["SQ_WAVES"] > 0:
+            print("    -> per wavefront: %.0f vector, %.0f scalar, %.0f LDS instructions" %
+                  (c["SQ_INSTS_VALU"] / c["SQ_WAVES"], c.get("SQ_INSTS_SALU", 0.0) / c["SQ_WAVES"],
+                   c.get("SQ_INSTS_LDS", 0.0) / c["SQ_WAVES"]))
+        if "SQ_ACTIVE_INST_VALU" in c and "SQ_BUSY_CYCLES" in c and c["SQ_BUSY_CYCLES"] > 0:
+            # SQ_ACTIVE_INST_* count in units of four cycles per SIMD (one per issued wave64 instruction on gfx950)
+            cycles = c["SQ_BUSY_CYCLES"] / 32.0
+            print("    -> vector ALU busy %.1f %% of SIMD cycles" % (100.0 * 4.0 * c["SQ_ACTIVE_INST_VALU"] / (cycles * 1024.0)))
+            if "SQ_ACTIVE_INST_LDS" in c:
+                print("    -> LDS busy %.1f %% of compute-unit cycles" % (100.0 * 4.0 * c["SQ_ACTIVE_INST_LDS"] / (cycles * 256.0)))
         if "SQ_INSTS_VALU" in c and "SQ_INSTS_MFMA" in c and c["SQ_INSTS_MFMA"] > 0:
             print("    -> vector instructions per matrix instruction %.2f" %
                   ((c["SQ_INSTS_VALU"] - c["SQ_INSTS_MFMA"]) / c["SQ_INSTS_MFMA"]))
