@@ -94,17 +94,18 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
     }
   }
 
-  for (int q0 = 0; q0 < g.Q; q0 += kDaTQ) {
-    __syncthreads();
+  // The values of a K-tile travel global memory -> registers -> LDS; the loads of tile t + 1 are issued before the
+  // matrix instructions of tile t, so their latency passes behind them.
+  constexpr int kPerThread = kDaTP * kDaTQ / 256;  // 16 values of each operand per thread and K-tile
+  static_assert(kDaTP == kDaTC && kPerThread == kDaTQ / 2 && kPerThread == kDaTP / 8, "staging roles");
+  float xr[kPerThread], yr[kPerThread];
+  auto load_tile = [&](int q0) {
     if (LINEAR) {
       const int q = q0 + (tid & 31);
 #pragma unroll
-      for (int j = 0; j < kDaTP / 8; ++j) {
-        const int pl = (tid >> 5) + 8 * j;
-        const int64_t m = p0 + pl;
-        float v = 0.0f;
-        if (m < g.P && q < g.Q) v = da_widen<T>(dY[m * g.Co + q]);
-        Xs[(tid & 31) * kDaSX + pl] = v;
+      for (int j = 0; j < kPerThread; ++j) {
+        const int64_t m = p0 + (tid >> 5) + 8 * j;
+        xr[j] = (m < g.P && q < g.Q) ? da_widen<T>(dY[m * g.Co + q]) : 0.0f;
       }
     } else {
       // q = (co, u, v) advanced incrementally: this thread walks q0 + (tid / 128) + 2 j
@@ -113,8 +114,8 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
       int co = q / taps;
       int t = q - co * taps;
       int u = t / g.KW, v = t - u * g.KW;
-#pragma unroll 4
-      for (int j = 0; j < kDaTQ / 2; ++j) {
+#pragma unroll
+      for (int j = 0; j < kPerThread; ++j) {
         float val = 0.0f;
         if (my_ok && q < g.Q) {
           const int top = my_ih + g.pad - u, left = my_iw + g.pad - v;
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
               val = da_widen<T>(dY[(((int64_t)my_b * g.Co + co) * g.OH + oh) * g.OW + ow]);
           }
         }
-        Xs[((tid >> 7) + 2 * j) * kDaSX + (tid & (kDaTP - 1))] = val;
+        xr[j] = val;
         q += 2;
         v += 2;
         while (v >= g.KW) {
@@ -143,26 +144,40 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
         }
       }
     }
-    // Y: thread -> (c = tid % 128, q = tid / 128 + 2 j)
-    {
-      const int c = c0 + (tid & (kDaTC - 1));
-#pragma unroll 4
-      for (int j = 0; j < kDaTQ / 2; ++j) {
-        const int ql = (tid >> 7) + 2 * j, q = q0 + ql;
-        float val = 0.0f;
-        if (c < g.Ci && q < g.Q) {
-          if (LINEAR) {
-            val = da_widen<T>(Wt[(int64_t)q * g.Ci + c]);
-          } else {
-            const int taps = g.KH * g.KW;
-            const int co = q / taps, t = q - co * taps;
-            val = da_widen<T>(Wt[((int64_t)co * g.Ci + c) * taps + t]);
-          }
+    const int c = c0 + (tid & (kDaTC - 1));
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+      const int q = q0 + (tid >> 7) + 2 * j;
+      float val = 0.0f;
+      if (c < g.Ci && q < g.Q) {
+        if (LINEAR) {
+          val = da_widen<T>(Wt[(int64_t)q * g.Ci + c]);
+        } else {
+          const int taps = g.KH * g.KW;
+          const int co = q / taps, t = q - co * taps;
+          val = da_widen<T>(Wt[((int64_t)co * g.Ci + c) * taps + t]);
         }
-        Ys[ql * kDaSY + (tid & (kDaTC - 1))] = val;
       }
+      yr[j] = val;
     }
+  };
+  // X: LINEAR thread -> (q = tid % 32, p = tid / 32 + 8 j); conv thread -> (p = tid % 128, q = tid / 128 + 2 j)
+  // Y: thread -> (c = tid % 128, q = tid / 128 + 2 j)
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+      if (LINEAR) Xs[(tid & 31) * kDaSX + (tid >> 5) + 8 * j] = xr[j];
+      else Xs[((tid >> 7) + 2 * j) * kDaSX + (tid & (kDaTP - 1))] = xr[j];
+      Ys[((tid >> 7) + 2 * j) * kDaSY + (tid & (kDaTC - 1))] = yr[j];
+    }
+  };
+
+  load_tile(0);
+  for (int q0 = 0; q0 < g.Q; q0 += kDaTQ) {
+    __syncthreads();  // the previous tile's readers are done
+    store_tile();
     __syncthreads();
+    if (q0 + kDaTQ < g.Q) load_tile(q0 + kDaTQ);
     const float* rows = LINEAR ? Xs : Ys;  // operand whose index becomes the rows of the result tiles
     const float* cols = LINEAR ? Ys : Xs;
     const int srow = LINEAR ? kDaSX : kDaSY, scol = LINEAR ? kDaSY : kDaSX;
