@@ -46,6 +46,22 @@ bool prof_next_events(hipEvent_t* start, hipEvent_t* stop);
       hipLaunchKernelGGL(kernel, grid, block, shmem, st, __VA_ARGS__);                                    \
   } while (0)
 
+// Work item (x, y) of the calling workgroup for kernels whose grid is (tiles, splits) and whose tiles of one split read
+// the same rows of the operands.  Workgroups go to the chip's eight XCDs (each with its own L2) round-robin in dispatch
+// order; here work item w = y * gridDim.x + x is handed out so that each XCD gets a run of consecutive w, i.e. whole
+// splits: its L2 then fetches a split's rows once for all of its tiles instead of once per XCD.  A bijection of the
+// grid onto itself for any grid size.
+#if defined(__HIPCC__)
+__device__ __forceinline__ void xcd_ordered_work_item(int* x, int* y) {
+  const uint32_t nx = gridDim.x, total = gridDim.x * gridDim.y;
+  const uint32_t b = blockIdx.y * gridDim.x + blockIdx.x;
+  const uint32_t xcd = b & 7u, j = b >> 3, base = total >> 3, rem = total & 7u;
+  const uint32_t w = xcd * base + (xcd < rem ? xcd : rem) + j;
+  *x = (int)(w % nx);
+  *y = (int)(w / nx);
+}
+#endif
+
 // Raises a kernel's dynamic-LDS limit once per (kernel, device): the attribute belongs to the device, the flag word is
 // one bit per device and is only ever OR-ed into, so host threads that race here at worst set the attribute twice.
 // `done` is a static of the calling launch function (one per kernel).

@@ -358,7 +358,8 @@ __global__ __launch_bounds__(512) void dw_linear_bf16_big_kernel(int64_t M, int6
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wo = wave & 3, wi = wave >> 2;
-  const int tile_id = blockIdx.x, split_id = blockIdx.y;
+  int tile_id, split_id;  // the tiles of a split share its token rows: whole splits per XCD
+  xcd_ordered_work_item(&tile_id, &split_id);
   const int64_t o0 = (int64_t)(tile_id / i_tiles) * kBigTO, i0 = (int64_t)(tile_id % i_tiles) * TI;
   const int64_t m_begin = (int64_t)split_id * rows_per_split;
   const int64_t m_end = min(m_begin + rows_per_split, M);
@@ -544,9 +545,11 @@ __global__ __launch_bounds__(256) void dw_conv1x1_bf16_kernel(int Nb, int Ci, in
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
-  const int o0 = (int)(blockIdx.x / i_tiles) * kPxTile, i0 = (int)(blockIdx.x % i_tiles) * kPxTile;
+  int tile_id, split_id;  // the tiles of a split share its pixels: whole splits per XCD
+  xcd_ordered_work_item(&tile_id, &split_id);
+  const int o0 = (tile_id / i_tiles) * kPxTile, i0 = (tile_id % i_tiles) * kPxTile;
   const int64_t n_ktiles = (int64_t)Nb * tiles_per_img;
-  const int64_t t_begin = (int64_t)blockIdx.y * ktiles_per_split;
+  const int64_t t_begin = (int64_t)split_id * ktiles_per_split;
   const int64_t t_end = min(t_begin + ktiles_per_split, n_ktiles);
 
   floatx16 acc[2][2];
@@ -617,7 +620,7 @@ __global__ __launch_bounds__(256) void dw_conv1x1_bf16_kernel(int Nb, int Ci, in
   }
 
   // 32x32 result tile: lane holds column lane%32 and rows 8*(v/4) + 4*(lane/32) + v%4, v = 0..15
-  float* __restrict__ dst = out + (int64_t)blockIdx.y * Co * Ci;
+  float* __restrict__ dst = out + (int64_t)split_id * Co * Ci;
   const int col = lane & 31, half = lane >> 5;
 #pragma unroll
   for (int p = 0; p < 2; ++p)

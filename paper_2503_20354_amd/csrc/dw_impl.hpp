@@ -543,12 +543,14 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
   extern __shared__ float smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int co_tile = blockIdx.x / gm.ci_tiles, ci_tile = blockIdx.x % gm.ci_tiles;
+  int tile_id, split_id;  // the tiles of a split share its positions (dY rows, input patches): whole splits per XCD
+  xcd_ordered_work_item(&tile_id, &split_id);
+  const int co_tile = tile_id / gm.ci_tiles, ci_tile = tile_id % gm.ci_tiles;
   const int co0 = co_tile * TCO, ci0 = ci_tile * TCI;
   const int u0 = blockIdx.z * KHC;
   const int PW = gm.PW, PS = gm.PS;
   const int buf_floats = TCO * SY + TCI * PS;
-  const int t_begin = blockIdx.y * gm.tiles_per_split;
+  const int t_begin = split_id * gm.tiles_per_split;
   const int t_end = min(t_begin + gm.tiles_per_split, gm.n_ktiles);
 
   // A zero area after every channel's patch in both buffers (written once): contraction positions past R*OW point
@@ -720,7 +722,7 @@ __global__ __attribute__((amdgpu_flat_work_group_size(512, 512))) void dw_conv_k
   }
 
   // ---- write this split's partial tile: lane holds rows 4*kk..4*kk+3 (co), column i16 (ci) of each 16x16 tile
-  float* __restrict__ dst = out + (int64_t)blockIdx.y * gm.n_w;
+  float* __restrict__ dst = out + (int64_t)split_id * gm.n_w;
 #pragma unroll
   for (int a = 0; a < MT; ++a) {
 #pragma unroll
