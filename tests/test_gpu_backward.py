@@ -279,6 +279,10 @@ GROUPED = [
     (8, 128, 16, 16, 128, 3, 1, 1, 32), (4, 256, 8, 8, 512, 3, 2, 1, 32), (2, 64, 32, 32, 64, 3, 1, 1, 64),
     (2, 320, 16, 32, 320, 3, 1, 1, 320), (3, 12, 9, 9, 24, 5, 2, 2, 4), (2, 6, 11, 11, 6, 7, 1, 3, 6),
     (2, 8, 8, 8, 8, 1, 1, 0, 2), (1, 4, 5, 5, 4, 3, 1, 0, 4),
+    # the tiled 3x3 kernel: a last workgroup with fewer groups, more output than input channels per group, bands that
+    # do not divide the map, many tiles per split
+    (3, 24, 12, 12, 24, 3, 1, 1, 6), (2, 32, 10, 10, 64, 3, 1, 1, 8), (1, 16, 72, 64, 16, 3, 1, 1, 4),
+    (40, 64, 8, 8, 64, 3, 1, 1, 8), (3, 100, 12, 12, 100, 3, 1, 1, 100),
 ]
 
 
