@@ -171,7 +171,9 @@ def run_config(cfg, steps, warmup, torch, surgeon, wl, dev):
             # launch per layer (and a read of dW for the few layers whose contraction is not split)
             "importance": {"bound": "hbm", "achieved": round(imp_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                            "frac": round(imp_gbps / PEAK_HBM_GBPS, 4), "launches": n_launch["importance"],
-                           "ms_per_step": round(ms["importance"] / steps, 4), "fused_into": "dw split reduction"},
+                           "ms_per_step": round(ms["importance"] / steps, 4), "fused_into": "dw split reduction",
+                           "note": "no read of dW is left: the time is one finishing launch per layer; achieved = 4*N_w over "
+                                   "that time (the stand-alone kernel's HBM rate is next.grad_importance_batched)"},
             "dw": {"ms_per_step": round(dw_stage_ms / steps, 4), "tflops_dense_equiv": round(dw_tf_stage, 3)},
             # layers with few kept elements (fp32 3x3 stride 1, <= 17 - 22 % kept): the sum of Eq. 2 over the kept elements
             # only, on the vector ALU; achieved = multiply-adds actually done (with the kernel's own pre-pass and reduction)
@@ -221,6 +223,17 @@ def next_rows(extras, torch, surgeon, wl, dev, cfg):
     out["da"] = {"bound": "mfma", "achieved": round(tf, 3), "peak": PEAK_MFMA_TFLOPS["f32"], "unit": "TFLOP/s",
                  "frac": round(tf / PEAK_MFMA_TFLOPS["f32"], 4), "ms": round(p["da"][0], 4), "launches": p["da"][1],
                  "note": "fp32 matrix cores for both dtypes (bf16 widened while staging)"}
+
+    # Eq. 4 as a call of its own over every layer's dW (the path above computes it inside the weight-gradient call and
+    # never reads dW again; this is the stand-alone, HBM-bound kernel for callers that have dW from elsewhere)
+    dWs = [e["dW"].reshape(-1) for e in st]
+    G_all = torch.empty(len(st), device=dev)
+    ws_gi = torch.empty(max(surgeon.surgeon_grad_importance_batched_ws_bytes(dWs), 16), dtype=torch.uint8, device=dev)
+    p = timed(lambda: surgeon.surgeon_grad_importance_batched(dWs, G_all, ws_gi))
+    gb = _rate(4.0 * sum(e["L"].n_w for e in st), p["importance"][0]) / 1e9
+    out["grad_importance_batched"] = {"bound": "hbm", "achieved": round(gb, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                      "frac": round(gb / PEAK_HBM_GBPS, 4), "ms": round(p["importance"][0], 4),
+                                      "launches": p["importance"][1]}
 
     # gradient step W <- W - lr dW (Alg. 1 line 14)
     def run_update():  # all layers in one call (at most 64 tensors per launch)

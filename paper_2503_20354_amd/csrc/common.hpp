@@ -103,7 +103,8 @@ int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, con
                        int64_t rows_per_split, int wide, hipStream_t st);
 int launch_conv1x1_bf16(int Nb, int Ci, int Co, int HW, const void* A_dense, const void* dY, float* out, int splits,
                         int64_t ktiles_per_split, hipStream_t st);
-// dense bf16 contraction with a 256 (out) x 128 (in) workgroup tile of eight wavefronts, for layers that fill it (dw_bf16.hip)
+// dense bf16 contraction with a 256 (out) x 128 (in) workgroup tile of eight wavefronts and LDS-direct loads, for layers
+// that fill it (dw_bf16.hip)
 int launch_linear_bf16_big(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,
                            int64_t rows_per_split, hipStream_t st);
 constexpr int kBf16BigTileO = 256, kBf16BigTileI = 128, kBf16BigTokens = 64;

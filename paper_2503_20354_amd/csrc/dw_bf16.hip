@@ -326,34 +326,68 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
 
 // ---------------------------------------------------------------------------------------------------------
 // The same contraction for layers that fill a 256 x 128 tile: eight wavefronts (two per SIMD) as 4 (out) x 2 (in), each
-// owning 2 x 2 matrix tiles of 32 x 32; 64 tokens per K-tile, two LDS buffers, one workgroup per compute unit.
-// What was measured on the chip and shapes this kernel:
+// owning 2 x 2 matrix tiles of 32 x 32; 64 tokens per K-tile; one workgroup per compute unit.
+//
+// K-tiles go from memory straight into LDS (buffer loads with the `lds` bit: lane l of a wavefront delivers its 16
+// bytes at M0 + 16 l), so no registers and no LDS store instructions are spent on staging, and three unpadded K-tile
+// buffers of 48 KB fit: two K-tiles are in flight behind the one being multiplied.  A load instruction covers 1024
+// contiguous LDS bytes (two token rows of the dY tile, four of the input tile), so rows cannot be padded against bank
+// conflicts; instead the four 64-byte segments that the transposing reads of four consecutive tokens touch are spread
+// over the banks by storing segment s of token t at position s ^ (t & 3) (the lanes of a load fetch the permuted
+// source chunk; the reads apply the same permutation).
+// The loads are inline asm (the compiler would otherwise wait for every outstanding LDS-direct load before any LDS
+// read): this kernel counts its own vmcnt.  Nothing else in the loop uses vmcnt.
+//
+// What was measured on the chip and shapes this kernel (ViT-B/16 layers, 12 608 tokens):
 //   * two wavefronts per SIMD drive the matrix pipeline at 2.4 PFLOP/s (one reaches 1.95), and one operand read of
 //     16 bytes per lane and matrix instruction still leaves 2.0 as long as a read is requested one K-step before it
 //     is used: the LDS port is not the bound, so the operands of K-step s+1 are read before the matrix work of step s;
-//   * a K-tile's trip from memory (streaming 48 KB through the vector memory path, the latency of the last load, the
-//     LDS store, the barrier) takes about as long as four K-tiles of matrix work, and with one K-tile in flight the
-//     kernel ran at the speed of that trip.  Two register sets keep two K-tiles in flight; the 256 x 256 tile (half
-//     the dY traffic) has room for one set only and was slower (69 against 65 us on a 2304 x 768 layer);
-//   * keeping all tiles of a split on one XCD (one L2) changed nothing: L2 misses are 134 MB per launch against 77 MB
-//     of distinct operand bytes, far from any bandwidth limit.
-// The 256 x 128 tile also halves the partial tiles a split contraction writes and re-reads: their total size is the
-// accumulator capacity in use on the chip.
+//   * a K-tile's trip from memory takes about as long as four K-tiles of matrix work.  The first version staged
+//     K-tiles through two register sets (global -> registers -> LDS stores, rows padded by 32 elements) and ran at
+//     590-700 TFLOP/s; the LDS-direct loads, which free the registers and remove the store phase, reach 870-890;
+//   * whole splits per XCD (xcd_ordered_work_item): 627 -> 697 TFLOP/s on the register-staged version, L2 misses per
+//     launch halved (373 -> 167 MB);
+//   * more K-tiles in flight do not help further: 32-token K-tiles in six buffers (five in flight) run at the speed of
+//     64-token K-tiles in three; one extra load per wavefront that touches the lines of a K-tile several tiles ahead
+//     (an L2 prefetch) is slower (loads return in order, so the LDS-direct loads queue behind it);
+//   * a 256 x 256 tile (32 tokens, four buffers; a third fewer operand bytes per flop) reaches 965 TFLOP/s as a
+//     kernel, but a split contraction writes and re-reads partial tiles whose total size is the accumulator capacity in
+//     use on the chip, twice as much with this tile: the layer as a whole is no faster, so it is not built in.
 // ---------------------------------------------------------------------------------------------------------
-constexpr int kBigTO = 256, kBigTok = 64;
-// Row padding of 32 elements: the row stride is 16 banks (mod 64), so the 4 token rows x 64 bytes that one half of a
-// transposing read touches cover all 64 banks exactly once (with 16 elements of padding neighbouring rows overlap by
-// half and the LDS spent as long on bank conflicts as on the reads themselves).
-constexpr int kBigPad = 32;
-constexpr size_t big_lds_bytes(int ti) { return (size_t)2 * kBigTok * ((kBigTO + kBigPad) + (ti + kBigPad)) * sizeof(uint16_t); }
+constexpr int kBigTO = 256;
+
+template <int TI>
+struct BigShape {
+  static constexpr int TOK = kBf16BigTokens;                 // tokens per K-tile
+  static constexpr int NBUF = (144 * 1024) / (TOK * (kBigTO + TI) * 2) > 6 ? 6 : (144 * 1024) / (TOK * (kBigTO + TI) * 2);  // K-tile buffers in LDS
+  static constexpr int YROW = kBigTO * 2, AROW = TI * 2;     // row bytes
+  static constexpr int YBYTES = TOK * YROW, ABYTES = TOK * AROW;
+  static constexpr int BUF = YBYTES + ABYTES;                // 48 KB / 32 KB
+  static constexpr int YI = YBYTES / 1024 / 8, AI = ABYTES / 1024 / 8;  // load instructions per wavefront and K-tile
+  static constexpr int LOADS = YI + AI;
+  static constexpr size_t LDS = (size_t)NBUF * BUF;          // 144 KB / 128 KB
+};
+
+__device__ __forceinline__ void lds_direct_load16(uint32_t lds_byte, uint32_t voff, u32x4 rsrc) {
+  // One wait state between the scalar write of M0 and the LDS-direct load that reads it.  M0 is a register the compiler
+  // reserves and writes itself right before the few instructions that read it; the kernel below contains none of those,
+  // so nothing else depends on its value.
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_byte), "v"(voff), "s"(rsrc) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt");
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
 
 template <int TI>
 __global__ __launch_bounds__(512) void dw_linear_bf16_big_kernel(int64_t M, int64_t K, int64_t N, int i_tiles,
                                                                  int64_t rows_per_split, const uint16_t* __restrict__ A,
                                                                  const uint16_t* __restrict__ dY, float* __restrict__ out) {
-  constexpr int SO = kBigTO + kBigPad, SI = TI + kBigPad, NB = TI / 64;
-  constexpr int CY = kBigTok * kBigTO / 8 / 512, CA = kBigTok * TI / 8 / 512;  // 16-byte chunks per thread and K-tile
-  constexpr int BUF = kBigTok * (SO + SI);
+  using S = BigShape<TI>;
+  constexpr int NB = TI / 64, TOK = S::TOK, NBUF = S::NBUF, YROW = S::YROW, AROW = S::AROW, YBYTES = S::YBYTES;
+  constexpr int ACH = AROW / 16;  // 16-byte chunks per input row
   extern __shared__ __attribute__((aligned(16))) uint16_t big_lds[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -372,127 +406,100 @@ __global__ __launch_bounds__(512) void dw_linear_bf16_big_kernel(int64_t M, int6
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[a][b][q] = 0.0f;
 
-  // Two register sets of staged chunks: the loads of K-tile t+2 are issued while tile t is multiplied and tile t+1
-  // waits in the other set, so every load has two tiles' worth of matrix time to arrive (one tile is about as long
-  // as a trip to memory, and with a single set the kernel ran at the speed of that trip).
-  // All global reads are buffer loads: a 32-bit byte offset per chunk that never changes (row inside the K-tile, column),
-  // the K-tile's first token in the scalar offset, and the hardware range check instead of compares and selects: the
-  // resources end with this split's last token (rows past it read 0) and a column past the matrix has an offset that is
-  // out of range for every buffer (the host takes this kernel only for operands below 2 GiB).
-  constexpr int DEPTH = TI == 128 ? 2 : 1;  // register sets of staged chunks (the wide tile has room for one)
-  u32x4 ry[DEPTH][CY], ra[DEPTH][CA];
-  const __amdgpu_buffer_rsrc_t r_dy = __builtin_amdgcn_make_buffer_rsrc((void*)dY, 0, (int)(m_end * N * 2), 0x00020000);
-  const __amdgpu_buffer_rsrc_t r_a = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, (int)(m_end * K * 2), 0x00020000);
-  uint32_t vy[CY], va[CA];
+  // Resources end at the split's last row.  The whole byte offset travels in the vector offset, which the hardware
+  // checks against that size: rows past the split's end (the last K-tile, and the loads issued past it) read zeros.
+  const uint64_t p_dy = (uint64_t)dY, p_a = (uint64_t)A;
+  const u32x4 r_dy = {(uint32_t)p_dy, (uint32_t)(p_dy >> 32) & 0xffffu, (uint32_t)(m_end * N * 2), 0x00020000u};
+  const u32x4 r_a = {(uint32_t)p_a, (uint32_t)(p_a >> 32) & 0xffffu, (uint32_t)(m_end * K * 2), 0x00020000u};
+  // this wavefront's loads of a K-tile: dY instructions YI wave .. (two tokens each), input instructions AI wave ..
+  // (1024 / AROW tokens each); per lane the source byte offset inside the K-tile's rows, 0x80000000 = no access
+  uint32_t vy[S::YI], va[S::AI];
 #pragma unroll
-  for (int j = 0; j < CY; ++j) {
-    const int c = tid + 512 * j, row = c / (kBigTO / 8), col = (c % (kBigTO / 8)) * 8;
-    vy[j] = o0 + col < N ? (uint32_t)((row * N + o0 + col) * 2) : 0x80000000u;
+  for (int j = 0; j < S::YI; ++j) {
+    const int tok = 2 * (S::YI * wave + j) + (lane >> 5), c = lane & 31;
+    const int lc = (((c >> 2) ^ (tok & 3)) << 2) | (c & 3);  // source chunk that belongs at chunk position c of this token
+    vy[j] = o0 + lc * 8 < N ? (uint32_t)((tok * N + o0 + lc * 8) * 2) : 0x80000000u;
   }
 #pragma unroll
-  for (int j = 0; j < CA; ++j) {
-    const int c = tid + 512 * j, row = c / (TI / 8), col = (c % (TI / 8)) * 8;
-    va[j] = i0 + col < K ? (uint32_t)((row * K + i0 + col) * 2) : 0x80000000u;
+  for (int j = 0; j < S::AI; ++j) {
+    const int tok = (64 / ACH) * (S::AI * wave + j) + lane / ACH, c = lane % ACH;
+    const int lc = (((c >> 2) ^ (tok & 3)) << 2) | (c & 3);
+    va[j] = i0 + lc * 8 < K ? (uint32_t)((tok * K + i0 + lc * 8) * 2) : 0x80000000u;
   }
-  auto load_tile = [&](int set, int64_t m0) {
-    const uint32_t sy = (uint32_t)(m0 * N * 2), sa = (uint32_t)(m0 * K * 2);
+  auto load_tile = [&](int buf, int64_t m0) {
+    // past 2 GiB the sum wraps into "no access" or stays above every resource size: the operands are below 2 GiB
+    const uint32_t sy = (uint32_t)min(m0 * N * 2, (int64_t)0x7fffffff), sa = (uint32_t)min(m0 * K * 2, (int64_t)0x7fffffff);
+    const uint32_t base = (uint32_t)(buf * S::BUF);
 #pragma unroll
-    for (int j = 0; j < CY; ++j) ry[set][j] = __builtin_amdgcn_raw_buffer_load_b128(r_dy, vy[j], sy, 0);
+    for (int j = 0; j < S::YI; ++j) lds_direct_load16(base + (uint32_t)((S::YI * wave + j) * 1024), vy[j] >= 0x80000000u ? vy[j] : vy[j] + sy, r_dy);
 #pragma unroll
-    for (int j = 0; j < CA; ++j) ra[set][j] = __builtin_amdgcn_raw_buffer_load_b128(r_a, va[j], sa, 0);
+    for (int j = 0; j < S::AI; ++j) lds_direct_load16(base + (uint32_t)(YBYTES + (S::AI * wave + j) * 1024), va[j] >= 0x80000000u ? va[j] : va[j] + sa, r_a);
   };
-  auto store_tile = [&](int set, int buf) {
-    uint16_t* ys = big_lds + buf * BUF;
-    uint16_t* as = ys + kBigTok * SO;
-#pragma unroll
-    for (int j = 0; j < CY; ++j) {
-      const int c = tid + 512 * j, row = c / (kBigTO / 8), col = (c % (kBigTO / 8)) * 8;
-      *reinterpret_cast<u32x4*>(&ys[row * SO + col]) = ry[set][j];
-    }
-#pragma unroll
-    for (int j = 0; j < CA; ++j) {
-      const int c = tid + 512 * j, row = c / (TI / 8), col = (c % (TI / 8)) * 8;
-      *reinterpret_cast<u32x4*>(&as[row * SI + col]) = ra[set][j];
-    }
-  };
-  // LDS address of a lane's first transposing read in each buffer: everything that depends on the lane or the
-  // wavefront is in these four pointers, the K-step and the matrix tile are compile-time offsets of the read
+
+  // LDS byte offsets of a lane's transposing reads inside a K-tile buffer, per matrix tile q of the wavefront
   typedef shortx4 __attribute__((address_space(3))) * lds_ptr;
-  const int blk = lane >> 4, s16 = lane & 15;  // 16-lane block: rows 16*(blk&1).., contraction half blk>>1
+  const int blk = lane >> 4, s16 = lane & 15;
   const int lane_tok = 8 * (blk >> 1) + (s16 >> 2), lane_col = 16 * (blk & 1) + 4 * (s16 & 3);
-  lds_ptr py[2], pa[2];
+  const int tl = lane_tok & 3;  // (token & 3) of every read of this lane: K-steps and the +4 rows keep it
+  uint32_t yoff[2], aoff[NB];
 #pragma unroll
-  for (int bq = 0; bq < 2; ++bq) {
-    py[bq] = (lds_ptr)(big_lds + bq * BUF + lane_tok * SO + wo * 64 + lane_col);
-    pa[bq] = (lds_ptr)(big_lds + bq * BUF + kBigTok * SO + lane_tok * SI + wi * (TI / 2) + lane_col);
-  }
+  for (int q = 0; q < 2; ++q) yoff[q] = (uint32_t)(lane_tok * YROW + (((wo * 2 + q) ^ tl) << 6) + lane_col * 2);
+#pragma unroll
+  for (int q = 0; q < NB; ++q) aoff[q] = (uint32_t)(YBYTES + lane_tok * AROW + (((wi * NB + q) ^ tl) << 6) + lane_col * 2);
+  char __attribute__((address_space(3))) * const lds_base = (char __attribute__((address_space(3))) *)big_lds;
+
   auto mfma_tile = [&](int buf) {
-    // the narrow tile has registers to spare: operands of K-step s+1 are read before the matrix instructions of step s
-    constexpr int SETS = TI == 128 ? 2 : 1;
-    bf16x8 a[SETS][2], b[SETS][NB];
-    auto read8 = [&](lds_ptr p, int elem_off, int stride) {
-      const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(p + elem_off / 4);
-      const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(p + (elem_off + 4 * stride) / 4);
+    bf16x8 a[2][2], b[2][NB];
+    auto read8 = [&](uint32_t byte_off, int row_bytes) {
+      const shortx4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds_base + byte_off));
+      const shortx4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(lds_base + byte_off + 4 * row_bytes));
       typedef short shortx8 __attribute__((ext_vector_type(8)));
       const shortx8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       return __builtin_bit_cast(bf16x8, both);
     };
     auto read_step = [&](int set, int ks) {
 #pragma unroll
-      for (int q = 0; q < 2; ++q) a[set][q] = read8(py[buf], ks * SO + q * 32, SO);
+      for (int q = 0; q < 2; ++q) a[set][q] = read8(yoff[q] + (uint32_t)(buf * S::BUF + ks * YROW), YROW);
 #pragma unroll
-      for (int q = 0; q < NB; ++q) b[set][q] = read8(pa[buf], ks * SI + q * 32, SI);
+      for (int q = 0; q < NB; ++q) b[set][q] = read8(aoff[q] + (uint32_t)(buf * S::BUF + ks * AROW), AROW);
     };
-    if (SETS == 2) read_step(0, 0);
+    read_step(0, 0);
 #pragma unroll
-    for (int s = 0; s < kBigTok / 16; ++s) {
-      if (SETS == 1) read_step(0, 16 * s);
-      else if (s + 1 < kBigTok / 16) read_step((s + 1) & 1, 16 * (s + 1));
+    for (int s = 0; s < TOK / 16; ++s) {
+      if (s + 1 < TOK / 16) read_step((s + 1) & 1, 16 * (s + 1));
 #pragma unroll
       for (int p = 0; p < 2; ++p)
 #pragma unroll
         for (int q = 0; q < NB; ++q)
-          acc[p][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s & (SETS - 1)][p], b[s & (SETS - 1)][q], acc[p][q], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);  // keeps the reads of later K-steps from piling up in registers
+          acc[p][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s & 1][p], b[s & 1][q], acc[p][q], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  const int64_t n_kt = m_begin < m_end ? (m_end - m_begin + kBigTok - 1) / kBigTok : 0;
+  const int64_t n_kt = m_begin < m_end ? (m_end - m_begin + TOK - 1) / TOK : 0;
+  // Every step issues the same number of loads (tiles past the split's end read zeros into a buffer nobody reads
+  // again), so one constant tells when a tile has landed: loads return in order, and the LOADS of the tile wanted next
+  // are followed by the (NBUF - 2) * LOADS of the younger tiles.
   if (n_kt > 0) {
-    load_tile(0, m_begin);
-    store_tile(0, 0);
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u) load_tile(u, m_begin + (int64_t)u * TOK);
+    wait_vmcnt<(NBUF - 2) * S::LOADS>();  // tile 0
   }
-  if constexpr (DEPTH == 2) {
-    if (n_kt > 1) load_tile(1, m_begin + kBigTok);
-    __syncthreads();
-    // tile t sits in LDS buffer t % 2; tile t+1 in register set (t+1) % 2; tile t+2 is requested into set t % 2
-    for (int64_t t = 0; t < n_kt; t += 2) {
-      if (t + 2 < n_kt) load_tile(0, m_begin + (t + 2) * kBigTok);
-      mfma_tile(0);
-      if (t + 1 < n_kt) store_tile(1, 1);
-      __syncthreads();
-      if (t + 1 >= n_kt) break;
-      if (t + 3 < n_kt) load_tile(1, m_begin + (t + 3) * kBigTok);
-      mfma_tile(1);
-      if (t + 2 < n_kt) store_tile(0, 0);
-      __syncthreads();
-    }
-  } else {
-    __syncthreads();
-    for (int64_t t = 0; t < n_kt; t += 2) {
-      if (t + 1 < n_kt) load_tile(0, m_begin + (t + 1) * kBigTok);
-      mfma_tile(0);
-      if (t + 1 < n_kt) store_tile(0, 1);
-      __syncthreads();
-      if (t + 1 >= n_kt) break;
-      if (t + 2 < n_kt) load_tile(0, m_begin + (t + 2) * kBigTok);
-      mfma_tile(1);
-      if (t + 2 < n_kt) store_tile(0, 0);
+  __syncthreads();
+  // tile t sits in buffer t % NBUF; tiles t + 1 .. t + NBUF - 1 are on their way into the others
+  for (int64_t t = 0; t < n_kt; t += NBUF) {
+#pragma unroll
+    for (int u = 0; u < NBUF; ++u) {
+      if (t + u >= n_kt) break;
+      // buffer (u + NBUF - 1) % NBUF was last read for tile t + u - 1, and every wavefront has passed the barrier since
+      load_tile((u + NBUF - 1) % NBUF, m_begin + (t + u + NBUF - 1) * TOK);
+      mfma_tile(u);
+      wait_vmcnt<(NBUF - 2) * S::LOADS>();  // tile t + u + 1 has landed
       __syncthreads();
     }
   }
+  wait_vmcnt<0>();  // the loads past the end have written their zeros before the LDS is given up
 
-  // 32x32 result tile: lane holds column lane%32 and rows 8*(v/4) + 4*(lane/32) + v%4, v = 0..15
   float* __restrict__ dst = out + (int64_t)split_id * N * K;
   const int col = lane & 31, half = lane >> 5;
 #pragma unroll
@@ -511,13 +518,14 @@ __global__ __launch_bounds__(512) void dw_linear_bf16_big_kernel(int64_t M, int6
 int launch_linear_bf16_big(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,
                            int64_t rows_per_split, hipStream_t st) {
   constexpr int TI = kBf16BigTileI;
+  static_assert(BigShape<TI>::TOK == kBf16BigTokens, "the planner sizes splits in K-tiles of this many tokens");
   const int i_tiles = (int)ceil_div(K, TI), o_tiles = (int)ceil_div(N, kBigTO);
   const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
   ProfScope prof(SURGEON_PROF_DW, st);
   static std::atomic<uint64_t> lds_set{0};
-  const int rc_lds = ensure_dynamic_lds((const void*)dw_linear_bf16_big_kernel<TI>, big_lds_bytes(TI), lds_set);
+  const int rc_lds = ensure_dynamic_lds((const void*)dw_linear_bf16_big_kernel<TI>, BigShape<TI>::LDS, lds_set);
   if (rc_lds != SURGEON_OK) return rc_lds;
-  SURGEON_LAUNCH(dw_linear_bf16_big_kernel<TI>, grid, dim3(512), big_lds_bytes(TI), st, M, K, N, i_tiles, rows_per_split,
+  SURGEON_LAUNCH(dw_linear_bf16_big_kernel<TI>, grid, dim3(512), BigShape<TI>::LDS, st, M, K, N, i_tiles, rows_per_split,
                  (const uint16_t*)A_dense, (const uint16_t*)dY, out);
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
