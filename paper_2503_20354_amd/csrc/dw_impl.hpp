@@ -468,9 +468,10 @@ struct RunStager {
 #pragma unroll
       for (int j = 0; j < NY; ++j) y[j] = DyVec<InT>::load(r_dy, y_voff[j], y_soff);
     } else {
-      // The hardware range check covers the VGPR offset only (not the scalar offset), so the whole offset goes there,
-      // and the resource of this K-tile ends with the last channel of image b: output channels past Co (last co tile)
-      // are then out of range and read 0 instead of the next image or memory behind dY.
+      // The range check is documented for the VGPR offset only (the compiler's buffer intrinsics exclude the scalar
+      // offset from it; gfx950 was measured to include it, which this code does not rely on), so the whole offset goes
+      // there, and the resource of this K-tile ends with the last channel of image b: output channels past Co (last co
+      // tile) are then out of range and read 0 instead of the next image or memory behind dY.
       const uint32_t step = (uint32_t)((kConvLoaders / P) * gm.OH * gm.OW) * ES;
       const __amdgpu_buffer_rsrc_t r_img = __builtin_amdgcn_make_buffer_rsrc(
           (void*)dy_ptr, 0, (int)((uint32_t)((b + 1) * gm.Co * gm.OH * gm.OW) * ES), kRawBufferWord3);
