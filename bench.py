@@ -224,6 +224,26 @@ def next_rows(extras, torch, surgeon, wl, dev, cfg):
                  "frac": round(tf / PEAK_MFMA_TFLOPS["f32"], 4), "ms": round(p["da"][0], 4), "launches": p["da"][1],
                  "note": "fp32 matrix cores for both dtypes (bf16 widened while staging)"}
 
+    # the same gradient for bf16 linear layers on the bf16 matrix cores (workspace entry), on the four layer shapes of a
+    # ViT-B/16 block at 12 608 tokens
+    rows, t_ms, fl = [], 0.0, 0.0
+    for name, (M, K, N) in {"qkv": (12608, 768, 2304), "proj": (12608, 768, 768), "fc1": (12608, 768, 3072),
+                            "fc2": (12608, 3072, 768)}.items():
+        dYb = wl.draw((M, N), "normal", "bf16", 77, device=dev)
+        Wb = (wl.draw((N, K), "normal", "bf16", 78, device=dev) * 0.05).to(torch.bfloat16)
+        dAb = torch.empty((M, K), dtype=torch.bfloat16, device=dev)
+        d = surgeon.linear_desc(M, K, N, surgeon.BF16, 0)
+        wsb = torch.empty(surgeon.surgeon_da_ws_bytes(d), dtype=torch.uint8, device=dev)
+        p = timed(lambda: surgeon.surgeon_da_ws(d, dYb, Wb, dAb, wsb))
+        t_ms += p["da"][0]
+        fl += 2.0 * M * K * N
+        rows.append((name, round(p["da"][0] * 1e3, 1)))
+        del dYb, Wb, dAb, wsb
+    tf = _rate(fl, t_ms) / 1e12
+    out["da_bf16_linear"] = {"bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_MFMA_TFLOPS["bf16"], "unit": "TFLOP/s",
+                             "frac": round(tf / PEAK_MFMA_TFLOPS["bf16"], 4), "ms": round(t_ms, 4),
+                             "us_per_layer": dict(rows), "what": "transpose of dY + contraction + finishing kernel"}
+
     # Eq. 4 as a call of its own over every layer's dW (the path above computes it inside the weight-gradient call and
     # never reads dW again; this is the stand-alone, HBM-bound kernel for callers that have dW from elsewhere)
     dWs = [e["dW"].reshape(-1) for e in st]

@@ -205,6 +205,18 @@ int surgeon_dw_from_packed_gi(const surgeon_layer_desc* desc, const void* vals, 
 int surgeon_da(const surgeon_layer_desc* desc, const void* dY, const void* W, void* dA, void* stream);
 
 /*
+ * The same gradient with a workspace, which lets bf16 linear layers run on the bf16 matrix cores: for LINEAR, bf16,
+ * M >= 256, M and K multiples of 8, N and K >= 64 and every operand below 2 GiB, dY is transposed once into `ws` and
+ * the contraction runs as the bf16 weight-gradient kernel does (fp32 accumulation, one rounding to bf16; the summation
+ * order differs from surgeon_da's, the result agrees to within one bf16 rounding).  Every other layer takes
+ * surgeon_da's route and needs no workspace (surgeon_da_ws_bytes reports 0).  W must then be 16-byte aligned.
+ * ws_bytes smaller than reported: SURGEON_ESIZE.  Deterministic.
+ */
+int surgeon_da_ws_bytes(const surgeon_layer_desc* desc, size_t* ws_bytes);
+int surgeon_da_ws(const surgeon_layer_desc* desc, const void* dY, const void* W, void* dA, void* ws, size_t ws_bytes,
+                  void* stream);
+
+/*
  * Alg. 1 line 14 as one plain gradient step, in place: W[j] <- W[j] - lr * dW[j] (the paper leaves its optimiser to an
  * appendix; anything more elaborate is the caller's).  W: n elements of dtype dt on the device; dW: n fp32 on the
  * device.  Computed as one fused multiply-add in fp32, bf16 weights rounded once to nearest even.

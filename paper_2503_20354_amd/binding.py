@@ -73,6 +73,10 @@ def load_library():
     L.surgeon_dw_from_packed_gi.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, vp, vp, sz, vp]
     L.surgeon_da.restype = ci
     L.surgeon_da.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp]
+    L.surgeon_da_ws_bytes.restype = ci
+    L.surgeon_da_ws_bytes.argtypes = [ctypes.POINTER(LayerDesc), ctypes.POINTER(sz)]
+    L.surgeon_da_ws.restype = ci
+    L.surgeon_da_ws.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, vp, sz, vp]
     L.surgeon_weight_update.restype = ci
     L.surgeon_weight_update.argtypes = [vp, vp, i64, f32, ci, vp]
     L.surgeon_weight_update_batched.restype = ci
@@ -236,6 +240,21 @@ def surgeon_da(desc: LayerDesc, dY, W, dA):
         if _dt(t) != desc.dtype:
             raise TypeError("%s does not have the layer's dtype" % name)
     _check(load_library().surgeon_da(ctypes.byref(desc), _ptr(dY), _ptr(W), _ptr(dA), _stream(dY.device)))
+
+
+def surgeon_da_ws_bytes(desc: LayerDesc) -> int:
+    wb = ctypes.c_size_t()
+    _check(load_library().surgeon_da_ws_bytes(ctypes.byref(desc), ctypes.byref(wb)))
+    return wb.value
+
+
+def surgeon_da_ws(desc: LayerDesc, dY, W, dA, ws):
+    """Eq. 2, first line, with a workspace: bf16 linear layers run on the bf16 matrix cores."""
+    for t, name in ((dY, "dY"), (W, "W"), (dA, "dA")):
+        _dev(t, name)
+    ws_bytes = 0 if ws is None else ws.numel() * ws.element_size()
+    _check(load_library().surgeon_da_ws(ctypes.byref(desc), _ptr(dY), _ptr(W), _ptr(dA), _ptr(ws), ws_bytes,
+                                        _stream(dY.device)))
 
 
 def surgeon_weight_update(W, dW, lr: float):

@@ -34,6 +34,13 @@ struct ProfScope {
   ~ProfScope();
   int prev_;
 };
+// While one lives, the launches of this thread are booked under `kind` whatever class their own ProfScope names (a
+// kernel shared by two entry points is then timed with the entry point that called it).
+struct ProfForce {
+  explicit ProfForce(int kind);
+  ~ProfForce();
+  int prev_;
+};
 // true while profiling is on and a class is current: hands out the two events of the next kernel
 bool prof_next_events(hipEvent_t* start, hipEvent_t* stop);
 

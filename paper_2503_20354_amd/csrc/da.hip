@@ -273,6 +273,71 @@ __global__ __launch_bounds__(256) void weight_update_batched_kernel(UpdateBatch 
   }
 }
 
+// ---- bf16 linear layers on the bf16 matrix cores ---------------------------------------------------------------
+// dA[m][k] = sum_n dY[m][n] * W[n][k] is the contraction of the bf16 weight-gradient kernel (out[o][i] = sum_t
+// Y[t][o] * X[t][i], the contraction index slow in both operands) with t = n, Y = dY transposed, X = W.  dY is
+// transposed once into the workspace (2 bytes read and written per element), the 256 x 128 kernel writes fp32 (partial)
+// results, and a finishing kernel adds the splits in index order and rounds once to bf16.
+
+// out[c][r] = in[r][c] for a [R][C] matrix of 2-byte elements: 64 x 64 tiles through LDS
+__global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
+                                                          int64_t R, int64_t C) {
+  __shared__ uint16_t tile[64][66];
+  const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int64_t r = r0 + ty + 4 * j, c = c0 + tx;
+    tile[ty + 4 * j][tx] = (r < R && c < C) ? in[r * C + c] : (uint16_t)0;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int64_t c = c0 + ty + 4 * j, r = r0 + tx;
+    if (c < C && r < R) out[c * R + r] = tile[tx][ty + 4 * j];
+  }
+}
+
+__global__ __launch_bounds__(256) void da_finish_bf16_kernel(const float* __restrict__ part, int splits, int64_t n,
+                                                             uint16_t* __restrict__ dA) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    float v = part[i];
+    for (int s = 1; s < splits; ++s) v += part[(int64_t)s * n + i];
+    dA[i] = f32_to_bf16_rne(v);
+  }
+}
+
+struct DaFastPlan {
+  bool ok;
+  int splits;
+  int64_t rows_per_split;
+  size_t off_part, ws_bytes;
+};
+
+// the bf16 matrix-core route needs 16-byte rows in both operands and 32-bit byte offsets
+static DaFastPlan plan_da_fast(const surgeon_layer_desc* d) {
+  DaFastPlan p;
+  p.ok = false;
+  p.splits = 0;
+  p.rows_per_split = 0;
+  p.off_part = p.ws_bytes = 0;
+  const int64_t big = (int64_t)1 << 31;
+  if (d->kind != SURGEON_LINEAR || d->dtype != SURGEON_BF16) return p;
+  if (d->M < 256 || d->K < 64 || d->N < 64 || d->M % 8 || d->K % 8) return p;
+  if (d->M * d->N * 2 >= big || d->N * d->K * 2 >= big || d->M * d->K * 4 >= big) return p;
+  const int64_t tiles = ceil_div(d->M, kBf16BigTileO) * ceil_div(d->K, kBf16BigTileI);
+  const int64_t k_tiles = ceil_div(d->N, kBf16BigTokens);
+  // one round of workgroups on the chip's 256 compute units; a split is at least four K-tiles long
+  int64_t splits = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(256 / std::max<int64_t>(tiles, 1), k_tiles / 4), 16));
+  const int64_t per = ceil_div(k_tiles, splits);
+  p.splits = (int)ceil_div(k_tiles, per);
+  p.rows_per_split = per * kBf16BigTokens;
+  p.off_part = align_up((size_t)d->M * d->N * 2, 256);
+  p.ws_bytes = p.off_part + align_up((size_t)p.splits * d->M * d->K * 4, 256);
+  p.ok = true;
+  return p;
+}
+
 }  // namespace surgeon
 
 using namespace surgeon;
@@ -323,7 +388,8 @@ extern "C" int surgeon_weight_update_batched(int l, void* const* Wt, const float
   return flush();
 }
 
-extern "C" int surgeon_da(const surgeon_layer_desc* d, const void* dY, const void* Wt, void* dA, void* stream) {
+static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt, void* dA, void* ws, size_t ws_bytes,
+                    bool use_ws, void* stream) {
   if (!d) return fail(SURGEON_EINVAL, "da: null descriptor");
   if (d->dtype != SURGEON_F32 && d->dtype != SURGEON_BF16) return fail(SURGEON_EINVAL, "da: bad dtype");
   DaGeom g;
@@ -362,10 +428,38 @@ extern "C" int surgeon_da(const surgeon_layer_desc* d, const void* dY, const voi
   if (!dY || !Wt || !dA) return fail(SURGEON_EINVAL, "da: null pointer");
   const size_t es = d->dtype == SURGEON_F32 ? 4 : 2;
   if (((uintptr_t)dY % es) || ((uintptr_t)Wt % es) || ((uintptr_t)dA % es)) return fail(SURGEON_EINVAL, "da: misaligned pointer");
+  hipStream_t st = (hipStream_t)stream;
+  if (use_ws) {
+    const DaFastPlan fp = plan_da_fast(d);
+    if (fp.ok) {
+      if (!ws || ws_bytes < fp.ws_bytes)
+        return fail(SURGEON_ESIZE, "da: workspace of %zu bytes needed, %zu given", fp.ws_bytes, ws_bytes);
+      if (((uintptr_t)ws % 16) || ((uintptr_t)Wt % 16)) return fail(SURGEON_EINVAL, "da: workspace / W not 16-byte aligned");
+      uint16_t* dYt = (uint16_t*)ws;
+      float* part = (float*)((char*)ws + fp.off_part);
+      {
+        ProfScope prof(SURGEON_PROF_DA, st);
+        SURGEON_LAUNCH(transpose16_kernel, dim3((unsigned)ceil_div(d->N, 64), (unsigned)ceil_div(d->M, 64)), dim3(256), 0, st,
+                       (const uint16_t*)dY, dYt, d->M, d->N);
+        SURGEON_LAUNCH_CHECK();
+      }
+      {
+        // contraction over n: "tokens" = N, out-features = M (from dY^T), in-features = K (from W)
+        ProfForce as_da(SURGEON_PROF_DA);
+        const int rc = launch_linear_bf16_big(d->N, d->K, d->M, Wt, dYt, part, fp.splits, fp.rows_per_split, st);
+        if (rc != SURGEON_OK) return rc;
+      }
+      ProfScope prof(SURGEON_PROF_DA, st);
+      const int64_t n_out = d->M * d->K;
+      SURGEON_LAUNCH(da_finish_bf16_kernel, dim3((unsigned)std::min<int64_t>(ceil_div(n_out, 256), 8192)), dim3(256), 0, st,
+                     (const float*)part, fp.splits, n_out, (uint16_t*)dA);
+      SURGEON_LAUNCH_CHECK();
+      return SURGEON_OK;
+    }
+  }
   const int64_t p_tiles = ceil_div(g.P, kDaTP), c_tiles = ceil_div(g.Ci, kDaTC);
   if (p_tiles > 0x7fffffff || c_tiles > 65535) return fail(SURGEON_EUNSUPPORTED, "da: too many tiles");
   const dim3 grid((unsigned)p_tiles, (unsigned)c_tiles);
-  hipStream_t st = (hipStream_t)stream;
   ProfScope prof(SURGEON_PROF_DA, st);
   if (d->dtype == SURGEON_F32) {
     if (linear)
@@ -382,6 +476,22 @@ extern "C" int surgeon_da(const surgeon_layer_desc* d, const void* dY, const voi
   }
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
+}
+
+extern "C" int surgeon_da(const surgeon_layer_desc* d, const void* dY, const void* Wt, void* dA, void* stream) {
+  return da_entry(d, dY, Wt, dA, nullptr, 0, false, stream);
+}
+
+extern "C" int surgeon_da_ws_bytes(const surgeon_layer_desc* d, size_t* ws_bytes) {
+  if (!d || !ws_bytes) return fail(SURGEON_EINVAL, "da_ws_bytes: null pointer");
+  if (d->dtype != SURGEON_F32 && d->dtype != SURGEON_BF16) return fail(SURGEON_EINVAL, "da_ws_bytes: bad dtype");
+  *ws_bytes = plan_da_fast(d).ws_bytes;
+  return SURGEON_OK;
+}
+
+extern "C" int surgeon_da_ws(const surgeon_layer_desc* d, const void* dY, const void* Wt, void* dA, void* ws, size_t ws_bytes,
+                             void* stream) {
+  return da_entry(d, dY, Wt, dA, ws, ws_bytes, true, stream);
 }
 
 extern "C" int surgeon_weight_update(void* Wt, const float* dW, int64_t n, float lr, int dt, void* stream) {

@@ -78,7 +78,10 @@ static bool g_prof_on = false;
 static thread_local int g_prof_kind = -1;  // class of the innermost live ProfScope on this thread
 static std::vector<ProfRecord> g_prof;
 
-ProfScope::ProfScope(int kind, hipStream_t) : prev_(g_prof_kind) { g_prof_kind = kind; }
+static thread_local int g_prof_force = -1;  // class that every ProfScope of this thread books under while a ProfForce lives
+ProfScope::ProfScope(int kind, hipStream_t) : prev_(g_prof_kind) { g_prof_kind = g_prof_force >= 0 ? g_prof_force : kind; }
+ProfForce::ProfForce(int kind) : prev_(g_prof_force) { g_prof_force = kind; }
+ProfForce::~ProfForce() { g_prof_force = prev_; }
 
 ProfScope::~ProfScope() { g_prof_kind = prev_; }
 

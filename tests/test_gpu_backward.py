@@ -130,6 +130,37 @@ def test_da_linear(dtype, M, K, N):
     assert_out_close(bits(dA), ref, dtype, (M, K, N))
 
 
+@pytest.mark.parametrize("M,K,N", [(256, 64, 64), (1000, 768, 96), (520, 320, 1280), (4096, 128, 512), (264, 72, 200),
+                                   (12608, 768, 768), (300, 129, 257), (100, 64, 64)])
+def test_da_linear_with_workspace(M, K, N):
+    """bf16 linear layers through the workspace entry: shapes that take the bf16 matrix cores (several tiles, ragged
+    tiles, a split contraction) and shapes that fall back to the workspace-less route, against the oracle and against
+    surgeon_da to one bf16 rounding."""
+    print("da_ws linear", (M, K, N), flush=True)
+    dY = wl.draw((M, N), "normal", "bf16", M + N + 15)
+    W = (wl.draw((N, K), "normal", "bf16", N + K + 16) * 0.1).to(dY.dtype)
+    desc = surgeon.linear_desc(M, K, N, sdt("bf16"), 0)
+    nb = surgeon.surgeon_da_ws_bytes(desc)
+    fast = M >= 256 and M % 8 == 0 and K % 8 == 0 and K >= 64 and N >= 64
+    assert (nb > 0) == fast
+    ws = torch.empty(max(nb, 16), dtype=torch.uint8, device=DEV)
+    dA = torch.empty((M, K), dtype=dY.dtype, device=DEV)
+    dA2 = torch.empty_like(dA)
+    dYd, Wd = dY.to(DEV), W.to(DEV)
+    surgeon.surgeon_da_ws(desc, dYd, Wd, dA, ws)
+    surgeon.surgeon_da(desc, dYd, Wd, dA2)
+    torch.cuda.synchronize()
+    if M <= 4096:
+        ref = oracle.da_linear(bits(dY), bits(W), M, K, N)
+        assert_out_close(bits(dA), ref, "bf16", (M, K, N))
+    # the two routes differ in fp32 summation order only: at most one bf16 rounding step apart (sums that cancel to
+    # about zero: the absolute floor of the fp32 accumulation, as in assert_out_close)
+    assert_out_close(bits(dA), bits(dA2), "bf16", ("two routes", M, K, N))
+    if fast:
+        with pytest.raises(surgeon.SurgeonError):
+            surgeon.surgeon_da_ws(desc, dYd, Wd, dA, ws[: nb - 256])
+
+
 DA_CONVS = [
     # Nb, Ci, H, W, Co, k, stride, pad
     (2, 16, 32, 32, 160, 3, 1, 1), (2, 160, 16, 16, 160, 3, 1, 1), (2, 160, 32, 32, 320, 3, 2, 1), (2, 16, 32, 32, 160, 1, 1, 0),
