@@ -138,8 +138,8 @@ int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, float r, int
  * bracket, once to pack) instead of five times.  A bracket that misses the threshold is detected on the device and
  * the call then selects over the whole group: the result is bit-identical for every value of the knob, only the time
  * differs.  Default 5 (a miss about once in a million groups); smaller values copy fewer elements and miss more often;
- * negative values make every bracket miss (a test hook for the full-width route).  Process-wide, not synchronised
- * with calls in flight on other threads.  Host only.  Outside [-100, 100]: SURGEON_EINVAL.
+ * negative values make every bracket miss (a test hook for the full-width route).  Process-wide; a call reads the
+ * value once when it starts.  Host only.  Outside [-100, 100]: SURGEON_EINVAL.
  */
 int surgeon_set_select_margin(float deviations);
 

@@ -1356,7 +1356,7 @@ static int run_global(const GroupPlan& p, const void* A, void* vals, uint64_t* m
                                  groups_word_aligned(p), st);
 }
 
-static float g_two_read_margin = 5.0f;
+static std::atomic<float> g_two_read_margin{5.0f};  // read once per call; a plain tuning value, no ordering needed
 
 template <typename BitsT>
 static int run_two_read(const GroupPlan& p, const void* A, void* vals, uint64_t* mask, uint32_t* idx, void* ws,
@@ -1384,7 +1384,7 @@ static int run_two_read(const GroupPlan& p, const void* A, void* vals, uint64_t*
   uint32_t* cand = (uint32_t*)w;
 
   SURGEON_LAUNCH((sel2_bracket_kernel<BitsT>), dim3((unsigned)p.n_groups), dim3(512), 0, st, (const BitsT*)A, p.n, p.g,
-                     p.n_groups, (uint32_t)p.k_full, (uint32_t)p.k_last, g_two_read_margin, sel, hist, replicas);
+                     p.n_groups, (uint32_t)p.k_full, (uint32_t)p.k_last, g_two_read_margin.load(std::memory_order_relaxed), sel, hist, replicas);
   SURGEON_LAUNCH_CHECK();
   const dim3 wgrid((unsigned)ceil_div(n_chunks, 4)), block(256);
   SURGEON_LAUNCH((sel2_collect_kernel<BitsT>), wgrid, block, 0, st, (const BitsT*)A, p.n, p.g, cpg, n_chunks,
@@ -1468,7 +1468,7 @@ extern "C" int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, f
 
 extern "C" int surgeon_set_select_margin(float deviations) {
   if (!(deviations >= -100.0f && deviations <= 100.0f)) return fail(SURGEON_EINVAL, "select margin %g outside [-100, 100]", (double)deviations);
-  g_two_read_margin = deviations;
+  g_two_read_margin.store(deviations, std::memory_order_relaxed);
   return SURGEON_OK;
 }
 
