@@ -218,6 +218,176 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
       }
 }
 
+// ---- 3x3, stride 1, pad 1 convolutions: the taps as shifted reads of one staged patch ---------------------------------
+// dA[b][ci][ih][iw] = sum_{co,u,v} dY[b][co][ih+1-u][iw+1-v] * W[co][ci][u][v].  A workgroup owns a band of R rows of
+// one image (P = R * W = 64 or 128 positions) and a tile of 16 NC input channels, and walks the output channels eight
+// at a time.  Per step it stages the eight channels' dY rows with halo once (zero outside the map) and the eight
+// filters' (ci, tap) blocks -- contiguous in memory -- as [tap][co][ci]; the contraction runs over (tap, co), so a
+// matrix instruction's four contraction elements are four output channels under one tap: the dY operand is the same
+// patch read at a per-tap offset, with no index arithmetic per element.  The next step's values are loaded into
+// registers before the matrix instructions of the current one.  Four wavefronts split the positions.
+constexpr int kDa3Co = 8;         // output channels per step
+
+template <typename T, int NC, int PB>  // NC: 16-channel blocks per tile; PB: 16-position blocks per wavefront (P = 64 PB)
+__global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int PS, const T* __restrict__ dY,
+                                                         const T* __restrict__ Wt, T* __restrict__ dA) {
+  constexpr int CT = 16 * NC;                   // input channels per tile
+  constexpr int WS = CT + 16;                   // LDS stride of a (tap, co) row of the filter tile: 16 banks past a multiple of 32
+  constexpr int TS = kDa3Co * WS + 4;           // ... of a tap: four banks apart, so that staging writes of one channel's taps spread
+  constexpr int WPER = kDa3Co * CT * 9 / 256;   // filter values per thread and step
+  static_assert((kDa3Co * CT * 9) % 256 == 0, "filter tile divides among the threads");
+  extern __shared__ float da3_lds[];
+  float* patch = da3_lds;                       // [co 8][PS]: rows r0-1 .. r0+R, columns -1 .. W
+  float* wt = da3_lds + kDa3Co * PS;            // [tap 9] x TS, inside a tap [co 8][WS]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i16 = lane & 15, kk = lane >> 4;
+  const int PW = g.W + 2, PP = (R + 2) * PW;
+  const int bands = g.H / R;
+  const int b = blockIdx.x / bands, r0 = (blockIdx.x - b * bands) * R;
+  const int ci0 = blockIdx.y * CT;
+  const int64_t hw = g.HW;
+
+  floatx4 acc[NC][PB];
+#pragma unroll
+  for (int a = 0; a < NC; ++a)
+#pragma unroll
+    for (int q = 0; q < PB; ++q) acc[a][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // Staging walks one output channel at a time, so a thread's addresses are the same in every channel up to a uniform
+  // offset: the few per-thread values below are all that stays live across the steps.
+  constexpr int XPER = 2;                         // dY values per thread and channel ((R + 2)(W + 2) <= 512)
+  constexpr int WCH = (CT * 9 + 255) / 256;       // filter values per thread and channel
+  int x_src[XPER];                                // offset inside a channel's map, -1 outside the map, -2 outside the patch
+#pragma unroll
+  for (int j = 0; j < XPER; ++j) {
+    const int rem = tid + 256 * j;
+    const int rr = rem / PW, cc = rem - rr * PW;
+    const int ih = r0 - 1 + rr, iw = cc - 1;
+    x_src[j] = rem >= PP ? -2 : (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) ? ih * g.W + iw : -1;
+  }
+  int w_dst[WCH];                                 // LDS index inside a channel's rows of the filter tile, -1: nothing to stage
+  bool w_ok[WCH];                                 // the input channel exists
+#pragma unroll
+  for (int j = 0; j < WCH; ++j) {
+    const int rem = tid + 256 * j;
+    const int ci = rem / 9, tap = rem - ci * 9;
+    w_dst[j] = rem < CT * 9 ? tap * TS + ci : -1;
+    w_ok[j] = rem < CT * 9 && ci0 + ci < g.Ci;
+  }
+  float xr[kDa3Co][XPER], wr[kDa3Co][WCH];
+  auto load_step = [&](int co0) {
+#pragma unroll
+    for (int c = 0; c < kDa3Co; ++c) {
+      const bool ch = co0 + c < g.Co;  // the last step of a channel count that 8 does not divide
+      const T* __restrict__ yc = dY + ((int64_t)b * g.Co + co0 + c) * hw;
+      const T* __restrict__ wc = Wt + ((int64_t)(co0 + c) * g.Ci + ci0) * 9;
+#pragma unroll
+      for (int j = 0; j < XPER; ++j) xr[c][j] = (ch && x_src[j] >= 0) ? da_widen<T>(yc[x_src[j]]) : 0.0f;
+#pragma unroll
+      for (int j = 0; j < WCH; ++j) wr[c][j] = (ch && w_ok[j]) ? da_widen<T>(wc[tid + 256 * j]) : 0.0f;
+    }
+  };
+  auto store_step = [&]() {
+#pragma unroll
+    for (int c = 0; c < kDa3Co; ++c) {
+#pragma unroll
+      for (int j = 0; j < XPER; ++j)
+        if (x_src[j] > -2) patch[c * PS + tid + 256 * j] = xr[c][j];
+#pragma unroll
+      for (int j = 0; j < WCH; ++j)
+        if (w_dst[j] >= 0) wt[w_dst[j] + c * WS] = wr[c][j];
+    }
+  };
+
+  // this lane's positions: block q of the wavefront, column i16 of the result tiles
+  int pos_off[PB];
+#pragma unroll
+  for (int q = 0; q < PB; ++q) {
+    const int p = (wave * PB + q) * 16 + i16;
+    const int ihl = p / g.W, iw = p - ihl * g.W;
+    pos_off[q] = ihl * PW + iw;
+  }
+
+  load_step(0);
+  for (int co0 = 0; co0 < g.Co; co0 += kDa3Co) {
+    __syncthreads();  // the previous step's readers are done
+    store_step();
+    __syncthreads();
+    if (co0 + kDa3Co < g.Co) load_step(co0 + kDa3Co);
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      const int u = tap / 3, v = tap - 3 * u;
+      const int tap_off = (2 - u) * PW + (2 - v);  // staged row ihl + 2 - u, column iw + 2 - v
+#pragma unroll
+      for (int sstep = 0; sstep < kDa3Co / 4; ++sstep) {
+        float av[NC], bv[PB];
+#pragma unroll
+        for (int a = 0; a < NC; ++a) av[a] = wt[tap * TS + (4 * sstep + kk) * WS + a * 16 + i16];
+#pragma unroll
+        for (int q = 0; q < PB; ++q) bv[q] = patch[(4 * sstep + kk) * PS + pos_off[q] + tap_off];
+#pragma unroll
+        for (int a = 0; a < NC; ++a)
+#pragma unroll
+          for (int q = 0; q < PB; ++q) acc[a][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv[q], acc[a][q], 0, 0, 0);
+      }
+    }
+  }
+
+  // result tile: the lane holds channels 4*kk .. 4*kk+3 (rows) of position i16 (column)
+#pragma unroll
+  for (int a = 0; a < NC; ++a)
+#pragma unroll
+    for (int q = 0; q < PB; ++q) {
+      const int p = (wave * PB + q) * 16 + i16;  // position inside the band: row r0 + p / W, column p % W
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int c = ci0 + a * 16 + 4 * kk + r;
+        if (c < g.Ci) da_store<T>(&dA[((int64_t)b * g.Ci + c) * hw + (int64_t)r0 * g.W + p], acc[a][q][r]);
+      }
+    }
+}
+
+template <typename T, int NC>
+static int launch_da3(const DaGeom& g, int R, const void* dY, const void* Wt, void* dA, hipStream_t st) {
+  const int PW = g.W + 2;
+  int PS = (R + 2) * PW;
+  PS += (48 - PS % 32) % 32;  // channel stride 16 banks past a multiple of 32: the four channels of a read spread over the banks
+  const size_t lds = ((size_t)kDa3Co * PS + (size_t)9 * (kDa3Co * (16 * NC + 16) + 4)) * sizeof(float);
+  const dim3 grid((unsigned)(g.Nb * (g.H / R)), (unsigned)ceil_div(g.Ci, 16 * NC));
+  ProfScope prof(SURGEON_PROF_DA, st);
+  if (R * g.W == 128) {
+    auto kernel = da_conv3x3_kernel<T, NC, 2>;
+    static std::atomic<uint64_t> lds_set{0};
+    if (lds > 48 * 1024) {
+      const int rc = ensure_dynamic_lds((const void*)kernel, 96 * 1024, lds_set);
+      if (rc != SURGEON_OK) return rc;
+    }
+    SURGEON_LAUNCH(kernel, grid, dim3(256), lds, st, g, R, PS, (const T*)dY, (const T*)Wt, (T*)dA);
+  } else {
+    auto kernel = da_conv3x3_kernel<T, NC, 1>;
+    static std::atomic<uint64_t> lds_set{0};
+    if (lds > 48 * 1024) {
+      const int rc = ensure_dynamic_lds((const void*)kernel, 96 * 1024, lds_set);
+      if (rc != SURGEON_OK) return rc;
+    }
+    SURGEON_LAUNCH(kernel, grid, dim3(256), lds, st, g, R, PS, (const T*)dY, (const T*)Wt, (T*)dA);
+  }
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+// rows per band for the 3x3 kernel, or 0 when the layer does not fit it
+static int da3_band_rows(const DaGeom& g) {
+  if (g.KH != 3 || g.KW != 3 || g.stride != 1 || g.pad != 1) return 0;
+  if (g.W < 8 || g.W > 128 || 128 % g.W) return 0;
+  if ((int64_t)g.Co * g.HW >= ((int64_t)1 << 31)) return 0;  // 32-bit offsets inside an image's dY
+  const int R128 = 128 / g.W;
+  const int R = g.H % R128 == 0 ? R128 : (g.H * g.W == 64 ? g.H : 0);  // 64 positions: e.g. one 8 x 8 image per tile
+  if (R > 0 && (R + 2) * (g.W + 2) > 512) return 0;  // a channel's patch is staged by two passes of the 256 threads
+  return R;
+}
+
 // Alg. 1 line 14 as one plain gradient step, in place: W <- W - lr * dW
 template <typename T>
 __global__ __launch_bounds__(256) void weight_update_kernel(T* __restrict__ Wt, const float* __restrict__ dW, int64_t n,
@@ -455,6 +625,21 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
                      (const float*)part, fp.splits, n_out, (uint16_t*)dA);
       SURGEON_LAUNCH_CHECK();
       return SURGEON_OK;
+    }
+  }
+  if (!linear) {
+    const int R = da3_band_rows(g);
+    if (R > 0 && (int64_t)g.Nb * (g.H / R) <= 0x7fffffff) {
+      // channel tile: 160 where it divides the channels (the widths of WideResNet), else 128, else 64
+      const int nc = g.Ci % 160 == 0 ? 10 : (g.Ci >= 128 ? 8 : 4);
+      if (d->dtype == SURGEON_F32) {
+        if (nc == 10) return launch_da3<float, 10>(g, R, dY, Wt, dA, st);
+        if (nc == 8) return launch_da3<float, 8>(g, R, dY, Wt, dA, st);
+        return launch_da3<float, 4>(g, R, dY, Wt, dA, st);
+      }
+      if (nc == 10) return launch_da3<uint16_t, 10>(g, R, dY, Wt, dA, st);
+      if (nc == 8) return launch_da3<uint16_t, 8>(g, R, dY, Wt, dA, st);
+      return launch_da3<uint16_t, 4>(g, R, dY, Wt, dA, st);
     }
   }
   const int64_t p_tiles = ceil_div(g.P, kDaTP), c_tiles = ceil_div(g.Ci, kDaTC);

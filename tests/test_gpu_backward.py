@@ -167,6 +167,10 @@ DA_CONVS = [
     (2, 160, 32, 32, 320, 1, 2, 0), (2, 3, 32, 32, 16, 3, 1, 1), (1, 3, 64, 64, 64, 7, 2, 3), (2, 64, 14, 14, 256, 1, 1, 0),
     (2, 5, 9, 9, 7, 5, 1, 2), (3, 6, 12, 12, 20, 3, 1, 0), (2, 40, 13, 13, 24, 3, 1, 1), (2, 8, 20, 20, 24, 5, 2, 1),
     (1, 64, 14, 14, 65, 3, 3, 1), (2, 130, 7, 7, 512, 3, 1, 1),
+    # 3x3 stride-1 pad-1 layers on maps the band kernel takes: every channel tile (64, 128, 160), 64 and 128 positions
+    # per band, channel counts that neither the tile nor the eight-channel step divides, maps 8 to 128 wide
+    (3, 130, 8, 8, 13, 3, 1, 1), (2, 24, 16, 8, 20, 3, 1, 1), (1, 8, 4, 64, 9, 3, 1, 1), (1, 5, 3, 128, 6, 3, 1, 1),
+    (2, 160, 8, 8, 24, 3, 1, 1), (1, 12, 4, 16, 8, 3, 1, 1), (2, 320, 16, 16, 40, 3, 1, 1),
 ]
 
 
