@@ -229,22 +229,22 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
 constexpr int kDa3Co = 8;         // output channels per step
 
 template <typename T, int NC, int PB>  // NC: 16-channel blocks per tile; PB: 16-position blocks per wavefront (P = 64 PB)
-__global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int PS, const T* __restrict__ dY,
+__global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int imgs, int PS, const T* __restrict__ dY,
                                                          const T* __restrict__ Wt, T* __restrict__ dA) {
   constexpr int CT = 16 * NC;                   // input channels per tile
   constexpr int WS = CT + 16;                   // LDS stride of a (tap, co) row of the filter tile: 16 banks past a multiple of 32
   constexpr int TS = kDa3Co * WS + 4;           // ... of a tap: four banks apart, so that staging writes of one channel's taps spread
-  constexpr int WPER = kDa3Co * CT * 9 / 256;   // filter values per thread and step
-  static_assert((kDa3Co * CT * 9) % 256 == 0, "filter tile divides among the threads");
   extern __shared__ float da3_lds[];
-  float* patch = da3_lds;                       // [co 8][PS]: rows r0-1 .. r0+R, columns -1 .. W
+  float* patch = da3_lds;                       // [co 8][PS]: per image of the tile rows r0-1 .. r0+R, columns -1 .. W
   float* wt = da3_lds + kDa3Co * PS;            // [tap 9] x TS, inside a tap [co 8][WS]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int i16 = lane & 15, kk = lane >> 4;
   const int PW = g.W + 2, PP = (R + 2) * PW;
   const int bands = g.H / R;
-  const int b = blockIdx.x / bands, r0 = (blockIdx.x - b * bands) * R;
+  // a tile is a band of one image, or -- maps of 64 pixels -- two whole images (imgs = 2, bands = 1)
+  const int b = (blockIdx.x / bands) * imgs, r0 = (blockIdx.x - (blockIdx.x / bands) * bands) * R;
+  const int RW = R * g.W;  // positions per image of the tile
   const int ci0 = blockIdx.y * CT;
   const int64_t hw = g.HW;
 
@@ -256,15 +256,16 @@ __global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int PS
 
   // Staging walks one output channel at a time, so a thread's addresses are the same in every channel up to a uniform
   // offset: the few per-thread values below are all that stays live across the steps.
-  constexpr int XPER = 2;                         // dY values per thread and channel ((R + 2)(W + 2) <= 512)
+  constexpr int XPER = 2;                         // dY values per thread and channel (imgs (R + 2)(W + 2) <= 512)
   constexpr int WCH = (CT * 9 + 255) / 256;       // filter values per thread and channel
   int x_src[XPER];                                // offset inside a channel's map, -1 outside the map, -2 outside the patch
 #pragma unroll
   for (int j = 0; j < XPER; ++j) {
-    const int rem = tid + 256 * j;
+    const int idx = tid + 256 * j;
+    const int img = idx / PP, rem = idx - img * PP;
     const int rr = rem / PW, cc = rem - rr * PW;
     const int ih = r0 - 1 + rr, iw = cc - 1;
-    x_src[j] = rem >= PP ? -2 : (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) ? ih * g.W + iw : -1;
+    x_src[j] = img >= imgs ? -2 : (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) ? img * g.Co * (int)hw + ih * g.W + iw : -1;
   }
   int w_dst[WCH];                                 // LDS index inside a channel's rows of the filter tile, -1: nothing to stage
   bool w_ok[WCH];                                 // the input channel exists
@@ -305,8 +306,9 @@ __global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int PS
 #pragma unroll
   for (int q = 0; q < PB; ++q) {
     const int p = (wave * PB + q) * 16 + i16;
-    const int ihl = p / g.W, iw = p - ihl * g.W;
-    pos_off[q] = ihl * PW + iw;
+    const int img = p / RW, pl = p - img * RW;
+    const int ihl = pl / g.W, iw = pl - ihl * g.W;
+    pos_off[q] = img * PP + ihl * PW + iw;
   }
 
   load_step(0);
@@ -339,11 +341,12 @@ __global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int PS
   for (int a = 0; a < NC; ++a)
 #pragma unroll
     for (int q = 0; q < PB; ++q) {
-      const int p = (wave * PB + q) * 16 + i16;  // position inside the band: row r0 + p / W, column p % W
+      const int p = (wave * PB + q) * 16 + i16;  // position inside the tile: image p / RW, then row-major from row r0
+      const int img = p / RW, pl = p - img * RW;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int c = ci0 + a * 16 + 4 * kk + r;
-        if (c < g.Ci) da_store<T>(&dA[((int64_t)b * g.Ci + c) * hw + (int64_t)r0 * g.W + p], acc[a][q][r]);
+        if (c < g.Ci) da_store<T>(&dA[((int64_t)(b + img) * g.Ci + c) * hw + (int64_t)r0 * g.W + pl], acc[a][q][r]);
       }
     }
 }
@@ -351,19 +354,20 @@ __global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int PS
 template <typename T, int NC>
 static int launch_da3(const DaGeom& g, int R, const void* dY, const void* Wt, void* dA, hipStream_t st) {
   const int PW = g.W + 2;
-  int PS = (R + 2) * PW;
+  const int imgs = (R * g.W == 64 && g.Nb % 2 == 0) ? 2 : 1;  // two 64-pixel images fill a 128-position tile
+  int PS = imgs * (R + 2) * PW;
   PS += (48 - PS % 32) % 32;  // channel stride 16 banks past a multiple of 32: the four channels of a read spread over the banks
   const size_t lds = ((size_t)kDa3Co * PS + (size_t)9 * (kDa3Co * (16 * NC + 16) + 4)) * sizeof(float);
-  const dim3 grid((unsigned)(g.Nb * (g.H / R)), (unsigned)ceil_div(g.Ci, 16 * NC));
+  const dim3 grid((unsigned)(g.Nb / imgs * (g.H / R)), (unsigned)ceil_div(g.Ci, 16 * NC));
   ProfScope prof(SURGEON_PROF_DA, st);
-  if (R * g.W == 128) {
+  if (imgs * R * g.W == 128) {
     auto kernel = da_conv3x3_kernel<T, NC, 2>;
     static std::atomic<uint64_t> lds_set{0};
     if (lds > 48 * 1024) {
       const int rc = ensure_dynamic_lds((const void*)kernel, 96 * 1024, lds_set);
       if (rc != SURGEON_OK) return rc;
     }
-    SURGEON_LAUNCH(kernel, grid, dim3(256), lds, st, g, R, PS, (const T*)dY, (const T*)Wt, (T*)dA);
+    SURGEON_LAUNCH(kernel, grid, dim3(256), lds, st, g, R, imgs, PS, (const T*)dY, (const T*)Wt, (T*)dA);
   } else {
     auto kernel = da_conv3x3_kernel<T, NC, 1>;
     static std::atomic<uint64_t> lds_set{0};
@@ -371,7 +375,7 @@ static int launch_da3(const DaGeom& g, int R, const void* dY, const void* Wt, vo
       const int rc = ensure_dynamic_lds((const void*)kernel, 96 * 1024, lds_set);
       if (rc != SURGEON_OK) return rc;
     }
-    SURGEON_LAUNCH(kernel, grid, dim3(256), lds, st, g, R, PS, (const T*)dY, (const T*)Wt, (T*)dA);
+    SURGEON_LAUNCH(kernel, grid, dim3(256), lds, st, g, R, imgs, PS, (const T*)dY, (const T*)Wt, (T*)dA);
   }
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
@@ -381,7 +385,7 @@ static int launch_da3(const DaGeom& g, int R, const void* dY, const void* Wt, vo
 static int da3_band_rows(const DaGeom& g) {
   if (g.KH != 3 || g.KW != 3 || g.stride != 1 || g.pad != 1) return 0;
   if (g.W < 8 || g.W > 128 || 128 % g.W) return 0;
-  if ((int64_t)g.Co * g.HW >= ((int64_t)1 << 31)) return 0;  // 32-bit offsets inside an image's dY
+  if ((int64_t)g.Co * g.HW >= ((int64_t)1 << 30)) return 0;  // 32-bit offsets inside the dY of a tile's (at most two) images
   const int R128 = 128 / g.W;
   const int R = g.H % R128 == 0 ? R128 : (g.H * g.W == 64 ? g.H : 0);  // 64 positions: e.g. one 8 x 8 image per tile
   if (R > 0 && (R + 2) * (g.W + 2) > 512) return 0;  // a channel's patch is staged by two passes of the 256 threads

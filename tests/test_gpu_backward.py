@@ -170,7 +170,7 @@ DA_CONVS = [
     # 3x3 stride-1 pad-1 layers on maps the band kernel takes: every channel tile (64, 128, 160), 64 and 128 positions
     # per band, channel counts that neither the tile nor the eight-channel step divides, maps 8 to 128 wide
     (3, 130, 8, 8, 13, 3, 1, 1), (2, 24, 16, 8, 20, 3, 1, 1), (1, 8, 4, 64, 9, 3, 1, 1), (1, 5, 3, 128, 6, 3, 1, 1),
-    (2, 160, 8, 8, 24, 3, 1, 1), (1, 12, 4, 16, 8, 3, 1, 1), (2, 320, 16, 16, 40, 3, 1, 1),
+    (2, 160, 8, 8, 24, 3, 1, 1), (1, 12, 4, 16, 8, 3, 1, 1), (2, 320, 16, 16, 40, 3, 1, 1), (4, 24, 4, 16, 16, 3, 1, 1),
 ]
 
 
