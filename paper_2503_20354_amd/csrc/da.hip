@@ -228,11 +228,20 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
 // registers before the matrix instructions of the current one.  Four wavefronts split the positions.
 constexpr int kDa3Co = 8;         // output channels per step
 
+constexpr int da3_filter_row_stride(int ct) {
+  int ws = ct + 16;
+  while (ws % 32 != 16 || ws * 9 < ((ct * 9 + 255) / 256) * 256) ws += 1;
+  return ws;
+}
+
 template <typename T, int NC, int PB>  // NC: 16-channel blocks per tile; PB: 16-position blocks per wavefront (P = 64 PB)
 __global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int imgs, int PS, const T* __restrict__ dY,
                                                          const T* __restrict__ Wt, T* __restrict__ dA) {
   constexpr int CT = 16 * NC;                   // input channels per tile
-  constexpr int WS = CT + 16;                   // LDS stride of a (tap, co) row of the filter tile: 16 banks past a multiple of 32
+  constexpr int WCH = (CT * 9 + 255) / 256;     // filter values per thread and channel
+  // LDS stride of a (tap, co) row of the filter tile: 16 banks past a multiple of 32, and wide enough for channel index
+  // (256 WCH - 1) / 9, the last one the staging threads write
+  constexpr int WS = da3_filter_row_stride(CT);
   constexpr int TS = kDa3Co * WS + 4;           // ... of a tap: four banks apart, so that staging writes of one channel's taps spread
   extern __shared__ float da3_lds[];
   float* patch = da3_lds;                       // [co 8][PS]: per image of the tile rows r0-1 .. r0+R, columns -1 .. W
@@ -257,7 +266,6 @@ __global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int im
   // Staging walks one output channel at a time, so a thread's addresses are the same in every channel up to a uniform
   // offset: the few per-thread values below are all that stays live across the steps.
   constexpr int XPER = 2;                         // dY values per thread and channel (imgs (R + 2)(W + 2) <= 512)
-  constexpr int WCH = (CT * 9 + 255) / 256;       // filter values per thread and channel
   int x_src[XPER];                                // offset inside a channel's map, -1 outside the map, -2 outside the patch
 #pragma unroll
   for (int j = 0; j < XPER; ++j) {
@@ -267,37 +275,41 @@ __global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int im
     const int ih = r0 - 1 + rr, iw = cc - 1;
     x_src[j] = img >= imgs ? -2 : (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) ? img * g.Co * (int)hw + ih * g.W + iw : -1;
   }
-  int w_dst[WCH];                                 // LDS index inside a channel's rows of the filter tile, -1: nothing to stage
+  int w_dst[WCH];                                 // LDS index inside a channel's rows of the filter tile
   bool w_ok[WCH];                                 // the input channel exists
 #pragma unroll
   for (int j = 0; j < WCH; ++j) {
     const int rem = tid + 256 * j;
     const int ci = rem / 9, tap = rem - ci * 9;
-    w_dst[j] = rem < CT * 9 ? tap * TS + ci : -1;
+    w_dst[j] = tap * TS + ci;
     w_ok[j] = rem < CT * 9 && ci0 + ci < g.Ci;
   }
   float xr[kDa3Co][XPER], wr[kDa3Co][WCH];
+  // Every load is issued unconditionally from an address inside the tensors (a channel past the end reads the last one,
+  // a position outside the map reads the map's first pixel); what must be zero is zeroed when the value goes to LDS,
+  // one step later, so nothing waits for a load before the matrix instructions that run in between.  The LDS writes
+  // are unconditional too: a thread with nothing to stage writes into the padding of the rows (PS >= 512 + 16 and WS
+  // leave room for the threads' whole index range).
   auto load_step = [&](int co0) {
 #pragma unroll
     for (int c = 0; c < kDa3Co; ++c) {
-      const bool ch = co0 + c < g.Co;  // the last step of a channel count that 8 does not divide
-      const T* __restrict__ yc = dY + ((int64_t)b * g.Co + co0 + c) * hw;
-      const T* __restrict__ wc = Wt + ((int64_t)(co0 + c) * g.Ci + ci0) * 9;
+      const int cc = min(co0 + c, g.Co - 1);
+      const T* __restrict__ yc = dY + ((int64_t)b * g.Co + cc) * hw;
+      const T* __restrict__ wc = Wt + ((int64_t)cc * g.Ci + ci0) * 9;
 #pragma unroll
-      for (int j = 0; j < XPER; ++j) xr[c][j] = (ch && x_src[j] >= 0) ? da_widen<T>(yc[x_src[j]]) : 0.0f;
+      for (int j = 0; j < XPER; ++j) xr[c][j] = da_widen<T>(yc[max(x_src[j], 0)]);
 #pragma unroll
-      for (int j = 0; j < WCH; ++j) wr[c][j] = (ch && w_ok[j]) ? da_widen<T>(wc[tid + 256 * j]) : 0.0f;
+      for (int j = 0; j < WCH; ++j) wr[c][j] = da_widen<T>(wc[w_ok[j] ? tid + 256 * j : 0]);
     }
   };
-  auto store_step = [&]() {
+  auto store_step = [&](int co0) {  // co0: the step the registers were loaded for
 #pragma unroll
     for (int c = 0; c < kDa3Co; ++c) {
+      const bool ch = co0 + c < g.Co;  // false on the last step of a channel count that 8 does not divide
 #pragma unroll
-      for (int j = 0; j < XPER; ++j)
-        if (x_src[j] > -2) patch[c * PS + tid + 256 * j] = xr[c][j];
+      for (int j = 0; j < XPER; ++j) patch[c * PS + tid + 256 * j] = (ch && x_src[j] >= 0) ? xr[c][j] : 0.0f;
 #pragma unroll
-      for (int j = 0; j < WCH; ++j)
-        if (w_dst[j] >= 0) wt[w_dst[j] + c * WS] = wr[c][j];
+      for (int j = 0; j < WCH; ++j) wt[w_dst[j] + c * WS] = (ch && w_ok[j]) ? wr[c][j] : 0.0f;
     }
   };
 
@@ -314,25 +326,34 @@ __global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int im
   load_step(0);
   for (int co0 = 0; co0 < g.Co; co0 += kDa3Co) {
     __syncthreads();  // the previous step's readers are done
-    store_step();
+    store_step(co0);
     __syncthreads();
     if (co0 + kDa3Co < g.Co) load_step(co0 + kDa3Co);
-#pragma unroll
-    for (int tap = 0; tap < 9; ++tap) {
+    // 18 contraction steps of four (tap, then half of the eight channels); the operands of step s + 1 are read from LDS
+    // before the matrix instructions of step s are issued, and the scheduling barriers keep that order, so that the
+    // reads' latency passes under 4 NC PB matrix instructions instead of in front of every few of them
+    constexpr int KS = 9 * kDa3Co / 4;
+    float av[2][NC], bv[2][PB];
+    auto read_operands = [&](int ks, float* a_out, float* b_out) {
+      const int tap = ks / (kDa3Co / 4), sstep = ks - tap * (kDa3Co / 4);
       const int u = tap / 3, v = tap - 3 * u;
       const int tap_off = (2 - u) * PW + (2 - v);  // staged row ihl + 2 - u, column iw + 2 - v
 #pragma unroll
-      for (int sstep = 0; sstep < kDa3Co / 4; ++sstep) {
-        float av[NC], bv[PB];
+      for (int a = 0; a < NC; ++a) a_out[a] = wt[tap * TS + (4 * sstep + kk) * WS + a * 16 + i16];
 #pragma unroll
-        for (int a = 0; a < NC; ++a) av[a] = wt[tap * TS + (4 * sstep + kk) * WS + a * 16 + i16];
+      for (int q = 0; q < PB; ++q) b_out[q] = patch[(4 * sstep + kk) * PS + pos_off[q] + tap_off];
+    };
+    read_operands(0, av[0], bv[0]);
 #pragma unroll
-        for (int q = 0; q < PB; ++q) bv[q] = patch[(4 * sstep + kk) * PS + pos_off[q] + tap_off];
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) read_operands(ks + 1, av[(ks + 1) & 1], bv[(ks + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int a = 0; a < NC; ++a)
+      for (int a = 0; a < NC; ++a)
 #pragma unroll
-          for (int q = 0; q < PB; ++q) acc[a][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[a], bv[q], acc[a][q], 0, 0, 0);
-      }
+        for (int q = 0; q < PB; ++q)
+          acc[a][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ks & 1][a], bv[ks & 1][q], acc[a][q], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
@@ -356,8 +377,9 @@ static int launch_da3(const DaGeom& g, int R, const void* dY, const void* Wt, vo
   const int PW = g.W + 2;
   const int imgs = (R * g.W == 64 && g.Nb % 2 == 0) ? 2 : 1;  // two 64-pixel images fill a 128-position tile
   int PS = imgs * (R + 2) * PW;
+  PS = std::max(PS, 512);     // the staging threads write 512 values per channel, whatever the patch holds
   PS += (48 - PS % 32) % 32;  // channel stride 16 banks past a multiple of 32: the four channels of a read spread over the banks
-  const size_t lds = ((size_t)kDa3Co * PS + (size_t)9 * (kDa3Co * (16 * NC + 16) + 4)) * sizeof(float);
+  const size_t lds = ((size_t)kDa3Co * PS + (size_t)9 * (kDa3Co * da3_filter_row_stride(16 * NC) + 4)) * sizeof(float);
   const dim3 grid((unsigned)(g.Nb / imgs * (g.H / R)), (unsigned)ceil_div(g.Ci, 16 * NC));
   ProfScope prof(SURGEON_PROF_DA, st);
   if (imgs * R * g.W == 128) {
