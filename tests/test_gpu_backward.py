@@ -171,6 +171,9 @@ DA_CONVS = [
     # per band, channel counts that neither the tile nor the eight-channel step divides, maps 8 to 128 wide
     (3, 130, 8, 8, 13, 3, 1, 1), (2, 24, 16, 8, 20, 3, 1, 1), (1, 8, 4, 64, 9, 3, 1, 1), (1, 5, 3, 128, 6, 3, 1, 1),
     (2, 160, 8, 8, 24, 3, 1, 1), (1, 12, 4, 16, 8, 3, 1, 1), (2, 320, 16, 16, 40, 3, 1, 1), (4, 24, 4, 16, 16, 3, 1, 1),
+    # ... and maps that leave part of a tile empty: a short last band, a last tile with fewer images, tiny and wide maps
+    (3, 20, 14, 14, 24, 3, 1, 1), (5, 8, 7, 7, 8, 3, 1, 1), (1, 6, 56, 56, 10, 3, 1, 1), (9, 4, 4, 4, 8, 3, 1, 1),
+    (1, 4, 5, 100, 4, 3, 1, 1), (2, 4, 3, 3, 4, 3, 1, 1), (1, 3, 1, 1, 5, 3, 1, 1), (2, 7, 40, 2, 9, 3, 1, 1),
 ]
 
 
