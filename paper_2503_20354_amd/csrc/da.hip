@@ -667,6 +667,9 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
       return SURGEON_OK;
     }
   }
+  if (!linear && d->dtype == SURGEON_BF16 && g.KH == 1 && g.KW == 1 && g.pad == 0 && (g.stride == 1 || g.stride == 2) &&
+      g.Nb <= 65535 && (int64_t)g.Ci * g.HW < ((int64_t)1 << 31))
+    return launch_da_conv1x1_bf16(g.Nb, g.Ci, g.Co, g.H, g.W, g.stride, Wt, dY, dA, st);
   if (!linear) {
     const Da3Plan plan = plan_da3(g);
     if (plan.ok) {

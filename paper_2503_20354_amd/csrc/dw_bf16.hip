@@ -226,11 +226,32 @@ __device__ __forceinline__ bf16x8 read_operand(const uint16_t* tile, int t0, int
   return __builtin_bit_cast(bf16x8, both);
 }
 
-// blockIdx.x = o_tile * i_tiles + i_tile, blockIdx.y = split along the tokens.
-template <int PO, int PI, int TOK, bool YALIGNED>
+// How a result leaves the kernel.  kOutSplitsF32: fp32, out[split][o][i] (the weight gradient's partial sums).  The other
+// two serve the activation gradient of 1x1 convolutions, where a batch entry is an image, o an input channel and i an
+// output pixel: kOutBf16 stores bf16 at out[o][i]; kOutBf16Stride2 stores pixel i = (oh, ow) at (2 oh, 2 ow) of a map
+// out_w wide and out_h high and zeros at the three other pixels of its 2 x 2 block (what a stride-2 layer's input
+// gradient holds there).
+enum { kOutSplitsF32 = 0, kOutBf16 = 1, kOutBf16Stride2 = 2 };
+struct BatchedOperands {
+  int64_t a_batch = 0, y_batch = 0, out_batch = 0;  // element strides of blockIdx.z
+  int out_w = 0, out_h = 0, in_w = 0;               // kOutBf16Stride2: dA's map, and the width of dY's map
+};
+
+__device__ __forceinline__ uint32_t bf16_bits_rne(float f) {  // round to nearest even; NaN stays NaN
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x0040u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// blockIdx.x = o_tile * i_tiles + i_tile, blockIdx.y = split along the tokens, blockIdx.z = batch entry.
+template <int PO, int PI, int TOK, bool YALIGNED, bool AALIGNED = true, int OUT = kOutSplitsF32>
 __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t K, int64_t N, int i_tiles,
                                                              int64_t rows_per_split, const uint16_t* __restrict__ A,
-                                                             const uint16_t* __restrict__ dY, float* __restrict__ out) {
+                                                             const uint16_t* __restrict__ dY, float* __restrict__ out,
+                                                             BatchedOperands bo) {
+  A += (int64_t)blockIdx.z * bo.a_batch;
+  dY += (int64_t)blockIdx.z * bo.y_batch;
   constexpr int TO = 64 * PO, TI = 64 * PI, SO = TO + kBfPad, SI = TI + kBfPad;
   constexpr int CY = TOK * TO / 8 / 256, CA = TOK * TI / 8 / 256;  // 16-byte chunks per thread and K-tile
   static_assert(TOK * TO / 8 % 256 == 0 && TOK * TI / 8 % 256 == 0 && TOK % 16 == 0, "tile shape");
@@ -262,7 +283,7 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
 #pragma unroll
     for (int j = 0; j < CA; ++j) {
       const int c = tid + 256 * j, row = c / (TI / 8), col = (c % (TI / 8)) * 8;
-      ra[j] = load_chunk<true>(A, m0 + row, m_end, i0 + col, K, K);
+      ra[j] = load_chunk<AALIGNED>(A, m0 + row, m_end, i0 + col, K, K);
     }
   };
   auto store_tile = [&](int buf) {
@@ -309,17 +330,38 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
   }
 
   // 32x32 result tile: lane holds column lane%32 and rows 8*(v/4) + 4*(lane/32) + v%4, v = 0..15
-  float* __restrict__ dst = out + (int64_t)blockIdx.y * N * K;
   const int col = lane & 31, half = lane >> 5;
 #pragma unroll
   for (int p = 0; p < PO; ++p)
 #pragma unroll
     for (int q = 0; q < PI; ++q) {
       const int64_t i = i0 + wn * 32 * PI + q * 32 + col;
+      int64_t at = i;  // where column i goes inside a row of the result
+      int map = 0;     // kOutBf16Stride2: bit 0 = the pixel right of (2 oh, 2 ow) exists, bit 1 = the row below exists
+      if constexpr (OUT == kOutBf16Stride2) {
+        const int oh = (int)(i / bo.in_w), ow = (int)(i - (int64_t)oh * bo.in_w);
+        at = (int64_t)2 * oh * bo.out_w + 2 * ow;
+        map = (2 * ow + 1 < bo.out_w ? 1 : 0) | (2 * oh + 1 < bo.out_h ? 2 : 0);
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int64_t o = o0 + wm * 32 * PO + p * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-        if (o < N && i < K) dst[o * K + i] = acc[p][q][v];
+        if (o < N && i < K) {
+          if constexpr (OUT == kOutSplitsF32) {
+            out[(int64_t)blockIdx.y * N * K + o * K + i] = acc[p][q][v];
+          } else if constexpr (OUT == kOutBf16) {
+            reinterpret_cast<uint16_t*>(out)[(int64_t)blockIdx.z * bo.out_batch + o * K + i] = (uint16_t)bf16_bits_rne(acc[p][q][v]);
+          } else {
+            uint16_t* __restrict__ px = reinterpret_cast<uint16_t*>(out) + (int64_t)blockIdx.z * bo.out_batch +
+                                        o * ((int64_t)bo.out_w * bo.out_h) + at;
+            px[0] = (uint16_t)bf16_bits_rne(acc[p][q][v]);
+            if (map & 1) px[1] = 0;
+            if (map & 2) {
+              px[bo.out_w] = 0;
+              if (map & 1) px[bo.out_w + 1] = 0;
+            }
+          }
+        }
       }
     }
 }
@@ -673,13 +715,57 @@ int launch_linear_bf16(int64_t M, int64_t K, int64_t N, const void* A_dense, con
   ProfScope prof(SURGEON_PROF_DW, st);
   if (N % 8 != 0)  // dY rows are not 16-byte aligned: element-wise dY loads (never chosen together with the wide tile)
     SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 2, kBf16LinearTokens, false>), grid, dim3(256), 0, st, M, K, N, i_tiles,
-                   rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);
+                   rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out, BatchedOperands{});
   else if (wide)
     SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 4, kBf16LinearTokensWide, true>), grid, dim3(256), 0, st, M, K, N, i_tiles,
-                   rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);
+                   rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out, BatchedOperands{});
   else
     SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 2, kBf16LinearTokens, true>), grid, dim3(256), 0, st, M, K, N, i_tiles,
-                   rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);
+                   rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out, BatchedOperands{});
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+// Activation gradient of a bf16 1x1 convolution without padding, stride 1 or 2 (Eq. 2, first line), image by image on
+// the contraction above: the "tokens" are the Co output channels, the filter W [co][ci] is the operand whose rows become
+// the result's rows, the image's dY [co][OH * OW] the one whose rows become its columns, and the result [ci][pixels] is
+// the image's NCHW slice of dA, stored as bf16 by the kernel itself (one split: a workgroup walks all of Co).
+int launch_da_conv1x1_bf16(int Nb, int Ci, int Co, int H, int W, int stride, const void* Wt, const void* dY, void* dA,
+                           hipStream_t st) {
+  const int OH = (H - 1) / stride + 1, OW = (W - 1) / stride + 1;
+  const int64_t px = (int64_t)OH * OW;
+  BatchedOperands bo;
+  bo.a_batch = (int64_t)Co * px;
+  bo.y_batch = 0;
+  bo.out_batch = (int64_t)Ci * H * W;
+  bo.out_w = W; bo.out_h = H; bo.in_w = OW;
+  // 64-pixel tiles where they leave fewer columns empty than 128-pixel tiles (7 x 7 maps: 49 of 64 instead of 128)
+  const bool narrow = ceil_div(px, 64) * 64 < ceil_div(px, 128) * 128;
+  const int tile_i = narrow ? 64 : 128;
+  const int i_tiles = (int)ceil_div(px, tile_i), o_tiles = (int)ceil_div(Ci, kBf16LinearTile);
+  const dim3 grid((unsigned)(o_tiles * i_tiles), 1, (unsigned)Nb);
+  const bool ya = Ci % 8 == 0 && ((uintptr_t)Wt % 16) == 0, aa = px % 8 == 0 && ((uintptr_t)dY % 16) == 0;
+  const int64_t M = Co, K = px, N = Ci;
+  ProfScope prof(SURGEON_PROF_DA, st);
+#define SURGEON_DA1X1(PI, YA, AA, OUT)                                                                                 \
+  SURGEON_LAUNCH((dw_linear_bf16_kernel<2, PI, kBf16LinearTokens, YA, AA, OUT>), grid, dim3(256), 0, st, M, K, N, i_tiles, \
+                 M, (const uint16_t*)dY, (const uint16_t*)Wt, (float*)dA, bo)
+#define SURGEON_DA1X1_ALIGN(PI, OUT)            \
+  do {                                          \
+    if (ya && aa) SURGEON_DA1X1(PI, true, true, OUT);        \
+    else if (ya) SURGEON_DA1X1(PI, true, false, OUT);        \
+    else if (aa) SURGEON_DA1X1(PI, false, true, OUT);        \
+    else SURGEON_DA1X1(PI, false, false, OUT);               \
+  } while (0)
+  if (stride == 1) {
+    if (narrow) SURGEON_DA1X1_ALIGN(1, kOutBf16);
+    else SURGEON_DA1X1_ALIGN(2, kOutBf16);
+  } else {
+    if (narrow) SURGEON_DA1X1_ALIGN(1, kOutBf16Stride2);
+    else SURGEON_DA1X1_ALIGN(2, kOutBf16Stride2);
+  }
+#undef SURGEON_DA1X1_ALIGN
+#undef SURGEON_DA1X1
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }
