@@ -218,6 +218,54 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
       }
 }
 
+// ---- layers with at most four input channels (a network's first convolution): one thread per pixel of dA --------------
+// A 128-channel matrix tile would be almost empty here.  The filter sits in LDS as fp32, four channels wide; a thread walks the taps that
+// reach its pixel under the layer's stride and, per tap, the output channels; its reads of dY coincide with its
+// neighbours' (the same or the adjacent output pixel).  fp32 accumulation in the order (tap, output channel).
+constexpr int kDaFewCi = 4;
+template <typename T>
+__global__ __launch_bounds__(256) void da_conv_fewch_kernel(DaGeom g, const T* __restrict__ dY, const T* __restrict__ Wt,
+                                                            T* __restrict__ dA) {
+  extern __shared__ floatx4 fw_lds[];  // [tap][co], the (up to) four input channels of a filter tap side by side
+  const int taps = g.KH * g.KW, n_w = g.Co * taps;
+  for (int i = threadIdx.x; i < n_w; i += 256) {
+    const int co = i / taps, t = i - co * taps;
+    floatx4 w4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int c = 0; c < g.Ci; ++c) w4[c] = da_widen<T>(Wt[((int64_t)co * g.Ci + c) * taps + t]);
+    fw_lds[t * g.Co + co] = w4;
+  }
+  __syncthreads();
+  const int64_t pos = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (pos >= g.P) return;
+  const int b = (int)(pos / g.HW), rem = (int)(pos - (int64_t)b * g.HW);
+  const int ih = rem / g.W, iw = rem - ih * g.W;
+  const int64_t ohw = (int64_t)g.OH * g.OW;
+  float acc[kDaFewCi] = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int u = 0; u < g.KH; ++u) {
+    const int th = ih + g.pad - u;
+    if (th < 0 || th % g.stride) continue;
+    const int oh = th / g.stride;
+    if (oh >= g.OH) continue;
+    for (int v = 0; v < g.KW; ++v) {
+      const int tw = iw + g.pad - v;
+      if (tw < 0 || tw % g.stride) continue;
+      const int ow = tw / g.stride;
+      if (ow >= g.OW) continue;
+      const T* __restrict__ y = dY + (int64_t)b * g.Co * ohw + (int64_t)oh * g.OW + ow;
+      const floatx4* __restrict__ w = fw_lds + (u * g.KW + v) * g.Co;
+      for (int co = 0; co < g.Co; ++co) {
+        const float yv = da_widen<T>(y[co * ohw]);
+        const floatx4 w4 = w[co];
+#pragma unroll
+        for (int c = 0; c < kDaFewCi; ++c) acc[c] = __builtin_fmaf(yv, w4[c], acc[c]);
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < kDaFewCi; ++c)
+    if (c < g.Ci) da_store<T>(&dA[((int64_t)b * g.Ci + c) * g.HW + rem], acc[c]);
+}
+
 // ---- 3x3, stride 1, pad 1 convolutions: the taps as shifted reads of one staged patch ---------------------------------
 // dA[b][ci][ih][iw] = sum_{co,u,v} dY[b][co][ih+1-u][iw+1-v] * W[co][ci][u][v].  A workgroup owns up to 128 positions
 // -- a band of R rows of one image, or several whole images of a small map -- and a tile of 16 NC input channels, and
@@ -670,6 +718,24 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
   if (!linear && d->dtype == SURGEON_BF16 && g.KH == 1 && g.KW == 1 && g.pad == 0 && (g.stride == 1 || g.stride == 2) &&
       g.Nb <= 65535 && (int64_t)g.Ci * g.HW < ((int64_t)1 << 31))
     return launch_da_conv1x1_bf16(g.Nb, g.Ci, g.Co, g.H, g.W, g.stride, Wt, dY, dA, st);
+  if (!linear && g.Ci <= kDaFewCi && (size_t)g.Q * 16 <= 64 * 1024 && ceil_div(g.P, 256) <= 0x7fffffff) {
+    const dim3 grid((unsigned)ceil_div(g.P, 256));
+    const size_t lds = (size_t)g.Q * 16;
+    static std::atomic<uint64_t> lds_f32{0}, lds_bf16{0};
+    ProfScope prof(SURGEON_PROF_DA, st);
+    if (d->dtype == SURGEON_F32) {
+      const int rc = ensure_dynamic_lds((const void*)da_conv_fewch_kernel<float>, 64 * 1024, lds_f32);
+      if (rc != SURGEON_OK) return rc;
+      SURGEON_LAUNCH(da_conv_fewch_kernel<float>, grid, dim3(256), lds, st, g, (const float*)dY, (const float*)Wt, (float*)dA);
+    } else {
+      const int rc = ensure_dynamic_lds((const void*)da_conv_fewch_kernel<uint16_t>, 64 * 1024, lds_bf16);
+      if (rc != SURGEON_OK) return rc;
+      SURGEON_LAUNCH(da_conv_fewch_kernel<uint16_t>, grid, dim3(256), lds, st, g, (const uint16_t*)dY, (const uint16_t*)Wt,
+                     (uint16_t*)dA);
+    }
+    SURGEON_LAUNCH_CHECK();
+    return SURGEON_OK;
+  }
   if (!linear) {
     const Da3Plan plan = plan_da3(g);
     if (plan.ok) {

@@ -172,12 +172,14 @@ DA_CONVS = [
     (3, 130, 8, 8, 13, 3, 1, 1), (2, 24, 16, 8, 20, 3, 1, 1), (1, 8, 4, 64, 9, 3, 1, 1), (1, 5, 3, 128, 6, 3, 1, 1),
     (2, 160, 8, 8, 24, 3, 1, 1), (1, 12, 4, 16, 8, 3, 1, 1), (2, 320, 16, 16, 40, 3, 1, 1), (4, 24, 4, 16, 16, 3, 1, 1),
     # ... and maps that leave part of a tile empty: a short last band, a last tile with fewer images, tiny and wide maps
-    (3, 20, 14, 14, 24, 3, 1, 1), (5, 8, 7, 7, 8, 3, 1, 1), (1, 6, 56, 56, 10, 3, 1, 1), (9, 4, 4, 4, 8, 3, 1, 1),
-    (1, 4, 5, 100, 4, 3, 1, 1), (2, 4, 3, 3, 4, 3, 1, 1), (1, 3, 1, 1, 5, 3, 1, 1), (2, 7, 40, 2, 9, 3, 1, 1),
+    (3, 20, 14, 14, 24, 3, 1, 1), (5, 8, 7, 7, 8, 3, 1, 1), (1, 6, 56, 56, 10, 3, 1, 1), (9, 6, 4, 4, 8, 3, 1, 1),
+    (1, 5, 5, 100, 4, 3, 1, 1), (2, 5, 3, 3, 4, 3, 1, 1), (1, 7, 1, 1, 5, 3, 1, 1), (2, 7, 40, 2, 9, 3, 1, 1),
     # 1x1 layers, stride 1 and 2 (bf16: the matrix-core route): channel counts and maps that 8 does not divide, odd maps
     # under stride 2 (the last row and column of dA have no partner), more channels than one tile
     (3, 20, 7, 7, 33, 1, 1, 0), (2, 24, 7, 7, 16, 1, 2, 0), (1, 130, 9, 5, 70, 1, 2, 0), (2, 264, 14, 14, 100, 1, 1, 0),
     (2, 8, 28, 28, 300, 1, 2, 0),
+    # at most four input channels (the per-pixel kernel): strides, pads and filter sizes
+    (2, 4, 9, 9, 6, 3, 2, 0), (3, 1, 5, 7, 3, 5, 1, 2), (2, 2, 6, 6, 5, 1, 1, 0), (1, 3, 37, 41, 70, 7, 2, 3),
 ]
 
 
