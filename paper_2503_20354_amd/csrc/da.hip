@@ -476,6 +476,155 @@ static int launch_da3(const DaGeom& g, const Da3Plan& plan, const void* dY, cons
   return SURGEON_OK;
 }
 
+// ---- 3x3, stride 2, pad 1 convolutions --------------------------------------------------------------------------------
+// Under stride 2 a pixel of dA receives only the taps whose offset has its parity: pixel (2 jh + ph, 2 jw + pw) takes
+// row tap u = 1 for ph = 0 (from dY row jh) and u = 0, 2 for ph = 1 (from rows jh + 1 and jh), and the same along the
+// columns, so the four pixels of a 2 x 2 cell split the nine taps 1 + 2 + 2 + 4 among them.  The kernel above is kept
+// in shape -- band patch of dY, filter tile as [tap][co][ci], contraction over (tap, co), operands read a step ahead --
+// with cells in place of positions: a wavefront owns 16 cells and four result blocks per channel block, one per pixel
+// of the cell, and each tap's matrix instructions go to the block of the pixel that tap reaches.  No matrix work is
+// spent on the taps that stride 2 rules out (the gathering kernel multiplies zeros there).
+template <typename T, int NC>
+__global__ __launch_bounds__(256) void da_conv3x3s2_kernel(DaGeom g, int RC, int PS, const T* __restrict__ dY,
+                                                           const T* __restrict__ Wt, T* __restrict__ dA) {
+  constexpr int CT = 16 * NC;
+  constexpr int WCH = (CT * 9 + 255) / 256;
+  constexpr int WS = da3_filter_row_stride(CT);
+  constexpr int TS = kDa3Co * WS + 4;
+  extern __shared__ float da3_lds[];
+  float* patch = da3_lds;             // [co 8][PS]: dY rows j0 .. j0+RC, columns 0 .. CW (zero past the map)
+  float* wt = da3_lds + kDa3Co * PS;  // [tap 9] x TS, inside a tap [co 8][WS]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i16 = lane & 15, kk = lane >> 4;
+  const int CW = (g.W + 1) / 2, CH = (g.H + 1) / 2;  // cells per row and column of the map
+  const int PW = CW + 1, PP = (RC + 1) * PW;
+  const int bands = (CH + RC - 1) / RC;
+  const int b = blockIdx.x / bands, j0 = (blockIdx.x - b * bands) * RC;
+  const int ci0 = blockIdx.y * CT;
+  const int64_t hw = g.HW, ohw = (int64_t)g.OH * g.OW;
+
+  floatx4 acc[NC][4];  // [channel block][2 ph + pw]
+#pragma unroll
+  for (int a = 0; a < NC; ++a)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[a][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  int x_src;  // this thread's value of a channel's patch: offset in the channel's dY map, -1: a zero
+  {
+    const int rr = tid / PW, cc = tid - rr * PW;
+    const int oh = j0 + rr, ow = cc;
+    x_src = (tid < PP && oh < g.OH && ow < g.OW) ? oh * g.OW + ow : -1;
+  }
+  int w_dst[WCH];
+  bool w_ok[WCH];
+#pragma unroll
+  for (int j = 0; j < WCH; ++j) {
+    const int rem = tid + 256 * j;
+    const int ci = rem / 9, tap = rem - ci * 9;
+    w_dst[j] = tap * TS + ci;
+    w_ok[j] = rem < CT * 9 && ci0 + ci < g.Ci;
+  }
+  float xr[kDa3Co], wr[kDa3Co][WCH];
+  // loads from addresses inside the tensors whatever the thread stages; zeros are put in when the values go to LDS
+  auto load_step = [&](int co0) {
+#pragma unroll
+    for (int c = 0; c < kDa3Co; ++c) {
+      const int cc = min(co0 + c, g.Co - 1);
+      const T* __restrict__ yc = dY + ((int64_t)b * g.Co + cc) * ohw;
+      const T* __restrict__ wc = Wt + ((int64_t)cc * g.Ci + ci0) * 9;
+      xr[c] = da_widen<T>(yc[max(x_src, 0)]);
+#pragma unroll
+      for (int j = 0; j < WCH; ++j) wr[c][j] = da_widen<T>(wc[w_ok[j] ? tid + 256 * j : 0]);
+    }
+  };
+  auto store_step = [&](int co0) {
+#pragma unroll
+    for (int c = 0; c < kDa3Co; ++c) {
+      const bool ch = co0 + c < g.Co;
+      patch[c * PS + tid] = (ch && x_src >= 0) ? xr[c] : 0.0f;  // PS >= 256: every thread has a slot
+#pragma unroll
+      for (int j = 0; j < WCH; ++j) wt[w_dst[j] + c * WS] = (ch && w_ok[j]) ? wr[c][j] : 0.0f;
+    }
+  };
+
+  // this lane's cell
+  const int cell = wave * 16 + i16;
+  const int jhl = cell / CW, jw = cell - jhl * CW;
+  const bool valid = jhl < RC && j0 + jhl < CH;
+  const int cell_off = valid ? jhl * PW + jw : 0;
+
+  load_step(0);
+  for (int co0 = 0; co0 < g.Co; co0 += kDa3Co) {
+    __syncthreads();
+    store_step(co0);
+    __syncthreads();
+    if (co0 + kDa3Co < g.Co) load_step(co0 + kDa3Co);
+    constexpr int KS = 9 * kDa3Co / 4;
+    float av[2][NC], bv[2];
+    auto read_operands = [&](int ks, float* a_out, float* b_out) {
+      const int tap = ks / (kDa3Co / 4), sstep = ks - tap * (kDa3Co / 4);
+      const int u = tap / 3, v = tap - 3 * u;
+      const int tap_off = (u == 0 ? PW : 0) + (v == 0 ? 1 : 0);  // taps 0 reach the next dY row / column, taps 1 and 2 the cell's own
+#pragma unroll
+      for (int a = 0; a < NC; ++a) a_out[a] = wt[tap * TS + (4 * sstep + kk) * WS + a * 16 + i16];
+      *b_out = patch[(4 * sstep + kk) * PS + cell_off + tap_off];
+    };
+    read_operands(0, av[0], &bv[0]);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) read_operands(ks + 1, av[(ks + 1) & 1], &bv[(ks + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);
+      const int tap = ks / (kDa3Co / 4), u = tap / 3, v = tap - 3 * u;
+      const int cls = (u != 1 ? 2 : 0) + (v != 1 ? 1 : 0);  // the pixel of the cell this tap reaches
+#pragma unroll
+      for (int a = 0; a < NC; ++a)
+        acc[a][cls] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[ks & 1][a], bv[ks & 1], acc[a][cls], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // the lane holds channels 4*kk .. 4*kk+3 of its cell's four pixels
+  if (valid) {
+    const int ih0 = 2 * (j0 + jhl), iw0 = 2 * jw;
+#pragma unroll
+    for (int a = 0; a < NC; ++a)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int c = ci0 + a * 16 + 4 * kk + r;
+        if (c >= g.Ci) continue;
+        T* __restrict__ px = dA + ((int64_t)b * g.Ci + c) * hw + (int64_t)ih0 * g.W + iw0;
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph)
+          if (ih0 + ph < g.H) {
+            da_store<T>(&px[ph * g.W], acc[a][2 * ph][r]);
+            if (iw0 + 1 < g.W) da_store<T>(&px[ph * g.W + 1], acc[a][2 * ph + 1][r]);
+          }
+      }
+  }
+}
+
+// cell rows per band for the stride-2 kernel, or 0 when the layer does not fit it
+static int da3s2_band_rows(const DaGeom& g) {
+  if (g.KH != 3 || g.KW != 3 || g.stride != 2 || g.pad != 1) return 0;
+  const int CW = (g.W + 1) / 2, CH = (g.H + 1) / 2;
+  if (CW > 64 || (int64_t)g.Nb * CH > 0x7fffffff) return 0;
+  return std::min(CH, 64 / CW);
+}
+
+template <typename T, int NC>
+static int launch_da3s2(const DaGeom& g, int RC, const void* dY, const void* Wt, void* dA, hipStream_t st) {
+  const int CH = (g.H + 1) / 2;
+  int PS = 256;               // one slot per staging thread; (RC + 1)(CW + 1) <= 130 of them hold the patch
+  PS += (48 - PS % 32) % 32;  // channel stride 16 banks past a multiple of 32
+  const size_t lds = ((size_t)kDa3Co * PS + (size_t)9 * (kDa3Co * da3_filter_row_stride(16 * NC) + 4)) * sizeof(float);
+  const dim3 grid((unsigned)(g.Nb * ceil_div(CH, RC)), (unsigned)ceil_div(g.Ci, 16 * NC));
+  ProfScope prof(SURGEON_PROF_DA, st);
+  SURGEON_LAUNCH((da_conv3x3s2_kernel<T, NC>), grid, dim3(256), lds, st, g, RC, PS, (const T*)dY, (const T*)Wt, (T*)dA);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
 // Alg. 1 line 14 as one plain gradient step, in place: W <- W - lr * dW
 template <typename T>
 __global__ __launch_bounds__(256) void weight_update_kernel(T* __restrict__ Wt, const float* __restrict__ dW, int64_t n,
@@ -735,6 +884,15 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
     }
     SURGEON_LAUNCH_CHECK();
     return SURGEON_OK;
+  }
+  if (!linear) {
+    const int RC = da3s2_band_rows(g);
+    if (RC > 0) {
+      const bool five = g.Ci % 80 == 0;  // 80-channel tiles where they divide the channels, else 64
+      if (d->dtype == SURGEON_F32)
+        return five ? launch_da3s2<float, 5>(g, RC, dY, Wt, dA, st) : launch_da3s2<float, 4>(g, RC, dY, Wt, dA, st);
+      return five ? launch_da3s2<uint16_t, 5>(g, RC, dY, Wt, dA, st) : launch_da3s2<uint16_t, 4>(g, RC, dY, Wt, dA, st);
+    }
   }
   if (!linear) {
     const Da3Plan plan = plan_da3(g);

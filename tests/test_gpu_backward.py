@@ -180,6 +180,10 @@ DA_CONVS = [
     (2, 8, 28, 28, 300, 1, 2, 0),
     # at most four input channels (the per-pixel kernel): strides, pads and filter sizes
     (2, 4, 9, 9, 6, 3, 2, 0), (3, 1, 5, 7, 3, 5, 1, 2), (2, 2, 6, 6, 5, 1, 1, 0), (1, 3, 37, 41, 70, 7, 2, 3),
+    # 3x3 stride-2 pad-1 layers (the cell kernel): even and odd maps, bands that do not fill a tile, 64- and 80-channel
+    # tiles with channels left over, the widest map it takes and one past it
+    (2, 24, 14, 14, 20, 3, 2, 1), (3, 70, 9, 7, 12, 3, 2, 1), (1, 8, 6, 128, 5, 3, 2, 1), (1, 8, 6, 130, 5, 3, 2, 1),
+    (2, 96, 32, 16, 40, 3, 2, 1), (2, 80, 16, 16, 33, 3, 2, 1), (1, 5, 1, 1, 4, 3, 2, 1),
 ]
 
 
