@@ -19,6 +19,10 @@ struct DaGeom {
   int64_t P;  // positions of dA: Nb * H * W
   int Q;      // contraction length: Co * KH * KW
   int HW;
+  // 1x1 layers with a stride (no padding) run on dY's own grid (H, W = dY's map, stride 1): position (oh, ow) is pixel
+  // (spread oh, spread ow) of a dA map spread_h x spread_w, and it also writes the zeros of the spread x spread block
+  // that starts there (no output pixel reaches those).  spread = 0: off.
+  int spread, spread_h, spread_w;
 };
 
 template <typename T>
@@ -212,7 +216,16 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
           const int64_t p = p0 + wp * 64 + b * 16 + i16;
           if (p < g.P && c < g.Ci) {
             const int64_t bimg = p / g.HW;
-            da_store<T>(&dA[(bimg * g.Ci + c) * g.HW + (p - bimg * g.HW)], acc[a][b][r]);
+            if (g.spread == 0) {
+              da_store<T>(&dA[(bimg * g.Ci + c) * g.HW + (p - bimg * g.HW)], acc[a][b][r]);
+            } else {
+              const int rem = (int)(p - bimg * g.HW);
+              const int oh = rem / g.W, ow = rem - oh * g.W;
+              T* __restrict__ px = dA + ((bimg * g.Ci + c) * g.spread_h + (int64_t)oh * g.spread) * g.spread_w + ow * g.spread;
+              for (int dh = 0; dh < g.spread && oh * g.spread + dh < g.spread_h; ++dh)
+                for (int dw = 0; dw < g.spread && ow * g.spread + dw < g.spread_w; ++dw)
+                  da_store<T>(&px[(int64_t)dh * g.spread_w + dw], (dh | dw) == 0 ? acc[a][b][r] : 0.0f);
+            }
           }
         }
       }
@@ -811,6 +824,7 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
     g.P = d->M;
     g.Q = (int)d->N;
     g.HW = 1;
+    g.spread = g.spread_h = g.spread_w = 0;
   } else if (d->kind == SURGEON_CONV2D) {
     if (d->Nb < 1 || d->Ci < 1 || d->H < 1 || d->W < 1 || d->Co < 1 || d->kh < 1 || d->kw < 1 || d->stride < 1 || d->pad < 0)
       return fail(SURGEON_EINVAL, "da: bad conv shape");
@@ -828,6 +842,7 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
     g.HW = g.H * g.W;
     g.P = (int64_t)g.Nb * g.HW;
     g.Q = g.Co * g.KH * g.KW;
+    g.spread = g.spread_h = g.spread_w = 0;
   } else {
     return fail(SURGEON_EINVAL, "da: bad layer kind %d", d->kind);
   }
@@ -908,6 +923,13 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
       if (nc == 8) return launch_da3<uint16_t, 8>(g, plan, dY, Wt, dA, st);
       return launch_da3<uint16_t, 4>(g, plan, dY, Wt, dA, st);
     }
+  }
+  if (!linear && g.KH == 1 && g.KW == 1 && g.pad == 0 && g.stride > 1) {
+    // a strided 1x1 layer: contract on dY's grid, a stride^2-th of dA's positions, and spread the result
+    g.spread = g.stride; g.spread_h = g.H; g.spread_w = g.W;
+    g.H = g.OH; g.W = g.OW; g.stride = 1;
+    g.HW = g.H * g.W;
+    g.P = (int64_t)g.Nb * g.HW;
   }
   const int64_t p_tiles = ceil_div(g.P, kDaTP), c_tiles = ceil_div(g.Ci, kDaTC);
   if (p_tiles > 0x7fffffff || c_tiles > 65535) return fail(SURGEON_EUNSUPPORTED, "da: too many tiles");

@@ -184,6 +184,8 @@ DA_CONVS = [
     # tiles with channels left over, the widest map it takes and one past it
     (2, 24, 14, 14, 20, 3, 2, 1), (3, 70, 9, 7, 12, 3, 2, 1), (1, 8, 6, 128, 5, 3, 2, 1), (1, 8, 6, 130, 5, 3, 2, 1),
     (2, 96, 32, 16, 40, 3, 2, 1), (2, 80, 16, 16, 33, 3, 2, 1), (1, 5, 1, 1, 4, 3, 2, 1),
+    # strided 1x1 layers outside the bf16 stride-2 route: stride 3, maps the stride does not divide
+    (2, 9, 10, 7, 12, 1, 3, 0), (1, 140, 15, 15, 30, 1, 2, 0),
 ]
 
 
