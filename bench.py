@@ -233,7 +233,27 @@ def next_rows(extras, torch, surgeon, wl, dev, cfg):
     tf = _rate(flops, p["da"][0]) / 1e12
     out["da"] = {"bound": "mfma", "achieved": round(tf, 3), "peak": PEAK_MFMA_TFLOPS["f32"], "unit": "TFLOP/s",
                  "frac": round(tf / PEAK_MFMA_TFLOPS["f32"], 4), "ms": round(p["da"][0], 4), "launches": p["da"][1],
-                 "note": "fp32 matrix cores for both dtypes (bf16 widened while staging)"}
+                 "note": "fp32 matrix cores for both dtypes (bf16 widened while staging): band kernel for 3x3 stride 1, "
+                         "cell kernel for 3x3 stride 2, gathering kernel for the rest"}
+
+    # the same gradient for bf16 1x1 convolutions on the bf16 matrix cores, on four ResNet-50 layer shapes at batch 64
+    rows, t_ms, fl = [], 0.0, 0.0
+    for name, (Ci, HWm, Co, stride) in {"c256_14_c1024": (256, 14, 1024, 1), "c64_56_c256": (64, 56, 256, 1),
+                                        "c512_7_c2048": (512, 7, 2048, 1), "c1024_14_c2048_s2": (1024, 14, 2048, 2)}.items():
+        OHm = (HWm - 1) // stride + 1
+        dYb = wl.draw((64, Co, OHm, OHm), "normal", "bf16", 87, device=dev)
+        Wb = (wl.draw((Co, Ci, 1, 1), "normal", "bf16", 88, device=dev) * 0.05).to(torch.bfloat16)
+        dAb = torch.empty((64, Ci, HWm, HWm), dtype=torch.bfloat16, device=dev)
+        d = surgeon.conv2d_desc(64, Ci, HWm, HWm, Co, 1, 1, stride, 0, surgeon.BF16, 0)
+        p = timed(lambda: surgeon.surgeon_da(d, dYb, Wb, dAb))
+        t_ms += p["da"][0]
+        fl += 2.0 * 64 * OHm * OHm * Ci * Co
+        rows.append((name, round(p["da"][0] * 1e3, 1)))
+        del dYb, Wb, dAb
+    tf = _rate(fl, t_ms) / 1e12
+    out["da_bf16_conv1x1"] = {"bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_MFMA_TFLOPS["bf16"], "unit": "TFLOP/s",
+                              "frac": round(tf / PEAK_MFMA_TFLOPS["bf16"], 4), "ms": round(t_ms, 4),
+                              "us_per_layer": dict(rows), "what": "one launch per layer, bf16 results stored by the kernel"}
 
     # the same gradient for bf16 linear layers on the bf16 matrix cores (workspace entry), on the four layer shapes of a
     # ViT-B/16 block at 12 608 tokens

@@ -185,18 +185,25 @@ int launch_unpack_dense(int dtype, const void* vals, const uint64_t* mask, const
 // port is the limit of this kernel) and needs a quarter less L2 traffic per flop.
 constexpr int kBfPad = 16;  // LDS row padding in elements: 4 consecutive rows hit distinct banks
 
-// one 16-byte chunk (8 bf16) of row `row`, columns col0..col0+7, zero outside the matrix.  ALIGNED: the row pitch is a
-// multiple of 8 elements, so a chunk is inside or outside as a whole and is one 16-byte load; otherwise the chunk is
-// gathered from eight 2-byte loads, each with its own column check.
-template <bool ALIGNED>
+// one 16-byte chunk (8 bf16) of row `row`, columns col0..col0+7, zero outside the matrix.  ALIGN = 8: the row pitch
+// is a multiple of 8 elements (and the base 16-byte aligned), so a chunk is inside or outside as a whole and is one
+// 16-byte load; ALIGN = 4: the same with halves of a chunk and two 8-byte loads; ALIGN = 1: the chunk is gathered from
+// eight 2-byte loads, each with its own column check.
+template <int ALIGN>
 __device__ __forceinline__ u32x4 load_chunk(const uint16_t* __restrict__ src, int64_t row, int64_t row_end, int64_t col0,
                                             int64_t n_cols, int64_t ld) {
-  if constexpr (ALIGNED) {
+  if constexpr (ALIGN == 8) {
     const bool ok = row < row_end && col0 < n_cols;
     const int64_t off = ok ? row * ld + col0 : 0;
     u32x4 v = *reinterpret_cast<const u32x4*>(src + off);
     if (!ok) v = u32x4{0, 0, 0, 0};
     return v;
+  } else if constexpr (ALIGN == 4) {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const bool ok0 = row < row_end && col0 < n_cols, ok1 = row < row_end && col0 + 4 < n_cols;
+    const u32x2 lo = *reinterpret_cast<const u32x2*>(src + (ok0 ? row * ld + col0 : 0));
+    const u32x2 hi = *reinterpret_cast<const u32x2*>(src + (ok1 ? row * ld + col0 + 4 : 0));
+    return u32x4{ok0 ? lo[0] : 0u, ok0 ? lo[1] : 0u, ok1 ? hi[0] : 0u, ok1 ? hi[1] : 0u};
   } else {
     u32x4 v = {0, 0, 0, 0};
     if (row < row_end && col0 < n_cols) {
@@ -245,7 +252,7 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float f) {  // round to neares
 }
 
 // blockIdx.x = o_tile * i_tiles + i_tile, blockIdx.y = split along the tokens, blockIdx.z = batch entry.
-template <int PO, int PI, int TOK, bool YALIGNED, bool AALIGNED = true, int OUT = kOutSplitsF32>
+template <int PO, int PI, int TOK, bool YALIGNED, int AALIGN = 8, int OUT = kOutSplitsF32>
 __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t K, int64_t N, int i_tiles,
                                                              int64_t rows_per_split, const uint16_t* __restrict__ A,
                                                              const uint16_t* __restrict__ dY, float* __restrict__ out,
@@ -278,12 +285,12 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
 #pragma unroll
     for (int j = 0; j < CY; ++j) {
       const int c = tid + 256 * j, row = c / (TO / 8), col = (c % (TO / 8)) * 8;
-      ry[j] = load_chunk<YALIGNED>(dY, m0 + row, m_end, o0 + col, N, N);
+      ry[j] = load_chunk<(YALIGNED ? 8 : 1)>(dY, m0 + row, m_end, o0 + col, N, N);
     }
 #pragma unroll
     for (int j = 0; j < CA; ++j) {
       const int c = tid + 256 * j, row = c / (TI / 8), col = (c % (TI / 8)) * 8;
-      ra[j] = load_chunk<AALIGNED>(A, m0 + row, m_end, i0 + col, K, K);
+      ra[j] = load_chunk<AALIGN>(A, m0 + row, m_end, i0 + col, K, K);
     }
   };
   auto store_tile = [&](int buf) {
@@ -744,7 +751,9 @@ int launch_da_conv1x1_bf16(int Nb, int Ci, int Co, int H, int W, int stride, con
   const int tile_i = narrow ? 64 : 128;
   const int i_tiles = (int)ceil_div(px, tile_i), o_tiles = (int)ceil_div(Ci, kBf16LinearTile);
   const dim3 grid((unsigned)(o_tiles * i_tiles), 1, (unsigned)Nb);
-  const bool ya = Ci % 8 == 0 && ((uintptr_t)Wt % 16) == 0, aa = px % 8 == 0 && ((uintptr_t)dY % 16) == 0;
+  const bool ya = Ci % 8 == 0 && ((uintptr_t)Wt % 16) == 0;
+  // dY's rows (one per output channel, px elements): 16-byte chunks, 8-byte halves (14 x 14 maps) or single elements
+  const int aa = (px % 8 == 0 && ((uintptr_t)dY % 16) == 0) ? 8 : (px % 4 == 0 && ((uintptr_t)dY % 8) == 0) ? 4 : 1;
   const int64_t M = Co, K = px, N = Ci;
   ProfScope prof(SURGEON_PROF_DA, st);
 #define SURGEON_DA1X1(PI, YA, AA, OUT)                                                                                 \
@@ -752,10 +761,11 @@ int launch_da_conv1x1_bf16(int Nb, int Ci, int Co, int H, int W, int stride, con
                  M, (const uint16_t*)dY, (const uint16_t*)Wt, (float*)dA, bo)
 #define SURGEON_DA1X1_ALIGN(PI, OUT)            \
   do {                                          \
-    if (ya && aa) SURGEON_DA1X1(PI, true, true, OUT);        \
-    else if (ya) SURGEON_DA1X1(PI, true, false, OUT);        \
-    else if (aa) SURGEON_DA1X1(PI, false, true, OUT);        \
-    else SURGEON_DA1X1(PI, false, false, OUT);               \
+    if (ya && aa == 8) SURGEON_DA1X1(PI, true, 8, OUT);      \
+    else if (ya && aa == 4) SURGEON_DA1X1(PI, true, 4, OUT); \
+    else if (ya) SURGEON_DA1X1(PI, true, 1, OUT);            \
+    else if (aa == 8) SURGEON_DA1X1(PI, false, 8, OUT);      \
+    else SURGEON_DA1X1(PI, false, 1, OUT);                   \
   } while (0)
   if (stride == 1) {
     if (narrow) SURGEON_DA1X1_ALIGN(1, kOutBf16);
