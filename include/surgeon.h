@@ -199,8 +199,10 @@ int surgeon_dw_from_packed_gi(const surgeon_layer_desc* desc, const void* vals, 
  *   LINEAR : dY [M x N], W [N x K] (a framework's weight), dA [M x K]:  dA[m][k] = sum_n dY[m][n] * W[n][k]
  *   CONV2D : dY [Nb, Co, OH, OW], W [Co, Ci, kh, kw], dA [Nb, Ci, H, W] (groups <= 1 only):
  *            dA[b][ci][ih][iw] = sum over (co, u, v) with oh*stride + u - pad == ih, ow*stride + v - pad == iw
- * dY, W and dA are device pointers of desc->dtype; accumulation is fp32 on the matrix cores, bf16 results are rounded
- * once to nearest even.  dA is overwritten.  No workspace.  Deterministic.
+ * dY, W and dA are device pointers of desc->dtype; products are exact (bf16 inputs widened or multiplied on the bf16
+ * matrix cores), accumulation is fp32 (matrix cores; vector ALU for layers with at most four input channels), bf16
+ * results are rounded once to nearest even.  Every element of dA is overwritten, also those a strided layer leaves
+ * zero.  No workspace.  Deterministic.
  */
 int surgeon_da(const surgeon_layer_desc* desc, const void* dY, const void* W, void* dA, void* stream);
 
