@@ -204,6 +204,39 @@ def test_da_conv(dtype, case):
     assert_out_close(bits(dA), ref, dtype, case)
 
 
+@pytest.mark.parametrize("seed", [401, 402, 403])
+def test_da_random_conv_shapes(seed):
+    """Seeded random layers over every route of the activation gradient (3x3 band and stride-2 cell kernels with
+    partly filled tiles, bf16 1x1 on the bf16 matrix cores with aligned and unaligned maps, few input channels,
+    strided 1x1 spread, the gathering kernel).  Each case prints its parameters before it touches the GPU."""
+    import random
+    rng = random.Random(seed)
+    done = 0
+    while done < 16:
+        dtype = rng.choice(["f32", "bf16"])
+        k, st, pad = rng.choice([(3, 1, 1), (3, 1, 1), (3, 2, 1), (3, 2, 1), (1, 1, 0), (1, 2, 0), (1, 3, 0), (3, 1, 0), (5, 2, 2)])
+        Nb = rng.randint(1, 5)
+        Ci = rng.choice([1, 3, 4, 5, 16, 31, 64, 80, 96, 130, 160, 200])
+        Co = rng.choice([1, 7, 8, 9, 24, 64, 100])
+        H = rng.choice([1, 2, 4, 7, 8, 9, 14, 16, 17, 28, 32, 33])
+        W = rng.choice([1, 2, 4, 7, 8, 9, 14, 16, 17, 28, 32, 33, 64, 100, 128, 130])
+        if H + 2 * pad < k or W + 2 * pad < k:
+            continue
+        OH, OW = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+        if Nb * Co * Ci * k * k * OH * OW > 2e8:
+            continue
+        case = (Nb, Ci, H, W, Co, k, st, pad)
+        print("da random conv", case, dtype, flush=True)
+        dY = wl.draw((Nb, Co, OH, OW), "normal", dtype, seed * 1000 + 2 * done)
+        Wt = (wl.draw((Co, Ci, k, k), "normal", dtype, seed * 1000 + 2 * done + 1) * 0.1).to(dY.dtype)
+        dA = torch.full((Nb, Ci, H, W), float("nan"), dtype=dY.dtype, device=DEV)  # every element must be overwritten
+        surgeon.surgeon_da(surgeon.conv2d_desc(Nb, Ci, H, W, Co, k, k, st, pad, sdt(dtype), 0), dY.to(DEV), Wt.to(DEV), dA)
+        torch.cuda.synchronize()
+        ref = oracle.da_conv2d(bits(dY), bits(Wt), Nb, Ci, H, W, Co, k, k, st, pad)
+        assert_out_close(bits(dA), ref, dtype, case)
+        done += 1
+
+
 @pytest.mark.parametrize("cfg,name", [(1, "s2b1.conv1"), (1, "s3b2.conv2"), (2, "s2b1.conv2"), (2, "s3b2.conv3"),
                                       (3, "blk0.qkv"), (3, "blk11.fc2"), (4, "st1b1.fc1"), (4, "dec.cls")])
 def test_da_full_size_sampled(cfg, name):
