@@ -221,7 +221,8 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
             } else {
               const int rem = (int)(p - bimg * g.HW);
               const int oh = rem / g.W, ow = rem - oh * g.W;
-              T* __restrict__ px = dA + ((bimg * g.Ci + c) * g.spread_h + (int64_t)oh * g.spread) * g.spread_w + ow * g.spread;
+              T* __restrict__ px =
+                  dA + ((bimg * g.Ci + c) * g.spread_h + (int64_t)oh * g.spread) * g.spread_w + ow * g.spread;
               for (int dh = 0; dh < g.spread && oh * g.spread + dh < g.spread_h; ++dh)
                 for (int dw = 0; dw < g.spread && ow * g.spread + dw < g.spread_w; ++dw)
                   da_store<T>(&px[(int64_t)dh * g.spread_w + dw], (dh | dw) == 0 ? acc[a][b][r] : 0.0f);
@@ -232,9 +233,10 @@ __global__ __launch_bounds__(256) void da_kernel(DaGeom g, const T* __restrict__
 }
 
 // ---- layers with at most four input channels (a network's first convolution): one thread per pixel of dA --------------
-// A 128-channel matrix tile would be almost empty here.  The filter sits in LDS as fp32, four channels wide; a thread walks the taps that
-// reach its pixel under the layer's stride and, per tap, the output channels; its reads of dY coincide with its
-// neighbours' (the same or the adjacent output pixel).  fp32 accumulation in the order (tap, output channel).
+// A 128-channel matrix tile would be almost empty here.  The filter sits in LDS as fp32, four channels wide; a thread
+// walks the taps that reach its pixel under the layer's stride and, per tap, the output channels; its reads of dY
+// coincide with its neighbours' (the same or the adjacent output pixel).  fp32 accumulation in the order (tap, output
+// channel).
 constexpr int kDaFewCi = 4;
 template <typename T>
 __global__ __launch_bounds__(256) void da_conv_fewch_kernel(DaGeom g, const T* __restrict__ dY, const T* __restrict__ Wt,
@@ -305,7 +307,7 @@ __global__ __launch_bounds__(256) void da_conv3x3_kernel(DaGeom g, int R, int im
   // LDS stride of a (tap, co) row of the filter tile: 16 banks past a multiple of 32, and wide enough for channel index
   // (256 WCH - 1) / 9, the last one the staging threads write
   constexpr int WS = da3_filter_row_stride(CT);
-  constexpr int TS = kDa3Co * WS + 4;           // ... of a tap: four banks apart, so that staging writes of one channel's taps spread
+  constexpr int TS = kDa3Co * WS + 4;           // ... of a tap: four banks on, so staging writes of a channel's taps spread
   extern __shared__ float da3_lds[];
   float* patch = da3_lds;                       // [co 8][PS]: per image of the tile rows r0-1 .. r0+R, columns -1 .. W
   float* wt = da3_lds + kDa3Co * PS;            // [tap 9] x TS, inside a tap [co 8][WS]
@@ -578,7 +580,8 @@ __global__ __launch_bounds__(256) void da_conv3x3s2_kernel(DaGeom g, int RC, int
     auto read_operands = [&](int ks, float* a_out, float* b_out) {
       const int tap = ks / (kDa3Co / 4), sstep = ks - tap * (kDa3Co / 4);
       const int u = tap / 3, v = tap - 3 * u;
-      const int tap_off = (u == 0 ? PW : 0) + (v == 0 ? 1 : 0);  // taps 0 reach the next dY row / column, taps 1 and 2 the cell's own
+      // taps 0 reach the next dY row / column, taps 1 and 2 the cell's own
+      const int tap_off = (u == 0 ? PW : 0) + (v == 0 ? 1 : 0);
 #pragma unroll
       for (int a = 0; a < NC; ++a) a_out[a] = wt[tap * TS + (4 * sstep + kk) * WS + a * 16 + i16];
       *b_out = patch[(4 * sstep + kk) * PS + cell_off + tap_off];
@@ -912,16 +915,20 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
   if (!linear) {
     const Da3Plan plan = plan_da3(g);
     if (plan.ok) {
-      // channel tile: 160 where it divides the channels (the widths of WideResNet), else 128, else 64
-      const int nc = g.Ci % 160 == 0 ? 10 : (g.Ci >= 128 ? 8 : 4);
+      // channel tile: 160 where it divides the channels (the widths of WideResNet), else 128, 64, 32 or 16
+      const int nc = g.Ci % 160 == 0 ? 10 : g.Ci >= 128 ? 8 : g.Ci > 32 ? 4 : g.Ci > 16 ? 2 : 1;
       if (d->dtype == SURGEON_F32) {
         if (nc == 10) return launch_da3<float, 10>(g, plan, dY, Wt, dA, st);
         if (nc == 8) return launch_da3<float, 8>(g, plan, dY, Wt, dA, st);
-        return launch_da3<float, 4>(g, plan, dY, Wt, dA, st);
+        if (nc == 4) return launch_da3<float, 4>(g, plan, dY, Wt, dA, st);
+        if (nc == 2) return launch_da3<float, 2>(g, plan, dY, Wt, dA, st);
+        return launch_da3<float, 1>(g, plan, dY, Wt, dA, st);
       }
       if (nc == 10) return launch_da3<uint16_t, 10>(g, plan, dY, Wt, dA, st);
       if (nc == 8) return launch_da3<uint16_t, 8>(g, plan, dY, Wt, dA, st);
-      return launch_da3<uint16_t, 4>(g, plan, dY, Wt, dA, st);
+      if (nc == 4) return launch_da3<uint16_t, 4>(g, plan, dY, Wt, dA, st);
+      if (nc == 2) return launch_da3<uint16_t, 2>(g, plan, dY, Wt, dA, st);
+      return launch_da3<uint16_t, 1>(g, plan, dY, Wt, dA, st);
     }
   }
   if (!linear && g.KH == 1 && g.KW == 1 && g.pad == 0 && g.stride > 1) {

@@ -357,7 +357,8 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
           if constexpr (OUT == kOutSplitsF32) {
             out[(int64_t)blockIdx.y * N * K + o * K + i] = acc[p][q][v];
           } else if constexpr (OUT == kOutBf16) {
-            reinterpret_cast<uint16_t*>(out)[(int64_t)blockIdx.z * bo.out_batch + o * K + i] = (uint16_t)bf16_bits_rne(acc[p][q][v]);
+            uint16_t* __restrict__ img = reinterpret_cast<uint16_t*>(out) + (int64_t)blockIdx.z * bo.out_batch;
+            img[o * K + i] = (uint16_t)bf16_bits_rne(acc[p][q][v]);
           } else {
             uint16_t* __restrict__ px = reinterpret_cast<uint16_t*>(out) + (int64_t)blockIdx.z * bo.out_batch +
                                         o * ((int64_t)bo.out_w * bo.out_h) + at;
