@@ -192,6 +192,80 @@ struct SelectEmitSlots {
 };
 
 // ---------------------------------------------------------------------------------------------------------
+// Histogram seeding of the threshold search (long groups).  Counting probes cost two vector instructions per element
+// each and about ten of them are needed from a cold start; a histogram over the top ten key bits costs about as much
+// as one and a half probes (its additions run on the LDS, which this kernel does not otherwise use), and its bin
+// counts, summed from the top, name the bin that holds the k-th largest key together with the exact counts at the
+// bin's two ends.  A second histogram over the next ten bits of the keys inside that bin leaves a bracket of 2^11
+// keys (fp32) or a single key (bf16) with exact counts at both ends, which the counting search then finishes -- in
+// most groups without a single probe, because the bracket's low end already has exactly k keys at or above it.
+// Zero keys are left out (count and position of the zeros follow from the total): a post-ReLU tensor would otherwise
+// send half of its elements to one LDS address.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int kHistBinBits = 10, kHistBins = 1 << kHistBinBits;
+constexpr int kHistMinSlots = 32;  // groups of at least 2048 elements take it
+
+// One level: bins of (rot key >> shift) & bin_mask over the rot keys in [key_lo, key_lo + key_width) (modulo 2^32; one
+// subtraction and one unsigned compare per key).  On return: bin = the bin that holds the want-th largest of those
+// keys, above = how many of them lie in higher bins, inside = how many in the bin itself.  Returns false when fewer
+// than `want` keys took part; above is then their number.  h: this wavefront's kHistBins words of LDS.
+template <int E, bool ALL_NONZERO>  // ALL_NONZERO: key_lo = 2 and the range runs to the top (level 1)
+__device__ __forceinline__ bool hist_level(const uint32_t (&kr)[E], uint32_t* h, int lane, int shift, uint32_t bin_mask,
+                                           uint32_t key_lo, uint32_t key_width, uint32_t want, uint32_t* bin,
+                                           uint32_t* above, uint32_t* inside) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4* h4 = reinterpret_cast<u32x4*>(h);
+#pragma unroll
+  for (int i = 0; i < kHistBins / 256; ++i) h4[lane + 64 * i] = u32x4{0u, 0u, 0u, 0u};
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  // The additions: per key one shift, one and-or (bin -> LDS byte address; the wavefront's region is 4 KB aligned), a
+  // compare that narrows exec to the keys that take part, and the LDS add -- the last two inside one asm statement
+  // that puts exec back, so the compiler sees no change of it.  (From C++ the same loop compiled to six vector
+  // instructions per key and cost as much as the probes it replaces.)  LDS instructions of a wavefront execute in
+  // order, so the reads below see the additions.
+  uint32_t base;  // in a vector register, so that mask (scalar) and base fit one and-or instruction
+  asm("v_mov_b32 %0, %1" : "=v"(base) : "s"((uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint32_t*)h));
+  const uint32_t one = 1u, byte_mask = bin_mask << 2;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const uint32_t addr = ((shift >= 2 ? kr[j] >> (shift - 2) : kr[j] << (2 - shift)) & byte_mask) | base;
+    uint64_t saved;
+    if constexpr (ALL_NONZERO)
+      asm volatile("s_mov_b64 %0, exec\n\tv_cmpx_le_u32_e32 2, %1\n\tds_add_u32 %2, %3\n\ts_mov_b64 exec, %0"
+                   : "=&s"(saved) : "v"(kr[j]), "v"(addr), "v"(one) : "vcc", "memory");
+    else
+      asm volatile("s_mov_b64 %0, exec\n\tv_cmpx_gt_u32_e32 %1, %2\n\tds_add_u32 %3, %4\n\ts_mov_b64 exec, %0"
+                   : "=&s"(saved) : "s"(key_width), "v"(kr[j] - key_lo), "v"(addr), "v"(one) : "vcc", "memory");
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  // lane l sums the 16 bins of chunk 63 - l, so that a prefix sum over the lanes runs from the highest keys down
+  uint32_t s = 0;
+#pragma unroll
+  for (int i = 0; i < kHistBins / 256; ++i) {
+    const u32x4 q = h4[(63 - lane) * (kHistBins / 256) + i];
+    s += (q[0] + q[1]) + (q[2] + q[3]);
+  }
+  const uint32_t incl = wave_incl_scan_u32(s, lane);
+  const uint64_t has = ballot64(incl >= want);
+  if (has == 0) {
+    *above = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    return false;
+  }
+  const int L = __builtin_ctzll(has);  // first lane, from the top, whose chunk reaches the want-th key
+  const uint32_t before = (uint32_t)__builtin_amdgcn_readlane((int)(incl - s), L);
+  // the chunk's 16 bins, highest first, on lanes 0..15 (every row of 16 lanes does the same)
+  const int chunk = 63 - L;
+  const uint32_t c = h[chunk * 16 + 15 - (lane & 15)];
+  const uint32_t run = row_incl_scan_u32(c) + before;
+  const uint64_t hit = ballot64(run >= want) & 0xffffull;
+  const int i = __builtin_ctzll(hit);  // non-empty: the chunk's total reaches want
+  *bin = (uint32_t)(chunk * 16 + 15 - i);
+  *inside = (uint32_t)__builtin_amdgcn_readlane((int)c, i);
+  *above = (uint32_t)__builtin_amdgcn_readlane((int)run, i) - *inside;
+  return true;
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // path 1: one wavefront per group, group in registers
 // ---------------------------------------------------------------------------------------------------------
 // group `grp` of one tensor, by the calling wavefront
@@ -241,10 +315,43 @@ __device__ __forceinline__ void select_pack_group(const BitsT* __restrict__ A, B
     int c_hi = 0;
     bool found = false;
     uint32_t thr2 = 0;
+    bool probe_nonzero = true, first_guess = true;
+    if constexpr (E >= kHistMinSlots) {
+      // two histogram levels put the bracket around the k-th largest key with exact counts at both ends
+      __shared__ __attribute__((aligned(16))) uint32_t hist_lds[4][kHistBins];
+      uint32_t* h = hist_lds[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
+      constexpr int S1 = Key<BitsT>::kBits + 1 - kHistBinBits;              // rot keys have kBits + 1 bits
+      constexpr int S2 = S1 - kHistBinBits > 1 ? S1 - kHistBinBits : 1;     // bit 0 is the sign
+      uint32_t b1 = 0, above1 = 0, in1 = 0;
+      first_guess = probe_nonzero = false;
+      // level 1: every key of non-zero magnitude (rot key >= 2)
+      if (!hist_level<E, true>(kr, h, lane, S1, (uint32_t)(kHistBins - 1), 2u, 0u - 2u, (uint32_t)k, &b1, &above1, &in1)) {
+        // fewer than k non-zero keys: the threshold is the tie at zero, and count(key >= 1) is the histogram's total
+        lo = 0;
+        hi = 1;
+        c_hi = (int)above1;
+      } else {
+        // level 2: the non-zero keys of bin b1 (at least k - above1 of them), by their next S1 - S2 bits
+        uint32_t b2 = 0, above2 = 0, in2 = 0;
+        const uint32_t bin_lo = max(b1 << S1, 2u);
+        hist_level<E, false>(kr, h, lane, S2, (1u << (S1 - S2)) - 1u, bin_lo, ((b1 + 1u) << S1) - bin_lo,
+                             (uint32_t)k - above1, &b2, &above2, &in2);
+        const uint32_t lo_rot = (b1 << S1) | (b2 << S2);
+        lo = max(lo_rot >> 1, 1u);  // the histogram holds no zero keys: its lowest bin starts at magnitude 1
+        hi = (lo_rot >> 1) + (1u << (S2 - 1));
+        c_hi = (int)(above1 + above2);
+        const int c_lo = c_hi + (int)in2;
+        f_lo = (float)(c_lo - k);
+        f_hi = (float)(c_hi - k);
+        if (c_lo == k) {
+          found = true;
+          thr2 = lo << 1;
+        }
+      }
+    }
     // first guess: 16 octaves below the largest magnitude (covers the populated range of typical activations)
     constexpr uint32_t kSixteenOctaves = 16u << (Key<BitsT>::kBits - 8);
-    bool probe_nonzero = true;
-    if (hi > kSixteenOctaves + 1u) {
+    if (first_guess && hi > kSixteenOctaves + 1u) {
       const uint32_t guess = hi - 1u - kSixteenOctaves;
       const int c = count_ge<E>(kr, guess << 1);
       if (c == k) {
