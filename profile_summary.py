@@ -77,7 +77,7 @@ def per_kernel_counters(path, only=None):
 def cmd_counters(args):
     header(args)
     acc, dur = per_kernel_counters(find(args.dir, "counter_collection.csv"))
-    order = sorted(acc, key=lambda n: -sum(dur[n].values()))[:args.top]
+    order = sorted((n for n in acc if args.only in n), key=lambda n: -sum(dur[n].values()))[:args.top]
     for n in order:
         d = list(dur[n].values())
         print("%s  dispatches=%d avg_us=%.1f" % (n, len(d), sum(d) / len(d)))
@@ -143,6 +143,7 @@ def main():
         p.add_argument("--title", default="rocprofv3 summary")
         p.add_argument("--command", default="")
         p.add_argument("--top", type=int, default=14)
+        p.add_argument("--only", default="", help="counters: kernels whose name contains this text")
     p = sub.add_parser("traffic")
     p.add_argument("--fetch", required=True)
     p.add_argument("--write", required=True)
