@@ -290,7 +290,8 @@ __global__ __launch_bounds__(256) void da_conv_fewch_kernel(DaGeom g, const T* _
 // one tap: the dY operand is the same patch read at a per-tap offset, with no index arithmetic per element.  The next
 // step's values are loaded into registers before the matrix instructions of the current one.  Four wavefronts split
 // the positions.  Measured on the three WideResNet-28-10 stages (200 images): 95 to 99 TFLOP/s, against 42 for the
-// gathering kernel above.
+// gathering kernel above.  Eight wavefronts of 16 positions each (four per SIMD on a compute unit instead of two) were
+// slower, 85 to 93: twice the filter-tile reads per matrix instruction, and 128 registers do not hold the 160-channel tile.
 constexpr int kDa3Co = 8;         // output channels per step
 
 constexpr int da3_filter_row_stride(int ct) {
