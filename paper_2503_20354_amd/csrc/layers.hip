@@ -402,10 +402,110 @@ __global__ __launch_bounds__(256) void dw_grouped3x3_kernel(Grouped3x3Geom g, Pa
   }
 }
 
+// ---- depthwise 3x3, stride 1, pad 1 (one filter per channel) -----------------------------------------------------------
+// dW[c][u][v] = sum_{b,oh,ow} dY[b][c][oh][ow] * A_pruned[b][c][oh+u-1][ow+v-1]: nine multiply-adds per pixel and two
+// elements read, an HBM-bound sum.  A workgroup owns one channel (and one split of the (image, band of R rows) units);
+// each of its four wavefronts takes units in turn: it un-packs the band's R + 2 input rows -- a contiguous run of the
+// flat tensor -- into its own zero-haloed LDS plane (eight elements per lane in flight: mask words and ranks first,
+// then the values), then walks the band's pixels with the lanes along the row: one coalesced dY load, nine LDS reads at
+// fixed offsets, nine multiply-adds into per-lane sums.  The lanes' sums are added in a fixed tree at the end, the
+// splits by the reduction kernel: deterministic.
+struct DepthwiseGeom {
+  int Nb, C, H, W, R, bands, n_units, units_per_split;
+  int w_shift;  // log2(W) when W is a power of two, else -1
+};
+constexpr int kDepthwiseBatch = 8;
+
+template <typename T>
+__global__ __launch_bounds__(256) void dw_depthwise3x3_kernel(DepthwiseGeom g, Packed<T> pk, const T* __restrict__ dY,
+                                                              float* __restrict__ out) {
+  extern __shared__ float dwl[];  // four planes of (R + 2) x (W + 2)
+  __shared__ float red[4][9];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = blockIdx.x;
+  const int PW = g.W + 2, region = (g.R + 2) * PW;
+  float* a = dwl + wave * region;
+  for (int i = lane; i < region; i += 64) a[i] = 0.0f;  // the halo columns stay zero from here on
+  float acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t) acc[t] = 0.0f;
+  const int u_begin = (int)blockIdx.y * g.units_per_split, u_end = min(u_begin + g.units_per_split, g.n_units);
+  for (int unit = u_begin + wave; unit < u_end; unit += 4) {
+    const int b = unit / g.bands, r0 = (unit - b * g.bands) * g.R;
+    const int64_t plane = ((int64_t)b * g.C + c) * g.H;  // row index of the plane's first row
+    const int rows_here = min(g.R, g.H - r0);
+    // staged row rr <-> input row r0 - 1 + rr; rows 0 .. rows_here + 1 are read.  Those outside the map are zero.
+    const int ih_lo = max(r0 - 1, 0), ih_hi = min(r0 + rows_here + 1, g.H);
+    if (r0 == 0)
+      for (int i = lane; i < g.W; i += 64) a[i + 1] = 0.0f;
+    if (r0 + rows_here == g.H)
+      for (int i = lane; i < g.W; i += 64) a[(rows_here + 1) * PW + i + 1] = 0.0f;
+    const int64_t e_lo = (plane + ih_lo) * g.W;
+    const int count = (ih_hi - ih_lo) * g.W;
+    float* a_rows = a + (ih_lo - (r0 - 1)) * PW + 1;
+    for (int i0 = 0; i0 < count; i0 += 64 * kDepthwiseBatch) {
+      uint64_t word[kDepthwiseBatch];
+      uint32_t rank[kDepthwiseBatch];
+#pragma unroll
+      for (int q = 0; q < kDepthwiseBatch; ++q) {
+        const int i = min(i0 + 64 * q + lane, count - 1);
+        const int64_t w = (e_lo + i) >> 6;
+        word[q] = pk.mask[w];
+        rank[q] = pk.word_rank[w];
+      }
+      float x[kDepthwiseBatch];
+#pragma unroll
+      for (int q = 0; q < kDepthwiseBatch; ++q) {
+        const int i = min(i0 + 64 * q + lane, count - 1);
+        const int bit = (int)((e_lo + i) & 63);
+        const bool kept = (word[q] >> bit) & 1ull;
+        int64_t pos = (int64_t)rank[q] + __popcll(word[q] & ((1ull << bit) - 1ull));
+        pos = pos > pk.k_last ? pk.k_last : pos;
+        x[q] = widen<T>(pk.vals[pos]);  // k_total >= 1 here: position k_last exists
+        x[q] = kept ? x[q] : 0.0f;
+      }
+#pragma unroll
+      for (int q = 0; q < kDepthwiseBatch; ++q) {
+        const int i = i0 + 64 * q + lane;
+        if (i < count) {
+          const int row = g.w_shift >= 0 ? i >> g.w_shift : i / g.W;
+          a_rows[row * PW + (i - row * g.W)] = x[q];
+        }
+      }
+    }
+    // the band's pixels, lanes along the rows
+    const int npix = rows_here * g.W;
+    const T* __restrict__ y = dY + (plane + r0) * g.W;
+    for (int q = lane; q < npix; q += 64) {
+      const int oh = g.w_shift >= 0 ? q >> g.w_shift : q / g.W;
+      const int ow = q - oh * g.W;
+      const float dy = widen<T>(y[q]);
+      const float* t = a + oh * PW + ow;  // tap (u, v) reads input (oh + u - 1, ow + v - 1) = staged (oh + u, ow + v)
+#pragma unroll
+      for (int u = 0; u < 3; ++u)
+#pragma unroll
+        for (int v = 0; v < 3; ++v) acc[u * 3 + v] = fmaf(dy, t[u * PW + v], acc[u * 3 + v]);
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    float v = acc[t];
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    if (lane == 0) red[wave][t] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < 9)
+    out[((int64_t)blockIdx.y * g.C + c) * 9 + threadIdx.x] =
+        (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
 struct GroupedPlan {
   GroupedGeom g;
   bool tiled;          // the 3x3 stride-1 pad-1 kernel with LDS tiles
   Grouped3x3Geom t;
+  bool depthwise;      // the depthwise 3x3 stride-1 pad-1 kernel
+  DepthwiseGeom dwg;
   size_t lds_bytes;
   int splits;
   int64_t n, n_words, n_rank_blocks;
@@ -434,13 +534,36 @@ int plan_grouped(const surgeon_layer_desc* d, GroupedPlan* p) {
   g.OW = (g.W + 2 * g.pad - g.KW) / g.stride + 1;
   g.n_pos = (int64_t)g.Nb * g.OH * g.OW;
   g.n_w = (int64_t)g.Co * g.Cig * g.KH * g.KW;
-  // Depthwise layers (one pair per group) keep the generic kernel: their tile would be 64 channels wide, a band of one
-  // or two rows with as much halo again, and the un-pack of the halo costs more than the tile saves (measured on a
-  // 1280-channel 64x64 layer: 290-360 us tiled, 200 us generic).
+  // Depthwise layers (one pair per group) do not take the tiled kernel: their tile would be 64 channels wide, a band of
+  // one or two rows with as much halo again, and the un-pack of the halo costs more than the tile saves (measured on a
+  // 1280-channel 64x64 layer: 290-360 us tiled, 200 us generic).  They have a kernel of their own, below.
   const int pairs_per_group = g.Cog * g.Cig;
   p->tiled = g.KH == 3 && g.KW == 3 && g.stride == 1 && g.pad == 1 && pairs_per_group >= 4 && pairs_per_group <= 64 &&
              64 % pairs_per_group == 0;
   p->lds_bytes = 0;
+  p->depthwise = false;
+  if (g.KH == 3 && g.KW == 3 && g.stride == 1 && g.pad == 1 && g.Cig == 1 && g.Cog == 1 && 3 * (g.W + 2) <= 2048) {
+    // bands of at most 2048 / (W + 2) - 2 rows (8 KB of LDS per wavefront), of about equal height
+    DepthwiseGeom& q = p->dwg;
+    const int r_max = std::min(g.H, 2048 / (g.W + 2) - 2);
+    q.Nb = g.Nb; q.C = g.Ci; q.H = g.H; q.W = g.W;
+    q.bands = (int)ceil_div(g.H, r_max);
+    q.R = (int)ceil_div(g.H, q.bands);
+    q.bands = (int)ceil_div(g.H, q.R);
+    q.w_shift = (g.W & (g.W - 1)) == 0 ? __builtin_ctz((unsigned)g.W) : -1;
+    const int64_t units = (int64_t)g.Nb * q.bands;
+    if (units <= 0x7fffffff) {
+      p->depthwise = true;
+      q.n_units = (int)units;
+      // about 1024 workgroups, at least one unit per wavefront
+      int64_t splits = std::max<int64_t>(1, std::min<int64_t>(ceil_div(1024, g.Ci), ceil_div(units, 4)));
+      splits = std::min<int64_t>(splits, 256);
+      q.units_per_split = (int)ceil_div(units, splits);
+      p->splits = (int)ceil_div(units, q.units_per_split);
+      p->lds_bytes = (size_t)4 * (q.R + 2) * (g.W + 2) * sizeof(float);
+      g.pos_per_split = 0;
+    }
+  }
   if (p->tiled) {
     Grouped3x3Geom& t = p->t;
     t.Nb = g.Nb; t.Ci = g.Ci; t.Co = g.Co; t.H = g.H; t.W = g.W; t.Cig = g.Cig; t.Cog = g.Cog; t.groups = g.groups;
@@ -461,7 +584,9 @@ int plan_grouped(const surgeon_layer_desc* d, GroupedPlan* p) {
     }
     if (t.R == 0) p->tiled = false;  // a single row does not fit: very wide maps keep the generic kernel
   }
-  if (p->tiled) {
+  if (p->depthwise) {
+    // planned above
+  } else if (p->tiled) {
     Grouped3x3Geom& t = p->t;
     t.bands = (int)ceil_div(g.H, t.R);
     t.n_tiles = g.Nb * t.bands;
@@ -527,7 +652,12 @@ static int run_grouped_t(const GroupedPlan& p, const surgeon_layer_desc* d, cons
   pk.n_words = p.n_words;
   float* out = p.splits > 1 ? part : dW;
   const dim3 grid((unsigned)(g.Co * g.Cig), (unsigned)p.splits);
-  if (p.tiled) {
+  if (p.depthwise) {
+    ProfScope prof(SURGEON_PROF_DW_GROUPED, st);
+    SURGEON_LAUNCH((dw_depthwise3x3_kernel<T>), dim3((unsigned)g.Ci, (unsigned)p.splits), dim3(256), p.lds_bytes, st, p.dwg, pk,
+                   (const T*)dY, out);
+    SURGEON_LAUNCH_CHECK();
+  } else if (p.tiled) {
     ProfScope prof(SURGEON_PROF_DW_GROUPED, st);
     static std::atomic<uint64_t> lds_set{0};  // this function is instantiated per element type = per kernel
     if (p.lds_bytes > 48 * 1024) {

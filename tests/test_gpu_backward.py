@@ -366,6 +366,10 @@ GROUPED = [
     # do not divide the map, many tiles per split
     (3, 24, 12, 12, 24, 3, 1, 1, 6), (2, 32, 10, 10, 64, 3, 1, 1, 8), (1, 16, 72, 64, 16, 3, 1, 1, 4),
     (40, 64, 8, 8, 64, 3, 1, 1, 8), (3, 100, 12, 12, 100, 3, 1, 1, 100),
+    # the depthwise 3x3 kernel: bands of unequal height, maps whose width is no power of two, planes that start inside a
+    # mask word, fewer units than wavefronts, many units per split, a wide map with short bands
+    (1, 40, 70, 64, 40, 3, 1, 1, 40), (2, 7, 7, 7, 7, 3, 1, 1, 7), (1, 3, 5, 200, 3, 3, 1, 1, 3), (50, 16, 14, 14, 16, 3, 1, 1, 16),
+    (1, 2, 1, 1, 2, 3, 1, 1, 2), (2, 1280, 16, 16, 1280, 3, 1, 1, 1280),
 ]
 
 
