@@ -335,6 +335,10 @@ def next_rows(extras, torch, surgeon, wl, dev, cfg):
         t_ms = p["dw_grouped"][0] + p["dw_aux"][0]
         g_out[name] = {"ms": round(t_ms, 4), "tflops_dense_equiv": round(_rate(fl, t_ms) / 1e12, 3),
                        "frac_of_fp32_vector_peak": round(_rate(fl, t_ms) / 1e12 / PEAK_VALU_F32_TFLOPS, 4)}
+        if groups == C:
+            # nine multiply-adds per pixel: bound by the bytes of the packed activation and dY, not by the vector ALU
+            nb = pk.k_total * es + 8 * ((A.numel() + 63) // 64) + dYg.numel() * es
+            g_out[name].update({"hbm_gbps": round(_rate(nb, t_ms) / 1e9, 1), "frac_of_hbm": round(_rate(nb, t_ms) / 1e9 / PEAK_HBM_GBPS, 4)})
     out["dw_grouped"] = dict(bound="alu", peak=PEAK_VALU_F32_TFLOPS, unit="TFLOP/s", **g_out)
 
     # selection over the whole tensor (group_len = n), the paper-literal scope: reported against 2*n*s + outputs
