@@ -509,6 +509,8 @@ struct GroupedPlan {
   size_t lds_bytes;
   int splits;
   int64_t n, n_words, n_rank_blocks;
+  int rank_words_per_group;  // > 0: closed-form group positions (rank_grouped_kernel), as in the plain layers' plan
+  int64_t rank_groups, rank_k_full;
   size_t off_rank, off_blocks, off_part, ws_bytes;
 };
 
@@ -607,6 +609,16 @@ int plan_grouped(const surgeon_layer_desc* d, GroupedPlan* p) {
   }
   p->n = (int64_t)g.Nb * g.Ci * g.H * g.W;
   p->n_words = ceil_div(p->n, 64);
+  p->rank_words_per_group = 0;
+  if (d->group_len > 0 && d->group_len % 64 == 0 && d->group_len <= kWaveRegMaxGroup && p->n > 0) {
+    GroupPlan gp;
+    if (make_group_plan(p->n, d->group_len, d->r, &gp) && gp.g % 64 == 0 && gp.k_total == d->k_total &&
+        gp.n_groups * gp.k_full < ((int64_t)1 << 32)) {  // gp.g: the group length after clamping to n
+      p->rank_words_per_group = (int)(gp.g / 64);
+      p->rank_groups = gp.n_groups;
+      p->rank_k_full = gp.k_full;
+    }
+  }
   p->n_rank_blocks = ceil_div(p->n_words, kRankWordsPerBlock);
   size_t off = 0;
   p->off_rank = off;
@@ -634,7 +646,12 @@ static int run_grouped_t(const GroupedPlan& p, const surgeon_layer_desc* d, cons
     SURGEON_LAUNCH_CHECK();
     return SURGEON_OK;
   }
-  {
+  if (p.rank_words_per_group > 0) {
+    ProfScope prof(SURGEON_PROF_DW_AUX, st);
+    SURGEON_LAUNCH(rank_grouped_kernel, dim3((unsigned)ceil_div(p.rank_groups, kRankBlock / 64)), dim3(kRankBlock), 0, st, mask,
+                   p.n_words, p.rank_words_per_group, p.rank_groups, (uint32_t)p.rank_k_full, word_rank);
+    SURGEON_LAUNCH_CHECK();
+  } else {
     ProfScope prof(SURGEON_PROF_DW_AUX, st);
     SURGEON_LAUNCH(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words, block_sum);
     SURGEON_LAUNCH_CHECK();

@@ -392,3 +392,11 @@ def test_dw_grouped_conv(dtype, case):
         assert_dw_close(dW, ref, dtype, case)
         o_G = oracle.grad_importance(ref)
         assert abs(G - o_G) <= 1e-5 * max(o_G, 1e-30)
+        # without the packing's (group_len, r) in the descriptor the rank table comes from the general prefix sum
+        # instead of the closed form: the same table, so the same bits
+        desc.group_len, desc.r = 0, 0.0
+        plain = torch.empty(dW.shape, device=DEV)
+        ws = torch.empty(max(16, surgeon.surgeon_dw_ws_bytes(desc)), dtype=torch.uint8, device=DEV)
+        surgeon.surgeon_dw_from_packed(desc, p.vals, p.mask, dY.to(DEV), plain, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(plain.cpu().numpy(), dW), (case, "hint vs no hint")
