@@ -273,7 +273,7 @@ def next_rows(extras, torch, surgeon, wl, dev, cfg):
     tf = _rate(fl, t_ms) / 1e12
     out["da_bf16_linear"] = {"bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_MFMA_TFLOPS["bf16"], "unit": "TFLOP/s",
                              "frac": round(tf / PEAK_MFMA_TFLOPS["bf16"], 4), "ms": round(t_ms, 4),
-                             "us_per_layer": dict(rows), "what": "transpose of dY + contraction + finishing kernel"}
+                             "us_per_layer": dict(rows), "what": "transpose of dY + contraction; the kernel stores bf16 itself when one split suffices"}
 
     # Eq. 4 as a call of its own over every layer's dW (the path above computes it inside the weight-gradient call and
     # never reads dW again; this is the stand-alone, HBM-bound kernel for callers that have dW from elsewhere)

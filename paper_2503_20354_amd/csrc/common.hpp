@@ -112,8 +112,9 @@ int launch_conv1x1_bf16(int Nb, int Ci, int Co, int HW, const void* A_dense, con
                         int64_t ktiles_per_split, hipStream_t st);
 // dense bf16 contraction with a 256 (out) x 128 (in) workgroup tile of eight wavefronts and LDS-direct loads, for layers
 // that fill it (dw_bf16.hip)
+// bf16_out: `out` is a bf16 matrix [N x K] that the kernel writes itself (needs splits == 1)
 int launch_linear_bf16_big(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,
-                           int64_t rows_per_split, hipStream_t st);
+                           int64_t rows_per_split, hipStream_t st, bool bf16_out = false);
 // activation gradient of a bf16 1x1 convolution (pad 0, stride 1 or 2) on the same matrix-core contraction, one image
 // per grid z (dw_bf16.hip); Nb <= 65535
 int launch_da_conv1x1_bf16(int Nb, int Ci, int Co, int H, int W, int stride, const void* Wt, const void* dY, void* dA,

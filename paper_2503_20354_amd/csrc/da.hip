@@ -757,7 +757,8 @@ static DaFastPlan plan_da_fast(const surgeon_layer_desc* d) {
   p.splits = (int)ceil_div(k_tiles, per);
   p.rows_per_split = per * kBf16BigTokens;
   p.off_part = align_up((size_t)d->M * d->N * 2, 256);
-  p.ws_bytes = p.off_part + align_up((size_t)p.splits * d->M * d->K * 4, 256);
+  // one split: the contraction kernel stores bf16 itself and there are no partial results
+  p.ws_bytes = p.off_part + (p.splits > 1 ? align_up((size_t)p.splits * d->M * d->K * 4, 256) : 0);
   p.ok = true;
   return p;
 }
@@ -872,8 +873,11 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
       {
         // contraction over n: "tokens" = N, out-features = M (from dY^T), in-features = K (from W)
         ProfForce as_da(SURGEON_PROF_DA);
-        const int rc = launch_linear_bf16_big(d->N, d->K, d->M, Wt, dYt, part, fp.splits, fp.rows_per_split, st);
+        const bool direct = fp.splits == 1;
+        const int rc = launch_linear_bf16_big(d->N, d->K, d->M, Wt, dYt, direct ? (float*)dA : part, fp.splits,
+                                              fp.rows_per_split, st, direct);
         if (rc != SURGEON_OK) return rc;
+        if (direct) return SURGEON_OK;
       }
       ProfScope prof(SURGEON_PROF_DA, st);
       const int64_t n_out = d->M * d->K;

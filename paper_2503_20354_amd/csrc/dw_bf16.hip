@@ -431,7 +431,8 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-template <int TI>
+// BF16OUT: one split, and the result goes out as bf16 at out[o][i] (the activation gradient's use of this kernel)
+template <int TI, bool BF16OUT = false>
 __global__ __launch_bounds__(512) void dw_linear_bf16_big_kernel(int64_t M, int64_t K, int64_t N, int i_tiles,
                                                                  int64_t rows_per_split, const uint16_t* __restrict__ A,
                                                                  const uint16_t* __restrict__ dY, float* __restrict__ out) {
@@ -560,18 +561,33 @@ __global__ __launch_bounds__(512) void dw_linear_bf16_big_kernel(int64_t M, int6
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int64_t o = o0 + wo * 64 + p * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-        if (o < N && i < K) dst[o * K + i] = acc[p][q][v];
+        if (o < N && i < K) {
+          if constexpr (BF16OUT)
+            reinterpret_cast<uint16_t*>(out)[o * K + i] = (uint16_t)bf16_bits_rne(acc[p][q][v]);
+          else
+            dst[o * K + i] = acc[p][q][v];
+        }
       }
     }
 }
 
 int launch_linear_bf16_big(int64_t M, int64_t K, int64_t N, const void* A_dense, const void* dY, float* out, int splits,
-                           int64_t rows_per_split, hipStream_t st) {
+                           int64_t rows_per_split, hipStream_t st, bool bf16_out) {
   constexpr int TI = kBf16BigTileI;
   static_assert(BigShape<TI>::TOK == kBf16BigTokens, "the planner sizes splits in K-tiles of this many tokens");
   const int i_tiles = (int)ceil_div(K, TI), o_tiles = (int)ceil_div(N, kBigTO);
   const dim3 grid((unsigned)(o_tiles * i_tiles), (unsigned)splits);
   ProfScope prof(SURGEON_PROF_DW, st);
+  if (bf16_out) {
+    if (splits != 1) return fail(SURGEON_EINVAL, "bf16 contraction: a bf16 result needs a single split");
+    static std::atomic<uint64_t> lds_set_bf16{0};
+    const int rc_lds = ensure_dynamic_lds((const void*)dw_linear_bf16_big_kernel<TI, true>, BigShape<TI>::LDS, lds_set_bf16);
+    if (rc_lds != SURGEON_OK) return rc_lds;
+    SURGEON_LAUNCH((dw_linear_bf16_big_kernel<TI, true>), grid, dim3(512), BigShape<TI>::LDS, st, M, K, N, i_tiles,
+                   rows_per_split, (const uint16_t*)A_dense, (const uint16_t*)dY, out);
+    SURGEON_LAUNCH_CHECK();
+    return SURGEON_OK;
+  }
   static std::atomic<uint64_t> lds_set{0};
   const int rc_lds = ensure_dynamic_lds((const void*)dw_linear_bf16_big_kernel<TI>, BigShape<TI>::LDS, lds_set);
   if (rc_lds != SURGEON_OK) return rc_lds;
