@@ -119,6 +119,8 @@ int launch_linear_bf16_big(int64_t M, int64_t K, int64_t N, const void* A_dense,
 // per grid z (dw_bf16.hip); Nb <= 65535
 int launch_da_conv1x1_bf16(int Nb, int Ci, int Co, int H, int W, int stride, const void* Wt, const void* dY, void* dA,
                            hipStream_t st);
+// activation gradient of a bf16 linear layer with dY read in place (dw_bf16.hip); N % 8 == 0, dY 16-byte aligned
+int launch_da_linear_bf16(int64_t M, int64_t K, int64_t N, const void* dY, const void* Wt, void* dA, hipStream_t st);
 constexpr int kBf16BigTileO = 256, kBf16BigTileI = 128, kBf16BigTokens = 64;
 constexpr int kBf16LinearTile = 128, kBf16LinearTokens = 64;          // 128 x 128 tile, 64 tokens per K-tile
 constexpr int kBf16LinearTileWide = 256, kBf16LinearTokensWide = 32;  // 128 (out) x 256 (in) tile, 32 tokens

@@ -887,6 +887,9 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
       return SURGEON_OK;
     }
   }
+  if (linear && d->dtype == SURGEON_BF16 && d->N % 8 == 0 && ((uintptr_t)dY % 16) == 0 && d->M >= 64 && d->K >= 64 &&
+      d->N >= 64 && ceil_div(d->M, kBf16LinearTile) * ceil_div(d->K, kBf16LinearTile) <= 0x7fffffff)
+    return launch_da_linear_bf16(d->M, d->K, d->N, dY, Wt, dA, st);
   if (!linear && d->dtype == SURGEON_BF16 && g.KH == 1 && g.KW == 1 && g.pad == 0 && (g.stride == 1 || g.stride == 2) &&
       g.Nb <= 65535 && (int64_t)g.Ci * g.HW < ((int64_t)1 << 31))
     return launch_da_conv1x1_bf16(g.Nb, g.Ci, g.Co, g.H, g.W, g.stride, Wt, dY, dA, st);

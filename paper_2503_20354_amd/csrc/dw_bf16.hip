@@ -252,7 +252,11 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float f) {  // round to neares
 }
 
 // blockIdx.x = o_tile * i_tiles + i_tile, blockIdx.y = split along the tokens, blockIdx.z = batch entry.
-template <int PO, int PI, int TOK, bool YALIGNED, int AALIGN = 8, int OUT = kOutSplitsF32>
+// YROWS: the dY operand is given with the contraction index fast -- dY[o][t], row pitch M -- as the activation
+// gradient of a linear layer has it (its "tokens" are the layer's out-features): the tile is then staged [o][t] and an
+// operand register set is a plain 16-byte LDS read, as in the 1x1 convolution kernel below; rows 144 bytes apart, so
+// eight rows cover all banks.  Needs M % 8 == 0 and 16-byte aligned rows (YALIGNED).
+template <int PO, int PI, int TOK, bool YALIGNED, int AALIGN = 8, int OUT = kOutSplitsF32, bool YROWS = false>
 __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t K, int64_t N, int i_tiles,
                                                              int64_t rows_per_split, const uint16_t* __restrict__ A,
                                                              const uint16_t* __restrict__ dY, float* __restrict__ out,
@@ -260,9 +264,11 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
   A += (int64_t)blockIdx.z * bo.a_batch;
   dY += (int64_t)blockIdx.z * bo.y_batch;
   constexpr int TO = 64 * PO, TI = 64 * PI, SO = TO + kBfPad, SI = TI + kBfPad;
+  constexpr int ST = TOK + 8;  // YROWS: row pitch of the [o][t] tile
   constexpr int CY = TOK * TO / 8 / 256, CA = TOK * TI / 8 / 256;  // 16-byte chunks per thread and K-tile
   static_assert(TOK * TO / 8 % 256 == 0 && TOK * TI / 8 % 256 == 0 && TOK % 16 == 0, "tile shape");
-  __shared__ __attribute__((aligned(16))) uint16_t Ys[2][TOK * SO];
+  static_assert(!YROWS || YALIGNED, "row-major dY tiles are loaded 16 bytes at a time");
+  __shared__ __attribute__((aligned(16))) uint16_t Ys[2][YROWS ? TO * ST : TOK * SO];
   __shared__ __attribute__((aligned(16))) uint16_t As[2][TOK * SI];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -284,8 +290,13 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
   auto load_tile = [&](int64_t m0) {
 #pragma unroll
     for (int j = 0; j < CY; ++j) {
-      const int c = tid + 256 * j, row = c / (TO / 8), col = (c % (TO / 8)) * 8;
-      ry[j] = load_chunk<(YALIGNED ? 8 : 1)>(dY, m0 + row, m_end, o0 + col, N, N);
+      if constexpr (YROWS) {
+        const int c = tid + 256 * j, row = c / (TOK / 8), col = (c % (TOK / 8)) * 8;  // row: out-feature, col: token
+        ry[j] = load_chunk<8>(dY, o0 + row, N, m0 + col, m_end, M);
+      } else {
+        const int c = tid + 256 * j, row = c / (TO / 8), col = (c % (TO / 8)) * 8;
+        ry[j] = load_chunk<(YALIGNED ? 8 : 1)>(dY, m0 + row, m_end, o0 + col, N, N);
+      }
     }
 #pragma unroll
     for (int j = 0; j < CA; ++j) {
@@ -296,8 +307,13 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
   auto store_tile = [&](int buf) {
 #pragma unroll
     for (int j = 0; j < CY; ++j) {
-      const int c = tid + 256 * j, row = c / (TO / 8), col = (c % (TO / 8)) * 8;
-      *reinterpret_cast<u32x4*>(&Ys[buf][row * SO + col]) = ry[j];
+      if constexpr (YROWS) {
+        const int c = tid + 256 * j, row = c / (TOK / 8), col = (c % (TOK / 8)) * 8;
+        *reinterpret_cast<u32x4*>(&Ys[buf][row * ST + col]) = ry[j];
+      } else {
+        const int c = tid + 256 * j, row = c / (TO / 8), col = (c % (TO / 8)) * 8;
+        *reinterpret_cast<u32x4*>(&Ys[buf][row * SO + col]) = ry[j];
+      }
     }
 #pragma unroll
     for (int j = 0; j < CA; ++j) {
@@ -323,7 +339,12 @@ __global__ __launch_bounds__(256) void dw_linear_bf16_kernel(int64_t M, int64_t 
       const int t0 = ks + 8 * (blk >> 1);
       bf16x8 a[PO], b[PI];
 #pragma unroll
-      for (int q = 0; q < PO; ++q) a[q] = read_operand<SO>(ys, t0, wm * 32 * PO + q * 32 + 16 * (blk & 1), lane);
+      for (int q = 0; q < PO; ++q) {
+        if constexpr (YROWS)  // row = out-feature lane % 32 of the block, eight tokens from t0 on
+          a[q] = *reinterpret_cast<const bf16x8*>(&ys[(wm * 32 * PO + q * 32 + (lane & 31)) * ST + t0]);
+        else
+          a[q] = read_operand<SO>(ys, t0, wm * 32 * PO + q * 32 + 16 * (blk & 1), lane);
+      }
 #pragma unroll
       for (int q = 0; q < PI; ++q) b[q] = read_operand<SI>(as, t0, wn * 32 * PI + q * 32 + 16 * (blk & 1), lane);
 #pragma unroll
@@ -793,6 +814,26 @@ int launch_da_conv1x1_bf16(int Nb, int Ci, int Co, int H, int W, int stride, con
   }
 #undef SURGEON_DA1X1_ALIGN
 #undef SURGEON_DA1X1
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
+// Activation gradient of a bf16 linear layer (Eq. 2, first line) on the same contraction, dY read where it lies:
+// dA[m][k] = sum_n dY[m][n] W[n][k] -- the contraction index n is the fast one of dY (row-major tiles, plain LDS
+// reads) and the slow one of W (the kernel's usual operand).  One split; the kernel stores bf16.  Needs N % 8 == 0 and
+// 16-byte aligned dY; K % 8 != 0 or an unaligned W take 2-byte loads.
+int launch_da_linear_bf16(int64_t M, int64_t K, int64_t N, const void* dY, const void* Wt, void* dA, hipStream_t st) {
+  const int i_tiles = (int)ceil_div(K, kBf16LinearTile), o_tiles = (int)ceil_div(M, kBf16LinearTile);
+  const dim3 grid((unsigned)(o_tiles * i_tiles), 1, 1);
+  const bool wa = K % 8 == 0 && ((uintptr_t)Wt % 16) == 0;
+  ProfScope prof(SURGEON_PROF_DA, st);
+  // kernel arguments: contraction length ("tokens") = N, in-features = K, out rows = M; A operand = W, dY operand = dY
+  if (wa)
+    SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 2, kBf16LinearTokens, true, 8, kOutBf16, true>), grid, dim3(256), 0, st, N, K, M,
+                   i_tiles, N, (const uint16_t*)Wt, (const uint16_t*)dY, (float*)dA, BatchedOperands{});
+  else
+    SURGEON_LAUNCH((dw_linear_bf16_kernel<2, 2, kBf16LinearTokens, true, 1, kOutBf16, true>), grid, dim3(256), 0, st, N, K, M,
+                   i_tiles, N, (const uint16_t*)Wt, (const uint16_t*)dY, (float*)dA, BatchedOperands{});
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }

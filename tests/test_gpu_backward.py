@@ -117,7 +117,10 @@ def test_gradient_importance_inside_the_linear_weight_gradient(M, K, N, dtype, r
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("M,K,N", [(64, 512, 256), (100, 70, 50), (300, 129, 257), (1, 64, 64), (517, 320, 1280),
-                                   (1000, 768, 19), (129, 8, 8)])
+                                   (1000, 768, 19), (129, 8, 8),
+                                   # bf16 with N % 8 == 0: dY read in place on the bf16 matrix cores; K that 8 does
+                                   # not divide (element-wise loads of W), rows and columns that leave tiles part empty
+                                   (130, 100, 72), (1000, 768, 96), (200, 65, 64), (257, 136, 200), (64, 64, 64)])
 def test_da_linear(dtype, M, K, N):
     print("da linear", (M, K, N), dtype, flush=True)
     dY = wl.draw((M, N), "normal", dtype, M + N + 5)
