@@ -258,6 +258,7 @@ def next_rows(extras, torch, surgeon, wl, dev, cfg):
     # the same gradient for bf16 linear layers on the bf16 matrix cores (workspace entry), on the four layer shapes of a
     # ViT-B/16 block at 12 608 tokens
     rows, t_ms, fl = [], 0.0, 0.0
+    rows_plain, t_plain = [], 0.0
     for name, (M, K, N) in {"qkv": (12608, 768, 2304), "proj": (12608, 768, 768), "fc1": (12608, 768, 3072),
                             "fc2": (12608, 3072, 768)}.items():
         dYb = wl.draw((M, N), "normal", "bf16", 77, device=dev)
@@ -269,11 +270,16 @@ def next_rows(extras, torch, surgeon, wl, dev, cfg):
         t_ms += p["da"][0]
         fl += 2.0 * M * K * N
         rows.append((name, round(p["da"][0] * 1e3, 1)))
+        p = timed(lambda: surgeon.surgeon_da(d, dYb, Wb, dAb))  # no workspace: dY read in place
+        t_plain += p["da"][0]
+        rows_plain.append((name, round(p["da"][0] * 1e3, 1)))
         del dYb, Wb, dAb, wsb
     tf = _rate(fl, t_ms) / 1e12
     out["da_bf16_linear"] = {"bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_MFMA_TFLOPS["bf16"], "unit": "TFLOP/s",
                              "frac": round(tf / PEAK_MFMA_TFLOPS["bf16"], 4), "ms": round(t_ms, 4),
-                             "us_per_layer": dict(rows), "what": "transpose of dY + contraction; the kernel stores bf16 itself when one split suffices"}
+                             "us_per_layer": dict(rows), "what": "transpose of dY + contraction; the kernel stores bf16 itself when one split suffices",
+                             "without_workspace": {"achieved": round(_rate(fl, t_plain) / 1e12, 1), "ms": round(t_plain, 4),
+                                                   "us_per_layer": dict(rows_plain), "what": "surgeon_da: dY read in place"}}
 
     # Eq. 4 as a call of its own over every layer's dW (the path above computes it inside the weight-gradient call and
     # never reads dW again; this is the stand-alone, HBM-bound kernel for callers that have dW from elsewhere)
