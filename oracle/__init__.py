@@ -60,6 +60,8 @@ def lib():
         L.oracle_da_linear_at.argtypes = [vp, vp, i64, i64, i64, ci, vp, i64, vp]
         L.oracle_da_conv2d.restype = ci
         L.oracle_da_conv2d.argtypes = [vp, vp] + [i64] * 9 + [ci, vp]
+        L.oracle_da_conv2d_grouped.restype = ci
+        L.oracle_da_conv2d_grouped.argtypes = [vp, vp] + [i64] * 10 + [ci, vp]
         L.oracle_da_conv2d_at.restype = ci
         L.oracle_da_conv2d_at.argtypes = [vp, vp] + [i64] * 9 + [ci, vp, i64, vp]
         L.oracle_weight_update.restype = ci
@@ -227,6 +229,18 @@ def da_conv2d(dY, W, Nb, Ci, H, Wd, Co, kh, kw, stride, pad):
     assert _dt(dY) == _dt(W) and dY.size == Nb * Co * OH * OW and W.size == Co * Ci * kh * kw
     dA = np.empty((Nb, Ci, H, Wd), dtype=dY.dtype)
     assert lib().oracle_da_conv2d(_p(dY), _p(W), Nb, Ci, H, Wd, Co, kh, kw, stride, pad, _dt(dY), _p(dA)) == 0
+    return dA
+
+
+def da_conv2d_grouped(dY, W, Nb, Ci, H, Wd, Co, kh, kw, stride, pad, groups):
+    """Activation gradient of a convolution with channel groups (W is [Co, Ci/groups, kh, kw])."""
+    dY, W = _c(dY), _c(W)
+    OH, OW = (H + 2 * pad - kh) // stride + 1, (Wd + 2 * pad - kw) // stride + 1
+    assert Ci % groups == 0 and Co % groups == 0
+    assert _dt(dY) == _dt(W) and dY.size == Nb * Co * OH * OW and W.size == Co * (Ci // groups) * kh * kw
+    dA = np.empty((Nb, Ci, H, Wd), dtype=dY.dtype)
+    assert lib().oracle_da_conv2d_grouped(_p(dY), _p(W), Nb, Ci, H, Wd, Co, kh, kw, stride, pad, groups, _dt(dY),
+                                          _p(dA)) == 0
     return dA
 
 

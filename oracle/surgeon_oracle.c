@@ -15,7 +15,7 @@
  *   oracle_dw_*_at         the same definitions evaluated at caller-chosen output entries only
  *   oracle_grad_importance Eq. 4
  *   oracle_layer_scores / oracle_layer_ratios   Eq. 5, 6, 7
- *   oracle_da_linear / oracle_da_conv2d (+ _at)  Eq. 2, first line: the activation gradient dA = dY . W
+ *   oracle_da_linear / oracle_da_conv2d (+ _at) / oracle_da_conv2d_grouped  Eq. 2, first line: the activation gradient dA = dY . W
  *   oracle_weight_update   Alg. 1 line 14 read as one plain gradient step W <- W - lr * dW (the paper defers its
  *                          optimiser settings to an appendix that is not available)
  *   oracle_affine_grad     gradients of a normalisation layer's scale and shift from the pruned normalised
@@ -425,6 +425,37 @@ int oracle_da_conv2d(const void* dY, const void* Wt, int64_t Nb, int64_t Ci, int
         for (int64_t iw = 0; iw < W; ++iw)
           store_rounded(dA, dt, ((b * Ci + ci) * H + ih) * W + iw,
                         conv_da_entry(dY, Wt, dt, Ci, Co, OH, OW, kh, kw, stride, pad, b, ci, ih, iw));
+    }
+  }
+  return 0;
+}
+
+/* The same for a convolution with channel groups: W is [Co, Ci/groups, kh, kw]; input channel ci belongs to group
+ * ci / (Ci/groups) and receives from that group's Co/groups output channels only. */
+int oracle_da_conv2d_grouped(const void* dY, const void* Wt, int64_t Nb, int64_t Ci, int64_t H, int64_t W, int64_t Co,
+                             int64_t kh, int64_t kw, int64_t stride, int64_t pad, int64_t groups, int dt, void* dA) {
+  const int64_t OH = (H + 2 * pad - kh) / stride + 1, OW = (W + 2 * pad - kw) / stride + 1;
+  const int64_t Cig = Ci / groups, Cog = Co / groups;
+#pragma omp parallel for schedule(static) collapse(2)
+  for (int64_t b = 0; b < Nb; ++b) {
+    for (int64_t ci = 0; ci < Ci; ++ci) {
+      const int64_t grp = ci / Cig, cig = ci % Cig;
+      for (int64_t ih = 0; ih < H; ++ih)
+        for (int64_t iw = 0; iw < W; ++iw) {
+          double acc = 0.0;
+          for (int64_t co = grp * Cog; co < (grp + 1) * Cog; ++co)
+            for (int64_t u = 0; u < kh; ++u) {
+              const int64_t top = ih + pad - u;
+              if (top < 0 || top % stride != 0 || top / stride >= OH) continue;
+              for (int64_t v = 0; v < kw; ++v) {
+                const int64_t left = iw + pad - v;
+                if (left < 0 || left % stride != 0 || left / stride >= OW) continue;
+                acc += elem_as_double(dY, dt, ((b * Co + co) * OH + top / stride) * OW + left / stride) *
+                       elem_as_double(Wt, dt, ((co * Cig + cig) * kh + u) * kw + v);
+              }
+            }
+          store_rounded(dA, dt, ((b * Ci + ci) * H + ih) * W + iw, acc);
+        }
     }
   }
   return 0;

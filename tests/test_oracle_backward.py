@@ -123,6 +123,38 @@ def test_adjoint_identity_ties_da_and_dw_to_the_forward_convolution(case):
     assert abs(float((dW.astype(np.float64) * Wt).sum()) - lhs) <= 1e-5 * scale
 
 
+GROUPED_CASES = [
+    # Nb, Ci, H, W, Co, kh, kw, stride, pad, groups
+    (2, 6, 9, 8, 4, 3, 3, 1, 1, 2), (1, 8, 7, 7, 8, 3, 3, 1, 1, 8), (2, 4, 10, 9, 12, 3, 3, 2, 1, 4), (1, 6, 8, 8, 6, 5, 5, 2, 2, 3),
+    (2, 4, 6, 6, 8, 1, 1, 1, 0, 2),
+]
+
+
+@pytest.mark.parametrize("case", GROUPED_CASES)
+def test_grouped_da_is_the_library_input_gradient_and_satisfies_the_adjoint_identity(case):
+    """Pins of the grouped activation gradient: the float64 library routine with `groups`; groups = 1 gives the plain
+    oracle back; <dA, A> = <dW, W> with the grouped weight gradient of the oracle."""
+    Nb, Ci, H, W, Co, kh, kw, st, pad, groups = case
+    rng = np.random.default_rng(11 + sum(case))
+    OH, OW = (H + 2 * pad - kh) // st + 1, (W + 2 * pad - kw) // st + 1
+    A = rng.standard_normal((Nb, Ci, H, W)).astype(np.float32)
+    dY = rng.standard_normal((Nb, Co, OH, OW)).astype(np.float32)
+    Wt = rng.standard_normal((Co, Ci // groups, kh, kw)).astype(np.float32)
+    dA = oracle.da_conv2d_grouped(dY, Wt, Nb, Ci, H, W, Co, kh, kw, st, pad, groups)
+    ref = torch.nn.grad.conv2d_input((Nb, Ci, H, W), torch.from_numpy(Wt).double(), torch.from_numpy(dY).double(),
+                                     stride=st, padding=pad, groups=groups).numpy()
+    assert dA.shape == ref.shape
+    assert np.allclose(dA, ref, rtol=1e-6, atol=1e-6)
+    vals, mask, _, _ = oracle.prune_pack(A.reshape(-1), A.size, 0.0)
+    dW = oracle.dw_conv2d_grouped(vals, mask, dY, Nb, Ci, H, W, Co, kh, kw, st, pad, groups)
+    lhs = float((dA.astype(np.float64) * A).sum())
+    assert abs(float((dW.astype(np.float64) * Wt).sum()) - lhs) <= 1e-5 * float(np.abs(dA.astype(np.float64) * A).sum())
+    # one group: the plain routine, bit for bit
+    W1 = rng.standard_normal((Co, Ci, kh, kw)).astype(np.float32)
+    assert np.array_equal(oracle.da_conv2d_grouped(dY, W1, Nb, Ci, H, W, Co, kh, kw, st, pad, 1),
+                          oracle.da_conv2d(dY, W1, Nb, Ci, H, W, Co, kh, kw, st, pad))
+
+
 def test_one_by_one_convolution_input_gradient_is_the_linear_one():
     rng = np.random.default_rng(3)
     Nb, Ci, H, W, Co = 2, 5, 4, 3, 7
