@@ -197,7 +197,8 @@ int surgeon_dw_from_packed_gi(const surgeon_layer_desc* desc, const void* vals, 
  * Eq. 2, first line: the activation gradient dA = dY . W of the layer `desc` describes (k_total, group_len, r and the
  * packed activation play no part: dA does not depend on A).
  *   LINEAR : dY [M x N], W [N x K] (a framework's weight), dA [M x K]:  dA[m][k] = sum_n dY[m][n] * W[n][k]
- *   CONV2D : dY [Nb, Co, OH, OW], W [Co, Ci, kh, kw], dA [Nb, Ci, H, W] (groups <= 1 only):
+ *   CONV2D : dY [Nb, Co, OH, OW], W [Co, Ci/groups, kh, kw], dA [Nb, Ci, H, W]; with groups > 1 an input channel
+ *            receives from the Co/groups output channels of its own group only:
  *            dA[b][ci][ih][iw] = sum over (co, u, v) with oh*stride + u - pad == ih, ow*stride + v - pad == iw
  * dY, W and dA are device pointers of desc->dtype; products are exact (bf16 inputs widened or multiplied on the bf16
  * matrix cores), accumulation is fp32 (matrix cores; vector ALU for layers with at most four input channels), bf16

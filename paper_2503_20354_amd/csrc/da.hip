@@ -281,6 +281,48 @@ __global__ __launch_bounds__(256) void da_conv_fewch_kernel(DaGeom g, const T* _
     if (c < g.Ci) da_store<T>(&dA[((int64_t)b * g.Ci + c) * g.HW + rem], acc[c]);
 }
 
+// ---- convolutions with channel groups (grouped and depthwise layers): one thread per pixel of dA ----------------------
+// Input channel ci receives from the Co / groups output channels of its group only: far too few for a matrix tile.
+// A workgroup owns one (image, input channel) plane; that channel's filter taps of the group's output channels sit in
+// LDS as fp32; a thread walks the taps that reach its pixel under the layer's stride and, per tap, the group's output
+// channels.  fp32 accumulation in the order (tap, output channel).
+template <typename T>
+__global__ __launch_bounds__(256) void da_conv_grouped_kernel(DaGeom g, int Cig, int Cog, const T* __restrict__ dY,
+                                                              const T* __restrict__ Wt, T* __restrict__ dA) {
+  extern __shared__ float gw_lds[];  // [output channel of the group][tap]
+  const int plane = blockIdx.x;      // b * Ci + ci
+  const int b = plane / g.Ci, ci = plane - b * g.Ci;
+  const int grp = ci / Cig, cig = ci - grp * Cig;
+  const int taps = g.KH * g.KW;
+  for (int i = threadIdx.x; i < Cog * taps; i += 256) {
+    const int co_l = i / taps, t = i - co_l * taps;
+    gw_lds[i] = da_widen<T>(Wt[((int64_t)(grp * Cog + co_l) * Cig + cig) * taps + t]);
+  }
+  __syncthreads();
+  const int64_t ohw = (int64_t)g.OH * g.OW;
+  const T* __restrict__ ybase = dY + ((int64_t)b * g.Co + (int64_t)grp * Cog) * ohw;
+  for (int pos = (int)blockIdx.y * 256 + (int)threadIdx.x; pos < g.HW; pos += (int)gridDim.y * 256) {
+    const int ih = pos / g.W, iw = pos - ih * g.W;
+    float acc = 0.0f;
+    for (int u = 0; u < g.KH; ++u) {
+      const int th = ih + g.pad - u;
+      if (th < 0 || th % g.stride) continue;
+      const int oh = th / g.stride;
+      if (oh >= g.OH) continue;
+      for (int v = 0; v < g.KW; ++v) {
+        const int tw = iw + g.pad - v;
+        if (tw < 0 || tw % g.stride) continue;
+        const int ow = tw / g.stride;
+        if (ow >= g.OW) continue;
+        const T* __restrict__ y = ybase + (int64_t)oh * g.OW + ow;
+        const float* __restrict__ w = gw_lds + u * g.KW + v;
+        for (int co_l = 0; co_l < Cog; ++co_l) acc = __builtin_fmaf(da_widen<T>(y[co_l * ohw]), w[co_l * taps], acc);
+      }
+    }
+    da_store<T>(&dA[(int64_t)plane * g.HW + pos], acc);
+  }
+}
+
 // ---- 3x3, stride 1, pad 1 convolutions: the taps as shifted reads of one staged patch ---------------------------------
 // dA[b][ci][ih][iw] = sum_{co,u,v} dY[b][co][ih+1-u][iw+1-v] * W[co][ci][u][v].  A workgroup owns up to 128 positions
 // -- a band of R rows of one image, or several whole images of a small map -- and a tile of 16 NC input channels, and
@@ -835,7 +877,8 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
       return fail(SURGEON_EINVAL, "da: bad conv shape");
     if (d->H + 2 * d->pad < d->kh || d->W + 2 * d->pad < d->kw)
       return fail(SURGEON_EINVAL, "da: filter larger than the padded input");
-    if (d->groups > 1) return fail(SURGEON_EUNSUPPORTED, "da: grouped convolutions are not implemented");
+    if (d->groups > 1 && (d->Ci % d->groups || d->Co % d->groups))
+      return fail(SURGEON_EINVAL, "da: groups = %lld does not divide the channel counts", (long long)d->groups);
     const int64_t big = (int64_t)1 << 31;
     if (d->Co * d->kh * d->kw >= big || d->H * d->W >= big || d->Ci >= big || d->Nb >= big)
       return fail(SURGEON_EUNSUPPORTED, "da: conv tensor too large");
@@ -886,6 +929,22 @@ static int da_entry(const surgeon_layer_desc* d, const void* dY, const void* Wt,
       SURGEON_LAUNCH_CHECK();
       return SURGEON_OK;
     }
+  }
+  if (!linear && d->groups > 1) {
+    const int Cig = (int)(d->Ci / d->groups), Cog = (int)(d->Co / d->groups);
+    const size_t lds = (size_t)Cog * g.KH * g.KW * sizeof(float);
+    if (lds > 48 * 1024) return fail(SURGEON_EUNSUPPORTED, "da: a group's filters for one input channel exceed 48 KB");
+    if ((int64_t)g.Nb * g.Ci > 0x7fffffff) return fail(SURGEON_EUNSUPPORTED, "da: too many (image, channel) planes");
+    const dim3 grid((unsigned)(g.Nb * g.Ci), (unsigned)std::min<int64_t>(ceil_div(g.HW, 256), 64));
+    ProfScope prof(SURGEON_PROF_DA, st);
+    if (d->dtype == SURGEON_F32)
+      SURGEON_LAUNCH(da_conv_grouped_kernel<float>, grid, dim3(256), lds, st, g, Cig, Cog, (const float*)dY, (const float*)Wt,
+                     (float*)dA);
+    else
+      SURGEON_LAUNCH(da_conv_grouped_kernel<uint16_t>, grid, dim3(256), lds, st, g, Cig, Cog, (const uint16_t*)dY,
+                     (const uint16_t*)Wt, (uint16_t*)dA);
+    SURGEON_LAUNCH_CHECK();
+    return SURGEON_OK;
   }
   if (linear && d->dtype == SURGEON_BF16 && d->N % 8 == 0 && ((uintptr_t)dY % 16) == 0 && d->M >= 64 && d->K >= 64 &&
       d->N >= 64 && ceil_div(d->M, kBf16LinearTile) * ceil_div(d->K, kBf16LinearTile) <= 0x7fffffff)

@@ -240,6 +240,33 @@ def test_da_random_conv_shapes(seed):
         done += 1
 
 
+DA_GROUPED = [
+    # Nb, Ci, H, W, Co, k, stride, pad, groups
+    (2, 64, 16, 16, 64, 3, 1, 1, 8), (2, 32, 9, 9, 64, 3, 2, 1, 4), (3, 40, 12, 10, 40, 3, 1, 1, 40), (1, 12, 7, 7, 24, 5, 2, 2, 3),
+    (2, 8, 8, 8, 8, 1, 1, 0, 2), (1, 130, 33, 17, 130, 3, 1, 1, 130), (2, 6, 40, 40, 12, 7, 1, 3, 6),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", DA_GROUPED)
+def test_da_grouped_conv(dtype, case):
+    """Activation gradient of grouped and depthwise layers against the oracle (outputs pre-filled with NaN)."""
+    Nb, Ci, H, W, Co, k, st, pad, groups = case
+    print("da grouped conv", case, dtype, flush=True)
+    OH, OW = (H + 2 * pad - k) // st + 1, (W + 2 * pad - k) // st + 1
+    dY = wl.draw((Nb, Co, OH, OW), "normal", dtype, sum(case) + 15)
+    Wt = (wl.draw((Co, Ci // groups, k, k), "normal", dtype, sum(case) + 16) * 0.1).to(dY.dtype)
+    dA = torch.full((Nb, Ci, H, W), float("nan"), dtype=dY.dtype, device=DEV)
+    desc = surgeon.conv2d_desc(Nb, Ci, H, W, Co, k, k, st, pad, sdt(dtype), 0, groups=groups)
+    surgeon.surgeon_da(desc, dY.to(DEV), Wt.to(DEV), dA)
+    torch.cuda.synchronize()
+    ref = oracle.da_conv2d_grouped(bits(dY), bits(Wt), Nb, Ci, H, W, Co, k, k, st, pad, groups)
+    assert_out_close(bits(dA), ref, dtype, case)
+    with pytest.raises(surgeon.SurgeonError):  # groups that do not divide the channels
+        surgeon.surgeon_da(surgeon.conv2d_desc(Nb, Ci, H, W, Co, k, k, st, pad, sdt(dtype), 0, groups=groups + 1 if Ci % (groups + 1) else 7 * Ci),
+                           dY.to(DEV), Wt.to(DEV), dA)
+
+
 @pytest.mark.parametrize("cfg,name", [(1, "s2b1.conv1"), (1, "s3b2.conv2"), (2, "s2b1.conv2"), (2, "s3b2.conv3"),
                                       (3, "blk0.qkv"), (3, "blk11.fc2"), (4, "st1b1.fc1"), (4, "dec.cls")])
 def test_da_full_size_sampled(cfg, name):
