@@ -123,10 +123,24 @@ static __global__ __launch_bounds__(1024) void rank_scan_kernel(uint32_t* __rest
   }
 }
 
+// SUM_BASE: block_base holds the blocks' plain sums and each block adds up the ones in front of it itself (for tables of
+// at most kRankFusedBlocks blocks -- tensors of up to 33.5 M elements -- this costs less than the single-block scan
+// launch in between)
+constexpr int kRankFusedBlocks = 512;
+template <bool SUM_BASE>
 static __global__ __launch_bounds__(kRankBlock) void rank_write_kernel(const uint64_t* __restrict__ mask, int64_t n_words,
                                                                 const uint32_t* __restrict__ block_base,
                                                                 uint32_t* __restrict__ word_rank) {
   __shared__ uint32_t lds4[kRankBlock / 64];
+  uint32_t first = 0;
+  if constexpr (SUM_BASE) {
+    uint32_t pre = 0;
+    for (int i = threadIdx.x; i < (int)blockIdx.x; i += kRankBlock) pre += block_base[i];
+    block_excl_scan_u32(pre, lds4, &first);
+    __syncthreads();  // lds4 is used again below
+  } else {
+    first = block_base[blockIdx.x];
+  }
   const int64_t w0 = (int64_t)blockIdx.x * kRankWordsPerBlock + threadIdx.x * 4;
   uint32_t c[4];
   uint32_t s = 0;
@@ -136,12 +150,32 @@ static __global__ __launch_bounds__(kRankBlock) void rank_write_kernel(const uin
     s += c[q];
   }
   uint32_t total;
-  uint32_t base = block_base[blockIdx.x] + block_excl_scan_u32(s, lds4, &total);
+  uint32_t base = first + block_excl_scan_u32(s, lds4, &total);
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     if (w0 + q < n_words) word_rank[w0 + q] = base;
     base += c[q];
   }
+}
+
+// the general rank table (kept elements in front of every mask word): two launches for tables of moderate size, three
+// (with a single-block scan of the block sums) beyond
+static inline int launch_rank_table(const uint64_t* mask, int64_t n_words, int64_t n_rank_blocks, uint32_t* block_sum,
+                                    uint32_t* word_rank, hipStream_t st) {
+  SURGEON_LAUNCH(rank_block_sum_kernel, dim3((unsigned)n_rank_blocks), dim3(kRankBlock), 0, st, mask, n_words, block_sum);
+  SURGEON_LAUNCH_CHECK();
+  if (n_rank_blocks <= kRankFusedBlocks) {
+    SURGEON_LAUNCH(rank_write_kernel<true>, dim3((unsigned)n_rank_blocks), dim3(kRankBlock), 0, st, mask, n_words,
+                   (const uint32_t*)block_sum, word_rank);
+    SURGEON_LAUNCH_CHECK();
+    return SURGEON_OK;
+  }
+  SURGEON_LAUNCH(rank_scan_kernel, dim3(1), dim3(1024), 0, st, block_sum, (int)n_rank_blocks);
+  SURGEON_LAUNCH_CHECK();
+  SURGEON_LAUNCH(rank_write_kernel<false>, dim3((unsigned)n_rank_blocks), dim3(kRankBlock), 0, st, mask, n_words,
+                 (const uint32_t*)block_sum, word_rank);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
 }
 
 // Rank table when every group of `words_per_group` mask words is known to hold exactly k_full kept elements
@@ -1291,14 +1325,8 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
                        mask, p.n_words, p.rank_words_per_group, p.rank_groups, (uint32_t)p.rank_k_full, word_rank);
     SURGEON_LAUNCH_CHECK();
   } else {
-  SURGEON_LAUNCH(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
-                     block_sum);
-  SURGEON_LAUNCH_CHECK();
-  SURGEON_LAUNCH(rank_scan_kernel, dim3(1), dim3(1024), 0, st, block_sum, (int)p.n_rank_blocks);
-  SURGEON_LAUNCH_CHECK();
-  SURGEON_LAUNCH(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
-                     (const uint32_t*)block_sum, word_rank);
-  SURGEON_LAUNCH_CHECK();
+  const int rc_rank = launch_rank_table(mask, p.n_words, p.n_rank_blocks, block_sum, word_rank, st);
+  if (rc_rank != SURGEON_OK) return rc_rank;
   }
   }
 

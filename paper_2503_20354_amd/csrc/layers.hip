@@ -212,13 +212,8 @@ static int run_affine(const AffinePlan& p, const void* vals, const uint64_t* mas
   float2* part = (float2*)(w + p.off_part);
   ProfScope prof(SURGEON_PROF_AFFINE, st);
   if (p.n > 0) {
-    SURGEON_LAUNCH(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words, block_sum);
-    SURGEON_LAUNCH_CHECK();
-    SURGEON_LAUNCH(rank_scan_kernel, dim3(1), dim3(1024), 0, st, block_sum, (int)p.n_rank_blocks);
-    SURGEON_LAUNCH_CHECK();
-    SURGEON_LAUNCH(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
-                   (const uint32_t*)block_sum, word_rank);
-    SURGEON_LAUNCH_CHECK();
+    const int rc_rank = launch_rank_table(mask, p.n_words, p.n_rank_blocks, block_sum, word_rank, st);
+    if (rc_rank != SURGEON_OK) return rc_rank;
   }
   Packed<T> pk;
   pk.vals = (const T*)vals;
@@ -653,13 +648,8 @@ static int run_grouped_t(const GroupedPlan& p, const surgeon_layer_desc* d, cons
     SURGEON_LAUNCH_CHECK();
   } else {
     ProfScope prof(SURGEON_PROF_DW_AUX, st);
-    SURGEON_LAUNCH(rank_block_sum_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words, block_sum);
-    SURGEON_LAUNCH_CHECK();
-    SURGEON_LAUNCH(rank_scan_kernel, dim3(1), dim3(1024), 0, st, block_sum, (int)p.n_rank_blocks);
-    SURGEON_LAUNCH_CHECK();
-    SURGEON_LAUNCH(rank_write_kernel, dim3((unsigned)p.n_rank_blocks), dim3(kRankBlock), 0, st, mask, p.n_words,
-                   (const uint32_t*)block_sum, word_rank);
-    SURGEON_LAUNCH_CHECK();
+    const int rc_rank = launch_rank_table(mask, p.n_words, p.n_rank_blocks, block_sum, word_rank, st);
+    if (rc_rank != SURGEON_OK) return rc_rank;
   }
   Packed<T> pk;
   pk.vals = (const T*)vals;

@@ -403,6 +403,25 @@ GROUPED = [
 ]
 
 
+def test_dw_depthwise_large_layer_without_packing_hint():
+    """41.9 M elements and no (group_len, r) in the descriptor: the rank table of a tensor this large comes from the
+    three-launch prefix sum (smaller ones fuse the middle launch away), and the depthwise kernel walks 10 bands per
+    plane."""
+    Nb, C, H, W = 1, 640, 256, 256
+    print("dw depthwise large, no hint", (Nb, C, H, W), flush=True)
+    A = wl.draw((Nb, C, H, W), "relu", "bf16", 901)
+    dY = wl.draw((Nb, C, H, W), "normal", "bf16", 902)
+    p = surgeon.prune_pack(A.to(DEV), 4096, 0.9)
+    desc = surgeon.conv2d_desc(Nb, C, H, W, C, 3, 3, 1, 1, surgeon.BF16, p.k_total, groups=C)
+    dW = torch.empty((C, 1, 3, 3), device=DEV)
+    ws = torch.empty(max(16, surgeon.surgeon_dw_ws_bytes(desc)), dtype=torch.uint8, device=DEV)
+    surgeon.surgeon_dw_from_packed(desc, p.vals, p.mask, dY.to(DEV), dW, ws)
+    torch.cuda.synchronize()
+    o_vals, o_mask, _, _ = oracle.prune_pack(bits(A).reshape(-1), 4096, 0.9)
+    ref = oracle.dw_conv2d_grouped(o_vals, o_mask, bits(dY), Nb, C, H, W, C, 3, 3, 1, 1, C)
+    assert_dw_close(dW.cpu().numpy(), ref, "bf16", "depthwise large")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("case", GROUPED)
 def test_dw_grouped_conv(dtype, case):
