@@ -34,8 +34,15 @@ template <>
 struct Key<uint16_t> {
   static constexpr int kBits = 15;
   static constexpr uint32_t kMask = 0x7fffu;
-  __device__ static __forceinline__ uint32_t rot(uint16_t b) { return (((uint32_t)b & 0x7fffu) << 1) | ((uint32_t)b >> 15); }
-  __device__ static __forceinline__ uint16_t unrot(uint32_t k) { return (uint16_t)((k >> 1) | ((k & 1u) << 15)); }
+  // both are a 16-bit rotation: two copies of the value side by side, then one bit-field extract (two instructions)
+  __device__ static __forceinline__ uint32_t rot(uint16_t b) {
+    const uint32_t x = ((uint32_t)b << 16) | (uint32_t)b;
+    return __builtin_amdgcn_ubfe(x, 15u, 16u);
+  }
+  __device__ static __forceinline__ uint16_t unrot(uint32_t k) {
+    const uint32_t x = (k << 16) | k;
+    return (uint16_t)__builtin_amdgcn_ubfe(x, 1u, 16u);
+  }
 };
 
 __device__ __forceinline__ uint64_t ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
