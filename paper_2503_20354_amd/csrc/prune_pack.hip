@@ -4,8 +4,9 @@
 // Three selection paths, chosen on the host from group_len:
 //   1. wave-in-registers (group_len % 64 == 0, group_len <= 4096): one wavefront owns one group, holds it in
 //      registers (lane l, slot j <-> element 64*j + l, so one wave ballot IS one 64-bit mask word), finds the
-//      threshold by counting with ballots, then compacts with mbcnt prefix ranks.  The activation is read from
-//      HBM exactly once and nothing but the packed result is written: select and pack are fused.
+//      threshold from two LDS histogram levels and a few counting probes, then compacts with mbcnt prefix ranks.  The
+//      activation is read from HBM exactly once and nothing but the packed result is written: select and pack are
+//      fused.
 //   2. wave-from-memory (other group_len <= 4096): same ownership, elements re-read from cache, bitwise search.
 //   3. global (group_len > 4096, including the whole-tensor scope): MSB-first radix select with per-group digit
 //      histograms in the workspace, then count / scan / pack kernels over 1024-element wave chunks.
@@ -199,7 +200,7 @@ struct SelectEmitSlots {
 };
 
 // ---------------------------------------------------------------------------------------------------------
-// Histogram seeding of the threshold search (long groups).  Counting probes cost two vector instructions per element
+// Histogram seeding of the threshold search.  Counting probes cost two vector instructions per element
 // each and about ten of them are needed from a cold start; a histogram over the top ten key bits costs about as much
 // as one and a half probes (its additions run on the LDS, which this kernel does not otherwise use), and its bin
 // counts, summed from the top, name the bin that holds the k-th largest key together with the exact counts at the
@@ -207,12 +208,13 @@ struct SelectEmitSlots {
 // keys (fp32) or a single key (bf16) with exact counts at both ends, which the counting search then finishes -- often
 // without a single probe, because the bracket's low end already has exactly k keys at or above it.  Measured on
 // 4096-element fp32 groups: 38.6 -> 21.7 vector instructions per 64 elements, after which the kernel is no longer
-// bound by vector issue (61 % busy) but by how much of its loads four wavefronts per SIMD can hide.
+// bound by vector issue (61 % busy) but by how much of its loads four wavefronts per SIMD can hide.  Short groups take
+// it too: their cold-start search was a chain of scalar pop-counts and branches per probe (64-512-element bf16 groups:
+// 0.88 -> 1.09 TB/s; 768-element groups +18 %).
 // Zero keys are left out (count and position of the zeros follow from the total): a post-ReLU tensor would otherwise
 // send half of its elements to one LDS address.
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kHistBinBits = 10, kHistBins = 1 << kHistBinBits;
-constexpr int kHistMinSlots = 32;  // groups of at least 2048 elements take it
 
 // One level: bins of (rot key >> shift) & bin_mask over the rot keys in [key_lo, key_lo + key_width) (modulo 2^32; one
 // subtraction and one unsigned compare per key).  On return: bin = the bin that holds the want-th largest of those
@@ -315,29 +317,22 @@ __device__ __forceinline__ void select_pack_group(const BitsT* __restrict__ A, B
     // f_lo = count(lo) - k >= 0 and f_hi = count(hi) - k < 0 drive a regula-falsi search on the integer key;
     // when one end moves twice in a row the other end's weight is halved (Illinois rule), so the bracket
     // shrinks super-linearly on smooth distributions and at least geometrically on plateaus of ties.
-    uint32_t m = 0;
-#pragma unroll
-    for (int j = 0; j < E; ++j) m = max(m, kr[j]);
-    m = wave_max_u32(m);
-    uint32_t lo = 0, hi = (m >> 1) + 1;
-    float f_lo = (float)(E * 64 - k), f_hi = (float)(-k);
+    uint32_t lo = 0, hi = 1;
+    float f_lo = 0.0f, f_hi = 0.0f;
     int c_hi = 0;
     bool found = false;
     uint32_t thr2 = 0;
-    bool probe_nonzero = true, first_guess = true;
-    if constexpr (E >= kHistMinSlots) {
+    {
       // two histogram levels put the bracket around the k-th largest key with exact counts at both ends
       __shared__ __attribute__((aligned(16))) uint32_t hist_lds[4][kHistBins];
       uint32_t* h = hist_lds[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)];
       constexpr int S1 = Key<BitsT>::kBits + 1 - kHistBinBits;              // rot keys have kBits + 1 bits
       constexpr int S2 = S1 - kHistBinBits > 1 ? S1 - kHistBinBits : 1;     // bit 0 is the sign
       uint32_t b1 = 0, above1 = 0, in1 = 0;
-      first_guess = probe_nonzero = false;
       // level 1: every key of non-zero magnitude (rot key >= 2)
       if (!hist_level<E, true>(kr, h, lane, S1, (uint32_t)(kHistBins - 1), 2u, 0u - 2u, (uint32_t)k, &b1, &above1, &in1)) {
-        // fewer than k non-zero keys: the threshold is the tie at zero, and count(key >= 1) is the histogram's total
-        lo = 0;
-        hi = 1;
+        // fewer than k non-zero keys: the threshold is the tie at zero (lo = 0, hi = 1), and count(key >= 1) is the
+        // histogram's total
         c_hi = (int)above1;
       } else {
         // level 2: the non-zero keys of bin b1 (at least k - above1 of them), by their next S1 - S2 bits
@@ -356,39 +351,6 @@ __device__ __forceinline__ void select_pack_group(const BitsT* __restrict__ A, B
           found = true;
           thr2 = lo << 1;
         }
-      }
-    }
-    // first guess: 16 octaves below the largest magnitude (covers the populated range of typical activations)
-    constexpr uint32_t kSixteenOctaves = 16u << (Key<BitsT>::kBits - 8);
-    if (first_guess && hi > kSixteenOctaves + 1u) {
-      const uint32_t guess = hi - 1u - kSixteenOctaves;
-      const int c = count_ge<E>(kr, guess << 1);
-      if (c == k) {
-        found = true;
-        thr2 = guess << 1;
-      } else if (c > k) {
-        lo = guess;
-        f_lo = (float)(c - k);
-        probe_nonzero = false;
-      } else {
-        hi = guess;
-        c_hi = c;
-        f_hi = (float)(c - k);
-      }
-    }
-    // the non-zero count settles post-ReLU groups whose threshold is the tie at zero in one probe
-    if (!found && probe_nonzero && hi > 1) {
-      const int c = count_ge<E>(kr, 2u);
-      if (c == k) {
-        found = true;
-        thr2 = 2u;
-      } else if (c > k) {
-        lo = 1;
-        f_lo = (float)(c - k);
-      } else {
-        hi = 1;
-        c_hi = c;
-        f_hi = (float)(c - k);
       }
     }
     int last_side = 0;  // +1: lo moved last, -1: hi moved last
