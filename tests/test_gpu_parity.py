@@ -228,6 +228,9 @@ CONV_SHAPES = [
     (2, 64, 56, 56, 64, 3, 1), (2, 64, 56, 56, 256, 1, 1), (2, 128, 56, 56, 128, 3, 2), (2, 512, 7, 7, 512, 3, 1),
     (2, 5, 9, 9, 7, 5, 1), (3, 6, 12, 12, 20, 3, 1), (2, 256, 14, 14, 1024, 1, 1), (2, 40, 13, 13, 24, 3, 1),
     (3, 64, 8, 8, 160, 3, 1), (2, 48, 24, 24, 32, 3, 2), (2, 33, 40, 40, 20, 3, 1),
+    # 1x1 layers on maps whose pixel count 4 does not divide (they stay on the fp32 matrix cores: the bf16 route staged
+    # element by element was measured no faster); the packed tensor then ends inside a mask word
+    (2, 70, 7, 7, 130, 1, 1), (1, 3, 7, 7, 5, 1, 1), (3, 64, 9, 5, 64, 1, 1), (5, 512, 7, 7, 256, 1, 1), (2, 8, 5, 5, 8, 1, 1),
 ]
 
 
