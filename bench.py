@@ -347,6 +347,26 @@ def next_rows(extras, torch, surgeon, wl, dev, cfg):
             g_out[name].update({"hbm_gbps": round(_rate(nb, t_ms) / 1e9, 1), "frac_of_hbm": round(_rate(nb, t_ms) / 1e9 / PEAK_HBM_GBPS, 4)})
     out["dw_grouped"] = dict(bound="alu", peak=PEAK_VALU_F32_TFLOPS, unit="TFLOP/s", **g_out)
 
+    # what the memory pattern of the fused select+pack kernel reaches without the selection (a fixed threshold instead of
+    # the search): every layer of the workload that is packed in 4096-element groups, the same bytes counted
+    thr_bits = int(torch.tensor(0.35, dtype=tdt).view(torch.int32 if es == 4 else torch.int16).item())
+    probe = [e for e in st if e["L"].n % 4096 == 0]
+    if probe:
+        kcap = 4096
+        big = torch.cat([e["A"].reshape(-1) for e in probe])  # one launch, as the batched call packs a pass in one or two
+        pv = torch.empty(big.numel(), dtype=tdt, device=dev)
+        pm = torch.empty(big.numel() // 64, dtype=torch.int64, device=dev)
+        p = timed(lambda: surgeon.surgeon_select_pack_pattern_probe(big, thr_bits, kcap, pv, pm))
+        kept = int((big.abs() >= 0.35).sum().item())
+        nb = big.numel() * (es + 1.0 / 8.0) + kept * es
+        gb = _rate(nb, p["select_other"][0]) / 1e9
+        out["select_pack_pattern_probe"] = {"bound": "hbm", "achieved": round(gb, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                            "frac": round(gb / PEAK_HBM_GBPS, 4), "ms": round(p["select_other"][0], 4),
+                                            "launches": p["select_other"][1], "kept_fraction": round(kept / big.numel(), 3),
+                                            "what": "loads, ballot / prefix-rank compaction, stores and mask words of select+pack with a "
+                                                    "fixed threshold: the rate the memory system gives this access pattern"}
+        del pv, pm, big
+
     # selection over the whole tensor (group_len = n), the paper-literal scope: reported against 2*n*s + outputs
     e = max(st, key=lambda x: x["L"].n)
     L = e["L"]

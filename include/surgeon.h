@@ -144,6 +144,18 @@ int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, float r, int
 int surgeon_set_select_margin(float deviations);
 
 /*
+ * Benchmark aid (not part of the method): the memory pattern of the fused select+pack kernel without its selection.
+ * One wavefront per group of 4096 elements issues the group's loads up front as that kernel does, keeps the elements
+ * whose magnitude bits are at least `threshold_bits` (a fixed threshold instead of a search), stores them compacted
+ * with the same ballot / prefix-rank walk at vals + group * k_cap (at most k_cap per group; the rest are dropped) and
+ * writes the group's 64 mask words.  What this runs at is what the memory system gives that access pattern.
+ * A: n elements of dt on the device, n a multiple of 4096; vals: (n / 4096) * k_cap elements; mask: n / 64 words.
+ * Timed under kernel class 4 (SURGEON_PROF_SELECT_OTHER).
+ */
+int surgeon_select_pack_pattern_probe(const void* A, int64_t n, int dt, uint32_t threshold_bits, int64_t k_cap, void* vals,
+                                      uint64_t* mask, void* stream);
+
+/*
  * Alg. 1 lines 6-7 for l tensors in one call: the same results, bit for bit, as l calls of surgeon_prune_pack without
  * idx.  The layers of a network are small next to the chip, so per-tensor launches each pay a launch gap and a ragged
  * tail; here tensors whose group lengths share a kernel variant go out in one launch (at most ten launches per 48

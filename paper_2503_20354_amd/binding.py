@@ -59,6 +59,8 @@ def load_library():
     L.surgeon_prune_pack.argtypes = [vp, i64, i64, f32, ci, vp, vp, vp, vp, sz, vp]
     L.surgeon_set_select_margin.restype = ci
     L.surgeon_set_select_margin.argtypes = [f32]
+    L.surgeon_select_pack_pattern_probe.restype = ci
+    L.surgeon_select_pack_pattern_probe.argtypes = [vp, i64, ci, ctypes.c_uint32, i64, vp, vp, vp]
     L.surgeon_prune_pack_batched.restype = ci
     L.surgeon_prune_pack_batched.argtypes = [ci, vp, vp, vp, vp, ci, vp, vp, vp]
     L.surgeon_dw_ws_bytes.restype = ci
@@ -177,6 +179,15 @@ def surgeon_prune_pack(A, group_len, r, vals, mask, idx=None, ws=None):
 def surgeon_set_select_margin(deviations: float):
     """Bracket width (standard deviations of the sample rank) of the two-read selection of long groups."""
     _check(load_library().surgeon_set_select_margin(float(deviations)))
+
+
+def surgeon_select_pack_pattern_probe(A, threshold_bits: int, k_cap: int, vals, mask):
+    """Benchmark aid: the memory pattern of the fused select+pack kernel with a fixed threshold instead of a search."""
+    _dev(A, "A")
+    _dev(vals, "vals")
+    _dev(mask, "mask")
+    _check(load_library().surgeon_select_pack_pattern_probe(_ptr(A), A.numel(), _dt(A), int(threshold_bits), int(k_cap),
+                                                            _ptr(vals), _ptr(mask), _stream(A.device)))
 
 
 def surgeon_prune_pack_batched(As, group_lens, ratios, vals, masks):

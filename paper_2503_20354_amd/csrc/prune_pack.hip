@@ -1550,6 +1550,55 @@ extern "C" int surgeon_prune_pack(const void* A, int64_t n, int64_t group_len, f
   return run_prune_pack<uint16_t>(p, A, vals, mask, idx, ws, st);
 }
 
+// ---- benchmark aid: the memory pattern of path 1 without its selection ----
+template <typename BitsT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void select_pack_pattern_probe_kernel(
+    const BitsT* __restrict__ A, BitsT* __restrict__ vals, uint64_t* __restrict__ mask, int64_t n_groups, uint32_t thr,
+    uint32_t k_cap) {
+  constexpr int E = 64;
+  const int lane = threadIdx.x & 63;
+  const int64_t grp = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (grp >= n_groups) return;
+  const BitsT* __restrict__ src = A + grp * (int64_t)(E * 64);
+  uint32_t kr[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) kr[j] = (uint32_t)src[j * 64 + lane];
+  BitsT* __restrict__ dst = vals + grp * (int64_t)k_cap;
+  uint32_t base = 0;
+  uint64_t word = 0;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const bool keep = (kr[j] & Key<BitsT>::kMask) >= thr;
+    const uint64_t b = ballot64(keep);
+    const uint32_t pos = lane_rank(b, base);
+    if (keep && pos < k_cap) dst[pos] = (BitsT)kr[j];
+    if (lane == j) word = b;
+    base += (uint32_t)__popcll(b);
+  }
+  mask[grp * E + lane] = word;
+}
+
+extern "C" int surgeon_select_pack_pattern_probe(const void* A, int64_t n, int dt, uint32_t threshold_bits, int64_t k_cap,
+                                                 void* vals, uint64_t* mask, void* stream) {
+  if (dt != SURGEON_F32 && dt != SURGEON_BF16) return fail(SURGEON_EINVAL, "pattern probe: bad dtype %d", dt);
+  if (n < 0 || n % 4096 || k_cap < 0 || k_cap > 4096) return fail(SURGEON_EINVAL, "pattern probe: n must be a multiple of 4096, k_cap in [0, 4096]");
+  if (n == 0) return SURGEON_OK;
+  if (!A || !vals || !mask) return fail(SURGEON_EINVAL, "pattern probe: null pointer");
+  const int64_t n_groups = n / 4096;
+  if (ceil_div(n_groups, 4) > 0x7fffffff) return fail(SURGEON_EUNSUPPORTED, "pattern probe: tensor too large");
+  hipStream_t st = (hipStream_t)stream;
+  ProfScope prof(SURGEON_PROF_SELECT_OTHER, st);
+  const dim3 grid((unsigned)ceil_div(n_groups, 4));
+  if (dt == SURGEON_F32)
+    SURGEON_LAUNCH(select_pack_pattern_probe_kernel<uint32_t>, grid, dim3(256), 0, st, (const uint32_t*)A, (uint32_t*)vals, mask,
+                   n_groups, threshold_bits, (uint32_t)k_cap);
+  else
+    SURGEON_LAUNCH(select_pack_pattern_probe_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)A, (uint16_t*)vals, mask,
+                   n_groups, threshold_bits, (uint32_t)k_cap);
+  SURGEON_LAUNCH_CHECK();
+  return SURGEON_OK;
+}
+
 extern "C" int surgeon_set_select_margin(float deviations) {
   if (!(deviations >= -100.0f && deviations <= 100.0f)) return fail(SURGEON_EINVAL, "select margin %g outside [-100, 100]", (double)deviations);
   g_two_read_margin.store(deviations, std::memory_order_relaxed);

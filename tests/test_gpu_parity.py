@@ -482,3 +482,27 @@ def test_prune_pack_batched_matches_single_calls_and_oracle(dtype):
     with pytest.raises(surgeon.SurgeonError) as e:
         surgeon.surgeon_prune_pack_batched([dev_A[0], dev_A[1]], [gs[0], 100], [0.5, 0.5], vals[:2], masks[:2])
     assert e.value.status == 3
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_select_pack_pattern_probe_keeps_what_its_threshold_says(dtype):
+    """The benchmark aid does what its header says: mask bit = magnitude bits >= threshold, the kept values of a group in
+    index order at group * k_cap, at most k_cap of them."""
+    n, k_cap = 5 * 4096, 700
+    A = wl.draw((n,), "normal", dtype, 77)
+    as_uint = (lambda t: host_bits(t).view(np.uint32)) if dtype == "f32" else (lambda t: host_bits(t).view(np.uint16))
+    bits = as_uint(A)
+    thr = 0.9
+    thr_bits = int(as_uint(torch.tensor([thr], dtype=A.dtype))[0])
+    vals = torch.zeros(5 * k_cap, dtype=A.dtype, device=DEV)
+    mask = torch.zeros(n // 64, dtype=torch.int64, device=DEV)
+    surgeon.surgeon_select_pack_pattern_probe(A.to(DEV), thr_bits, k_cap, vals, mask)
+    torch.cuda.synchronize()
+    mag = bits & (0x7fffffff if dtype == "f32" else 0x7fff)
+    keep = mag >= thr_bits
+    want_mask = np.packbits(keep.reshape(-1, 64), axis=1, bitorder="little").view(np.uint64).reshape(-1)
+    assert np.array_equal(mask.cpu().numpy().view(np.uint64), want_mask)
+    got = as_uint(vals.cpu())
+    for g in range(5):
+        kept = bits[g * 4096:(g + 1) * 4096][keep[g * 4096:(g + 1) * 4096]][:k_cap]
+        assert np.array_equal(got[g * k_cap:g * k_cap + kept.size], kept)
