@@ -296,12 +296,12 @@ __device__ __forceinline__ void select_pack_group(const BitsT* __restrict__ A, B
   uint32_t kr[E];
   if (len == E * 64) {
 #pragma unroll
-    for (int j = 0; j < E; ++j) kr[j] = (uint32_t)src[j * 64 + lane];
+    for (int j = 0; j < E; ++j) kr[j] = (uint32_t)__builtin_nontemporal_load(&src[j * 64 + lane]);
 #pragma unroll
     for (int j = 0; j < E; ++j) kr[j] = Key<BitsT>::rot((BitsT)kr[j]);
   } else {
 #pragma unroll
-    for (int j = 0; j < E; ++j) kr[j] = (uint32_t)src[min(j * 64 + lane, len - 1)];
+    for (int j = 0; j < E; ++j) kr[j] = (uint32_t)__builtin_nontemporal_load(&src[min(j * 64 + lane, len - 1)]);
 #pragma unroll
     for (int j = 0; j < E; ++j) kr[j] = (j * 64 + lane < len) ? Key<BitsT>::rot((BitsT)kr[j]) : 0u;
   }
