@@ -459,11 +459,16 @@ struct PackBatch {
 
 template <int E, typename BitsT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(kSelectWaves<BitsT>))) void select_pack_wave_reg_batched_kernel(PackBatch bt) {
-  // the tensor of this workgroup = number of boundaries at or below its index (independent compares: the table comes in
-  // with a few wide scalar loads); entries past the last tensor hold the total, which no index reaches
+  // the tensor of this workgroup = the last boundary at or below its index, by a branch-free binary search whose six
+  // steps are scalar loads from the argument block (47 independent compares compile to a compare, a select and a lane
+  // read each: a fifth of the vector instructions of a 768-element group); entries past the last tensor hold the
+  // total, which no index reaches
   int t = 0;
 #pragma unroll
-  for (int i = 1; i < kPackBatch; ++i) t += ((int)blockIdx.x >= bt.first_block[i]) ? 1 : 0;
+  for (int step = 32; step >= 1; step >>= 1) {
+    const int c = min(t + step, kPackBatch);
+    t = (int)blockIdx.x >= bt.first_block[c] ? c : t;
+  }
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t grp = (int64_t)((int)blockIdx.x - bt.first_block[t]) * 4 + wave;
   if (grp >= bt.n_groups[t]) return;
