@@ -706,9 +706,13 @@ struct UpdateBatch {
 
 template <typename T>
 __global__ __launch_bounds__(256) void weight_update_batched_kernel(UpdateBatch bt, float lr) {
+  // the tensor of this workgroup: the last boundary at or below its index (branch-free binary search, scalar loads)
   int t = 0;
 #pragma unroll
-  for (int i = 1; i < kUpdateBatch; ++i) t += ((int)blockIdx.x >= bt.first_block[i]) ? 1 : 0;
+  for (int step = kUpdateBatch / 2; step >= 1; step >>= 1) {
+    const int c = t + step;  // <= kUpdateBatch - 1
+    t = (int)blockIdx.x >= bt.first_block[c] ? c : t;
+  }
   T* __restrict__ Wt = (T*)bt.Wt[t];
   const float* __restrict__ dW = bt.dW[t];
   const int64_t n = bt.n[t];

@@ -113,12 +113,15 @@ struct ImpBatch {
 template <bool VEC4>
 __global__ __launch_bounds__(kImpBlock) void sumsq_batched_partial_kernel(ImpBatch bt, double* __restrict__ partial) {
   __shared__ double lds[kImpBlock / 64];
-  // the layer of this workgroup = number of layer boundaries at or below its index.  Counted over the whole table
-  // (entries past the last layer hold the total, which no index reaches): the compares are independent, so the
-  // table comes in with a few wide scalar loads instead of one dependent load per layer.
+  // the layer of this workgroup = the last layer boundary at or below its index (entries past the last layer hold
+  // the total, which no index reaches), by a branch-free binary search: six dependent scalar loads.  Counting
+  // independent compares over the whole table compiles to a compare, a select and a lane read per entry.
   int layer = 0;
 #pragma unroll
-  for (int i = 1; i < kImpBatch; ++i) layer += ((int)blockIdx.x >= bt.first_block[i]) ? 1 : 0;
+  for (int step = kImpBatch / 2; step >= 1; step >>= 1) {
+    const int c = layer + step;  // <= kImpBatch - 1
+    layer = (int)blockIdx.x >= bt.first_block[c] ? c : layer;
+  }
   const float* __restrict__ x = bt.ptr[layer];
   const int64_t begin = (int64_t)((int)blockIdx.x - bt.first_block[layer]) * kImpChunk;
   const int64_t end = min(begin + kImpChunk, bt.n[layer]);
