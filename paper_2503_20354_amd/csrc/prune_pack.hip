@@ -220,14 +220,21 @@ constexpr int kHistBinBits = 10, kHistBins = 1 << kHistBinBits;
 // subtraction and one unsigned compare per key).  On return: bin = the bin that holds the want-th largest of those
 // keys, above = how many of them lie in higher bins, inside = how many in the bin itself.  Returns false when fewer
 // than `want` keys took part; above is then their number.  h: this wavefront's kHistBins words of LDS.
-template <int E, bool ALL_NONZERO>  // ALL_NONZERO: key_lo = 2 and the range runs to the top (level 1)
+// BINS <= 64 (the second level of 16-bit keys has 32): one bin per lane, so a single word per lane is cleared and read
+// back and one wavefront scan finds the bin.
+template <int E, bool ALL_NONZERO, int BINS = kHistBins>  // ALL_NONZERO: key_lo = 2, the range runs to the top (level 1)
 __device__ __forceinline__ bool hist_level(const uint32_t (&kr)[E], uint32_t* h, int lane, int shift, uint32_t bin_mask,
                                            uint32_t key_lo, uint32_t key_width, uint32_t want, uint32_t* bin,
                                            uint32_t* above, uint32_t* inside) {
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   u32x4* h4 = reinterpret_cast<u32x4*>(h);
+  static_assert(BINS == kHistBins || BINS <= 64, "either the full table or one bin per lane");
+  if constexpr (BINS <= 64) {
+    h[lane] = 0u;
+  } else {
 #pragma unroll
-  for (int i = 0; i < kHistBins / 256; ++i) h4[lane + 64 * i] = u32x4{0u, 0u, 0u, 0u};
+    for (int i = 0; i < kHistBins / 256; ++i) h4[lane + 64 * i] = u32x4{0u, 0u, 0u, 0u};
+  }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   // The additions: per key one shift, one and-or (bin -> LDS byte address; the wavefront's region is 4 KB aligned), a
   // compare that narrows exec to the keys that take part, and the LDS add -- the last two inside one asm statement
@@ -249,6 +256,21 @@ __device__ __forceinline__ bool hist_level(const uint32_t (&kr)[E], uint32_t* h,
                    : "=&s"(saved) : "s"(key_width), "v"(kr[j] - key_lo), "v"(addr), "v"(one) : "vcc", "memory");
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  if constexpr (BINS <= 64) {
+    // lane l holds bin 63 - l (bins from BINS up were cleared and never added to)
+    const uint32_t c = h[63 - lane];
+    const uint32_t incl = wave_incl_scan_u32(c, lane);
+    const uint64_t has = ballot64(incl >= want);
+    if (has == 0) {
+      *above = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+      return false;
+    }
+    const int L = __builtin_ctzll(has);
+    *bin = (uint32_t)(63 - L);
+    *inside = (uint32_t)__builtin_amdgcn_readlane((int)c, L);
+    *above = (uint32_t)__builtin_amdgcn_readlane((int)incl, L) - *inside;
+    return true;
+  }
   // lane l sums the 16 bins of chunk 63 - l, so that a prefix sum over the lanes runs from the highest keys down
   uint32_t s = 0;
 #pragma unroll
@@ -338,7 +360,8 @@ __device__ __forceinline__ void select_pack_group(const BitsT* __restrict__ A, B
         // level 2: the non-zero keys of bin b1 (at least k - above1 of them), by their next S1 - S2 bits
         uint32_t b2 = 0, above2 = 0, in2 = 0;
         const uint32_t bin_lo = max(b1 << S1, 2u);
-        hist_level<E, false>(kr, h, lane, S2, (1u << (S1 - S2)) - 1u, bin_lo, ((b1 + 1u) << S1) - bin_lo,
+        constexpr int kBins2 = (1 << (S1 - S2)) <= 64 ? (1 << (S1 - S2)) : kHistBins;
+        hist_level<E, false, kBins2>(kr, h, lane, S2, (1u << (S1 - S2)) - 1u, bin_lo, ((b1 + 1u) << S1) - bin_lo,
                              (uint32_t)k - above1, &b2, &above2, &in2);
         const uint32_t lo_rot = (b1 << S1) | (b2 << S2);
         lo = max(lo_rot >> 1, 1u);  // the histogram holds no zero keys: its lowest bin starts at magnitude 1
