@@ -35,14 +35,17 @@ template <>
 struct Key<uint16_t> {
   static constexpr int kBits = 15;
   static constexpr uint32_t kMask = 0x7fffu;
-  // both are a 16-bit rotation: two copies of the value side by side, then one bit-field extract (two instructions)
+  // a 16-bit rotation: two copies of the value side by side, then one bit-field extract (two instructions)
   __device__ static __forceinline__ uint32_t rot(uint16_t b) {
     const uint32_t x = ((uint32_t)b << 16) | (uint32_t)b;
     return __builtin_amdgcn_ubfe(x, 15u, 16u);
   }
+  // (the low 16 bits of (k << 15) | (k >> 1); one shift and one shift-or, tied down because the compiler otherwise
+  // rewrites the pair as a 32-bit multiply, which runs at a quarter of the rate)
   __device__ static __forceinline__ uint16_t unrot(uint32_t k) {
-    const uint32_t x = (k << 16) | k;
-    return (uint16_t)__builtin_amdgcn_ubfe(x, 1u, 16u);
+    uint32_t r;
+    asm("v_lshl_or_b32 %0, %1, 15, %2" : "=v"(r) : "v"(k), "v"(k >> 1));
+    return (uint16_t)r;
   }
 };
 
