@@ -202,6 +202,38 @@ struct SelectEmitSlots {
   }
 };
 
+// The same walk for a threshold key with ties: everything above the threshold magnitude is kept and, in index order,
+// the first `need` elements equal to it.  Per slot two compares; whether the slot lies before the cut (keep its ties),
+// behind it (drop them) or holds it (a scalar loop strips the surplus ties from the top, once per group) is decided on
+// the scalar unit from the running count of ties, so no keep word makes the trip through a lane and back.
+template <int J, int E, typename BitsT, bool WITH_IDX>
+struct TieEmitSlots {
+  __device__ static __forceinline__ void run(const uint32_t (&kr)[E], int lane, uint32_t thr2, uint32_t need, uint32_t eq_before,
+                                             uint32_t base, uint32_t& w_lo, uint32_t& w_hi, __amdgpu_buffer_rsrc_t r_vals,
+                                             __amdgpu_buffer_rsrc_t r_idx) {
+    if constexpr (J < E) {
+      const uint64_t b_ge = ballot64(kr[J] >= thr2);
+      const uint64_t b_gt = ballot64(kr[J] > (thr2 | 1u));  // both signs of the threshold magnitude are ties
+      const uint64_t eq = b_ge & ~b_gt;
+      const uint32_t ce = (uint32_t)__popcll(eq);
+      uint64_t b = b_ge;
+      if (__builtin_expect(eq_before + ce > need, 0)) {
+        uint64_t rest = eq;  // the ties of this slot that are not kept: all but its lowest need - eq_before
+        for (uint32_t i = eq_before; i < need; ++i) rest &= rest - 1;
+        b = b_ge & ~rest;
+      }
+      const bool keep = __builtin_amdgcn_inverse_ballot_w64(b);
+      const uint32_t pos = lane_rank(b, base);
+      store_or_drop(r_vals, Key<BitsT>::unrot(kr[J]), keep ? pos * (uint32_t)sizeof(BitsT) : 0xffffffffu);
+      if constexpr (WITH_IDX) store_or_drop(r_idx, (uint32_t)(J * 64 + lane), keep ? pos * 4u : 0xffffffffu);
+      asm volatile("s_nop 1\n\tv_writelane_b32 %0, %2, %4\n\tv_writelane_b32 %1, %3, %4"
+                   : "+v"(w_lo), "+v"(w_hi) : "s"((uint32_t)b), "s"((uint32_t)(b >> 32)), "n"(J));
+      TieEmitSlots<J + 1, E, BitsT, WITH_IDX>::run(kr, lane, thr2, need, eq_before + ce, base + (uint32_t)__popcll(b), w_lo,
+                                                   w_hi, r_vals, r_idx);
+    }
+  }
+};
+
 // ---------------------------------------------------------------------------------------------------------
 // Histogram seeding of the threshold search.  Counting probes cost two vector instructions per element
 // each and about ten of them are needed from a cold start; a histogram over the top ten key bits costs about as much
@@ -418,24 +450,40 @@ __device__ __forceinline__ void select_pack_group(const BitsT* __restrict__ A, B
       // and the first `need` elements equal to it in index order.
       thr2 = lo << 1;
       const uint32_t need = (uint32_t)(k - c_hi);
-      uint32_t gt_lo = 0, gt_hi = 0;
-      CollectWords<0, E, false>::run(kr, thr2, w_lo, w_hi);      // >= threshold
-      CollectWords<0, E, true>::run(kr, thr2 | 1u, gt_lo, gt_hi);  // >  threshold (both signs share thr2 | 1)
-      const uint64_t eq = (((uint64_t)w_hi << 32) | w_lo) & ~(((uint64_t)gt_hi << 32) | gt_lo);
-      const uint32_t ce = (uint32_t)__popcll(eq);
-      const uint32_t e_incl = wave_incl_scan_u32(ce, lane), e_base = e_incl - ce;  // tied elements in earlier slots
-      if (e_incl > need) {  // not all of this slot's tied elements are kept
-        uint64_t keep_eq = 0;
-        if (e_base < need) {  // the cut falls inside this slot (at most one lane): its lowest need - e_base tied bits
-          const uint32_t want = need - e_base;
-          int p = 0;
+      if constexpr (sizeof(BitsT) == 2) {
+        // 16-bit keys: a 4096-element group has several elements per key value around its threshold, so this is the
+        // usual way out and gets the one-walk form (ResNet-50 / ViT / segmentation workloads +1-4 %)
+        const __amdgpu_buffer_rsrc_t r_vals = __builtin_amdgcn_make_buffer_rsrc(
+            vals + grp * (int64_t)k_full, 0, k * (int)sizeof(BitsT), kBufferRsrcWord3);
+        const __amdgpu_buffer_rsrc_t r_idx = __builtin_amdgcn_make_buffer_rsrc(
+            WITH_IDX ? idx + grp * (int64_t)k_full : (uint32_t*)nullptr, 0, WITH_IDX ? k * 4 : 0, kBufferRsrcWord3);
+        TieEmitSlots<0, E, BitsT, WITH_IDX>::run(kr, lane, thr2, need, 0u, 0u, w_lo, w_hi, r_vals, r_idx);
+        const int n_words = (len + 63) >> 6;
+        if (lane < n_words) mask[(gstart >> 6) + lane] = ((uint64_t)w_hi << 32) | w_lo;
+        return;
+      } else {
+        // 32-bit keys: ties are the exception (a plateau of zeros behind a ReLU, a clipped maximum); the keep words are
+        // collected on the lanes, the cut is found there, and the generic pack below emits them (the one-walk form
+        // here made the kernel a third longer and the headline workload 1 % slower)
+        uint32_t gt_lo = 0, gt_hi = 0;
+        CollectWords<0, E, false>::run(kr, thr2, w_lo, w_hi);      // >= threshold
+        CollectWords<0, E, true>::run(kr, thr2 | 1u, gt_lo, gt_hi);  // >  threshold (both signs share thr2 | 1)
+        const uint64_t eq = (((uint64_t)w_hi << 32) | w_lo) & ~(((uint64_t)gt_hi << 32) | gt_lo);
+        const uint32_t ce = (uint32_t)__popcll(eq);
+        const uint32_t e_incl = wave_incl_scan_u32(ce, lane), e_base = e_incl - ce;  // tied elements in earlier slots
+        if (e_incl > need) {  // not all of this slot's tied elements are kept
+          uint64_t keep_eq = 0;
+          if (e_base < need) {  // the cut falls inside this slot (at most one lane): its lowest need - e_base tied bits
+            const uint32_t want = need - e_base;
+            int p = 0;
 #pragma unroll
-          for (int step = 32; step >= 1; step >>= 1)
-            if ((uint32_t)__popcll(eq & low_bits64(p + step)) < want) p += step;
-          keep_eq = eq & low_bits64(p + 1);
+            for (int step = 32; step >= 1; step >>= 1)
+              if ((uint32_t)__popcll(eq & low_bits64(p + step)) < want) p += step;
+            keep_eq = eq & low_bits64(p + 1);
+          }
+          w_lo = gt_lo | (uint32_t)keep_eq;
+          w_hi = gt_hi | (uint32_t)(keep_eq >> 32);
         }
-        w_lo = gt_lo | (uint32_t)keep_eq;
-        w_hi = gt_hi | (uint32_t)(keep_eq >> 32);
       }
     }
   }
