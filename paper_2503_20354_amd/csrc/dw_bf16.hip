@@ -56,16 +56,21 @@ __global__ __launch_bounds__(256) void unpack_dense_kernel(const T* __restrict__
 
 // The same un-pack when every group of `words_per_group` mask words is known to hold exactly k_full kept elements (the
 // packing's group length is a multiple of 64, at most 4096): one wavefront per group finds its words' positions with
-// a popcount and a prefix sum over the lanes, so no rank table is needed, and then expands word by word with all 64
-// lanes on the 64 elements of a word (reads of vals and writes of dense are contiguous).
+// a popcount and a prefix sum over the lanes, so no rank table is needed.  The group's kept values are contiguous in
+// `vals`: the wavefront copies them into its part of LDS with coalesced loads and expands from there (lane l builds 8
+// consecutive elements, one 16-byte store), so the per-element gathers run on the LDS instead of as 64-address
+// 2-byte loads through the texture path, with 32-bit positions and no clamps.  `lds_per_wave` >= k_full + 1 elements.
 template <typename T>
 __global__ __launch_bounds__(256) void unpack_grouped_kernel(const T* __restrict__ vals, const uint64_t* __restrict__ mask,
                                                              int64_t n_words, int words_per_group, int64_t n_groups,
-                                                             uint32_t k_full, int64_t k_last, int64_t n,
+                                                             uint32_t k_full, int64_t k_last, int64_t n, int lds_per_wave,
                                                              T* __restrict__ dense) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char unpack_lds[];
   const int lane = threadIdx.x & 63;
-  const int64_t grp = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t grp = (int64_t)blockIdx.x * 4 + wave;
   if (grp >= n_groups) return;
+  T* lv = reinterpret_cast<T*>(unpack_lds) + (size_t)wave * lds_per_wave;
   const int64_t w0 = grp * words_per_group;
   const bool has_word = lane < words_per_group && w0 + lane < n_words;
   const uint64_t word = has_word ? mask[w0 + lane] : 0ull;
@@ -76,9 +81,30 @@ __global__ __launch_bounds__(256) void unpack_grouped_kernel(const T* __restrict
     const uint32_t up = (uint32_t)__shfl_up((int)incl, off, 64);
     if (lane >= off) incl += up;
   }
-  const uint32_t rank = (uint32_t)grp * k_full + incl - c;
+  const uint32_t rank = incl - c;  // position of the word's first kept value inside the group
+  // the group's kept values -> LDS (a mask that disagrees with the hint cannot carry the copy past the group's part
+  // of LDS or past the end of vals)
+  const int64_t v0 = grp * (int64_t)k_full;
+  const uint32_t v_left = (uint32_t)max(min(k_last + 1 - v0, (int64_t)k_full), (int64_t)0);  // values from v0 to the end
+  const uint32_t k_here = min((uint32_t)__builtin_amdgcn_readlane((int)incl, 63), v_left);
+  const T* __restrict__ gv = vals + v0;
+  for (uint32_t i0 = 0; i0 < k_here; i0 += 256) {  // wave-uniform trip count; four loads in flight per lane
+    uint32_t idx[4];
+    T t[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      idx[q] = min(i0 + 64u * q + (uint32_t)lane, k_here - 1u);  // past the end: the last value again (same address)
+      t[q] = gv[idx[q]];
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) lv[idx[q]] = t[q];
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   const int n_here = (int)min((int64_t)words_per_group, n_words - w0);
-  // 8 words = 512 elements per step: lane l expands byte l % 8 of word l / 8 (8 consecutive elements, one 16-byte store)
+  const int sh = 8 * (lane & 7);
+  // 8 words = 512 elements per step: lane l expands byte l % 8 of word l / 8
   for (int j0 = 0; j0 < n_here; j0 += 8) {
     const int src = j0 + (lane >> 3);
     const bool has = src < n_here;
@@ -86,19 +112,16 @@ __global__ __launch_bounds__(256) void unpack_grouped_kernel(const T* __restrict
     const uint32_t w_hi = (uint32_t)__shfl((int)(uint32_t)(word >> 32), src & 63, 64);
     const uint32_t r0 = (uint32_t)__shfl((int)rank, src & 63, 64);
     const uint64_t w = has ? (((uint64_t)w_hi << 32) | w_lo) : 0ull;
-    const int sh = 8 * (lane & 7);
     const uint32_t bits = (uint32_t)(w >> sh) & 0xffu;
-    const int64_t first = (int64_t)r0 + __popcll(w & ((1ull << sh) - 1ull));
+    const uint32_t first = min(r0 + (uint32_t)__popcll(w & ((1ull << sh) - 1ull)), k_here);
     T v[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
-      int64_t pos = first + __builtin_popcount(bits & ((1u << t) - 1u));
-      pos = pos > k_last ? k_last : pos;
-      v[t] = vals[pos];
+      // at most k_here for a dropped element behind the last kept one: inside the wavefront's part of LDS
+      const uint32_t pos = min(first + (uint32_t)__builtin_popcount(bits & ((1u << t) - 1u)), k_here);
+      const T x = lv[pos];
+      v[t] = ((bits >> t) & 1u) ? x : (T)0;
     }
-#pragma unroll
-    for (int t = 0; t < 8; ++t)
-      if (!((bits >> t) & 1u)) v[t] = (T)0;
     const int64_t e0 = (w0 + src) * 64 + sh;
     if (has && e0 + 8 <= n) {
 #pragma unroll
@@ -153,10 +176,13 @@ int launch_unpack_grouped(const void* vals, const uint64_t* mask, int64_t n_word
     SURGEON_LAUNCH(unpack_grouped_short_kernel<uint16_t>, dim3((unsigned)ceil_div(n_groups, 4)), dim3(256), 0, st,
                    (const uint16_t*)vals, mask, n_words, words_per_group, n_groups, (uint32_t)k_full, k_total - 1, n,
                    (uint16_t*)dense);
-  else
-    SURGEON_LAUNCH(unpack_grouped_kernel<uint16_t>, dim3((unsigned)ceil_div(n_groups, 4)), dim3(256), 0, st,
-                   (const uint16_t*)vals, mask, n_words, words_per_group, n_groups, (uint32_t)k_full, k_total - 1, n,
-                   (uint16_t*)dense);
+  else {
+    // LDS: each of the four wavefronts holds its group's kept values (and one element of slack)
+    const int lds_per_wave = (int)align_up((size_t)k_full + 1, 8);
+    SURGEON_LAUNCH(unpack_grouped_kernel<uint16_t>, dim3((unsigned)ceil_div(n_groups, 4)), dim3(256),
+                   (size_t)4 * lds_per_wave * sizeof(uint16_t), st, (const uint16_t*)vals, mask, n_words, words_per_group,
+                   n_groups, (uint32_t)k_full, k_total - 1, n, lds_per_wave, (uint16_t*)dense);
+  }
   SURGEON_LAUNCH_CHECK();
   return SURGEON_OK;
 }
