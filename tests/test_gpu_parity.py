@@ -320,6 +320,43 @@ def test_dw_group_hint_changes_nothing():
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("case", [("linear", 300, 320, 192, 320, 0.9), ("linear", 257, 768, 256, 768, 0.0),
+                                  ("linear", 130, 3072, 128, 3072, 0.5), ("linear", 64, 4096, 64, 4096, 0.0),
+                                  ("linear", 96, 4096, 72, 4096, 0.97), ("conv1x1", 3, 70, 8, 96, 4096, 0.6),
+                                  ("conv1x1", 5, 64, 12, 128, 4096, 0.0)])
+def test_dw_bf16_dense_copy_with_and_without_the_hint(case):
+    """bf16 linear and 1x1 layers rebuild the dense activation first; with the packing hint one wavefront per group
+    expands its kept values from LDS (every group length up to 4096, nothing dropped, nearly everything dropped, a
+    ragged last group), without it the rank-table kernel does.  Same bits either way, and the oracle's dW."""
+    print("dense copy", case, flush=True)
+    if case[0] == "linear":
+        _, M, K, N, g, r = case
+        A = wl.draw((M, K), "normal", "bf16", 31)
+        dY = wl.draw((M, N), "normal", "bf16", 32)
+        p, (o_vals, o_mask) = check_pack(A, g, r, want_idx=False)
+        plain = surgeon.linear_desc(M, K, N, surgeon.BF16, p.k_total)
+        hinted = surgeon.linear_desc(M, K, N, surgeon.BF16, p.k_total, group_len=g, r=r)
+        shape = (N, K)
+        ref = oracle.dw_linear(o_vals, o_mask, host_bits(dY), M, K, N)
+    else:
+        _, Nb, Ci, HW, Co, g, r = case
+        A = wl.draw((Nb, Ci, HW, HW), "relu", "bf16", 33)
+        dY = wl.draw((Nb, Co, HW, HW), "normal", "bf16", 34)
+        p, (o_vals, o_mask) = check_pack(A, g, r, want_idx=False)
+        plain = surgeon.conv2d_desc(Nb, Ci, HW, HW, Co, 1, 1, 1, 0, surgeon.BF16, p.k_total)
+        hinted = surgeon.conv2d_desc(Nb, Ci, HW, HW, Co, 1, 1, 1, 0, surgeon.BF16, p.k_total, group_len=g, r=r)
+        shape = (Co, Ci, 1, 1)
+        ref = oracle.dw_conv2d(o_vals, o_mask, host_bits(dY), Nb, Ci, HW, HW, Co, 1, 1, 1, 0)
+    ws = torch.empty(max(surgeon.surgeon_dw_ws_bytes(plain), surgeon.surgeon_dw_ws_bytes(hinted)), dtype=torch.uint8, device=DEV)
+    a, b = torch.empty(shape, device=DEV), torch.empty(shape, device=DEV)
+    dYd = dY.to(DEV)
+    surgeon.surgeon_dw_from_packed(plain, p.vals, p.mask, dYd, a, ws)
+    surgeon.surgeon_dw_from_packed(hinted, p.vals, p.mask, dYd, b, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    assert_dw_close(b.cpu().numpy(), ref, "bf16")
+
+
 def test_dw_is_deterministic():
     shape = (8, 160, 32, 32, 160, 3, 1)
     Nb, Ci, H, W, Co, k, st = shape
