@@ -852,24 +852,51 @@ __global__ __attribute__((amdgpu_flat_work_group_size(256, 256))) void dw_linear
 
 // adds the split partials in index order.  GI: also the sum of squares of what this workgroup wrote (Eq. 4's sum folded
 // into the pass that produces dW, so that the gradient is not read again): fp64, fixed order, one partial per workgroup.
-template <bool GI>
+// VEC: four consecutive weights per thread with 16-byte accesses (n_w a multiple of 4, dW 16-byte aligned; the partials
+// start on a 256-byte boundary of the workspace).  Each weight's additions run in split order either way.
+template <bool GI, bool VEC>
 static __global__ __launch_bounds__(256) void dw_reduce_splits_kernel(const float* __restrict__ part, int n_splits, int64_t n_w,
                                                                float* __restrict__ dW, double* __restrict__ sq_partial) {
   double sq = 0.0;
-  for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n_w; x += (int64_t)gridDim.x * 256) {
-    // eight loads in flight at a time; the additions stay in split order, so the result does not depend on the batching
-    float s = 0.0f;
-    int k = 0;
-    for (; k + 8 <= n_splits; k += 8) {
-      float v[8];
+  if constexpr (VEC) {
+    const int64_t n4 = n_w >> 2;
+    const float4* __restrict__ part4 = reinterpret_cast<const float4*>(part);
+    float4* __restrict__ dW4 = reinterpret_cast<float4*>(dW);
+    for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n4; x += (int64_t)gridDim.x * 256) {
+      float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      int k = 0;
+      for (; k + 4 <= n_splits; k += 4) {  // four 16-byte loads in flight; the additions stay in split order
+        float4 v[4];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) v[q] = part[(int64_t)(k + q) * n_w + x];
+        for (int q = 0; q < 4; ++q) v[q] = part4[(int64_t)(k + q) * n4 + x];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) s += v[q];
+        for (int q = 0; q < 4; ++q) {
+          s.x += v[q].x; s.y += v[q].y; s.z += v[q].z; s.w += v[q].w;
+        }
+      }
+      for (; k < n_splits; ++k) {
+        const float4 v = part4[(int64_t)k * n4 + x];
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+      }
+      dW4[x] = s;
+      if (GI) sq += ((double)s.x * (double)s.x + (double)s.y * (double)s.y) + ((double)s.z * (double)s.z + (double)s.w * (double)s.w);
     }
-    for (; k < n_splits; ++k) s += part[(int64_t)k * n_w + x];
-    dW[x] = s;
-    if (GI) sq += (double)s * (double)s;
+  } else {
+    for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < n_w; x += (int64_t)gridDim.x * 256) {
+      // eight loads in flight at a time; the additions stay in split order, so the result does not depend on the batching
+      float s = 0.0f;
+      int k = 0;
+      for (; k + 8 <= n_splits; k += 8) {
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = part[(int64_t)(k + q) * n_w + x];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s += v[q];
+      }
+      for (; k < n_splits; ++k) s += part[(int64_t)k * n_w + x];
+      dW[x] = s;
+      if (GI) sq += (double)s * (double)s;
+    }
   }
   if (GI) {
     __shared__ double wave_sq[4];
@@ -1361,16 +1388,26 @@ int run_dw(const DwPlan& p, const surgeon_layer_desc* d, const void* vals, const
   if (rc != SURGEON_OK) return rc;
   if (p.splits > 1) {
     // with Gradient Importance: at most 1024 workgroups, so that the finishing launch adds 4 partials per thread
-    const int blocks = (int)std::min<int64_t>(ceil_div(p.n_w, 256), G_out ? 1024 : kGiPartials);
+    // 16-byte accesses pay once there are enough weights to fill the chip with a quarter of the threads
+    const bool vec = p.n_w % 4 == 0 && p.n_w >= (1 << 19) && ((uintptr_t)dW % 16) == 0 && ((uintptr_t)part % 16) == 0;
+    const int blocks = (int)std::min<int64_t>(ceil_div(vec ? p.n_w / 4 : p.n_w, 256), G_out ? 1024 : kGiPartials);
     ProfScope prof(aux_class, st);
     if (G_out) {
-      SURGEON_LAUNCH(dw_reduce_splits_kernel<true>, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w,
-                     dW, sq_partial);
+      if (vec)
+        SURGEON_LAUNCH((dw_reduce_splits_kernel<true, true>), dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits,
+                       p.n_w, dW, sq_partial);
+      else
+        SURGEON_LAUNCH((dw_reduce_splits_kernel<true, false>), dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits,
+                       p.n_w, dW, sq_partial);
       SURGEON_LAUNCH_CHECK();
       return launch_sumsq_final(sq_partial, blocks, p.n_w, G_out, st);
     }
-    SURGEON_LAUNCH(dw_reduce_splits_kernel<false>, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, p.n_w, dW,
-                   (double*)nullptr);
+    if (vec)
+      SURGEON_LAUNCH((dw_reduce_splits_kernel<false, true>), dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits,
+                     p.n_w, dW, (double*)nullptr);
+    else
+      SURGEON_LAUNCH((dw_reduce_splits_kernel<false, false>), dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits,
+                     p.n_w, dW, (double*)nullptr);
     SURGEON_LAUNCH_CHECK();
   } else if (G_out) {
     // the matrix-core kernel wrote dW itself: one read of it (small, mostly still in cache) for the sum of squares

@@ -688,12 +688,12 @@ static int run_grouped_t(const GroupedPlan& p, const surgeon_layer_desc* d, cons
     const int blocks = (int)std::min<int64_t>(ceil_div(g.n_w, 256), kGiPartials);
     ProfScope prof(SURGEON_PROF_DW_AUX, st);
     if (G_out) {
-      SURGEON_LAUNCH(dw_reduce_splits_kernel<true>, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, g.n_w, dW,
+      SURGEON_LAUNCH((dw_reduce_splits_kernel<true, false>), dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, g.n_w, dW,
                      sq_partial);
       SURGEON_LAUNCH_CHECK();
       return launch_sumsq_final(sq_partial, blocks, g.n_w, G_out, st);
     }
-    SURGEON_LAUNCH(dw_reduce_splits_kernel<false>, dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, g.n_w, dW,
+    SURGEON_LAUNCH((dw_reduce_splits_kernel<false, false>), dim3(blocks), dim3(256), 0, st, (const float*)part, p.splits, g.n_w, dW,
                    (double*)nullptr);
     SURGEON_LAUNCH_CHECK();
   } else if (G_out) {
