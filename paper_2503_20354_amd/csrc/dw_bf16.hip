@@ -172,7 +172,17 @@ int launch_unpack_grouped(const void* vals, const uint64_t* mask, int64_t n_word
                           int64_t k_full, int64_t n, int64_t k_total, void* dense, hipStream_t st) {
   if (n == 0) return SURGEON_OK;
   ProfScope prof(SURGEON_PROF_DW_AUX, st);
-  if (words_per_group <= 4)
+  if (words_per_group <= 4 && 64 % words_per_group == 0) {
+    // groups of one, two or four mask words: 64 words' worth of consecutive groups are one wavefront's unit.  Every
+    // group but the tensor's last holds exactly k_full values, so the unit is a group of 64 words with that many times
+    // k_full values as far as the kernel is concerned (a sixteenth to a quarter of the wavefronts, 16-byte stores).
+    const int per = 64 / words_per_group;
+    const int64_t k_unit = k_full * per;
+    const int lds_per_wave = (int)align_up((size_t)k_unit + 1, 8);
+    SURGEON_LAUNCH(unpack_grouped_kernel<uint16_t>, dim3((unsigned)ceil_div(ceil_div(n_groups, per), 4)), dim3(256),
+                   (size_t)4 * lds_per_wave * sizeof(uint16_t), st, (const uint16_t*)vals, mask, n_words, 64,
+                   ceil_div(n_groups, per), (uint32_t)k_unit, k_total - 1, n, lds_per_wave, (uint16_t*)dense);
+  } else if (words_per_group <= 4)
     SURGEON_LAUNCH(unpack_grouped_short_kernel<uint16_t>, dim3((unsigned)ceil_div(n_groups, 4)), dim3(256), 0, st,
                    (const uint16_t*)vals, mask, n_words, words_per_group, n_groups, (uint32_t)k_full, k_total - 1, n,
                    (uint16_t*)dense);

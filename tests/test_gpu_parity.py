@@ -322,12 +322,14 @@ def test_dw_group_hint_changes_nothing():
 
 @pytest.mark.parametrize("case", [("linear", 300, 320, 192, 320, 0.9), ("linear", 257, 768, 256, 768, 0.0),
                                   ("linear", 130, 3072, 128, 3072, 0.5), ("linear", 64, 4096, 64, 4096, 0.0),
-                                  ("linear", 96, 4096, 72, 4096, 0.97), ("conv1x1", 3, 70, 8, 96, 4096, 0.6),
+                                  ("linear", 96, 4096, 72, 4096, 0.97), ("linear", 1003, 64, 64, 64, 0.5),
+                                  ("linear", 333, 128, 96, 128, 0.9), ("linear", 257, 256, 64, 256, 0.0),
+                                  ("linear", 130, 192, 64, 192, 0.7), ("conv1x1", 3, 70, 8, 96, 4096, 0.6),
                                   ("conv1x1", 5, 64, 12, 128, 4096, 0.0)])
 def test_dw_bf16_dense_copy_with_and_without_the_hint(case):
     """bf16 linear and 1x1 layers rebuild the dense activation first; with the packing hint one wavefront per group
-    expands its kept values from LDS (every group length up to 4096, nothing dropped, nearly everything dropped, a
-    ragged last group), without it the rank-table kernel does.  Same bits either way, and the oracle's dW."""
+    expands its kept values from LDS (every group length up to 4096, groups of one to four mask words taken 64 words at a
+    time, nothing dropped, nearly everything dropped, a ragged last group), without it the rank-table kernel does.  Same bits either way, and the oracle's dW."""
     print("dense copy", case, flush=True)
     if case[0] == "linear":
         _, M, K, N, g, r = case
